@@ -1,0 +1,367 @@
+"""Plain fp64 CPU oracle for FREE's parallel verification pass.
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+cpu-baseline leg of the benchmark.  The product path never imports it and it
+imports nothing from the product package.  NumPy only; every floating-point
+quantity is float64.  No blocking, fusion or reordering: each function is the
+definition written out so it can be checked against the paper by eye.
+
+What it follows
+---------------
+* Verification of one draft: Alg. 2 (accept with probability
+  min(1, q(x^)/p(x^)), reflect on rejection), with the likelihood ratio in the
+  form of Eq. (qp) and the relaxed rule of Eq. (acc_relax).
+* Sequential check of the K drafts of a round, stopping at the first
+  rejection: Alg. 1, inner verification loop; Sec. 3.3.
+* Noise prediction -> transition mean with the fixed posterior variance:
+  Eq. (ddpm_update), App. C.
+* The packed target forward: the paper only cites the class-conditional DiT;
+  the architecture below (patchify, sinusoidal timestep + label embedding,
+  adaLN-Zero blocks, final adaLN layer, unpatchify) is the public DiT design
+  restated as formulas.  Conventions the paper does not fix are listed in the
+  module-level constants and in the function docstrings.
+
+Pins (see tests): closed-form acceptance rate of App. D, preservation of the
+target marginal (App. B, unbiasedness), reflection invariants (Lemmas 1-2),
+lambda=1 reduction and monotonicity (Sec. 3.4), the DDPM posterior identities
+for the schedule, adaLN-Zero identity blocks, permutation/packing invariance,
+and agreement with an independent implementation built from library routines.
+The DiT forward has no published activations to compare against: beyond those
+invariants and the library-routine cross-check it is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+F64 = np.float64
+
+LN_EPS = 1e-6            # LayerNorm epsilon (no affine parameters, biased variance)
+MAX_PERIOD = 10000.0     # base of both sinusoidal embeddings
+TIE_WINDOW = 1e-4        # |lambda*l - log u| below this is flagged as a tie
+
+
+# ----------------------------------------------------------------------------
+# Diffusion schedule and eps -> mean  (Eq. ddpm_update; App. C)
+# ----------------------------------------------------------------------------
+def ddpm_schedule(T: int = 1000, beta_start: float = 1e-4, beta_end: float = 0.02) -> dict:
+    """Linear-beta DDPM schedule, 0-indexed (index i is network timestep i).
+
+    beta_i linear from beta_start to beta_end; alpha = 1 - beta;
+    alphabar_i = prod_{j<=i} alpha_j with alphabar_{-1} = 1;
+    posterior variance betatilde_i = beta_i (1 - alphabar_{i-1}) / (1 - alphabar_i);
+    sigma_i = sqrt(betatilde_i) (App. C: the fixed variance is the posterior one).
+    `sigma_clipped` replaces index 0 (where betatilde = 0) by index 1 so that a
+    verification step never divides by zero.
+    """
+    i = np.arange(T, dtype=F64)
+    beta = beta_start + (beta_end - beta_start) * i / (T - 1)
+    alpha = 1.0 - beta
+    alphabar = np.cumprod(alpha)
+    alphabar_prev = np.concatenate([[1.0], alphabar[:-1]])
+    beta_tilde = beta * (1.0 - alphabar_prev) / (1.0 - alphabar)
+    sigma = np.sqrt(beta_tilde)
+    sigma_clipped = sigma.copy()
+    sigma_clipped[0] = sigma[1]
+    return dict(T=T, beta=beta, alpha=alpha, alphabar=alphabar, alphabar_prev=alphabar_prev,
+                beta_tilde=beta_tilde, sigma=sigma, sigma_clipped=sigma_clipped)
+
+
+def eps_to_mean(x: np.ndarray, eps: np.ndarray, i: int, sched: dict) -> np.ndarray:
+    """Transition mean of Eq. (ddpm_update) without the noise term:
+    m = (x - (1 - alpha_i) / sqrt(1 - alphabar_i) * eps) / sqrt(alpha_i)."""
+    x = np.asarray(x, F64)
+    eps = np.asarray(eps, F64)
+    a = sched["alpha"][i]
+    ab = sched["alphabar"][i]
+    return (x - (1.0 - a) / math.sqrt(1.0 - ab) * eps) / math.sqrt(a)
+
+
+def mean_coefficients(i, sched: dict):
+    """(coef_x, coef_eps) with m = coef_x * x + coef_eps * eps, same formula."""
+    a = sched["alpha"][i]
+    ab = sched["alphabar"][i]
+    return 1.0 / np.sqrt(a), -(1.0 - a) / (np.sqrt(1.0 - ab) * np.sqrt(a))
+
+
+# ----------------------------------------------------------------------------
+# Verification (Alg. 2, Eq. qp, Eq. acc_relax)
+# ----------------------------------------------------------------------------
+def log_ratio(m_hat, m, sigma: float, x_hat) -> float:
+    """log of N(x^; m, s^2 I) / N(x^; m^, s^2 I) in the form of Eq. (qp):
+    (m - m^)^T (x^ - mid) / s^2 with mid = (m + m^)/2."""
+    m_hat = np.asarray(m_hat, F64).ravel()
+    m = np.asarray(m, F64).ravel()
+    x_hat = np.asarray(x_hat, F64).ravel()
+    mid = 0.5 * (m + m_hat)
+    return float(np.dot(m - m_hat, x_hat - mid) / (float(sigma) ** 2))
+
+
+def reflect(m_hat, m, x_hat) -> np.ndarray:
+    """Rejection branch of Alg. 2: e = (m^ - m)/||m^ - m||,
+    x = m + (I - 2 e e^T)(x^ - m^)."""
+    m_hat = np.asarray(m_hat, F64)
+    m = np.asarray(m, F64)
+    x_hat = np.asarray(x_hat, F64)
+    diff = (m_hat - m).ravel()
+    e = diff / math.sqrt(float(np.dot(diff, diff)))
+    r = (x_hat - m_hat).ravel()
+    out = m.ravel() + r - 2.0 * e * float(np.dot(e, r))
+    return out.reshape(m.shape)
+
+
+def verification(m_hat, m, sigma: float, x_hat, u: float, lam: float = 1.0):
+    """Alg. 2 with the relaxed rule of Eq. (acc_relax); lam = 1 is the strict rule.
+
+    Returns (x, accepted, l, tie) where l is the unscaled log-ratio of Eq. (qp).
+    The test u <= min(1, exp(lam*l)) is taken in the log domain,
+    log u <= min(0, lam*l), which is the same decision (log is monotone) and
+    cannot overflow; u = 0 always accepts.  If m^ == m the ratio is one, the
+    draft is accepted whatever u is and the (undefined) direction e is never
+    formed.  `tie` flags decisions within TIE_WINDOW of the threshold.
+    """
+    m_hat = np.asarray(m_hat, F64)
+    m = np.asarray(m, F64)
+    x_hat = np.asarray(x_hat, F64)
+    diff = (m_hat - m).ravel()
+    s2 = float(np.dot(diff, diff))
+    l = log_ratio(m_hat, m, sigma, x_hat)
+    if s2 == 0.0:
+        return x_hat.copy(), True, l, False
+    thr = min(0.0, float(lam) * l)
+    if u <= 0.0:
+        return x_hat.copy(), True, l, False
+    logu = math.log(u)
+    accepted = logu <= thr
+    tie = abs(float(lam) * l - logu) < TIE_WINDOW
+    if accepted:
+        return x_hat.copy(), True, l, tie
+    return reflect(m_hat, m, x_hat), False, l, tie
+
+
+def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None) -> dict:
+    """The K drafts of each trajectory checked in order (Alg. 1, verification loop).
+
+    m_target, m_draft, x_draft: [n_traj, K, d]; sigma, u, lam: [n_traj, K]
+    (lam None => strict rule everywhere).  For every (trajectory, draft) the
+    log-ratio and the stand-alone decision are recorded; n_accept is the number
+    of drafts accepted before the first rejection, and x_out holds the
+    reflected sample of that first rejected draft (zeros where nothing was
+    rejected: has_reflect marks the rows that were written).
+    """
+    m_target = np.asarray(m_target, F64)
+    m_draft = np.asarray(m_draft, F64)
+    x_draft = np.asarray(x_draft, F64)
+    n_traj, K, d = m_target.shape
+    sigma = np.asarray(sigma, F64).reshape(n_traj, K)
+    u = np.asarray(u, F64).reshape(n_traj, K)
+    lam = np.ones((n_traj, K), F64) if lam is None else np.asarray(lam, F64).reshape(n_traj, K)
+    lr = np.zeros((n_traj, K), F64)
+    acc = np.zeros((n_traj, K), np.uint8)
+    tie = np.zeros((n_traj, K), bool)
+    n_accept = np.zeros(n_traj, np.int32)
+    x_out = np.zeros((n_traj, d), F64)
+    has_reflect = np.zeros(n_traj, bool)
+    for n in range(n_traj):
+        first_reject = K
+        for k in range(K):
+            x, ok, l, tk = verification(m_draft[n, k], m_target[n, k], sigma[n, k],
+                                        x_draft[n, k], u[n, k], lam[n, k])
+            lr[n, k] = l
+            acc[n, k] = 1 if ok else 0
+            tie[n, k] = tk
+            if not ok and first_reject == K:
+                first_reject = k
+                x_out[n] = x
+                has_reflect[n] = True
+        n_accept[n] = first_reject
+    return dict(log_ratio=lr, accept=acc, n_accept=n_accept, x_out=x_out,
+                has_reflect=has_reflect, tie=tie)
+
+
+# ----------------------------------------------------------------------------
+# DiT forward (public DiT architecture restated; the paper only cites it)
+# ----------------------------------------------------------------------------
+def silu(v):
+    return v / (1.0 + np.exp(-v))
+
+
+def gelu_tanh(v):
+    """tanh form of GELU: 0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3)))."""
+    return 0.5 * v * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (v + 0.044715 * v ** 3)))
+
+
+def layer_norm(v):
+    """LayerNorm over the last axis, no affine, biased variance, eps = LN_EPS."""
+    mu = v.mean(axis=-1, keepdims=True)
+    var = ((v - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (v - mu) / np.sqrt(var + LN_EPS)
+
+
+def linear(v, w, b):
+    """y = v W^T + b with W stored [out, in]."""
+    return v @ np.asarray(w, F64).T + np.asarray(b, F64)
+
+
+def timestep_embedding(t, dim: int) -> np.ndarray:
+    """[cos(t w_j) | sin(t w_j)], w_j = MAX_PERIOD^(-j/(dim/2)), j < dim/2."""
+    half = dim // 2
+    w = np.exp(-math.log(MAX_PERIOD) * np.arange(half, dtype=F64) / half)
+    ang = np.asarray(t, F64).reshape(-1, 1) * w.reshape(1, -1)
+    return np.concatenate([np.cos(ang), np.sin(ang)], axis=1)
+
+
+def pos_embed_2d(gh: int, gw: int, dim: int) -> np.ndarray:
+    """Fixed 2-D sin-cos table [gh*gw, dim] for token (i, j), row-major:
+    [sin(j w) | cos(j w) | sin(i w) | cos(i w)], w_k = MAX_PERIOD^(-k/(dim/4))."""
+    q = dim // 4
+    w = 1.0 / MAX_PERIOD ** (np.arange(q, dtype=F64) / q)
+    ii, jj = np.meshgrid(np.arange(gh, dtype=F64), np.arange(gw, dtype=F64), indexing="ij")
+    aj = jj.reshape(-1, 1) * w
+    ai = ii.reshape(-1, 1) * w
+    return np.concatenate([np.sin(aj), np.cos(aj), np.sin(ai), np.cos(ai)], axis=1)
+
+
+def patchify(x, p: int) -> np.ndarray:
+    """[B, C, H, W] -> [B, (H/p)(W/p), C p p]; tokens row-major over the patch
+    grid, each patch flattened over (c, ph, pw)."""
+    B, C, H, W = x.shape
+    gh, gw = H // p, W // p
+    v = x.reshape(B, C, gh, p, gw, p)
+    v = v.transpose(0, 2, 4, 1, 3, 5)          # B, gh, gw, C, ph, pw
+    return v.reshape(B, gh * gw, C * p * p)
+
+
+def unpatchify(tok, p: int, c_out: int, gh: int, gw: int) -> np.ndarray:
+    """[B, gh gw, p p c_out] with per-token order (ph, pw, c) -> [B, c_out, gh p, gw p]."""
+    B = tok.shape[0]
+    v = tok.reshape(B, gh, gw, p, p, c_out)
+    v = v.transpose(0, 5, 1, 3, 2, 4)          # B, c, gh, ph, gw, pw
+    return v.reshape(B, c_out, gh * p, gw * p)
+
+
+def conditioning(w: dict, cfg: dict, t, y) -> np.ndarray:
+    """c = MLP(timestep_embedding(t)) + label_table[y]; returns c (before SiLU)."""
+    temb = timestep_embedding(t, cfg["t_freq_dim"])
+    h = silu(linear(temb, w["t_w1"], w["t_b1"]))
+    h = linear(h, w["t_w2"], w["t_b2"])
+    return h + np.asarray(w["y_table"], F64)[np.asarray(y, np.int64)]
+
+
+def attention(q, k, v) -> np.ndarray:
+    """softmax(q k^T / sqrt(d_h)) v for one head; q, k, v: [N, d_h]."""
+    s = (q @ k.T) / math.sqrt(q.shape[-1])
+    s = s - s.max(axis=-1, keepdims=True)
+    p = np.exp(s)
+    p = p / p.sum(axis=-1, keepdims=True)
+    return p @ v
+
+
+def self_attention(xn, wqkv, bqkv, wproj, bproj, heads: int) -> np.ndarray:
+    """Multi-head self-attention of one sample, xn: [N, D].  QKV rows are
+    ordered [q | k | v], each split into `heads` consecutive groups of d_h."""
+    N, D = xn.shape
+    dh = D // heads
+    qkv = linear(xn, wqkv, bqkv)
+    q, k, v = qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:]
+    out = np.empty((N, D), F64)
+    for h in range(heads):
+        sl = slice(h * dh, (h + 1) * dh)
+        out[:, sl] = attention(q[:, sl], k[:, sl], v[:, sl])
+    return linear(out, wproj, bproj)
+
+
+def dit_block(xb, sc, w: dict, l: int, heads: int) -> np.ndarray:
+    """One adaLN-Zero block on one sample: xb [N, D], sc = SiLU(c) [D]."""
+    D = xb.shape[1]
+    mod = linear(sc, w[f"blk{l}.ada_w"], w[f"blk{l}.ada_b"])
+    sh1, sc1, g1, sh2, sc2, g2 = (mod[i * D:(i + 1) * D] for i in range(6))
+    a = self_attention(layer_norm(xb) * (1.0 + sc1) + sh1,
+                       w[f"blk{l}.qkv_w"], w[f"blk{l}.qkv_b"],
+                       w[f"blk{l}.proj_w"], w[f"blk{l}.proj_b"], heads)
+    xb = xb + g1 * a
+    hmid = gelu_tanh(linear(layer_norm(xb) * (1.0 + sc2) + sh2,
+                            w[f"blk{l}.fc1_w"], w[f"blk{l}.fc1_b"]))
+    xb = xb + g2 * linear(hmid, w[f"blk{l}.fc2_w"], w[f"blk{l}.fc2_b"])
+    return xb
+
+
+def dit_forward(w: dict, cfg: dict, x, t, y, samples=None):
+    """Forward of the packed batch: every state has its own timestep and label.
+
+    x: [B, C, H, W]; t, y: [B].  Returns (out [B, 2C, H, W], top_feat [B, N, D]):
+    `out` holds the noise prediction in channels [0, C) and the (unused, App. C)
+    learned-variance channels in [C, 2C); `top_feat` is the output of the last
+    block (the paper's feature f).  `samples` restricts the work to a subset of
+    the batch rows (each row is independent of the others).
+    """
+    x = np.asarray(x, F64)
+    B, C, H, W = x.shape
+    p, D, depth, heads = cfg["patch"], cfg["hidden"], cfg["depth"], cfg["heads"]
+    gh, gw = H // p, W // p
+    rows = list(range(B)) if samples is None else list(samples)
+    t = np.asarray(t)
+    y = np.asarray(y)
+    c = conditioning(w, cfg, t[rows], y[rows])
+    sc = silu(c)
+    tok = linear(patchify(x[rows], p), w["patch_w"], w["patch_b"]) + pos_embed_2d(gh, gw, D)
+    c_out = 2 * C if cfg.get("learn_sigma", 1) else C
+    out_tok = np.empty((len(rows), gh * gw, p * p * c_out), F64)
+    feat = np.empty((len(rows), gh * gw, D), F64)
+    for r in range(len(rows)):
+        xb = tok[r]
+        for l in range(depth):
+            xb = dit_block(xb, sc[r], w, l, heads)
+        feat[r] = xb
+        mod = linear(sc[r], w["fin_ada_w"], w["fin_ada_b"])
+        sh, scl = mod[:D], mod[D:]
+        out_tok[r] = linear(layer_norm(xb) * (1.0 + scl) + sh, w["fin_w"], w["fin_b"])
+    return unpatchify(out_tok, p, c_out, gh, gw), feat
+
+
+def cfg_combine(eps_cond, eps_null, scale: float) -> np.ndarray:
+    """Classifier-free guidance: eps = eps_null + s (eps_cond - eps_null)."""
+    eps_cond = np.asarray(eps_cond, F64)
+    eps_null = np.asarray(eps_null, F64)
+    return eps_null + float(scale) * (eps_cond - eps_null)
+
+
+def round_means(w: dict, cfg: dict, x_states, t, y: int, cfg_scale: float, coef_x, coef_eps):
+    """Target means of one round: packed forward on the K states (twice the
+    batch, second half with the null label, when cfg_scale > 1), guidance on
+    the noise channels, then m_k = coef_x[k] x_k + coef_eps[k] eps_k."""
+    x_states = np.asarray(x_states, F64)
+    K, C = x_states.shape[0], x_states.shape[1]
+    t = np.asarray(t)
+    if cfg_scale > 1.0:
+        xx = np.concatenate([x_states, x_states], axis=0)
+        tt = np.concatenate([t, t])
+        yy = np.concatenate([np.full(K, y), np.full(K, cfg["num_classes"])])
+        out, _ = dit_forward(w, cfg, xx, tt, yy)
+        eps = cfg_combine(out[:K, :C], out[K:, :C], cfg_scale)
+    else:
+        out, _ = dit_forward(w, cfg, x_states, t, np.full(K, y))
+        eps = out[:, :C]
+    cx = np.asarray(coef_x, F64).reshape(K, 1, 1, 1)
+    ce = np.asarray(coef_eps, F64).reshape(K, 1, 1, 1)
+    return cx * x_states + ce * eps
+
+
+def spec_round(w: dict, cfg: dict, x_states, x_last, m_draft, t, y: int, cfg_scale: float,
+               coef_x, coef_eps, sigma, u, lam=None) -> dict:
+    """One verification round (Alg. 1: packed target forward + verification loop).
+
+    x_states [K, C, H, W] = (x_a, x^_{a+1}, ..., x^_{a+K-1}) are run through the
+    target; draft k+1 (x_states[k+1], and x_last for k = K-1) is verified against
+    (m_draft[k], m_k, sigma[k])."""
+    x_states = np.asarray(x_states, F64)
+    K = x_states.shape[0]
+    m = round_means(w, cfg, x_states, t, y, cfg_scale, coef_x, coef_eps)
+    xd = np.concatenate([x_states[1:], np.asarray(x_last, F64)[None]], axis=0)
+    res = spec_verify(m.reshape(1, K, -1), np.asarray(m_draft, F64).reshape(1, K, -1),
+                      xd.reshape(1, K, -1), np.asarray(sigma).reshape(1, K),
+                      np.asarray(u).reshape(1, K),
+                      None if lam is None else np.asarray(lam).reshape(1, K))
+    res["m_target"] = m.reshape(K, -1)
+    return res
