@@ -1,0 +1,196 @@
+/*
+ * free_mi355x.h - C ABI of the MI355X (gfx950) implementation of FREE's
+ * parallel verification pass: the packed target forward of Alg. 1 ("compute
+ * means ... in parallel") followed by the sequential verification loop of
+ * Alg. 1 with the per-draft test of Alg. 2.
+ *
+ * Conventions
+ * -----------
+ *  - Every entry point returns an int32_t status (FREE_OK or a negative
+ *    FREE_ERR_*).  Nothing throws, aborts or prints.
+ *  - Unless a parameter is marked [host], tensor pointers are DEVICE pointers
+ *    owned by the caller.  The hot-path calls (dit_forward_packed,
+ *    spec_verify, spec_round) never allocate or free: scratch memory comes
+ *    from a caller-provided device workspace whose size is given by the
+ *    *_workspace_bytes functions.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Hot-path calls only enqueue work and return; outputs are valid after the
+ *    caller synchronises the stream.  Calls that share a workspace must be
+ *    ordered on one stream.
+ *  - Argument checks are host-side (null pointers, shapes).  Values that live
+ *    in device memory (timesteps, labels, sigma, u, lambda) are NOT range
+ *    checked: a timestep is any int, a label must lie in [0, num_classes]
+ *    (num_classes = the null label), sigma must be > 0, u in [0, 1],
+ *    lambda in [0, 1]; violating that is the caller's error.
+ *  - Latents are [B, C, H, W] fp32, contiguous (the paper's x in R^d with
+ *    d = C*H*W).  Per-draft scalars are [n_traj, K] fp32.
+ */
+#ifndef FREE_MI355X_H
+#define FREE_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FREE_OK              0
+#define FREE_ERR_NULL       -1   /* a required pointer is NULL */
+#define FREE_ERR_SHAPE      -2   /* inconsistent or unsupported sizes */
+#define FREE_ERR_RANGE      -3   /* a host-side scalar is out of range */
+#define FREE_ERR_DTYPE      -4   /* unknown compute mode */
+#define FREE_ERR_WORKSPACE  -5   /* workspace missing, misaligned or too small */
+#define FREE_ERR_HIP        -6   /* HIP runtime error; see free_last_hip_error */
+
+#define FREE_FP32 0   /* fp32 weights and activations, fp32 accumulation */
+#define FREE_BF16 1   /* bf16 large matrices and activations, fp32 accumulation,
+                         fp32 residual stream, statistics and softmax */
+
+#define FREE_MAX_DRAFTS 256   /* largest K accepted by spec_verify / spec_round */
+
+/* Class-conditional DiT geometry.  The paper uses DiT-XL/2 (Sec. 4): in_ch 4,
+ * patch 2, hidden 1152, depth 28, heads 16, mlp_hidden 4608, 1000 classes,
+ * learn_sigma 1 (8 output channels; the variance half is ignored, App. C).
+ * Constraints: lat_h, lat_w multiples of patch; hidden a multiple of heads,
+ * of 8 and of 4 (2-D sin-cos table); mlp_hidden a multiple of 8; t_freq_dim
+ * even; in FREE_BF16 mode hidden/heads must be a multiple of 8 and <= 128. */
+typedef struct free_dit_config {
+    int32_t in_ch, lat_h, lat_w, patch, hidden, depth, heads, mlp_hidden;
+    int32_t num_classes, learn_sigma, t_freq_dim, mode;
+} free_dit_config;
+
+typedef struct free_dit_s* free_dit_t;   /* opaque model handle */
+
+/* ---- utilities (host only, no GPU needed) -------------------------------- */
+
+const char* free_version(void);
+const char* free_status_string(int32_t status);
+/* hipError_t of the last failing HIP call seen by this thread (0 = none). */
+int32_t free_last_hip_error(void);
+
+/* Linear-beta DDPM schedule and the coefficients of the one-step update
+ * (Eq. ddpm_update, App. C), 0-indexed by network timestep i in [0, T):
+ *   coef_x[i]   = 1 / sqrt(alpha_i)
+ *   coef_eps[i] = -(1 - alpha_i) / (sqrt(1 - alphabar_i) * sqrt(alpha_i))
+ *   sigma[i]    = sqrt(betatilde_i), betatilde_i the posterior variance;
+ *                 index 0 (where betatilde = 0) takes the value of index 1.
+ * so that the transition mean is m = coef_x * x + coef_eps * eps.
+ * All three outputs are [host] arrays of T doubles; any may be NULL. */
+int32_t free_ddpm_schedule(int32_t T, double beta_start, double beta_end,
+                           double* coef_x, double* coef_eps, double* sigma);
+
+/* Number of weight pointers free_dit_create expects: 7 + 10*depth + 4. */
+int32_t free_weight_count(const free_dit_config* cfg);
+
+/* ---- model handle ---------------------------------------------------------
+ * weight_ptrs: [host] array of n_ptrs DEVICE pointers, borrowed (the caller
+ * keeps them alive and unchanged until free_dit_destroy), in this order, all
+ * matrices [out, in] row-major:
+ *   patch_w [hidden, in_ch*patch^2] (flattened over c, ph, pw), patch_b,
+ *   t_w1 [hidden, t_freq_dim], t_b1, t_w2 [hidden, hidden], t_b2,
+ *   y_table [num_classes+1, hidden] (last row = null label),
+ *   then per block: ada_w [6*hidden, hidden] (rows: shift1, scale1, gate1,
+ *   shift2, scale2, gate2), ada_b, qkv_w [3*hidden, hidden] (rows: q | k | v,
+ *   each head-major), qkv_b, proj_w, proj_b, fc1_w [mlp_hidden, hidden],
+ *   fc1_b, fc2_w [hidden, mlp_hidden], fc2_b,
+ *   then fin_ada_w [2*hidden, hidden] (shift, scale), fin_ada_b,
+ *   fin_w [patch^2*c_out, hidden] (rows ordered ph, pw, c), fin_b.
+ * Element types: in FREE_BF16 mode ada_w, qkv_w, proj_w, fc1_w, fc2_w,
+ * fin_ada_w and fin_w are bf16; everything else, and everything in FREE_FP32
+ * mode, is fp32.  All pointers must be 16-byte aligned.
+ * free_dit_create is not a hot-path call: it allocates a small device table
+ * (positional embedding, pointer table) that free_dit_destroy releases. */
+int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_ptrs,
+                        int32_t n_ptrs, free_dit_t* out);
+int32_t free_dit_destroy(free_dit_t h);
+
+/* Device workspace (bytes, 256-byte aligned) for a forward on B packed states;
+ * also sufficient for spec_round with the same B.  0 on a bad configuration. */
+size_t free_workspace_bytes(const free_dit_config* cfg, int32_t B);
+
+/* ---- the packed target forward (Alg. 1, "in parallel"; Sec. 3.3) ----------
+ * One forward of the class-conditional DiT on B packed states, each with its
+ * own timestep t[b] and label y[b] (int32, device).
+ *   x        [B, C, H, W] fp32
+ *   eps_out  [B, c_out, H, W] fp32, c_out = 2C with learn_sigma: channels
+ *            [0, C) are the noise prediction, [C, 2C) the unused variance.
+ *   top_feat [B, N, hidden] fp32 or NULL: output of the last block (the
+ *            feature f of Alg. 1). */
+int32_t dit_forward_packed(free_dit_t h, const float* x, const int32_t* t, const int32_t* y,
+                           int32_t B, float* eps_out, float* top_feat,
+                           void* workspace, size_t ws_bytes, void* stream);
+
+/* ---- verification (Alg. 2; Eq. qp; Eq. acc_relax; Alg. 1 inner loop) ------
+ * n_traj independent trajectories, K drafts each, d elements per state.
+ *   m_target, m_draft, x_draft  [n_traj, K, d] fp32
+ *   sigma, u                    [n_traj, K] fp32
+ *   lambda                      [n_traj, K] fp32 or NULL (strict rule)
+ * For every (trajectory, draft):
+ *   l = (m - m^)^T (x^ - (m + m^)/2) / sigma^2               (Eq. qp)
+ *   accepted iff log u <= min(0, lambda * l)  (u <= min(1, exp(lambda l)));
+ *   u = 0 or m^ == m always accepts.
+ * Outputs:
+ *   log_ratio [n_traj, K] fp32  unscaled l
+ *   accept    [n_traj, K] uint8 stand-alone decision of each draft
+ *   n_accept  [n_traj]    int32 number of drafts accepted before the first
+ *                               rejection (K if none was rejected)
+ *   x_out     [n_traj, d] fp32  reflected sample of the first rejected draft,
+ *                               x = m + (I - 2 e e^T)(x^ - m^), e = (m^ - m)/||m^ - m||;
+ *                               rows with n_accept == K are left untouched.
+ * Sums over d are accumulated in fp64 in a fixed order: results are
+ * deterministic run to run. */
+size_t spec_verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d);
+int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_draft,
+                    const float* sigma, const float* u, const float* lambda,
+                    int32_t n_traj, int32_t K, int64_t d,
+                    float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out,
+                    void* workspace, size_t ws_bytes, void* stream);
+
+/* ---- one verification round of one trajectory (Alg. 1 body after drafting) -
+ * Packed forward on the K states x_states = (x_a, x^_{a+1}, ..., x^_{a+K-1})
+ * at timesteps t[0..K) with label y; with cfg_scale > 1 the batch is doubled
+ * with the null label and eps = eps_null + cfg_scale (eps_cond - eps_null);
+ * then m_k = coef_x[k] x_k + coef_eps[k] eps_k (Eq. ddpm_update) and draft
+ * k+1 (x_states[k+1]; x_last for k = K-1) is verified against
+ * (m_draft[k], m_k, sigma[k]) exactly as in spec_verify with n_traj = 1.
+ *   x_states [K, C, H, W], x_last [C, H, W], m_draft [K, d]   fp32, device
+ *   t [K] int32 device; y, cfg_scale [host] scalars
+ *   coef_x, coef_eps, sigma, u [K] fp32 device; lambda [K] or NULL
+ *   m_target_out [K, d] or NULL; log_ratio [K]; accept [K]; n_accept [1];
+ *   x_out [d] (written only when n_accept < K). */
+int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, const float* m_draft,
+                   const int32_t* t, int32_t y, float cfg_scale,
+                   const float* coef_x, const float* coef_eps, const float* sigma,
+                   const float* u, const float* lambda, int32_t K,
+                   float* m_target_out, float* log_ratio, uint8_t* accept,
+                   int32_t* n_accept, float* x_out,
+                   void* workspace, size_t ws_bytes, void* stream);
+
+/* ---- single DiT operators, exported for per-kernel parity tests -----------
+ * (the pieces of the adaLN-Zero block that dit_forward_packed chains).
+ * dtype = FREE_FP32 (A, W, out fp32) or FREE_BF16 (A, W, out bf16). */
+#define FREE_EPI_BIAS       0   /* out = A W^T + bias                          */
+#define FREE_EPI_BIAS_GELU  1   /* out = gelu_tanh(A W^T + bias)               */
+#define FREE_EPI_GATE_RESID 2   /* resid[m,n] += gate[m / rows_per_sample, n] *
+                                   (A W^T + bias)[m,n]; resid fp32 [M, N],
+                                   gate fp32 with row stride gate_stride       */
+int32_t free_op_linear(const void* A, const void* W, const float* bias, int32_t M, int32_t N,
+                       int32_t Kdim, int32_t dtype, int32_t epilogue, void* out,
+                       float* resid, const float* gate, int32_t gate_stride,
+                       int32_t rows_per_sample, void* stream);
+/* out[b, n, h*dh + :] = softmax(q k^T / sqrt(dh)) v per (sample, head);
+ * qkv [B*N, 3*heads*dh] rows ordered q | k | v, out [B*N, heads*dh]; dh <= 128. */
+int32_t free_op_attention(const void* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh,
+                          int32_t dtype, void* out, void* stream);
+/* out[m, :] = LayerNorm(x[m, :]) * (1 + scale[m / rows_per_sample, :]) + shift[...]
+ * (no affine, biased variance, eps 1e-6); x fp32 [M, D]; shift/scale fp32 with
+ * row stride mod_stride; out fp32 or bf16 per dtype. */
+int32_t free_op_ln_modulate(const float* x, const float* shift, const float* scale,
+                            int32_t mod_stride, int32_t M, int32_t D, int32_t rows_per_sample,
+                            int32_t dtype, void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREE_MI355X_H */

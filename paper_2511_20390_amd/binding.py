@@ -1,0 +1,244 @@
+"""ctypes binding over libfree_mi355x.so (the C ABI declared in include/free_mi355x.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch is used for device memory and the current HIP stream.  There
+is no fallback: a missing library raises, a non-zero status raises FreeError.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfree_mi355x.so")
+
+FREE_OK = 0
+FREE_ERR_NULL, FREE_ERR_SHAPE, FREE_ERR_RANGE, FREE_ERR_DTYPE, FREE_ERR_WORKSPACE, FREE_ERR_HIP = -1, -2, -3, -4, -5, -6
+FREE_FP32, FREE_BF16 = 0, 1
+EPI_BIAS, EPI_BIAS_GELU, EPI_GATE_RESID = 0, 1, 2
+MODES = {"fp32": FREE_FP32, "bf16": FREE_BF16}
+
+EXPORTED_SYMBOLS = [
+    "free_version", "free_status_string", "free_last_hip_error", "free_ddpm_schedule",
+    "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
+    "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
+    "free_op_linear", "free_op_attention", "free_op_ln_modulate",
+]
+
+
+class FreeError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = load().free_status_string(status).decode()
+        if status == FREE_ERR_HIP:
+            msg += f" (hipError {load().free_last_hip_error()})"
+        super().__init__(f"{where}: status {status}: {msg}")
+
+
+class FreeDitConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("in_ch", "lat_h", "lat_w", "patch", "hidden", "depth", "heads",
+                                          "mlp_hidden", "num_classes", "learn_sigma", "t_freq_dim", "mode")]
+
+
+_lib = None
+
+
+def load():
+    """Open the library (once) and declare the signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` to build it")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    lib.free_version.restype = C.c_char_p
+    lib.free_status_string.restype = C.c_char_p
+    lib.free_status_string.argtypes = [i32]
+    lib.free_last_hip_error.restype = i32
+    lib.free_ddpm_schedule.restype = i32
+    lib.free_ddpm_schedule.argtypes = [i32, C.c_double, C.c_double, vp, vp, vp]
+    lib.free_weight_count.restype = i32
+    lib.free_weight_count.argtypes = [C.POINTER(FreeDitConfig)]
+    lib.free_dit_create.restype = i32
+    lib.free_dit_create.argtypes = [C.POINTER(FreeDitConfig), C.POINTER(vp), i32, C.POINTER(vp)]
+    lib.free_dit_destroy.restype = i32
+    lib.free_dit_destroy.argtypes = [vp]
+    lib.free_workspace_bytes.restype = sz
+    lib.free_workspace_bytes.argtypes = [C.POINTER(FreeDitConfig), i32]
+    lib.dit_forward_packed.restype = i32
+    lib.dit_forward_packed.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.spec_verify_workspace_bytes.restype = sz
+    lib.spec_verify_workspace_bytes.argtypes = [i32, i32, i64]
+    lib.spec_verify.restype = i32
+    lib.spec_verify.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp, sz, vp]
+    lib.spec_round.restype = i32
+    lib.spec_round.argtypes = [vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.free_op_linear.restype = i32
+    lib.free_op_linear.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, i32, vp]
+    lib.free_op_attention.restype = i32
+    lib.free_op_attention.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.free_op_ln_modulate.restype = i32
+    lib.free_op_ln_modulate.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status, where):
+    if status != FREE_OK:
+        raise FreeError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_config(cfg: dict, mode: str) -> FreeDitConfig:
+    return FreeDitConfig(cfg["in_ch"], cfg["lat_h"], cfg["lat_w"], cfg["patch"], cfg["hidden"], cfg["depth"],
+                         cfg["heads"], cfg["mlp_hidden"], cfg["num_classes"], cfg["learn_sigma"],
+                         cfg["t_freq_dim"], MODES[mode])
+
+
+def free_ddpm_schedule(T: int = 1000, beta_start: float = 1e-4, beta_end: float = 0.02):
+    """Host-only: (coef_x, coef_eps, sigma) float64 arrays of length T."""
+    cx, ce, sg = (np.empty(T, np.float64) for _ in range(3))
+    _check(load().free_ddpm_schedule(T, beta_start, beta_end, cx.ctypes.data, ce.ctypes.data, sg.ctypes.data),
+           "free_ddpm_schedule")
+    return cx, ce, sg
+
+
+def spec_verify_workspace_bytes(n_traj: int, K: int, d: int) -> int:
+    return load().spec_verify_workspace_bytes(n_traj, K, d)
+
+
+def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None, out=None, workspace=None):
+    """Device tensors in, dict of device tensors out.  m_*, x_draft: [n_traj, K, d] fp32."""
+    import torch
+    n_traj, K, d = m_target.shape
+    dev = m_target.device
+    if out is None:
+        out = dict(log_ratio=torch.empty(n_traj, K, dtype=torch.float32, device=dev),
+                   accept=torch.empty(n_traj, K, dtype=torch.uint8, device=dev),
+                   n_accept=torch.empty(n_traj, dtype=torch.int32, device=dev),
+                   x_out=torch.zeros(n_traj, d, dtype=torch.float32, device=dev))
+    if workspace is None:
+        workspace = torch.empty(max(256, spec_verify_workspace_bytes(n_traj, K, d)), dtype=torch.uint8, device=dev)
+    _check(load().spec_verify(_ptr(m_target), _ptr(m_draft), _ptr(x_draft), _ptr(sigma), _ptr(u), _ptr(lam),
+                              n_traj, K, d, _ptr(out["log_ratio"]), _ptr(out["accept"]), _ptr(out["n_accept"]),
+                              _ptr(out["x_out"]), _ptr(workspace), workspace.numel(), _stream()), "spec_verify")
+    return out
+
+
+class FreeDit:
+    """Model handle: borrows the caller's device weight tensors (kept alive here)."""
+
+    def __init__(self, cfg: dict, weights: dict, mode: str = "bf16", device="cuda:0"):
+        import torch
+        from . import synth
+        self.cfg, self.mode, self.device = dict(cfg), mode, torch.device(device)
+        self.ccfg = make_config(cfg, mode)
+        self.tensors = []
+        for name, shape in synth.weight_spec(cfg):
+            a = torch.from_numpy(np.ascontiguousarray(weights[name], dtype=np.float32)).reshape(shape)
+            a = a.to(self.device)
+            if mode == "bf16" and synth.is_big_matrix(name):
+                a = a.to(torch.bfloat16)
+            self.tensors.append(a.contiguous())
+        n = load().free_weight_count(C.byref(self.ccfg))
+        if n != len(self.tensors):
+            raise FreeError(n if n < 0 else FREE_ERR_SHAPE, "free_weight_count")
+        arr = (C.c_void_p * n)(*[t.data_ptr() for t in self.tensors])
+        self.handle = C.c_void_p()
+        _check(load().free_dit_create(C.byref(self.ccfg), arr, n, C.byref(self.handle)), "free_dit_create")
+        self._ws = {}
+        self.C, self.H, self.W = cfg["in_ch"], cfg["lat_h"], cfg["lat_w"]
+        self.c_out = self.C * (2 if cfg["learn_sigma"] else 1)
+        self.ntok = (self.H // cfg["patch"]) * (self.W // cfg["patch"])
+        self.d = self.C * self.H * self.W
+
+    def close(self):
+        if getattr(self, "handle", None) is not None and self.handle.value:
+            load().free_dit_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_bytes(self, B: int) -> int:
+        return load().free_workspace_bytes(C.byref(self.ccfg), B)
+
+    def workspace(self, B: int):
+        import torch
+        if B not in self._ws:
+            self._ws[B] = torch.empty(self.workspace_bytes(B), dtype=torch.uint8, device=self.device)
+        return self._ws[B]
+
+    def dit_forward_packed(self, x, t, y, want_feat=False):
+        import torch
+        B = x.shape[0]
+        eps = torch.empty(B, self.c_out, self.H, self.W, dtype=torch.float32, device=self.device)
+        feat = torch.empty(B, self.ntok, self.cfg["hidden"], dtype=torch.float32, device=self.device) if want_feat else None
+        ws = self.workspace(B)
+        _check(load().dit_forward_packed(self.handle, _ptr(x), _ptr(t), _ptr(y), B, _ptr(eps), _ptr(feat),
+                                         _ptr(ws), ws.numel(), _stream()), "dit_forward_packed")
+        return (eps, feat) if want_feat else eps
+
+    def spec_round(self, x_states, x_last, m_draft, t, y: int, cfg_scale: float, coef_x, coef_eps, sigma, u,
+                   lam=None, want_means=True, out=None):
+        import torch
+        K = x_states.shape[0]
+        B = K * (2 if cfg_scale > 1.0 else 1)
+        dev = self.device
+        if out is None:
+            out = dict(m_target=torch.empty(K, self.d, dtype=torch.float32, device=dev) if want_means else None,
+                       log_ratio=torch.empty(K, dtype=torch.float32, device=dev),
+                       accept=torch.empty(K, dtype=torch.uint8, device=dev),
+                       n_accept=torch.empty(1, dtype=torch.int32, device=dev),
+                       x_out=torch.zeros(self.d, dtype=torch.float32, device=dev))
+        ws = self.workspace(B)
+        _check(load().spec_round(self.handle, _ptr(x_states), _ptr(x_last), _ptr(m_draft), _ptr(t), int(y),
+                                 float(cfg_scale), _ptr(coef_x), _ptr(coef_eps), _ptr(sigma), _ptr(u), _ptr(lam),
+                                 K, _ptr(out["m_target"]), _ptr(out["log_ratio"]), _ptr(out["accept"]),
+                                 _ptr(out["n_accept"]), _ptr(out["x_out"]), _ptr(ws), ws.numel(), _stream()),
+               "spec_round")
+        return out
+
+
+def op_linear(A, W, bias, mode: str, epilogue: int = EPI_BIAS, resid=None, gate=None, rows_per_sample: int = 1):
+    import torch
+    M, K = A.shape
+    N = W.shape[0]
+    out = None
+    if epilogue != EPI_GATE_RESID:
+        out = torch.empty(M, N, dtype=A.dtype, device=A.device)
+    _check(load().free_op_linear(_ptr(A), _ptr(W), _ptr(bias), M, N, K, MODES[mode], epilogue, _ptr(out),
+                                 _ptr(resid), _ptr(gate), 0 if gate is None else gate.stride(0),
+                                 rows_per_sample, _stream()), "free_op_linear")
+    return resid if epilogue == EPI_GATE_RESID else out
+
+
+def op_attention(qkv, B: int, N: int, heads: int, dh: int, mode: str):
+    import torch
+    out = torch.empty(B * N, heads * dh, dtype=qkv.dtype, device=qkv.device)
+    _check(load().free_op_attention(_ptr(qkv), B, N, heads, dh, MODES[mode], _ptr(out), _stream()),
+           "free_op_attention")
+    return out
+
+
+def op_ln_modulate(x, shift, scale, rows_per_sample: int, mode: str):
+    import torch
+    M, D = x.shape
+    out = torch.empty(M, D, dtype=torch.float32 if mode == "fp32" else torch.bfloat16, device=x.device)
+    _check(load().free_op_ln_modulate(_ptr(x), _ptr(shift), _ptr(scale), shift.stride(0), M, D, rows_per_sample,
+                                      MODES[mode], _ptr(out), _stream()), "free_op_ln_modulate")
+    return out

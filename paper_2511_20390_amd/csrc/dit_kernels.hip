@@ -1,0 +1,579 @@
+// Straightforward kernels of the class-conditional DiT forward (the network the
+// packed target pass of Alg. 1 evaluates; the paper cites DiT and fixes none of
+// its internals).  Everything that is not a large dense contraction lives here:
+// conditioning MLP, adaLN modulation GEMV, patch embedding, LayerNorm+modulate,
+// final layer + unpatchify, guidance + eps->mean (Eq. ddpm_update).  It also
+// holds the plain (non-MFMA) linear and attention kernels used by the fp32 mode
+// and as the shape fallback of the bf16 mode.
+#include "free_internal.h"
+
+namespace freemi {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ inline float wave_sum_f(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// Conditioning: c = W2 silu(W1 temb(t) + b1) + b2 + table[y];  sc = silu(c)
+// ---------------------------------------------------------------------------
+// temb[b, :] = [cos(t w_j) | sin(t w_j)], w_j = 10000^(-j/half).  The angle is
+// formed in fp64 (t up to 999 times w_0 = 1 would lose 4 digits in fp32).
+__global__ void timestep_embed_kernel(const int32_t* __restrict__ t, int32_t B, int32_t tfreq,
+                                      float* __restrict__ temb) {
+    const int half = tfreq / 2;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * half) return;
+    const int b = idx / half, j = idx % half;
+    const double w = exp(-9.210340371976184 * static_cast<double>(j) / static_cast<double>(half));
+    const double ang = static_cast<double>(t[b]) * w;
+    temb[b * tfreq + j] = static_cast<float>(cos(ang));
+    temb[b * tfreq + half + j] = static_cast<float>(sin(ang));
+}
+
+// out[b, j] = act(sum_i in[b, i] W[j, i] + bias[j] + table[row[b], j]); one wavefront per (b, j).
+template <bool SILU>
+__global__ __launch_bounds__(kThreads) void small_linear_kernel(
+    const float* __restrict__ in, int32_t B, int32_t K, int32_t N, const float* __restrict__ W,
+    const float* __restrict__ bias, const float* __restrict__ table, const int32_t* __restrict__ row,
+    float* __restrict__ out) {
+    const int j = blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const int b = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    if (j >= N) return;
+    const float* x = in + static_cast<int64_t>(b) * K;
+    const float* w = W + static_cast<int64_t>(j) * K;
+    float acc = 0.f;
+    for (int i = lane; i < K; i += 64) acc = fmaf(x[i], w[i], acc);
+    acc = wave_sum_f(acc);
+    if (lane == 0) {
+        float v = acc + bias[j];
+        if (table) v += table[static_cast<int64_t>(row[b]) * N + j];
+        out[static_cast<int64_t>(b) * N + j] = SILU ? silu_f(v) : v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// adaLN modulation for all blocks and the final layer in one launch:
+//   mod[b, r] = sum_i sc[b, i] W_r[i] + bias_r
+// Rows come from n_mats matrices (device pointer table); HBM-bound on the
+// weights (a third of all DiT parameters), every weight byte is read once.
+// ---------------------------------------------------------------------------
+constexpr int kAdaBatch = 16;   // batch rows kept in LDS / accumulators per pass
+
+template <typename WT>
+struct WVec;
+template <>
+struct WVec<float> {
+    static constexpr int N = 4;
+    typedef float4 raw;
+    __device__ static void unpack(const raw& r, float* f) { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
+};
+template <>
+struct WVec<bf16_t> {
+    static constexpr int N = 8;
+    typedef uint4 raw;
+    __device__ static void unpack(const raw& r, float* f) {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
+template <typename WT>
+__global__ __launch_bounds__(kThreads) void adaln_kernel(
+    const float* __restrict__ sc, int32_t B, int32_t D, const void* const* __restrict__ w_tab,
+    const float* const* __restrict__ b_tab, const int32_t* __restrict__ row_start, int32_t n_mats,
+    int32_t total_rows, int32_t rows_per_wave, float* __restrict__ mod) {
+    extern __shared__ float sh_sc[];                 // [min(B, kAdaBatch), D]
+    constexpr int V = WVec<WT>::N;
+    const int lane = threadIdx.x & 63;
+    const int wave_global = blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const int r_lo = wave_global * rows_per_wave;
+    const int nvec = D / V;
+
+    for (int b0 = 0; b0 < B; b0 += kAdaBatch) {
+        const int nb = (B - b0 < kAdaBatch) ? B - b0 : kAdaBatch;
+        __syncthreads();
+        for (int i = threadIdx.x; i < nb * D; i += kThreads) sh_sc[i] = sc[static_cast<int64_t>(b0) * D + i];
+        __syncthreads();
+        int mat = 0;
+        for (int rr = 0; rr < rows_per_wave; ++rr) {
+            const int r = r_lo + rr;
+            if (r >= total_rows) break;
+            while (mat + 1 < n_mats && r >= row_start[mat + 1]) ++mat;
+            const int lr = r - row_start[mat];
+            const WT* w = static_cast<const WT*>(w_tab[mat]) + static_cast<int64_t>(lr) * D;
+            float acc[kAdaBatch];
+#pragma unroll
+            for (int b = 0; b < kAdaBatch; ++b) acc[b] = 0.f;
+            for (int c = lane; c < nvec; c += 64) {
+                const typename WVec<WT>::raw raw = reinterpret_cast<const typename WVec<WT>::raw*>(w)[c];
+                float wf[V];
+                WVec<WT>::unpack(raw, wf);
+#pragma unroll
+                for (int b = 0; b < kAdaBatch; ++b) {
+                    if (b < nb) {
+                        const float* s = sh_sc + b * D + c * V;
+#pragma unroll
+                        for (int v = 0; v < V; ++v) acc[b] = fmaf(wf[v], s[v], acc[b]);
+                    }
+                }
+            }
+            const float bias = b_tab[mat][lr];
+#pragma unroll
+            for (int b = 0; b < kAdaBatch; ++b) {
+                if (b < nb) {
+                    const float v = wave_sum_f(acc[b]);
+                    if (lane == 0) mod[static_cast<int64_t>(b0 + b) * total_rows + r] = v + bias;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Patch embedding: token (gi, gj) of sample b = W_p . flatten_{c,ph,pw}(patch) + b_p + pos
+// x_mod: sample b reads latent b % x_mod (guidance duplicates the K states).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void patch_embed_kernel(
+    const float* __restrict__ x, int32_t x_mod, int32_t C, int32_t H, int32_t W, int32_t p, int32_t D,
+    const float* __restrict__ pw, const float* __restrict__ pb, const float* __restrict__ pos,
+    float* __restrict__ out) {
+    extern __shared__ float patch[];                 // [C p p]
+    const int gw = W / p;
+    const int n = blockIdx.x, b = blockIdx.y;
+    const int gi = n / gw, gj = n % gw;
+    const int plen = C * p * p;
+    const float* xb = x + static_cast<int64_t>(b % x_mod) * C * H * W;
+    for (int q = threadIdx.x; q < plen; q += kThreads) {
+        const int c = q / (p * p), ph = (q / p) % p, pq = q % p;
+        patch[q] = xb[(static_cast<int64_t>(c) * H + gi * p + ph) * W + gj * p + pq];
+    }
+    __syncthreads();
+    const int64_t row = static_cast<int64_t>(b) * gridDim.x + n;
+    for (int j = threadIdx.x; j < D; j += kThreads) {
+        float acc = pb[j];
+        const float* w = pw + static_cast<int64_t>(j) * plen;
+        for (int q = 0; q < plen; ++q) acc = fmaf(patch[q], w[q], acc);
+        out[row * D + j] = acc + pos[static_cast<int64_t>(n) * D + j];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm (no affine, biased variance, eps 1e-6) + per-sample modulate.
+// One wavefront per row; statistics in fp32, two-pass (mean, then centred
+// second moment), wavefront-shuffle reductions.
+// ---------------------------------------------------------------------------
+template <typename OT>
+__global__ __launch_bounds__(kThreads) void ln_modulate_kernel(
+    const float* __restrict__ x, RowVec shift, RowVec scale, int32_t M, int32_t D, OT* __restrict__ out) {
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const float* xr = x + row * D;
+    float s = 0.f;
+    for (int i = lane; i < D; i += 64) s += xr[i];
+    const float mean = wave_sum_f(s) / static_cast<float>(D);
+    float q = 0.f;
+    for (int i = lane; i < D; i += 64) {
+        const float c = xr[i] - mean;
+        q = fmaf(c, c, q);
+    }
+    const float rstd = rsqrtf(wave_sum_f(q) / static_cast<float>(D) + kLnEps);
+    const float* sh = shift.base + (row / shift.rows_per_sample) * shift.stride;
+    const float* sc = scale.base + (row / scale.rows_per_sample) * scale.stride;
+    OT* o = out + row * D;
+    for (int i = lane; i < D; i += 64) {
+        const float v = (xr[i] - mean) * rstd;
+        store_f(o + i, fmaf(v, 1.0f + sc[i], sh[i]));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Plain tiled linear layer: out = epilogue(A[M,K] W[N,K]^T + bias), fp32 accumulate.
+// 64x64 tile, 16-deep K slices in LDS, 4x4 outputs per thread.
+// ---------------------------------------------------------------------------
+template <typename T, int EPI>
+__global__ __launch_bounds__(kThreads) void linear_simple_kernel(
+    const T* __restrict__ A, const T* __restrict__ W, const float* __restrict__ bias, int32_t M, int32_t N,
+    int32_t K, T* __restrict__ out, float* __restrict__ resid, RowVec gate) {
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float sA[BK][BM + 4];
+    __shared__ float sW[BK][BN + 4];
+    const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        // each thread loads 4 elements of each tile: tile element e = threadIdx.x + 256 i
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = threadIdx.x + kThreads * i;
+            const int r = e / BK, kk = e % BK;
+            const int gm = m0 + r, gn = n0 + r, gk = k0 + kk;
+            sA[kk][r] = (gm < M && gk < K) ? load_f(A + static_cast<int64_t>(gm) * K + gk) : 0.f;
+            sW[kk][r] = (gn < N && gk < K) ? load_f(W + static_cast<int64_t>(gn) * K + gk) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            float a[4], w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = sA[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = sW[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int gm = m0 + ty * 4 + i;
+        if (gm >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gn = n0 + tx * 4 + j;
+            if (gn >= N) continue;
+            float v = acc[i][j] + bias[gn];
+            const int64_t o = static_cast<int64_t>(gm) * N + gn;
+            if (EPI == FREE_EPI_BIAS) {
+                store_f(out + o, v);
+            } else if (EPI == FREE_EPI_BIAS_GELU) {
+                store_f(out + o, gelu_tanh_f(v));
+            } else {
+                const float g = gate.base[static_cast<int64_t>(gm / gate.rows_per_sample) * gate.stride + gn];
+                resid[o] = fmaf(g, v, resid[o]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Plain attention: one thread per query row, K/V tiles broadcast from LDS,
+// online softmax in fp32.
+// ---------------------------------------------------------------------------
+template <typename T, int DH>
+__global__ __launch_bounds__(128) void attention_simple_kernel(const T* __restrict__ qkv, int32_t N,
+                                                               int32_t heads, int32_t dh,
+                                                               T* __restrict__ out) {
+    constexpr int BQ = 128, BKV = 32;
+    __shared__ float sK[BKV][DH];
+    __shared__ float sV[BKV][DH];
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int D = heads * dh;
+    const int64_t row0 = static_cast<int64_t>(b) * N;
+    const int qi = blockIdx.x * BQ + threadIdx.x;
+    const bool active = qi < N;
+    const float scale = 1.0f / sqrtf(static_cast<float>(dh));
+
+    float q[DH], o[DH];
+#pragma unroll
+    for (int i = 0; i < DH; ++i) {
+        q[i] = (active && i < dh) ? load_f(qkv + (row0 + qi) * 3 * D + h * dh + i) * scale : 0.f;
+        o[i] = 0.f;
+    }
+    float mx = -INFINITY, l = 0.f;
+
+    for (int kv0 = 0; kv0 < N; kv0 += BKV) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < BKV * DH; e += BQ) {
+            const int r = e / DH, c = e % DH;
+            const int kv = kv0 + r;
+            float kk = 0.f, vv = 0.f;
+            if (kv < N && c < dh) {
+                const T* base = qkv + (row0 + kv) * 3 * D + h * dh + c;
+                kk = load_f(base + D);
+                vv = load_f(base + 2 * D);
+            }
+            sK[r][c] = kk;
+            sV[r][c] = vv;
+        }
+        __syncthreads();
+        const int nkv = (N - kv0 < BKV) ? N - kv0 : BKV;
+        float s[BKV];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < BKV; ++r) {
+            float a = 0.f;
+#pragma unroll
+            for (int i = 0; i < DH; ++i) a = fmaf(q[i], sK[r][i], a);
+            s[r] = (r < nkv) ? a : -INFINITY;
+            tmax = fmaxf(tmax, s[r]);
+        }
+        const float nm = fmaxf(mx, tmax);
+        const float corr = expf(mx - nm);
+        l *= corr;
+#pragma unroll
+        for (int i = 0; i < DH; ++i) o[i] *= corr;
+#pragma unroll
+        for (int r = 0; r < BKV; ++r) {
+            const float pr = expf(s[r] - nm);          // exp(-inf) = 0 for padded keys
+            l += pr;
+#pragma unroll
+            for (int i = 0; i < DH; ++i) o[i] = fmaf(pr, sV[r][i], o[i]);
+        }
+        mx = nm;
+    }
+    if (active) {
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int i = 0; i < DH; ++i)
+            if (i < dh) store_f(out + (row0 + qi) * D + h * dh + i, o[i] * inv);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Final layer: LN + modulate, Linear(D -> p^2 c_out), unpatchify to [B, c_out, H, W].
+// One wavefront per token.
+// ---------------------------------------------------------------------------
+template <typename WT>
+__global__ __launch_bounds__(kThreads) void final_layer_kernel(
+    const float* __restrict__ x, RowVec shift, RowVec scale, int32_t M, int32_t gh, int32_t gw, int32_t p,
+    int32_t c_out, int32_t D, const WT* __restrict__ w, const float* __restrict__ bias,
+    float* __restrict__ out) {
+    constexpr int OC = 8;                                // outputs per pass
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const float* xr = x + row * D;
+    float s = 0.f;
+    for (int i = lane; i < D; i += 64) s += xr[i];
+    const float mean = wave_sum_f(s) / static_cast<float>(D);
+    float q = 0.f;
+    for (int i = lane; i < D; i += 64) {
+        const float c = xr[i] - mean;
+        q = fmaf(c, c, q);
+    }
+    const float rstd = rsqrtf(wave_sum_f(q) / static_cast<float>(D) + kLnEps);
+    const float* sh = shift.base + (row / shift.rows_per_sample) * shift.stride;
+    const float* sc = scale.base + (row / scale.rows_per_sample) * scale.stride;
+    const int ntok = gh * gw;
+    const int b = static_cast<int>(row / ntok), n = static_cast<int>(row % ntok);
+    const int gi = n / gw, gj = n % gw;
+    const int P = p * p * c_out;
+    const int H = gh * p, Wd = gw * p;
+    for (int o0 = 0; o0 < P; o0 += OC) {
+        float acc[OC];
+#pragma unroll
+        for (int k = 0; k < OC; ++k) acc[k] = 0.f;
+        for (int i = lane; i < D; i += 64) {
+            const float v = fmaf((xr[i] - mean) * rstd, 1.0f + sc[i], sh[i]);
+#pragma unroll
+            for (int k = 0; k < OC; ++k)
+                if (o0 + k < P) acc[k] = fmaf(v, load_f(w + static_cast<int64_t>(o0 + k) * D + i), acc[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < OC; ++k) {
+            const float v = wave_sum_f(acc[k]);
+            const int o = o0 + k;
+            if (lane == 0 && o < P) {
+                const int c = o % c_out, pq = (o / c_out) % p, ph = o / (c_out * p);
+                out[((static_cast<int64_t>(b) * c_out + c) * H + gi * p + ph) * Wd + gj * p + pq] = v + bias[o];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Guidance + eps -> mean (Eq. ddpm_update): m_k = coef_x[k] x_k + coef_eps[k] eps_k,
+// eps = eps_null + s (eps_cond - eps_null) when the batch carries both halves.
+// ---------------------------------------------------------------------------
+__global__ void eps_to_mean_kernel(const float* __restrict__ eps_out, const float* __restrict__ x_states,
+                                   const float* __restrict__ coef_x, const float* __restrict__ coef_eps,
+                                   float cfg_scale, int32_t use_cfg, int32_t K, int32_t C, int32_t c_out,
+                                   int64_t hw, float* __restrict__ m_out) {
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t per = static_cast<int64_t>(C) * hw;
+    if (idx >= per * K) return;
+    const int k = static_cast<int>(idx / per);
+    const int64_t rem = idx % per;                        // c * hw + s
+    float eps = eps_out[static_cast<int64_t>(k) * c_out * hw + rem];
+    if (use_cfg) {
+        const float en = eps_out[static_cast<int64_t>(K + k) * c_out * hw + rem];
+        eps = fmaf(cfg_scale, eps - en, en);
+    }
+    m_out[idx] = fmaf(coef_x[k], x_states[idx], coef_eps[k] * eps);
+}
+
+__global__ void pack_cond_kernel(const int32_t* __restrict__ t, int32_t y, int32_t null_label, int32_t K,
+                                 int32_t dup, int32_t* __restrict__ t_out, int32_t* __restrict__ y_out) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= K * dup) return;
+    t_out[b] = t[b % K];
+    y_out[b] = (b < K) ? y : null_label;
+}
+
+}  // namespace
+
+// ============================ host launch wrappers ============================
+
+int32_t launch_conditioning(const int32_t* t, const int32_t* y, int32_t B, int32_t D, int32_t tfreq,
+                            const float* w1, const float* b1, const float* w2, const float* b2,
+                            const float* ytab, float* h1, float* sc, hipStream_t s) {
+    // h1 doubles as [B, tfreq] timestep embedding followed by [B, D] hidden
+    float* temb = h1;
+    float* hid = h1 + static_cast<int64_t>(B) * tfreq;
+    const int n = B * (tfreq / 2);
+    hipLaunchKernelGGL(timestep_embed_kernel, dim3((n + 255) / 256), dim3(256), 0, s, t, B, tfreq, temb);
+    if (!launch_ok()) return FREE_ERR_HIP;
+    dim3 g((D + kWaves - 1) / kWaves, B);
+    hipLaunchKernelGGL(small_linear_kernel<true>, g, dim3(kThreads), 0, s, temb, B, tfreq, D, w1, b1,
+                       static_cast<const float*>(nullptr), static_cast<const int32_t*>(nullptr), hid);
+    if (!launch_ok()) return FREE_ERR_HIP;
+    hipLaunchKernelGGL(small_linear_kernel<true>, g, dim3(kThreads), 0, s, hid, B, D, D, w2, b2, ytab, y, sc);
+    if (!launch_ok()) return FREE_ERR_HIP;
+    return FREE_OK;
+}
+
+int32_t launch_adaln(const float* sc, int32_t B, int32_t D, const void* const* w_tab,
+                     const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
+                     int32_t total_rows, int32_t dtype, float* mod, hipStream_t s) {
+    const int rows_per_wave = 8;
+    const int waves = (total_rows + rows_per_wave - 1) / rows_per_wave;
+    const int blocks = (waves + kWaves - 1) / kWaves;
+    const int nb = B < kAdaBatch ? B : kAdaBatch;
+    const size_t lds = static_cast<size_t>(nb) * D * sizeof(float);
+    if (lds > 150 * 1024) return FREE_ERR_SHAPE;
+    if (dtype == FREE_BF16) {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(adaln_kernel<bf16_t>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))))
+            return FREE_ERR_HIP;
+        hipLaunchKernelGGL(adaln_kernel<bf16_t>, dim3(blocks), dim3(kThreads), lds, s, sc, B, D, w_tab, b_tab,
+                           row_start, n_mats, total_rows, rows_per_wave, mod);
+    } else {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(adaln_kernel<float>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))))
+            return FREE_ERR_HIP;
+        hipLaunchKernelGGL(adaln_kernel<float>, dim3(blocks), dim3(kThreads), lds, s, sc, B, D, w_tab, b_tab,
+                           row_start, n_mats, total_rows, rows_per_wave, mod);
+    }
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_patch_embed(const float* x, int32_t x_mod, int32_t B, int32_t C, int32_t H, int32_t W,
+                           int32_t p, int32_t D, const float* pw, const float* pb, const float* pos,
+                           float* out, hipStream_t s) {
+    const int ntok = (H / p) * (W / p);
+    const size_t lds = static_cast<size_t>(C) * p * p * sizeof(float);
+    hipLaunchKernelGGL(patch_embed_kernel, dim3(ntok, B), dim3(kThreads), lds, s, x, x_mod, C, H, W, p, D, pw,
+                       pb, pos, out);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_ln_modulate(const float* x, RowVec shift, RowVec scale, int32_t M, int32_t D, int32_t dtype,
+                           void* out, hipStream_t s) {
+    const int blocks = (M + kWaves - 1) / kWaves;
+    if (dtype == FREE_BF16)
+        hipLaunchKernelGGL(ln_modulate_kernel<bf16_t>, dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, D,
+                           static_cast<bf16_t*>(out));
+    else
+        hipLaunchKernelGGL(ln_modulate_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, D,
+                           static_cast<float*>(out));
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+template <typename T>
+static int32_t linear_simple_t(const T* A, const T* W, const float* bias, int32_t M, int32_t N, int32_t K,
+                               int32_t epi, T* out, float* resid, RowVec gate, hipStream_t s) {
+    dim3 g((N + 63) / 64, (M + 63) / 64);
+    switch (epi) {
+        case FREE_EPI_BIAS:
+            hipLaunchKernelGGL((linear_simple_kernel<T, FREE_EPI_BIAS>), g, dim3(kThreads), 0, s, A, W, bias, M, N,
+                               K, out, resid, gate);
+            break;
+        case FREE_EPI_BIAS_GELU:
+            hipLaunchKernelGGL((linear_simple_kernel<T, FREE_EPI_BIAS_GELU>), g, dim3(kThreads), 0, s, A, W, bias,
+                               M, N, K, out, resid, gate);
+            break;
+        case FREE_EPI_GATE_RESID:
+            hipLaunchKernelGGL((linear_simple_kernel<T, FREE_EPI_GATE_RESID>), g, dim3(kThreads), 0, s, A, W, bias,
+                               M, N, K, out, resid, gate);
+            break;
+        default:
+            return FREE_ERR_RANGE;
+    }
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_linear_simple(const void* A, const void* W, const float* bias, int32_t M, int32_t N, int32_t K,
+                             int32_t dtype, int32_t epi, void* out, float* resid, RowVec gate, hipStream_t s) {
+    if (dtype == FREE_BF16)
+        return linear_simple_t(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, M, N, K, epi,
+                               static_cast<bf16_t*>(out), resid, gate, s);
+    return linear_simple_t(static_cast<const float*>(A), static_cast<const float*>(W), bias, M, N, K, epi,
+                           static_cast<float*>(out), resid, gate, s);
+}
+
+template <typename T>
+static int32_t attention_simple_t(const T* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh, T* out,
+                                  hipStream_t s) {
+    dim3 g((N + 127) / 128, heads, B);
+#define FREE_ATTN_CASE(DHMAX)                                                                          \
+    hipLaunchKernelGGL((attention_simple_kernel<T, DHMAX>), g, dim3(128), 0, s, qkv, N, heads, dh, out)
+    if (dh <= 16) FREE_ATTN_CASE(16);
+    else if (dh <= 32) FREE_ATTN_CASE(32);
+    else if (dh <= 64) FREE_ATTN_CASE(64);
+    else if (dh <= 72) FREE_ATTN_CASE(72);
+    else if (dh <= 128) FREE_ATTN_CASE(128);
+    else return FREE_ERR_SHAPE;
+#undef FREE_ATTN_CASE
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_attention_simple(const void* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh, int32_t dtype,
+                                void* out, hipStream_t s) {
+    if (dtype == FREE_BF16)
+        return attention_simple_t(static_cast<const bf16_t*>(qkv), B, N, heads, dh, static_cast<bf16_t*>(out), s);
+    return attention_simple_t(static_cast<const float*>(qkv), B, N, heads, dh, static_cast<float*>(out), s);
+}
+
+int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B, int32_t gh, int32_t gw,
+                           int32_t p, int32_t c_out, int32_t D, const void* w, const float* bias, int32_t dtype,
+                           float* out, hipStream_t s) {
+    const int M = B * gh * gw;
+    const int blocks = (M + kWaves - 1) / kWaves;
+    if (dtype == FREE_BF16)
+        hipLaunchKernelGGL(final_layer_kernel<bf16_t>, dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, gh,
+                           gw, p, c_out, D, static_cast<const bf16_t*>(w), bias, out);
+    else
+        hipLaunchKernelGGL(final_layer_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, gh,
+                           gw, p, c_out, D, static_cast<const float*>(w), bias, out);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const float* coef_x,
+                           const float* coef_eps, float cfg_scale, int32_t K, int32_t C, int32_t c_out,
+                           int64_t hw, float* m_out, hipStream_t s) {
+    const int64_t n = static_cast<int64_t>(K) * C * hw;
+    const int use_cfg = cfg_scale > 1.0f ? 1 : 0;
+    hipLaunchKernelGGL(eps_to_mean_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, eps_out,
+                       x_states, coef_x, coef_eps, cfg_scale, use_cfg, K, C, c_out, hw, m_out);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_t K, int32_t dup,
+                         int32_t* t_out, int32_t* y_out, hipStream_t s) {
+    const int n = K * dup;
+    hipLaunchKernelGGL(pack_cond_kernel, dim3((n + 63) / 64), dim3(64), 0, s, t, y, null_label, K, dup, t_out,
+                       y_out);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+}  // namespace freemi

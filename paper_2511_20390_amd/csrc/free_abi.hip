@@ -1,0 +1,418 @@
+// C-ABI entry points of libfree_mi355x: argument checks, the model handle, the
+// workspace carve-up and the chaining of kernels for the packed target forward
+// (Alg. 1, "compute means ... in parallel"), the verification loop (Alg. 2 inside
+// Alg. 1) and a whole round.  All arithmetic runs in the HIP kernels; the only
+// host-side mathematics is the diffusion schedule helper (Eq. ddpm_update) and the
+// fixed positional table computed once at handle creation.
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "free_internal.h"
+
+namespace freemi {
+
+static thread_local int32_t g_last_hip_error = 0;
+void note_hip_error(hipError_t e) { g_last_hip_error = static_cast<int32_t>(e); }
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Dims {
+    int32_t C, H, W, p, D, depth, heads, dh, F, classes, c_out, tfreq, mode;
+    int32_t gh, gw, ntok, P;
+    int64_t d;            // latent size C*H*W
+    int32_t mod_rows;     // depth*6D + 2D
+};
+
+bool make_dims(const free_dit_config* c, Dims* o) {
+    if (!c) return false;
+    if (c->in_ch < 1 || c->lat_h < 1 || c->lat_w < 1 || c->patch < 1 || c->hidden < 8 || c->depth < 0 ||
+        c->heads < 1 || c->mlp_hidden < 8 || c->num_classes < 1 || c->t_freq_dim < 2)
+        return false;
+    if (c->lat_h % c->patch || c->lat_w % c->patch) return false;
+    if (c->hidden % c->heads || c->hidden % 8 || c->mlp_hidden % 8 || c->t_freq_dim % 2) return false;
+    if (c->mode != FREE_FP32 && c->mode != FREE_BF16) return false;
+    const int dh = c->hidden / c->heads;
+    if (dh > 128) return false;
+    if (c->mode == FREE_BF16 && dh % 8) return false;
+    o->C = c->in_ch; o->H = c->lat_h; o->W = c->lat_w; o->p = c->patch; o->D = c->hidden;
+    o->depth = c->depth; o->heads = c->heads; o->dh = dh; o->F = c->mlp_hidden;
+    o->classes = c->num_classes; o->c_out = c->in_ch * (c->learn_sigma ? 2 : 1);
+    o->tfreq = c->t_freq_dim; o->mode = c->mode;
+    o->gh = c->lat_h / c->patch; o->gw = c->lat_w / c->patch; o->ntok = o->gh * o->gw;
+    o->P = c->patch * c->patch * o->c_out;
+    o->d = static_cast<int64_t>(c->in_ch) * c->lat_h * c->lat_w;
+    o->mod_rows = c->depth * 6 * c->hidden + 2 * c->hidden;
+    return true;
+}
+
+// Workspace carve-up for a forward on B packed states (offsets in bytes).
+struct WsLayout {
+    size_t cond_h, sc, mod, tpack, ypack, xres, xn, qkv, att, hmid, eps, mtarget, vpart, total;
+};
+
+WsLayout make_layout(const Dims& d, int32_t B) {
+    WsLayout L;
+    const size_t es = d.mode == FREE_BF16 ? 2 : 4;
+    const size_t M = static_cast<size_t>(B) * d.ntok;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    L.cond_h = take(static_cast<size_t>(B) * (d.tfreq + d.D) * 4);
+    L.sc = take(static_cast<size_t>(B) * d.D * 4);
+    L.mod = take(static_cast<size_t>(B) * d.mod_rows * 4);
+    L.tpack = take(static_cast<size_t>(B) * 4);
+    L.ypack = take(static_cast<size_t>(B) * 4);
+    L.xres = take(M * d.D * 4);
+    L.xn = take(M * d.D * es);
+    L.qkv = take(M * 3 * d.D * es);
+    L.att = take(M * d.D * es);
+    L.hmid = take(M * d.F * es);
+    L.eps = take(static_cast<size_t>(B) * d.c_out * d.H * d.W * 4);
+    L.mtarget = take(static_cast<size_t>(B) * d.d * 4);
+    L.vpart = take(verify_workspace_bytes(1, B, d.d));
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+}  // namespace freemi
+
+using namespace freemi;
+
+struct free_dit_s {
+    free_dit_config cfg;
+    Dims dims;
+    std::vector<const void*> w;         // borrowed device pointers, in ABI order
+    // device-side tables owned by the handle
+    void* dev_block = nullptr;
+    const void* const* ada_w_tab = nullptr;
+    const float* const* ada_b_tab = nullptr;
+    const int32_t* ada_row_start = nullptr;
+    const float* pos = nullptr;
+    int device = 0;
+
+    const void* blk(int l, int which) const { return w[7 + 10 * l + which]; }
+    const void* fin(int which) const { return w[7 + 10 * dims.depth + which]; }
+};
+
+namespace {
+
+enum { W_PATCH_W = 0, W_PATCH_B, W_T_W1, W_T_B1, W_T_W2, W_T_B2, W_Y_TABLE };
+enum { B_ADA_W = 0, B_ADA_B, B_QKV_W, B_QKV_B, B_PROJ_W, B_PROJ_B, B_FC1_W, B_FC1_B, B_FC2_W, B_FC2_B };
+enum { F_ADA_W = 0, F_ADA_B, F_W, F_B };
+
+int32_t linear_dispatch(const Dims& d, const void* A, const void* W, const float* bias, int32_t M, int32_t N,
+                        int32_t K, int32_t epi, void* out, float* resid, RowVec gate, hipStream_t s) {
+    if (d.mode == FREE_BF16 && mfma_linear_supported(M, N, K))
+        return launch_linear_mfma(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, M, N, K, epi,
+                                  static_cast<bf16_t*>(out), resid, gate, s);
+    return launch_linear_simple(A, W, bias, M, N, K, d.mode, epi, out, resid, gate, s);
+}
+
+int32_t attention_dispatch(const Dims& d, const void* qkv, int32_t B, void* out, hipStream_t s) {
+    if (d.mode == FREE_BF16 && mfma_attention_supported(d.ntok, d.dh))
+        return launch_attention_mfma(static_cast<const bf16_t*>(qkv), B, d.ntok, d.heads, d.dh,
+                                     static_cast<bf16_t*>(out), s);
+    return launch_attention_simple(qkv, B, d.ntok, d.heads, d.dh, d.mode, out, s);
+}
+
+#define FREE_TRY(expr)                      \
+    do {                                    \
+        int32_t st__ = (expr);              \
+        if (st__ != FREE_OK) return st__;   \
+    } while (0)
+
+// The packed forward.  x_mod: packed state b reads latent b % x_mod.
+int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t* t, const int32_t* y, int32_t B,
+                     float* eps_out, float* top_feat, char* ws, hipStream_t s) {
+    const Dims& d = h->dims;
+    const WsLayout L = make_layout(d, B);
+    const int32_t M = B * d.ntok;
+    float* cond_h = reinterpret_cast<float*>(ws + L.cond_h);
+    float* sc = reinterpret_cast<float*>(ws + L.sc);
+    float* mod = reinterpret_cast<float*>(ws + L.mod);
+    float* xres = reinterpret_cast<float*>(ws + L.xres);
+    void* xn = ws + L.xn;
+    void* qkv = ws + L.qkv;
+    void* att = ws + L.att;
+    void* hmid = ws + L.hmid;
+
+    FREE_TRY(launch_conditioning(t, y, B, d.D, d.tfreq, static_cast<const float*>(h->w[W_T_W1]),
+                                 static_cast<const float*>(h->w[W_T_B1]), static_cast<const float*>(h->w[W_T_W2]),
+                                 static_cast<const float*>(h->w[W_T_B2]),
+                                 static_cast<const float*>(h->w[W_Y_TABLE]), cond_h, sc, s));
+    FREE_TRY(launch_adaln(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1, d.mod_rows,
+                          d.mode, mod, s));
+    FREE_TRY(launch_patch_embed(x, x_mod, B, d.C, d.H, d.W, d.p, d.D, static_cast<const float*>(h->w[W_PATCH_W]),
+                                static_cast<const float*>(h->w[W_PATCH_B]), h->pos, xres, s));
+    auto vec = [&](int l, int which) {
+        RowVec r;
+        r.base = mod + static_cast<int64_t>(l) * 6 * d.D + static_cast<int64_t>(which) * d.D;
+        r.stride = d.mod_rows;
+        r.rows_per_sample = d.ntok;
+        return r;
+    };
+    for (int l = 0; l < d.depth; ++l) {
+        // x += gate1 * Proj(Attn(LN(x)(1+scale1)+shift1))
+        FREE_TRY(launch_ln_modulate(xres, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn, s));
+        FREE_TRY(linear_dispatch(d, xn, h->blk(l, B_QKV_W), static_cast<const float*>(h->blk(l, B_QKV_B)), M,
+                                 3 * d.D, d.D, FREE_EPI_BIAS, qkv, nullptr, RowVec{nullptr, 0, 1}, s));
+        FREE_TRY(attention_dispatch(d, qkv, B, att, s));
+        FREE_TRY(linear_dispatch(d, att, h->blk(l, B_PROJ_W), static_cast<const float*>(h->blk(l, B_PROJ_B)), M,
+                                 d.D, d.D, FREE_EPI_GATE_RESID, nullptr, xres, vec(l, 2), s));
+        // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
+        FREE_TRY(launch_ln_modulate(xres, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn, s));
+        FREE_TRY(linear_dispatch(d, xn, h->blk(l, B_FC1_W), static_cast<const float*>(h->blk(l, B_FC1_B)), M, d.F,
+                                 d.D, FREE_EPI_BIAS_GELU, hmid, nullptr, RowVec{nullptr, 0, 1}, s));
+        FREE_TRY(linear_dispatch(d, hmid, h->blk(l, B_FC2_W), static_cast<const float*>(h->blk(l, B_FC2_B)), M,
+                                 d.D, d.F, FREE_EPI_GATE_RESID, nullptr, xres, vec(l, 5), s));
+    }
+    if (top_feat) {
+        if (!hip_ok(hipMemcpyAsync(top_feat, xres, static_cast<size_t>(M) * d.D * 4, hipMemcpyDeviceToDevice, s)))
+            return FREE_ERR_HIP;
+    }
+    RowVec fsh{mod + static_cast<int64_t>(d.depth) * 6 * d.D, d.mod_rows, d.ntok};
+    RowVec fsc{mod + static_cast<int64_t>(d.depth) * 6 * d.D + d.D, d.mod_rows, d.ntok};
+    FREE_TRY(launch_final_layer(xres, fsh, fsc, B, d.gh, d.gw, d.p, d.c_out, d.D, h->fin(F_W),
+                                static_cast<const float*>(h->fin(F_B)), d.mode, eps_out, s));
+    return FREE_OK;
+}
+
+int32_t check_ws(const void* ws, size_t ws_bytes, size_t need) {
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) || ws_bytes < need) return FREE_ERR_WORKSPACE;
+    return FREE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* free_version(void) { return "free-mi355x 0.1 (gfx950)"; }
+
+const char* free_status_string(int32_t st) {
+    switch (st) {
+        case FREE_OK: return "ok";
+        case FREE_ERR_NULL: return "a required pointer is NULL";
+        case FREE_ERR_SHAPE: return "inconsistent or unsupported sizes";
+        case FREE_ERR_RANGE: return "scalar argument out of range";
+        case FREE_ERR_DTYPE: return "unknown compute mode";
+        case FREE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case FREE_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int32_t free_last_hip_error(void) { return g_last_hip_error; }
+
+int32_t free_ddpm_schedule(int32_t T, double beta_start, double beta_end, double* coef_x, double* coef_eps,
+                           double* sigma) {
+    if (T < 2) return FREE_ERR_SHAPE;
+    if (!(beta_start > 0.0) || !(beta_end >= beta_start) || !(beta_end < 1.0)) return FREE_ERR_RANGE;
+    double abar = 1.0, abar_prev = 1.0, sigma1 = 0.0;
+    for (int i = 0; i < T; ++i) {
+        const double beta = beta_start + (beta_end - beta_start) * static_cast<double>(i) / (T - 1);
+        const double alpha = 1.0 - beta;
+        abar_prev = abar;
+        abar *= alpha;
+        if (coef_x) coef_x[i] = 1.0 / std::sqrt(alpha);
+        if (coef_eps) coef_eps[i] = -beta / (std::sqrt(1.0 - abar) * std::sqrt(alpha));
+        const double var = beta * (1.0 - abar_prev) / (1.0 - abar);      // posterior variance
+        if (sigma) sigma[i] = std::sqrt(var);
+        if (i == 1) sigma1 = std::sqrt(var);
+    }
+    if (sigma) sigma[0] = sigma1;          // index 0 has zero variance: clipped to index 1
+    return FREE_OK;
+}
+
+int32_t free_weight_count(const free_dit_config* cfg) {
+    Dims d;
+    if (!make_dims(cfg, &d)) return FREE_ERR_SHAPE;
+    return 7 + 10 * d.depth + 4;
+}
+
+int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_ptrs, int32_t n_ptrs,
+                        free_dit_t* out) {
+    if (!cfg || !weight_ptrs || !out) return FREE_ERR_NULL;
+    if (cfg->mode != FREE_FP32 && cfg->mode != FREE_BF16) return FREE_ERR_DTYPE;
+    Dims d;
+    if (!make_dims(cfg, &d)) return FREE_ERR_SHAPE;
+    if (n_ptrs != 7 + 10 * d.depth + 4) return FREE_ERR_SHAPE;
+    for (int i = 0; i < n_ptrs; ++i) {
+        if (!weight_ptrs[i]) return FREE_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(weight_ptrs[i]) & 15u) return FREE_ERR_SHAPE;
+    }
+    free_dit_s* h = new (std::nothrow) free_dit_s();
+    if (!h) return FREE_ERR_HIP;
+    h->cfg = *cfg;
+    h->dims = d;
+    h->w.assign(weight_ptrs, weight_ptrs + n_ptrs);
+    if (!hip_ok(hipGetDevice(&h->device))) { delete h; return FREE_ERR_HIP; }
+
+    // device block: [w_tab (depth+1 ptrs) | b_tab (depth+1 ptrs) | row_start (depth+2 ints) | pos (ntok*D floats)]
+    const int n_mats = d.depth + 1;
+    const size_t off_w = 0;
+    const size_t off_b = align_up(off_w + n_mats * sizeof(void*));
+    const size_t off_r = align_up(off_b + n_mats * sizeof(void*));
+    const size_t off_p = align_up(off_r + (n_mats + 1) * sizeof(int32_t));
+    const size_t total = off_p + static_cast<size_t>(d.ntok) * d.D * sizeof(float);
+    std::vector<char> host(total, 0);
+    const void** wt = reinterpret_cast<const void**>(host.data() + off_w);
+    const void** bt = reinterpret_cast<const void**>(host.data() + off_b);
+    int32_t* rs = reinterpret_cast<int32_t*>(host.data() + off_r);
+    for (int l = 0; l < d.depth; ++l) {
+        wt[l] = h->blk(l, B_ADA_W);
+        bt[l] = h->blk(l, B_ADA_B);
+        rs[l] = l * 6 * d.D;
+    }
+    wt[d.depth] = h->fin(F_ADA_W);
+    bt[d.depth] = h->fin(F_ADA_B);
+    rs[d.depth] = d.depth * 6 * d.D;
+    rs[d.depth + 1] = d.mod_rows;
+    // fixed 2-D sin-cos table: token (i, j) -> [sin(j w) | cos(j w) | sin(i w) | cos(i w)], w_k = 10000^(-k/(D/4))
+    float* pos = reinterpret_cast<float*>(host.data() + off_p);
+    const int q = d.D / 4;
+    for (int i = 0; i < d.gh; ++i)
+        for (int j = 0; j < d.gw; ++j) {
+            float* row = pos + (static_cast<size_t>(i) * d.gw + j) * d.D;
+            for (int k = 0; k < q; ++k) {
+                const double w = std::pow(10000.0, -static_cast<double>(k) / q);
+                row[k] = static_cast<float>(std::sin(j * w));
+                row[q + k] = static_cast<float>(std::cos(j * w));
+                row[2 * q + k] = static_cast<float>(std::sin(i * w));
+                row[3 * q + k] = static_cast<float>(std::cos(i * w));
+            }
+        }
+    if (!hip_ok(hipMalloc(&h->dev_block, total))) { delete h; return FREE_ERR_HIP; }
+    if (!hip_ok(hipMemcpy(h->dev_block, host.data(), total, hipMemcpyHostToDevice))) {
+        (void)hipFree(h->dev_block);
+        delete h;
+        return FREE_ERR_HIP;
+    }
+    char* db = static_cast<char*>(h->dev_block);
+    h->ada_w_tab = reinterpret_cast<const void* const*>(db + off_w);
+    h->ada_b_tab = reinterpret_cast<const float* const*>(db + off_b);
+    h->ada_row_start = reinterpret_cast<const int32_t*>(db + off_r);
+    h->pos = reinterpret_cast<const float*>(db + off_p);
+    *out = h;
+    return FREE_OK;
+}
+
+int32_t free_dit_destroy(free_dit_t h) {
+    if (!h) return FREE_ERR_NULL;
+    int32_t st = FREE_OK;
+    if (h->dev_block && !hip_ok(hipFree(h->dev_block))) st = FREE_ERR_HIP;
+    delete h;
+    return st;
+}
+
+size_t free_workspace_bytes(const free_dit_config* cfg, int32_t B) {
+    Dims d;
+    if (!make_dims(cfg, &d) || B < 1) return 0;
+    return make_layout(d, B).total;
+}
+
+int32_t dit_forward_packed(free_dit_t h, const float* x, const int32_t* t, const int32_t* y, int32_t B,
+                           float* eps_out, float* top_feat, void* workspace, size_t ws_bytes, void* stream) {
+    if (!h || !x || !t || !y || !eps_out) return FREE_ERR_NULL;
+    if (B < 1 || static_cast<int64_t>(B) * h->dims.ntok > INT32_MAX / 4) return FREE_ERR_SHAPE;
+    FREE_TRY(check_ws(workspace, ws_bytes, make_layout(h->dims, B).total));
+    return forward_impl(h, x, B, t, y, B, eps_out, top_feat, static_cast<char*>(workspace),
+                        static_cast<hipStream_t>(stream));
+}
+
+size_t spec_verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d) {
+    if (K > FREE_MAX_DRAFTS) return 0;
+    return verify_workspace_bytes(n_traj, K, d);
+}
+
+int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_draft, const float* sigma,
+                    const float* u, const float* lambda, int32_t n_traj, int32_t K, int64_t d, float* log_ratio,
+                    uint8_t* accept, int32_t* n_accept, float* x_out, void* workspace, size_t ws_bytes,
+                    void* stream) {
+    if (!m_target || !m_draft || !x_draft || !sigma || !u || !log_ratio || !accept || !n_accept || !x_out)
+        return FREE_ERR_NULL;
+    if (n_traj < 0 || K < 1 || K > FREE_MAX_DRAFTS || d < 1) return FREE_ERR_SHAPE;
+    if (n_traj == 0) return FREE_OK;
+    VerifyArgs a{m_target, m_draft, x_draft, nullptr, sigma, u, lambda, n_traj, K, d,
+                 log_ratio, accept, n_accept, x_out};
+    return launch_verify(a, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, const float* m_draft,
+                   const int32_t* t, int32_t y, float cfg_scale, const float* coef_x, const float* coef_eps,
+                   const float* sigma, const float* u, const float* lambda, int32_t K, float* m_target_out,
+                   float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out, void* workspace,
+                   size_t ws_bytes, void* stream) {
+    if (!h || !x_states || !x_last || !m_draft || !t || !coef_x || !coef_eps || !sigma || !u || !log_ratio ||
+        !accept || !n_accept || !x_out)
+        return FREE_ERR_NULL;
+    const Dims& d = h->dims;
+    if (K < 1 || K > FREE_MAX_DRAFTS) return FREE_ERR_SHAPE;
+    if (y < 0 || y > d.classes) return FREE_ERR_RANGE;
+    if (!(cfg_scale == cfg_scale)) return FREE_ERR_RANGE;
+    const int32_t dup = cfg_scale > 1.0f ? 2 : 1;
+    const int32_t B = K * dup;
+    const WsLayout L = make_layout(d, B);
+    FREE_TRY(check_ws(workspace, ws_bytes, L.total));
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t* tp = reinterpret_cast<int32_t*>(ws + L.tpack);
+    int32_t* yp = reinterpret_cast<int32_t*>(ws + L.ypack);
+    float* eps = reinterpret_cast<float*>(ws + L.eps);
+    float* mt = m_target_out ? m_target_out : reinterpret_cast<float*>(ws + L.mtarget);
+    FREE_TRY(launch_pack_cond(t, y, d.classes, K, dup, tp, yp, s));
+    FREE_TRY(forward_impl(h, x_states, K, tp, yp, B, eps, nullptr, ws, s));
+    FREE_TRY(launch_eps_to_mean(eps, x_states, coef_x, coef_eps, cfg_scale, K, d.C, d.c_out,
+                                static_cast<int64_t>(d.H) * d.W, mt, s));
+    VerifyArgs a{mt, m_draft, x_states, x_last, sigma, u, lambda, 1, K, d.d, log_ratio, accept, n_accept, x_out};
+    return launch_verify(a, ws + L.vpart, verify_workspace_bytes(1, K, d.d), s);
+}
+
+int32_t free_op_linear(const void* A, const void* W, const float* bias, int32_t M, int32_t N, int32_t Kdim,
+                       int32_t dtype, int32_t epilogue, void* out, float* resid, const float* gate,
+                       int32_t gate_stride, int32_t rows_per_sample, void* stream) {
+    if (!A || !W || !bias) return FREE_ERR_NULL;
+    if (dtype != FREE_FP32 && dtype != FREE_BF16) return FREE_ERR_DTYPE;
+    if (M < 1 || N < 1 || Kdim < 1) return FREE_ERR_SHAPE;
+    if (epilogue == FREE_EPI_GATE_RESID) {
+        if (!resid || !gate) return FREE_ERR_NULL;
+        if (rows_per_sample < 1) return FREE_ERR_SHAPE;
+    } else if (epilogue == FREE_EPI_BIAS || epilogue == FREE_EPI_BIAS_GELU) {
+        if (!out) return FREE_ERR_NULL;
+    } else {
+        return FREE_ERR_RANGE;
+    }
+    Dims d{};
+    d.mode = dtype;
+    RowVec g{gate, gate_stride, rows_per_sample > 0 ? rows_per_sample : 1};
+    return linear_dispatch(d, A, W, bias, M, N, Kdim, epilogue, out, resid, g, static_cast<hipStream_t>(stream));
+}
+
+int32_t free_op_attention(const void* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh, int32_t dtype,
+                          void* out, void* stream) {
+    if (!qkv || !out) return FREE_ERR_NULL;
+    if (dtype != FREE_FP32 && dtype != FREE_BF16) return FREE_ERR_DTYPE;
+    if (B < 1 || N < 1 || heads < 1 || dh < 1 || dh > 128) return FREE_ERR_SHAPE;
+    Dims d{};
+    d.mode = dtype;
+    d.ntok = N;
+    d.heads = heads;
+    d.dh = dh;
+    return attention_dispatch(d, qkv, B, out, static_cast<hipStream_t>(stream));
+}
+
+int32_t free_op_ln_modulate(const float* x, const float* shift, const float* scale, int32_t mod_stride, int32_t M,
+                            int32_t D, int32_t rows_per_sample, int32_t dtype, void* out, void* stream) {
+    if (!x || !shift || !scale || !out) return FREE_ERR_NULL;
+    if (dtype != FREE_FP32 && dtype != FREE_BF16) return FREE_ERR_DTYPE;
+    if (M < 1 || D < 1 || rows_per_sample < 1) return FREE_ERR_SHAPE;
+    return launch_ln_modulate(x, RowVec{shift, mod_stride, rows_per_sample},
+                              RowVec{scale, mod_stride, rows_per_sample}, M, D, dtype, out,
+                              static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+// Internal declarations shared by the translation units of libfree_mi355x.
+// Host-side launch wrappers only; every kernel lives in exactly one .hip file.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/free_mi355x.h"
+
+namespace freemi {
+
+// ---- bf16 storage type: raw bits, round-to-nearest-even conversion ----------
+struct bf16_t {
+    uint16_t v;
+};
+
+__host__ __device__ inline float bf16_to_float(bf16_t h) {
+    union { uint32_t u; float f; } c;
+    c.u = static_cast<uint32_t>(h.v) << 16;
+    return c.f;
+}
+
+__host__ __device__ inline bf16_t float_to_bf16(float f) {
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    uint32_t u = c.u;
+    bf16_t r;
+    if ((u & 0x7fffffffu) > 0x7f800000u) {          // NaN stays NaN
+        r.v = static_cast<uint16_t>((u >> 16) | 0x40u);
+        return r;
+    }
+    u += 0x7fffu + ((u >> 16) & 1u);
+    r.v = static_cast<uint16_t>(u >> 16);
+    return r;
+}
+
+__device__ inline float load_f(const float* p) { return *p; }
+__device__ inline float load_f(const bf16_t* p) { return bf16_to_float(*p); }
+__device__ inline void store_f(float* p, float v) { *p = v; }
+__device__ inline void store_f(bf16_t* p, float v) { *p = float_to_bf16(v); }
+
+__host__ __device__ inline float gelu_tanh_f(float v) {
+    const float k = 0.7978845608028654f;            // sqrt(2/pi)
+    float inner = k * (v + 0.044715f * v * v * v);
+    return 0.5f * v * (1.0f + tanhf(inner));
+}
+
+__host__ __device__ inline float silu_f(float v) { return v / (1.0f + expf(-v)); }
+
+constexpr float kLnEps = 1e-6f;
+
+// Per-sample modulation / gate vector of an epilogue or a LayerNorm:
+// value for (row m, column n) = base[(m / rows_per_sample) * stride + n].
+struct RowVec {
+    const float* base;
+    int32_t stride;
+    int32_t rows_per_sample;
+};
+
+// Thread-local HIP error memo (free_last_hip_error).
+void note_hip_error(hipError_t e);
+inline bool hip_ok(hipError_t e) {
+    if (e != hipSuccess) { note_hip_error(e); return false; }
+    return true;
+}
+inline bool launch_ok() { return hip_ok(hipGetLastError()); }
+
+// ---- verification (verify.hip) -------------------------------------------------
+struct VerifyArgs {
+    const float* m_target;   // [n_traj, K, d]
+    const float* m_draft;    // [n_traj, K, d]
+    const float* x_draft;    // [n_traj, K, d]; or, when x_last != nullptr, the K packed
+                             // states of ONE trajectory: draft k is x_draft + (k+1) d
+    const float* x_last;     // nullptr, or the K-th draft of the single trajectory
+    const float* sigma; const float* u; const float* lambda;
+    int32_t n_traj, K; int64_t d;
+    float* log_ratio; uint8_t* accept; int32_t* n_accept; float* x_out;
+};
+size_t verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d);
+int32_t launch_verify(const VerifyArgs& a, void* ws, size_t ws_bytes, hipStream_t s);
+
+// ---- simple DiT kernels, both dtypes (dit_kernels.hip) ---------------------------
+int32_t launch_conditioning(const int32_t* t, const int32_t* y, int32_t B, int32_t D, int32_t tfreq,
+                            const float* w1, const float* b1, const float* w2, const float* b2,
+                            const float* ytab, float* h1, float* sc, hipStream_t s);
+// mod[b, r] = sum_i sc[b, i] W_r[i] + bias_r; rows r come from n_mats matrices of
+// rows_per_mat rows each (device pointer tables), plus they are laid out back to
+// back in mod with the given offsets.
+int32_t launch_adaln(const float* sc, int32_t B, int32_t D, const void* const* w_tab,
+                     const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
+                     int32_t total_rows, int32_t dtype, float* mod, hipStream_t s);
+int32_t launch_patch_embed(const float* x, int32_t x_mod, int32_t B, int32_t C, int32_t H, int32_t W,
+                           int32_t p, int32_t D, const float* pw, const float* pb, const float* pos,
+                           float* out, hipStream_t s);
+int32_t launch_ln_modulate(const float* x, RowVec shift, RowVec scale, int32_t M, int32_t D,
+                           int32_t dtype, void* out, hipStream_t s);
+int32_t launch_linear_simple(const void* A, const void* W, const float* bias, int32_t M, int32_t N,
+                             int32_t K, int32_t dtype, int32_t epi, void* out, float* resid,
+                             RowVec gate, hipStream_t s);
+int32_t launch_attention_simple(const void* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh,
+                                int32_t dtype, void* out, hipStream_t s);
+int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B, int32_t gh, int32_t gw,
+                           int32_t p, int32_t c_out, int32_t D, const void* w, const float* bias,
+                           int32_t dtype, float* out, hipStream_t s);
+int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const float* coef_x,
+                           const float* coef_eps, float cfg_scale, int32_t K, int32_t C, int32_t c_out,
+                           int64_t hw, float* m_out, hipStream_t s);
+int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_t K, int32_t dup,
+                         int32_t* t_out, int32_t* y_out, hipStream_t s);
+
+// ---- MFMA kernels, bf16 only (gemm_mfma.hip, attn_mfma.hip) ------------------------
+bool mfma_linear_supported(int32_t M, int32_t N, int32_t K);
+int32_t launch_linear_mfma(const bf16_t* A, const bf16_t* W, const float* bias, int32_t M, int32_t N,
+                           int32_t K, int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s);
+bool mfma_attention_supported(int32_t N, int32_t dh);
+int32_t launch_attention_mfma(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh,
+                              bf16_t* out, hipStream_t s);
+
+}  // namespace freemi

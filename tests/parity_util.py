@@ -1,0 +1,137 @@
+"""Helpers shared by the GPU parity tests and the smoke check: run the HIP path
+through the C-ABI binding and the oracle on the same seeded inputs and compare."""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+from oracle import free_oracle as fo
+from paper_2511_20390_amd import synth
+
+# tolerances fixed by the benchmark spec
+DIT_REL_L2 = {"fp32": 1e-4, "bf16": 2e-2}
+TIE_WINDOW = 1e-4
+REFLECT_REL = 1e-5
+
+
+def rel_l2(a, b) -> float:
+    a = np.asarray(a, np.float64).ravel()
+    b = np.asarray(b, np.float64).ravel()
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def to_dev(a, dtype=None):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to("cuda:0")
+
+
+def weights_for(cfg, mode, seed=0, **kw):
+    return synth.make_weights(cfg, seed=seed, bf16_values=(mode == "bf16"), **kw)
+
+
+def compare_verify(gpu: dict, ref: dict, lam, u, label="") -> dict:
+    """Bit-exact decisions except flagged ties; log-ratio and reflected samples close."""
+    acc_g = gpu["accept"].cpu().numpy().reshape(ref["accept"].shape)
+    nacc_g = gpu["n_accept"].cpu().numpy().reshape(ref["n_accept"].shape)
+    lr_g = gpu["log_ratio"].cpu().numpy().reshape(ref["log_ratio"].shape).astype(np.float64)
+    x_g = gpu["x_out"].cpu().numpy().reshape(ref["x_out"].shape).astype(np.float64)
+    tie = ref["tie"]
+    mism = (acc_g != ref["accept"]) & ~tie
+    assert not mism.any(), f"{label}: {int(mism.sum())} decision mismatches outside the tie window"
+    # log-ratio: fp32 output of an fp64 sum
+    np.testing.assert_allclose(lr_g, ref["log_ratio"], rtol=2e-6, atol=2e-6, err_msg=label)
+    clean = ~tie.any(axis=1)
+    np.testing.assert_array_equal(nacc_g[clean], ref["n_accept"][clean], err_msg=label)
+    K = ref["accept"].shape[1]
+    n_reflect = 0
+    for n in np.nonzero(clean & (ref["n_accept"] < K))[0]:
+        err = np.linalg.norm(x_g[n] - ref["x_out"][n]) / np.linalg.norm(ref["x_out"][n])
+        assert err < REFLECT_REL, f"{label}: reflected sample of trajectory {n} off by {err:.2e}"
+        n_reflect += 1
+    return dict(ties=int(tie.sum()), reflected=n_reflect, accepted=int(acc_g.sum()))
+
+
+def run_verify_parity(n_traj, K, d, delta, seed, relaxed=False, label=""):
+    from paper_2511_20390_amd import binding
+    sched = fo.ddpm_schedule()
+    vi = synth.make_verify_inputs(n_traj, K, d, delta, seed, sched["sigma_clipped"])
+    lam = vi["lam"] if relaxed else None
+    ref = fo.spec_verify(vi["m_target"], vi["m_draft"], vi["x_draft"], vi["sigma"], vi["u"], lam)
+    import torch
+    sentinel = torch.full((n_traj, d), 7.25, dtype=torch.float32, device="cuda:0")
+    out = dict(log_ratio=torch.empty(n_traj, K, dtype=torch.float32, device="cuda:0"),
+               accept=torch.empty(n_traj, K, dtype=torch.uint8, device="cuda:0"),
+               n_accept=torch.empty(n_traj, dtype=torch.int32, device="cuda:0"), x_out=sentinel)
+    gpu = binding.spec_verify(to_dev(vi["m_target"]), to_dev(vi["m_draft"]), to_dev(vi["x_draft"]),
+                              to_dev(vi["sigma"]), to_dev(vi["u"]), None if lam is None else to_dev(lam), out=out)
+    torch.cuda.synchronize()
+    stats = compare_verify(gpu, ref, lam, vi["u"], label or f"verify n={n_traj} K={K} d={d} delta={delta}")
+    # rows without a rejection must be left untouched
+    x_g = gpu["x_out"].cpu().numpy()
+    nacc = gpu["n_accept"].cpu().numpy()
+    assert np.all(x_g[nacc == K] == 7.25)
+    stats["ref"] = ref
+    stats["inputs"] = vi
+    return stats
+
+
+def round_case(name, mode, K, cfg_scale, seed, calibrated=True):
+    """Inputs of one round.  With `calibrated`, the draft means are placed around the
+    ORACLE's target means at the distance that gives a 50% acceptance rate, so the
+    round has mixed outcomes; the drafts are samples of those proposals."""
+    cfg = synth.dit_config(name)
+    w = weights_for(cfg, mode, seed)
+    sched = fo.ddpm_schedule()
+    ri = synth.make_round_inputs(cfg, K, seed, sched["sigma_clipped"], 0.05 if name == "tiny" else 0.1)
+    cx, ce = fo.mean_coefficients(ri["t"], sched)
+    ri["coef_x"], ri["coef_eps"] = cx.astype(np.float32), ce.astype(np.float32)
+    return cfg, w, sched, ri
+
+
+def run_round_parity(name, mode="fp32", K=6, cfg_scale=4.0, seed=0, verbose=False, samples=None):
+    """spec_round on the GPU vs the oracle: (i) target means within the DiT tolerance,
+    (ii) the GPU decisions equal the oracle's verification applied to the GPU means
+    (composition), (iii) information only: agreement with the all-oracle round."""
+    import torch
+    from paper_2511_20390_amd import binding
+    cfg, w, sched, ri = round_case(name, mode, K, cfg_scale, seed)
+    d = synth.latent_dim(cfg)
+    x_states = ri["x_states"].astype(np.float64)
+    # oracle means for the states as given
+    cx64, ce64 = ri["coef_x"].astype(np.float64), ri["coef_eps"].astype(np.float64)
+    m_ref = fo.round_means(w, cfg, x_states, ri["t"], ri["y"], cfg_scale, cx64, ce64).reshape(K, d)
+    # calibrated draft means around the oracle means (mixed accept / reject)
+    rng = np.random.default_rng(seed + 1234)
+    sig = ri["sigma"].astype(np.float64)
+    m_draft = (m_ref + (1.349 / math.sqrt(d)) * sig[:, None] * rng.standard_normal((K, d))).astype(np.float32)
+    model = binding.FreeDit(cfg, w, mode)
+    lam = None
+    out = model.spec_round(to_dev(ri["x_states"]), to_dev(ri["x_last"]), to_dev(m_draft), to_dev(ri["t"]),
+                           ri["y"], cfg_scale, to_dev(ri["coef_x"]), to_dev(ri["coef_eps"]), to_dev(ri["sigma"]),
+                           to_dev(ri["u"]), lam)
+    torch.cuda.synchronize()
+    m_gpu = out["m_target"].cpu().numpy().astype(np.float64)
+    # (i) means: the eps error is what the tolerance speaks of; means inherit it scaled
+    eps_ref = (m_ref - cx64[:, None] * x_states.reshape(K, d)) / ce64[:, None]
+    eps_gpu = (m_gpu - cx64[:, None] * x_states.reshape(K, d)) / ce64[:, None]
+    err_eps = rel_l2(eps_gpu, eps_ref)
+    err_m = rel_l2(m_gpu, m_ref)
+    # (ii) composition: oracle verification on the GPU-produced means
+    xd = np.concatenate([ri["x_states"][1:], ri["x_last"][None]], 0).reshape(K, d)
+    ref = fo.spec_verify(m_gpu[None], m_draft[None], xd[None], ri["sigma"][None], ri["u"][None], lam)
+    stats = compare_verify(dict(accept=out["accept"], n_accept=out["n_accept"], log_ratio=out["log_ratio"],
+                                x_out=out["x_out"]), ref, lam, ri["u"], f"round {name}/{mode}")
+    full = fo.spec_verify(m_ref[None], m_draft[None], xd[None], ri["sigma"][None], ri["u"][None], lam)
+    stats.update(err_eps=err_eps, err_m=err_m,
+                 agree_full=int((full["accept"] == out["accept"].cpu().numpy().reshape(1, K)).sum()))
+    if verbose:
+        print(f"round {name}/{mode}: eps rel-L2 {err_eps:.3e}, mean rel-L2 {err_m:.3e}, "
+              f"n_accept gpu {int(out['n_accept'].item())} (oracle-on-gpu-means {int(ref['n_accept'][0])}, "
+              f"all-oracle {int(full['n_accept'][0])}), ties {stats['ties']}")
+    assert err_eps <= DIT_REL_L2[mode], f"eps rel-L2 {err_eps:.3e} > {DIT_REL_L2[mode]}"
+    model.close()
+    return stats

@@ -1,0 +1,127 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the public
+header declares, its host-side schedule helper agrees with the oracle, and argument
+errors are reported as status codes before any GPU call is made."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import free_oracle as fo
+from paper_2511_20390_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "free_mi355x.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_][a-z0-9_]*)\s*\(", text)) - {"defined"})
+
+
+def test_header_symbols_are_exported_and_bound(lib):
+    names = _declared_functions()
+    assert {"dit_forward_packed", "spec_verify", "spec_round"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+    assert sorted(binding.EXPORTED_SYMBOLS) == names
+
+
+def test_version_and_status_strings(lib):
+    assert b"gfx950" in lib.free_version()
+    seen = {lib.free_status_string(s) for s in range(0, -7, -1)}
+    assert len(seen) == 7 and lib.free_status_string(-99) == b"unknown status"
+
+
+def test_schedule_helper_matches_oracle(lib):
+    cx, ce, sg = binding.free_ddpm_schedule()
+    s = fo.ddpm_schedule()
+    ocx, oce = fo.mean_coefficients(np.arange(1000), s)
+    np.testing.assert_allclose(cx, ocx, rtol=1e-13)
+    np.testing.assert_allclose(ce, oce, rtol=1e-12)
+    np.testing.assert_allclose(sg, s["sigma_clipped"], rtol=1e-12)
+    assert lib.free_ddpm_schedule(1, 1e-4, 0.02, None, None, None) == binding.FREE_ERR_SHAPE
+    assert lib.free_ddpm_schedule(10, 0.0, 0.02, None, None, None) == binding.FREE_ERR_RANGE
+    assert lib.free_ddpm_schedule(10, 1e-4, 0.02, None, None, None) == binding.FREE_OK
+
+
+def test_weight_count_and_workspace(lib):
+    for name in ("tiny", "small", "xl2_512"):
+        cfg = synth.dit_config(name)
+        cc = binding.make_config(cfg, "bf16")
+        assert lib.free_weight_count(C.byref(cc)) == len(synth.weight_spec(cfg)) == 7 + 10 * cfg["depth"] + 4
+        b6, b12 = lib.free_workspace_bytes(C.byref(cc), 6), lib.free_workspace_bytes(C.byref(cc), 12)
+        assert 0 < b6 < b12 and b6 % 256 == 0
+        cc32 = binding.make_config(cfg, "fp32")
+        assert lib.free_workspace_bytes(C.byref(cc32), 6) > b6
+    bad = binding.make_config(dict(synth.dit_config("tiny"), hidden=60), "fp32")     # 60 % 8 != 0
+    assert lib.free_weight_count(C.byref(bad)) == binding.FREE_ERR_SHAPE
+    assert lib.free_workspace_bytes(C.byref(bad), 6) == 0
+    bad = binding.make_config(dict(synth.dit_config("tiny"), lat_h=7), "fp32")
+    assert lib.free_workspace_bytes(C.byref(bad), 6) == 0
+    assert lib.free_workspace_bytes(C.byref(cc), 0) == 0
+
+
+def test_argument_errors_are_status_codes(lib):
+    one = C.c_void_p(256)            # never dereferenced: the checks fail first
+    # spec_verify: null pointer, bad shape
+    assert lib.spec_verify(None, one, one, one, one, None, 1, 6, 64, one, one, one, one, one, 4096, None) == binding.FREE_ERR_NULL
+    assert lib.spec_verify(one, one, one, one, one, None, 1, 0, 64, one, one, one, one, one, 4096, None) == binding.FREE_ERR_SHAPE
+    assert lib.spec_verify(one, one, one, one, one, None, 1, 257, 64, one, one, one, one, one, 4096, None) == binding.FREE_ERR_SHAPE
+    assert lib.spec_verify(one, one, one, one, one, None, 1, 6, 0, one, one, one, one, one, 4096, None) == binding.FREE_ERR_SHAPE
+    assert lib.spec_verify(one, one, one, one, one, None, 0, 6, 64, one, one, one, one, one, 4096, None) == binding.FREE_OK
+    # missing / too small workspace
+    assert lib.spec_verify(one, one, one, one, one, None, 1, 6, 64, one, one, one, one, None, 0, None) == binding.FREE_ERR_WORKSPACE
+    assert lib.spec_verify(one, one, one, one, one, None, 4, 6, 4096, one, one, one, one, one, 8, None) == binding.FREE_ERR_WORKSPACE
+    assert lib.spec_verify_workspace_bytes(64, 6, 16384) >= 64 * 6 * 16
+    assert lib.spec_verify_workspace_bytes(64, 300, 16384) == 0
+    # model handle
+    cc = binding.make_config(synth.dit_config("tiny"), "fp32")
+    h = C.c_void_p()
+    assert lib.free_dit_create(C.byref(cc), None, 31, C.byref(h)) == binding.FREE_ERR_NULL
+    arr = (C.c_void_p * 31)(*([256] * 31))
+    assert lib.free_dit_create(C.byref(cc), arr, 30, C.byref(h)) == binding.FREE_ERR_SHAPE
+    arr[3] = None
+    assert lib.free_dit_create(C.byref(cc), arr, 31, C.byref(h)) == binding.FREE_ERR_NULL
+    arr[3] = 260                     # misaligned
+    assert lib.free_dit_create(C.byref(cc), arr, 31, C.byref(h)) == binding.FREE_ERR_SHAPE
+    cc.mode = 5
+    assert lib.free_dit_create(C.byref(cc), arr, 31, C.byref(h)) == binding.FREE_ERR_DTYPE
+    assert lib.free_dit_destroy(None) == binding.FREE_ERR_NULL
+    assert lib.dit_forward_packed(None, one, one, one, 6, one, None, one, 1 << 20, None) == binding.FREE_ERR_NULL
+    assert lib.spec_round(None, one, one, one, one, 0, 4.0, one, one, one, one, None, 6, None, one, one, one, one,
+                          one, 1 << 20, None) == binding.FREE_ERR_NULL
+    # single operators
+    assert lib.free_op_linear(one, one, one, 4, 4, 8, 7, 0, one, None, None, 0, 1, None) == binding.FREE_ERR_DTYPE
+    assert lib.free_op_linear(one, one, one, 4, 4, 8, 0, 9, one, None, None, 0, 1, None) == binding.FREE_ERR_RANGE
+    assert lib.free_op_linear(one, one, one, 4, 4, 8, 0, 2, one, None, None, 0, 1, None) == binding.FREE_ERR_NULL
+    assert lib.free_op_attention(one, 1, 16, 2, 200, 0, one, None) == binding.FREE_ERR_SHAPE
+    assert lib.free_op_ln_modulate(one, one, None, 8, 4, 8, 1, 0, one, None) == binding.FREE_ERR_NULL
+
+
+def test_synth_is_deterministic_and_bf16_rounding_is_exact():
+    cfg = synth.dit_config("tiny")
+    a, b = synth.make_weights(cfg, 3), synth.make_weights(cfg, 3)
+    assert all(np.array_equal(a[k], b[k]) for k in a)
+    w = synth.make_weights(cfg, 3, bf16_values=True)
+    import torch
+    for k, v in w.items():
+        assert np.array_equal(torch.from_numpy(v).to(torch.bfloat16).float().numpy(), v)
+    # round-to-nearest-even against torch's conversion
+    x = np.random.default_rng(0).standard_normal(10000).astype(np.float32) * 3
+    assert np.array_equal(synth.bf16_round(x), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
+    s = fo.ddpm_schedule()
+    r1 = synth.make_round_inputs(cfg, 6, 5, s["sigma_clipped"])
+    assert list(r1["t"]) == list(range(r1["t"][0], r1["t"][0] - 6, -1)) and r1["t"][-1] >= 0
+    v = synth.make_verify_inputs(3, 6, 64, 0.1, 1, s["sigma_clipped"])
+    assert v["m_target"].shape == (3, 6, 64) and (v["sigma"] > 0).all() and ((v["lam"] > 0) & (v["lam"] <= 1)).all()

@@ -1,0 +1,86 @@
+"""GPU parity of spec_verify against the oracle (through the C ABI)."""
+import math
+
+import numpy as np
+import pytest
+from scipy.special import ndtr
+
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("relaxed", [False, True])
+@pytest.mark.parametrize("delta", [0.01, 0.1, 0.5, 1.0])
+def test_verify_parity_medium(delta, relaxed):
+    # several chunks per pair and a ragged tail (d = 3*1024 + 4*37)
+    st = pu.run_verify_parity(n_traj=16, K=6, d=3220, delta=delta * 2.0, seed=int(delta * 100), relaxed=relaxed)
+    print(st["ties"], st["reflected"], st["accepted"])
+
+
+@pytest.mark.parametrize("n_traj,K,d", [(1, 1, 1), (3, 2, 5), (2, 6, 1023), (5, 3, 4096), (2, 7, 4099), (1, 256, 8)])
+def test_verify_parity_edge_shapes(n_traj, K, d):
+    # odd d exercises the scalar (unaligned) path; mixed outcomes via a small delta
+    pu.run_verify_parity(n_traj, K, d, delta=1.349 / math.sqrt(d), seed=d, relaxed=(d % 2 == 0))
+
+
+def test_verify_mixed_prefix_lengths():
+    st = pu.run_verify_parity(n_traj=64, K=6, d=2048, delta=0.6 / math.sqrt(2048), seed=9)
+    nacc = st["ref"]["n_accept"]
+    assert len(set(nacc.tolist())) >= 4            # several different first-rejection positions
+
+
+def test_verify_degenerate_inputs():
+    import torch
+    from paper_2511_20390_amd import binding
+    from oracle import free_oracle as fo
+    rng = np.random.default_rng(0)
+    n, K, d = 4, 3, 520
+    m = rng.standard_normal((n, K, d)).astype(np.float32)
+    mh = m.copy()                                   # equal means: always accepted, whatever u
+    mh[1, 1] += 0.5                                 # one clear rejection
+    mh[2, 0] += 1e-3
+    x = (mh + 0.1 * rng.standard_normal((n, K, d))).astype(np.float32)
+    sigma = np.full((n, K), 0.1, np.float32)
+    u = np.ones((n, K), np.float32)
+    u[2, 0] = 0.0                                   # u = 0 always accepts
+    ref = fo.spec_verify(m, mh, x, sigma, u)
+    gpu = binding.spec_verify(*(pu.to_dev(a) for a in (m, mh, x, sigma, u)))
+    torch.cuda.synchronize()
+    pu.compare_verify(gpu, ref, None, u, "degenerate")
+    assert gpu["n_accept"].cpu().tolist() == [3, 1, 3, 3]
+
+
+def test_verify_is_deterministic_run_to_run():
+    import torch
+    from paper_2511_20390_amd import binding, synth
+    from oracle import free_oracle as fo
+    vi = synth.make_verify_inputs(8, 6, 16384, 0.01, 3, fo.ddpm_schedule()["sigma_clipped"])
+    args = [pu.to_dev(vi[k]) for k in ("m_target", "m_draft", "x_draft", "sigma", "u")]
+    a = binding.spec_verify(*args)
+    b = binding.spec_verify(*args)
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k])
+
+
+@pytest.mark.parametrize("delta", [0.01, 0.1, 0.5, 1.0])
+def test_verify_full_size_config(delta):
+    """64 trajectories x 6 drafts x 4x64x64 latent: full comparison with the oracle
+    plus the closed-form acceptance rate of App. D at the realised distances."""
+    st = pu.run_verify_parity(n_traj=64, K=6, d=16384, delta=delta, seed=40 + int(delta * 100), relaxed=False)
+    vi, ref = st["inputs"], st["ref"]
+    dist = np.linalg.norm(vi["m_draft"].astype(np.float64) - vi["m_target"], axis=-1) / vi["sigma"]
+    expect = 2 * ndtr(-dist / 2)
+    n = expect.size
+    rate = st["accepted"] / n
+    se = math.sqrt(max(float((expect * (1 - expect)).mean()), 1e-12) / n)
+    assert abs(rate - expect.mean()) < 4.5 * se + 1e-9
+    if delta == 0.01:
+        assert 0.35 < rate < 0.7                   # closed form at ||dm|| = delta sigma sqrt(d): 0.522
+    else:
+        assert st["accepted"] == 0
+
+
+def test_verify_full_size_relaxed():
+    pu.run_verify_parity(n_traj=64, K=6, d=16384, delta=0.01, seed=77, relaxed=True)
