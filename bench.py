@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the parallel verification pass on one MI355X.
+
+A step is one whole verification round (spec_round): packed DiT-XL/2 forward on
+K=6 states (x2 with classifier-free guidance 4.0 -> 12 states, 12288 tokens) at
+the 512^2 latent shape, guidance + eps->mean, and the sequential verification of
+the six drafts.  Inputs and random-init weights are synthetic and resident in
+HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py --gpus 1 --steps 20 --warmup 3
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def forward_flops(cfg, B):
+    """Algorithmic FLOPs of one packed forward: 2MNK for the linear layers, 4 N D per token per
+    block for attention, plus the adaLN modulation GEMV."""
+    from paper_2511_20390_amd import synth
+    N, D, F, L = synth.n_tokens(cfg), cfg["hidden"], cfg["mlp_hidden"], cfg["depth"]
+    M = B * N
+    per = {"gemm_qkv": 2.0 * M * D * 3 * D, "gemm_proj": 2.0 * M * D * D, "gemm_fc1": 2.0 * M * D * F,
+           "gemm_fc2": 2.0 * M * D * F, "attention": 4.0 * M * N * D}
+    total = L * sum(per.values()) + 2.0 * B * D * (L * 6 * D + 2 * D)
+    return per, total
+
+
+def bench_round(args):
+    import torch
+    from paper_2511_20390_amd import binding, synth
+    cfg = synth.dit_config(args.config)
+    K, scale, mode = args.K, args.cfg_scale, args.mode
+    B = K * (2 if scale > 1 else 1)
+    t0 = time.time()
+    w = synth.make_weights(cfg, seed=0, bf16_values=(mode == "bf16"))
+    model = binding.FreeDit(cfg, w, mode)
+    cx, ce, sg = binding.free_ddpm_schedule()
+    ri = synth.make_round_inputs(cfg, K, seed=0, sigma_table=sg, draft_noise=0.1)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    a = dict(x_states=dev(ri["x_states"]), x_last=dev(ri["x_last"]), m_draft=dev(ri["m_draft"]), t=dev(ri["t"]),
+             coef_x=dev(cx[ri["t"]].astype(np.float32)), coef_eps=dev(ce[ri["t"]].astype(np.float32)),
+             sigma=dev(ri["sigma"]), u=dev(ri["u"]), lam=dev(ri["lam"]))
+    out = model.spec_round(a["x_states"], a["x_last"], a["m_draft"], a["t"], ri["y"], scale, a["coef_x"],
+                           a["coef_eps"], a["sigma"], a["u"], a["lam"] if args.relaxed else None)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step():
+        model.spec_round(a["x_states"], a["x_last"], a["m_draft"], a["t"], ri["y"], scale, a["coef_x"],
+                         a["coef_eps"], a["sigma"], a["u"], a["lam"] if args.relaxed else None, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations: the same steps again, every launch bracketed by HIP events on its stream
+    binding.profile_begin()
+    for _ in range(args.steps):
+        step()
+    prof = binding.profile_end()
+    per, total_flops = forward_flops(cfg, B)
+    kernels = {}
+    for name, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        ent = {"ms_per_step": ms / args.steps, "launches_per_step": n // args.steps, "avg_us": ms * 1e3 / n}
+        if name in per:
+            ent["tflops"] = per[name] / (ms / n * 1e-3) / 1e12
+        kernels[name] = ent
+    dom = max((k for k in kernels if k in per), key=lambda k: kernels[k]["ms_per_step"])
+    peak = PEAK_BF16_TFLOPS if mode == "bf16" else PEAK_FP32_TFLOPS
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": peak,
+                "unit": "TFLOP/s", "frac": kernels[dom]["tflops"] / peak, "traffic": None,
+                "avg_launch_us": kernels[dom]["avg_us"],
+                "measured": "HIP events around every launch of this kernel, same steps repeated right after the timed region"}
+    fwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if not k.startswith("verify") and k != "eps_to_mean")
+    res = {
+        "ms_per_step": ms_per_step, "kernels": kernels, "roofline": roofline,
+        "forward": {"algorithmic_tflop": total_flops / 1e12, "ms_sum_of_kernels": fwd_ms,
+                    "tflops_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12,
+                    "frac_of_peak_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12 / peak},
+        "tokens_per_round": B * synth.n_tokens(cfg), "setup_s": setup_s,
+        "n_accept": int(out["n_accept"].item()), "B": B,
+    }
+    model.close()
+    return res, cfg, w, ri, (cx, ce, sg)
+
+
+def bench_verify(args, n_sets=6):
+    """spec_verify alone at 64 x 6 x 16384 fp32, rotating over n_sets distinct input sets
+    (> 256 MB in total) so that the Infinity Cache cannot stand in for HBM."""
+    import torch
+    from paper_2511_20390_amd import binding, synth
+    n_traj, K, d = 64, 6, 16384
+    _, _, sg = binding.free_ddpm_schedule()
+    sets = []
+    for i in range(n_sets):
+        vi = synth.make_verify_inputs(n_traj, K, d, 0.01, 100 + i, sg)
+        sets.append([torch.from_numpy(vi[k]).to("cuda:0") for k in ("m_target", "m_draft", "x_draft", "sigma", "u")])
+    out = binding.spec_verify(*sets[0])
+    ws = torch.empty(binding.spec_verify_workspace_bytes(n_traj, K, d), dtype=torch.uint8, device="cuda:0")
+    reps = 5
+    for i in range(n_sets):
+        binding.spec_verify(*sets[i], out=out, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for r in range(reps):
+        for i in range(n_sets):
+            binding.spec_verify(*sets[i], out=out, workspace=ws)
+    torch.cuda.synchronize()
+    call_us = (time.perf_counter() - t0) * 1e6 / (reps * n_sets)
+    binding.profile_begin()
+    for r in range(reps):
+        for i in range(n_sets):
+            binding.spec_verify(*sets[i], out=out, workspace=ws)
+    prof = binding.profile_end()
+    binding.profile_begin()
+    for r in range(reps * n_sets):
+        binding.spec_verify(*sets[0], out=out, workspace=ws)
+    warm = binding.profile_end()
+    ms, n = prof["verify_partial"]
+    bytes_partial = n_traj * K * 3 * d * 4
+    gbs = bytes_partial / (ms / n * 1e-3) / 1e9
+    wms, wn = warm["verify_partial"]
+    nrej = int((out["n_accept"] < K).sum().item())
+    return {"kernel": "verify_partial_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": gbs / PEAK_HBM_GBS, "traffic": None, "avg_launch_us": ms * 1e3 / n,
+            "warm_cache_GBs": bytes_partial / (wms / wn * 1e-3) / 1e9,
+            "finish_avg_us": prof["verify_finish"][0] * 1e3 / prof["verify_finish"][1],
+            "call_us_back_to_back": call_us, "rounds_per_s_64traj": 64e6 / call_us,
+            "algorithmic_bytes": bytes_partial, "reflected_rows": nrej,
+            "workload": "64 traj x 6 drafts x 16384 fp32, 6 rotating input sets (453 MB)"}
+
+
+def cpu_baseline(cfg, w, ri, sched, args):
+    """The oracle on the host cores: one of the K packed states (with its null-label twin under
+    guidance: 2 of the 12 forwards) plus the verification of one draft, scaled to a round."""
+    from oracle import free_oracle as fo
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    cx, ce, sg = sched
+    t = ri["t"][:1]
+    t0 = time.perf_counter()
+    fo.spec_round(w, cfg, ri["x_states"][:1], ri["x_states"][1], ri["m_draft"][:1], t, ri["y"], args.cfg_scale,
+                  cx[t], ce[t], ri["sigma"][:1], ri["u"][:1], None)
+    dt = time.perf_counter() - t0
+    per_round = dt * args.K
+    return {"value": 1.0 / per_round, "unit": "rounds/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 of {args.K} packed states (2 of {2 * args.K} DiT forwards + 1 draft verified) in "
+                      f"{dt:.1f} s, scaled x{args.K}", "seconds_per_round_scaled": per_round}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="xl2_512")
+    ap.add_argument("--mode", default="bf16", choices=["bf16", "fp32"])
+    ap.add_argument("--K", type=int, default=6)
+    ap.add_argument("--cfg-scale", type=float, default=4.0)
+    ap.add_argument("--relaxed", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-verify-bench", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the packed states of a round share one device); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2511_20390_amd import binding
+    binding.load()          # fails loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+
+    res, cfg, w, ri, sched = bench_round(args)
+    rounds_per_s = 1e3 / res["ms_per_step"]
+    line = {
+        "metric": "packed DiT-XL/2 verify rounds/s at 512^2 (K=6)", "value": rounds_per_s, "unit": "rounds/s",
+        "tokens_per_s": rounds_per_s * res["tokens_per_round"],
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.mode, "data": "synthetic",
+        "config": {"workload": f"spec_round: DiT-XL/2 {args.config} latent, K={args.K} drafts, "
+                               f"guidance {args.cfg_scale} (packed batch {res['B']}, {res['tokens_per_round']} tokens), "
+                               f"{'relaxed' if args.relaxed else 'strict'} rule",
+                   "packed_batch": res["B"], "tokens": res["tokens_per_round"]},
+        "roofline": res["roofline"], "forward": res["forward"], "kernels": res["kernels"],
+    }
+    if not args.no_verify_bench:
+        line["roofline_verify"] = bench_verify(args)
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, w, ri, sched, args)
+        line["cpu_baseline"]["gpu_over_cpu"] = rounds_per_s / line["cpu_baseline"]["value"]
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -167,6 +167,21 @@ int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, con
                    int32_t* n_accept, float* x_out,
                    void* workspace, size_t ws_bytes, void* stream);
 
+/* ---- per-kernel timing for benchmarks -------------------------------------
+ * Between free_profile_begin and free_profile_end every kernel launch of the
+ * hot-path calls is bracketed by two HIP events recorded on the launch stream.
+ * free_profile_end waits for the last event and returns, per category, the
+ * summed elapsed milliseconds and the number of bracketed launches ([host]
+ * arrays of FREE_PROF_NCAT entries).  Process-global and not thread-safe;
+ * the events are created on first use and reused.  Categories, in order:
+ * conditioning, adaln, patch_embed, ln_modulate, gemm_qkv, attention,
+ * gemm_proj, gemm_fc1, gemm_fc2, final_layer, eps_to_mean, verify_partial,
+ * verify_finish. */
+#define FREE_PROF_NCAT 13
+int32_t free_profile_begin(void);
+int32_t free_profile_end(float* ms, int32_t* launches);
+const char* free_profile_category_name(int32_t category);
+
 /* ---- single DiT operators, exported for per-kernel parity tests -----------
  * (the pieces of the adaLN-Zero block that dit_forward_packed chains).
  * dtype = FREE_FP32 (A, W, out fp32) or FREE_BF16 (A, W, out bf16). */

@@ -25,7 +25,9 @@ EXPORTED_SYMBOLS = [
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
     "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
+    "free_profile_begin", "free_profile_end", "free_profile_category_name",
 ]
+PROF_NCAT = 13
 
 
 class FreeError(RuntimeError):
@@ -82,6 +84,11 @@ def load():
     lib.free_op_attention.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
     lib.free_op_ln_modulate.restype = i32
     lib.free_op_ln_modulate.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.free_profile_begin.restype = i32
+    lib.free_profile_end.restype = i32
+    lib.free_profile_end.argtypes = [vp, vp]
+    lib.free_profile_category_name.restype = C.c_char_p
+    lib.free_profile_category_name.argtypes = [i32]
     _lib = lib
     return lib
 
@@ -112,6 +119,18 @@ def free_ddpm_schedule(T: int = 1000, beta_start: float = 1e-4, beta_end: float 
     _check(load().free_ddpm_schedule(T, beta_start, beta_end, cx.ctypes.data, ce.ctypes.data, sg.ctypes.data),
            "free_ddpm_schedule")
     return cx, ce, sg
+
+
+def profile_begin():
+    _check(load().free_profile_begin(), "free_profile_begin")
+
+
+def profile_end() -> dict:
+    """{category: (total_ms, launches)} for the launches since profile_begin."""
+    ms = np.zeros(PROF_NCAT, np.float32)
+    cnt = np.zeros(PROF_NCAT, np.int32)
+    _check(load().free_profile_end(ms.ctypes.data, cnt.ctypes.data), "free_profile_end")
+    return {load().free_profile_category_name(c).decode(): (float(ms[c]), int(cnt[c])) for c in range(PROF_NCAT)}
 
 
 def spec_verify_workspace_bytes(n_traj: int, K: int, d: int) -> int:

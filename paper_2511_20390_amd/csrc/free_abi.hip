@@ -16,6 +16,37 @@ namespace freemi {
 static thread_local int32_t g_last_hip_error = 0;
 void note_hip_error(hipError_t e) { g_last_hip_error = static_cast<int32_t>(e); }
 
+// ---- per-kernel timing ------------------------------------------------------------
+namespace {
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev;      // pairs: 2*slot = start, 2*slot+1 = stop
+    std::vector<int> cat;            // category of each used slot
+    size_t used = 0;
+};
+Profiler g_prof;
+constexpr size_t kMaxProfSlots = 8192;
+}  // namespace
+
+ProfScope::ProfScope(int c, hipStream_t s) : slot(-1), stream(s) {
+    if (!g_prof.on || g_prof.used >= kMaxProfSlots) return;
+    const size_t k = g_prof.used;
+    while (g_prof.ev.size() < 2 * (k + 1)) {
+        hipEvent_t e;
+        if (!hip_ok(hipEventCreate(&e))) return;
+        g_prof.ev.push_back(e);
+    }
+    if (!hip_ok(hipEventRecord(g_prof.ev[2 * k], s))) return;
+    if (g_prof.cat.size() <= k) g_prof.cat.resize(k + 1);
+    g_prof.cat[k] = c;
+    g_prof.used = k + 1;
+    slot = static_cast<int>(k);
+}
+
+ProfScope::~ProfScope() {
+    if (slot >= 0) (void)hip_ok(hipEventRecord(g_prof.ev[2 * slot + 1], stream));
+}
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -141,14 +172,23 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     void* att = ws + L.att;
     void* hmid = ws + L.hmid;
 
+    {
+    ProfScope prof(PROF_COND, s);
     FREE_TRY(launch_conditioning(t, y, B, d.D, d.tfreq, static_cast<const float*>(h->w[W_T_W1]),
                                  static_cast<const float*>(h->w[W_T_B1]), static_cast<const float*>(h->w[W_T_W2]),
                                  static_cast<const float*>(h->w[W_T_B2]),
                                  static_cast<const float*>(h->w[W_Y_TABLE]), cond_h, sc, s));
+    }
+    {
+    ProfScope prof(PROF_ADALN, s);
     FREE_TRY(launch_adaln(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1, d.mod_rows,
                           d.mode, mod, s));
+    }
+    {
+    ProfScope prof(PROF_PATCH, s);
     FREE_TRY(launch_patch_embed(x, x_mod, B, d.C, d.H, d.W, d.p, d.D, static_cast<const float*>(h->w[W_PATCH_W]),
                                 static_cast<const float*>(h->w[W_PATCH_B]), h->pos, xres, s));
+    }
     auto vec = [&](int l, int which) {
         RowVec r;
         r.base = mod + static_cast<int64_t>(l) * 6 * d.D + static_cast<int64_t>(which) * d.D;
@@ -158,18 +198,39 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     };
     for (int l = 0; l < d.depth; ++l) {
         // x += gate1 * Proj(Attn(LN(x)(1+scale1)+shift1))
-        FREE_TRY(launch_ln_modulate(xres, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn, s));
-        FREE_TRY(linear_dispatch(d, xn, h->blk(l, B_QKV_W), static_cast<const float*>(h->blk(l, B_QKV_B)), M,
-                                 3 * d.D, d.D, FREE_EPI_BIAS, qkv, nullptr, RowVec{nullptr, 0, 1}, s));
-        FREE_TRY(attention_dispatch(d, qkv, B, att, s));
-        FREE_TRY(linear_dispatch(d, att, h->blk(l, B_PROJ_W), static_cast<const float*>(h->blk(l, B_PROJ_B)), M,
-                                 d.D, d.D, FREE_EPI_GATE_RESID, nullptr, xres, vec(l, 2), s));
+        {
+            ProfScope prof(PROF_LN_MOD, s);
+            FREE_TRY(launch_ln_modulate(xres, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn, s));
+        }
+        {
+            ProfScope prof(PROF_GEMM_QKV, s);
+            FREE_TRY(linear_dispatch(d, xn, h->blk(l, B_QKV_W), static_cast<const float*>(h->blk(l, B_QKV_B)), M,
+                                     3 * d.D, d.D, FREE_EPI_BIAS, qkv, nullptr, RowVec{nullptr, 0, 1}, s));
+        }
+        {
+            ProfScope prof(PROF_ATTN, s);
+            FREE_TRY(attention_dispatch(d, qkv, B, att, s));
+        }
+        {
+            ProfScope prof(PROF_GEMM_PROJ, s);
+            FREE_TRY(linear_dispatch(d, att, h->blk(l, B_PROJ_W), static_cast<const float*>(h->blk(l, B_PROJ_B)),
+                                     M, d.D, d.D, FREE_EPI_GATE_RESID, nullptr, xres, vec(l, 2), s));
+        }
         // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
-        FREE_TRY(launch_ln_modulate(xres, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn, s));
-        FREE_TRY(linear_dispatch(d, xn, h->blk(l, B_FC1_W), static_cast<const float*>(h->blk(l, B_FC1_B)), M, d.F,
-                                 d.D, FREE_EPI_BIAS_GELU, hmid, nullptr, RowVec{nullptr, 0, 1}, s));
-        FREE_TRY(linear_dispatch(d, hmid, h->blk(l, B_FC2_W), static_cast<const float*>(h->blk(l, B_FC2_B)), M,
-                                 d.D, d.F, FREE_EPI_GATE_RESID, nullptr, xres, vec(l, 5), s));
+        {
+            ProfScope prof(PROF_LN_MOD, s);
+            FREE_TRY(launch_ln_modulate(xres, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn, s));
+        }
+        {
+            ProfScope prof(PROF_GEMM_FC1, s);
+            FREE_TRY(linear_dispatch(d, xn, h->blk(l, B_FC1_W), static_cast<const float*>(h->blk(l, B_FC1_B)), M,
+                                     d.F, d.D, FREE_EPI_BIAS_GELU, hmid, nullptr, RowVec{nullptr, 0, 1}, s));
+        }
+        {
+            ProfScope prof(PROF_GEMM_FC2, s);
+            FREE_TRY(linear_dispatch(d, hmid, h->blk(l, B_FC2_W), static_cast<const float*>(h->blk(l, B_FC2_B)),
+                                     M, d.D, d.F, FREE_EPI_GATE_RESID, nullptr, xres, vec(l, 5), s));
+        }
     }
     if (top_feat) {
         if (!hip_ok(hipMemcpyAsync(top_feat, xres, static_cast<size_t>(M) * d.D * 4, hipMemcpyDeviceToDevice, s)))
@@ -177,6 +238,7 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     }
     RowVec fsh{mod + static_cast<int64_t>(d.depth) * 6 * d.D, d.mod_rows, d.ntok};
     RowVec fsc{mod + static_cast<int64_t>(d.depth) * 6 * d.D + d.D, d.mod_rows, d.ntok};
+    ProfScope prof(PROF_FINAL, s);
     FREE_TRY(launch_final_layer(xres, fsh, fsc, B, d.gh, d.gw, d.p, d.c_out, d.D, h->fin(F_W),
                                 static_cast<const float*>(h->fin(F_B)), d.mode, eps_out, s));
     return FREE_OK;
@@ -207,6 +269,34 @@ const char* free_status_string(int32_t st) {
 }
 
 int32_t free_last_hip_error(void) { return g_last_hip_error; }
+
+int32_t free_profile_begin(void) {
+    g_prof.used = 0;
+    g_prof.on = true;
+    return FREE_OK;
+}
+
+int32_t free_profile_end(float* ms, int32_t* launches) {
+    g_prof.on = false;
+    if (!ms || !launches) return FREE_ERR_NULL;
+    for (int c = 0; c < FREE_PROF_NCAT; ++c) { ms[c] = 0.f; launches[c] = 0; }
+    for (size_t k = 0; k < g_prof.used; ++k) {
+        if (!hip_ok(hipEventSynchronize(g_prof.ev[2 * k + 1]))) return FREE_ERR_HIP;
+        float t = 0.f;
+        if (!hip_ok(hipEventElapsedTime(&t, g_prof.ev[2 * k], g_prof.ev[2 * k + 1]))) return FREE_ERR_HIP;
+        ms[g_prof.cat[k]] += t;
+        launches[g_prof.cat[k]] += 1;
+    }
+    g_prof.used = 0;
+    return FREE_OK;
+}
+
+const char* free_profile_category_name(int32_t c) {
+    static const char* names[FREE_PROF_NCAT] = {"conditioning", "adaln", "patch_embed", "ln_modulate", "gemm_qkv",
+                                                "attention", "gemm_proj", "gemm_fc1", "gemm_fc2", "final_layer",
+                                                "eps_to_mean", "verify_partial", "verify_finish"};
+    return (c >= 0 && c < FREE_PROF_NCAT) ? names[c] : "unknown";
+}
 
 int32_t free_ddpm_schedule(int32_t T, double beta_start, double beta_end, double* coef_x, double* coef_eps,
                            double* sigma) {
@@ -366,8 +456,11 @@ int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, con
     float* mt = m_target_out ? m_target_out : reinterpret_cast<float*>(ws + L.mtarget);
     FREE_TRY(launch_pack_cond(t, y, d.classes, K, dup, tp, yp, s));
     FREE_TRY(forward_impl(h, x_states, K, tp, yp, B, eps, nullptr, ws, s));
-    FREE_TRY(launch_eps_to_mean(eps, x_states, coef_x, coef_eps, cfg_scale, K, d.C, d.c_out,
-                                static_cast<int64_t>(d.H) * d.W, mt, s));
+    {
+        ProfScope prof(PROF_EPS2MEAN, s);
+        FREE_TRY(launch_eps_to_mean(eps, x_states, coef_x, coef_eps, cfg_scale, K, d.C, d.c_out,
+                                    static_cast<int64_t>(d.H) * d.W, mt, s));
+    }
     VerifyArgs a{mt, m_draft, x_states, x_last, sigma, u, lambda, 1, K, d.d, log_ratio, accept, n_accept, x_out};
     return launch_verify(a, ws + L.vpart, verify_workspace_bytes(1, K, d.d), s);
 }

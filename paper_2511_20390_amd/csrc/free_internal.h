@@ -66,6 +66,22 @@ inline bool hip_ok(hipError_t e) {
 }
 inline bool launch_ok() { return hip_ok(hipGetLastError()); }
 
+// ---- optional per-kernel timing (free_profile_begin / free_profile_end) --------
+// When profiling is on, a ProfScope records a HIP event on the launch stream before
+// and after the launches it brackets; otherwise it does nothing.
+enum ProfCat {
+    PROF_COND = 0, PROF_ADALN, PROF_PATCH, PROF_LN_MOD, PROF_GEMM_QKV, PROF_ATTN, PROF_GEMM_PROJ,
+    PROF_GEMM_FC1, PROF_GEMM_FC2, PROF_FINAL, PROF_EPS2MEAN, PROF_VERIFY_PARTIAL, PROF_VERIFY_FINISH,
+    PROF_NCAT
+};
+static_assert(PROF_NCAT == FREE_PROF_NCAT, "category count is part of the ABI");
+struct ProfScope {
+    ProfScope(int cat, hipStream_t s);
+    ~ProfScope();
+    int slot;
+    hipStream_t stream;
+};
+
 // ---- verification (verify.hip) -------------------------------------------------
 struct VerifyArgs {
     const float* m_target;   // [n_traj, K, d]

@@ -215,6 +215,8 @@ int32_t launch_verify(const VerifyArgs& a, void* ws, size_t ws_bytes, hipStream_
     const bool vec = (a.d % 4 == 0) && aligned16(a.m_target) && aligned16(a.m_draft) &&
                      aligned16(a.x_draft) && (a.x_last == nullptr || aligned16(a.x_last));
     dim3 g1(p.splits, static_cast<unsigned>(pairs));
+    {
+    ProfScope prof(PROF_VERIFY_PARTIAL, s);
     if (vec) {
         hipLaunchKernelGGL(verify_partial_kernel<true>, g1, dim3(kThreads), 0, s, a.m_target, a.m_draft,
                            a.x_draft, a.x_last, a.K, a.d, p.chunk, partial);
@@ -222,7 +224,9 @@ int32_t launch_verify(const VerifyArgs& a, void* ws, size_t ws_bytes, hipStream_
         hipLaunchKernelGGL(verify_partial_kernel<false>, g1, dim3(kThreads), 0, s, a.m_target, a.m_draft,
                            a.x_draft, a.x_last, a.K, a.d, p.chunk, partial);
     }
+    }
     if (!launch_ok()) return FREE_ERR_HIP;
+    ProfScope prof(PROF_VERIFY_FINISH, s);
     const unsigned rchunks = static_cast<unsigned>((a.d + kReflectChunk - 1) / kReflectChunk);
     hipLaunchKernelGGL(verify_finish_kernel, dim3(rchunks, a.n_traj), dim3(kThreads), 0, s, a.m_target,
                        a.m_draft, a.x_draft, a.x_last, a.sigma, a.u, a.lambda, a.K, a.d, p.splits, partial,
