@@ -1,8 +1,296 @@
-// placeholder until the MFMA attention lands
+// Flash-style softmax attention on bf16 MFMA for the DiT blocks of the packed
+// target forward (Alg. 1): per (sample, head), out = softmax(q k^T / sqrt(dh)) v,
+// non-causal, fp32 online softmax, Q/K/V tiles staged in LDS.
+//
+// Formulation chosen for the CDNA accumulator layout: the score tile is computed
+// TRANSPOSED, S^T = K Q^T (rows = keys, columns = queries), with
+// v_mfma_f32_32x32x16_bf16.  In the accumulator layout a lane then owns one query
+// column (lane % 32) and half of the key rows, so
+//   * the softmax statistics of a query are lane-local (one exchange with lane^32),
+//   * the probabilities are already in the B-operand layout of the second product
+//     O^T = V^T P^T (rows = head dim, columns = queries): no shuffle, no LDS trip,
+//   * rescaling O^T by the per-query factor is a per-lane scalar multiply.
+// The key order inside each 32-key block is permuted when K is written to LDS
+// (bits 2 and 3 of the row index swapped) so that the 8 probabilities a lane feeds
+// to one MFMA belong to 8 CONSECUTIVE keys: the matching V^T operand is then a
+// single 16-byte LDS read.  V is transposed on its way into LDS.
+// Head dim 72 (DiT-XL): the contraction over d is padded 72 -> 80 with zero chunks
+// in LDS; the O^T rows are padded 72 -> 96 and the pad rows are never stored.
+#include <cmath>
+
 #include "free_internal.h"
+
 namespace freemi {
-bool mfma_attention_supported(int32_t, int32_t) { return false; }
-int32_t launch_attention_mfma(const bf16_t*, int32_t, int32_t, int32_t, int32_t, bf16_t*, hipStream_t) {
-    return FREE_ERR_SHAPE;
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int BKV = 64;                   // keys per LDS tile
+constexpr int VROW = 144;                 // bytes per V^T row in LDS: 64 keys (128 B) + 16 B pad, odd # of 16-B chunks
+
+__device__ inline int swap_bits_2_3(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+    // round-to-nearest-even on both halves (inputs are finite and non-negative here)
+    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+    a += 0x7fffu + ((a >> 16) & 1u);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (a >> 16) | (b & 0xffff0000u);
 }
+
+template <int DH, int QT>
+__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __restrict__ qkv, int32_t N,
+                                                             int32_t heads, float scale_log2,
+                                                             bf16_t* __restrict__ out) {
+    constexpr int KSTEPS = (DH + 15) / 16;            // MFMA k-steps over the head dim (S^T)
+    constexpr int DCH = DH / 8;                       // 16-byte chunks per Q/K/V row
+    constexpr int DT = (DH + 31) / 32;                // 32-row tiles of O^T
+    constexpr int KROW = ((2 * KSTEPS) | 1) * 16;     // bytes per K row in LDS (odd # of chunks)
+    constexpr int BQ = 4 * 32 * QT;                   // queries per workgroup
+    constexpr int NLD = (BKV * DCH + kThreads - 1) / kThreads;   // 16-byte loads per thread per tile
+    __shared__ __attribute__((aligned(16))) char sK[BKV * KROW];
+    __shared__ __attribute__((aligned(16))) char sV[DT * 32 * VROW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int D = heads * DH;
+    const int64_t row0 = static_cast<int64_t>(b) * N;
+    const int q_base = blockIdx.x * BQ + wave * 32 * QT;
+    const size_t row_bytes = static_cast<size_t>(3) * D * 2;
+    const char* qkv_b = reinterpret_cast<const char*>(qkv);
+
+    // zero the pad chunks of K (d in [DH, 16*KSTEPS)) and the pad rows of V^T once
+    for (int i = tid; i < BKV * (KROW / 16); i += kThreads) {
+        const int c = i % (KROW / 16);
+        if (c >= DCH) *reinterpret_cast<u32x4_t*>(sK + (i / (KROW / 16)) * KROW + c * 16) = u32x4_t{0, 0, 0, 0};
+    }
+    for (int i = tid; i < (DT * 32 - DH) * (VROW / 16); i += kThreads)
+        *reinterpret_cast<u32x4_t*>(sV + DH * VROW + i * 16) = u32x4_t{0, 0, 0, 0};
+
+    // Q^T fragments (B operand of S^T): lane holds query column l32, k-slots d = 16 ks + 8 g + j
+    bf16x8_t qf[QT][KSTEPS];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        int q = q_base + qt * 32 + l32;
+        if (q >= N) q = N - 1;
+        const char* src = qkv_b + (row0 + q) * row_bytes + static_cast<size_t>(h) * DH * 2;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const int c = 2 * ks + g;
+            u32x4_t v = {0, 0, 0, 0};
+            if (c < DCH) v = *reinterpret_cast<const u32x4_t*>(src + c * 16);
+            qf[qt][ks] = __builtin_bit_cast(bf16x8_t, v);
+        }
+    }
+
+    // global -> register staging of one K/V tile
+    u32x4_t kreg[NLD], vreg[NLD];
+    auto fetch = [&](int kv0) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int idx = tid + kThreads * i;
+            if (idx < BKV * DCH) {
+                {   // K: lanes walk the chunks of a row (coalesced)
+                    int kv = kv0 + idx / DCH;
+                    if (kv >= N) kv = N - 1;
+                    kreg[i] = *reinterpret_cast<const u32x4_t*>(qkv_b + (row0 + kv) * row_bytes +
+                                                                 static_cast<size_t>(D + h * DH) * 2 + (idx % DCH) * 16);
+                }
+                {   // V: lanes walk the keys of one chunk (conflict-free transposed LDS writes)
+                    int kv = kv0 + (idx & (BKV - 1));
+                    if (kv >= N) kv = N - 1;
+                    vreg[i] = *reinterpret_cast<const u32x4_t*>(qkv_b + (row0 + kv) * row_bytes +
+                                                                 static_cast<size_t>(2 * D + h * DH) * 2 + (idx / BKV) * 16);
+                }
+            }
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int idx = tid + kThreads * i;
+            if (idx < BKV * DCH) {
+                const int r = idx / DCH;
+                const int lr = (r & ~31) | swap_bits_2_3(r & 31);
+                *reinterpret_cast<u32x4_t*>(sK + lr * KROW + (idx % DCH) * 16) = kreg[i];
+                const int kv = idx & (BKV - 1), c = idx / BKV;
+                const uint32_t w[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    *reinterpret_cast<uint16_t*>(sV + (8 * c + 2 * e) * VROW + kv * 2) = static_cast<uint16_t>(w[e] & 0xffffu);
+                    *reinterpret_cast<uint16_t*>(sV + (8 * c + 2 * e + 1) * VROW + kv * 2) = static_cast<uint16_t>(w[e] >> 16);
+                }
+            }
+        }
+    };
+
+    f32x16_t o[DT][QT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[dt][qt][e] = 0.f;
+    float m_run[QT], l_run[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
+
+    const int ntiles = (N + BKV - 1) / BKV;
+    fetch(0);
+    for (int t = 0; t < ntiles; ++t) {
+        const int kv0 = t * BKV;
+        __syncthreads();                       // previous tile fully consumed (and pad zeroing done)
+        stash();
+        __syncthreads();
+        if (t + 1 < ntiles) fetch(kv0 + BKV);
+
+        // ---- S^T = K Q^T for the two 32-key blocks of the tile
+        f32x16_t st[2][QT];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) st[kb][qt][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            bf16x8_t kf[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+                kf[kb] = *reinterpret_cast<const bf16x8_t*>(sK + (kb * 32 + l32) * KROW + (2 * ks + g) * 16);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+                    st[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[qt][ks], st[kb][qt], 0, 0, 0);
+        }
+        // keys past N (last tile only): accumulator register e of block kb holds the key
+        // kv0 + 32 kb + 16 (e/8) + 8 g + 4 ((e/4)%2) + e%4   (LDS rows were permuted on the way in)
+        if (kv0 + BKV > N) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int kv = kv0 + 32 * kb + 16 * (e >> 3) + 8 * g + 4 * ((e >> 2) & 1) + (e & 3);
+                    if (kv >= N) {
+#pragma unroll
+                        for (int qt = 0; qt < QT; ++qt) st[kb][qt][e] = -INFINITY;
+                    }
+                }
+        }
+
+        // ---- online softmax per query column, probabilities packed straight into MFMA operands
+        bf16x8_t pf[QT][2][2];
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            float mx = st[0][qt][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[kb][qt][e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[qt], mx);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * scale_log2);
+            const float mb = m_new * scale_log2;
+            float sum = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    float p[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        p[j] = __builtin_amdgcn_exp2f(fmaf(st[kb][qt][8 * hh + j], scale_log2, -mb));
+                        sum += p[j];
+                    }
+                    u32x4_t pk = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
+                                  pack_bf16x2(p[6], p[7])};
+                    pf[qt][kb][hh] = __builtin_bit_cast(bf16x8_t, pk);
+                }
+            l_run[qt] = l_run[qt] * alpha + sum;
+            if (__any(m_new > m_run[qt])) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) o[dt][qt][e] *= alpha;
+            }
+            m_run[qt] = m_new;
+        }
+
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sV + (dt * 32 + l32) * VROW +
+                                                                            (kb * 32 + hh * 16 + g * 8) * 2);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt)
+                        o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][kb][hh], o[dt][qt], 0, 0, 0);
+                }
+            }
+    }
+
+    // ---- normalise and store: register e of O^T tile dt is row d = 32 dt + 8 (e/4) + 4 g + e%4, column l32
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int q = q_base + qt * 32 + l32;
+        const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
+        if (q >= N) continue;
+        const float inv = 1.0f / l_tot;
+        char* dst = reinterpret_cast<char*>(out) + ((row0 + q) * D + static_cast<size_t>(h) * DH) * 2;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const int d = 32 * dt + 8 * e4 + 4 * g;
+                if (d < DH) {
+                    u32x2_t v = {pack_bf16x2(o[dt][qt][4 * e4] * inv, o[dt][qt][4 * e4 + 1] * inv),
+                                 pack_bf16x2(o[dt][qt][4 * e4 + 2] * inv, o[dt][qt][4 * e4 + 3] * inv)};
+                    *reinterpret_cast<u32x2_t*>(dst + d * 2) = v;
+                }
+            }
+    }
 }
+
+template <int DH>
+int32_t launch_dh(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, bf16_t* out, hipStream_t s) {
+    const float scale_log2 = 1.4426950408889634f / std::sqrt(static_cast<float>(DH));
+    if (N >= 512) {
+        dim3 grid((N + 255) / 256, heads, B);
+        hipLaunchKernelGGL((attn_mfma_kernel<DH, 2>), grid, dim3(kThreads), 0, s, qkv, N, heads, scale_log2, out);
+    } else {
+        dim3 grid((N + 127) / 128, heads, B);
+        hipLaunchKernelGGL((attn_mfma_kernel<DH, 1>), grid, dim3(kThreads), 0, s, qkv, N, heads, scale_log2, out);
+    }
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+}  // namespace
+
+bool mfma_attention_supported(int32_t N, int32_t dh) {
+    return N >= 1 && (dh == 16 || dh == 64 || dh == 72 || dh == 128);
+}
+
+int32_t launch_attention_mfma(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh, bf16_t* out,
+                              hipStream_t s) {
+    if (reinterpret_cast<uintptr_t>(qkv) & 15u) return FREE_ERR_SHAPE;
+    if (B > 65535 || heads > 65535) return FREE_ERR_SHAPE;
+    switch (dh) {
+        case 16: return launch_dh<16>(qkv, B, N, heads, out, s);
+        case 64: return launch_dh<64>(qkv, B, N, heads, out, s);
+        case 72: return launch_dh<72>(qkv, B, N, heads, out, s);
+        case 128: return launch_dh<128>(qkv, B, N, heads, out, s);
+        default: return FREE_ERR_SHAPE;
+    }
+}
+
+}  // namespace freemi
