@@ -1,21 +1,30 @@
 // bf16 MFMA GEMM for the dense projections of the DiT blocks (QKV, attention
 // out-projection, MLP FC1/FC2 of the packed target forward, Alg. 1):
-//   C[M,N] = A[M,K] . W[N,K]^T  (+bias, fused epilogue), fp32 accumulation.
+//   C[M,N] = X[M,K] . W[N,K]^T  (+bias, fused epilogue), fp32 accumulation.
 // Both operands are K-contiguous, which is exactly the per-lane operand layout of
 // v_mfma_f32_32x32x16_bf16 (lane l: row/col l%32, 8 consecutive k at 8*(l/32)).
 //
-// Tiling (gfx950: 64-wide wavefronts, 160 KB LDS per CU, 512 VGPR+AGPR per lane):
-//   workgroup = 256 threads = 4 wavefronts in a WGM x WGN grid, macro tile BM x BN,
-//   K slices of 64; each wavefront owns (BM/WGM) x (BN/WGN) as TM x TN MFMA tiles
-//   of 32x32, accumulators stay in registers for the whole K loop.
-//   LDS: two stages of [BM + BN rows][64 bf16]; the 16-byte chunk index of every
-//   row is XOR-swizzled with (row % 8) so that the 8 lanes served per LDS cycle by
-//   ds_read_b128 hit 8 distinct chunk columns (no bank conflicts) while global
-//   loads stay 128-byte coalesced.  The next K slice is fetched into registers
-//   while the current one is multiplied (one barrier per slice).
-//   Workgroup ids are remapped so that the 8 XCDs (round-robin dispatch) each work
-//   on a compact, L2-friendly group of tiles.
+// Design for gfx950 (64-wide wavefronts, 160 KB LDS per CU, 512 VGPR+AGPR per lane):
+//  * workgroup = 256 threads = 4 wavefronts in a WGM x WGN grid, macro tile BM x BN,
+//    K slices of 64; each wavefront owns (BM/WGM) x (BN/WGN) as TM x TN MFMA tiles,
+//    accumulators stay in AGPRs for the whole K loop.
+//  * the MFMA takes the WEIGHT rows as its A operand and the activation rows as its
+//    B operand, i.e. it accumulates C^T tiles: a lane then owns one output ROW m
+//    (lane % 32) and runs of 4 consecutive output columns n per register group.  The
+//    epilogue therefore needs no transposition: one v_permlane32_swap pairs the two
+//    half-waves' runs into 8 consecutive bf16 (a 16-byte store), and the fp32
+//    residual update is a float4 read-modify-write.
+//  * LDS: two stages of [BM + BN rows][64 bf16]; the 16-byte chunk index of a row is
+//    XOR-swizzled with (row % 8): ds_read_b128 fragment reads are bank-conflict free
+//    and global loads stay 128-byte coalesced.
+//  * software pipeline: global loads run two slices ahead (slice kt+2 is in flight
+//    in registers while slice kt+1 is written to the other LDS stage and slice kt is
+//    multiplied); MFMA operand fragments are double-buffered in registers so every
+//    LDS read is issued one k-step before its use.  One barrier per slice.
+//  * workgroup ids are remapped so that each of the 8 XCDs (round-robin dispatch)
+//    works on a compact, L2-friendly group of tiles.
 #include <cmath>
+#include <type_traits>
 
 #include "free_internal.h"
 
@@ -24,8 +33,12 @@ namespace freemi {
 namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int BK = 64;                    // bf16 elements per K slice (128 bytes per row)
@@ -39,9 +52,32 @@ __device__ inline float gelu_fast(float v) {
     return v * __frcp_rn(1.0f + __expf(-2.0f * u));
 }
 
+__device__ inline uint32_t pack2(float lo, float hi) {
+    const f32x2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));   // v_cvt_pk_bf16_f32 (RNE)
+}
+
+// Issue-order hints for one k-step of MF MFMAs: every MFMA is followed by at most one
+// fragment read (NR of them) and its share of N_OTHER instructions of class OTHER (LDS
+// writes or global loads), so the matrix pipe never waits behind a burst of memory
+// instructions.
+constexpr int kMfma = 0x008, kVmemRd = 0x020, kDsRd = 0x100, kDsWr = 0x200;
+template <int Q, int MF, int NR, bool READS, int OTHER, int N_OTHER>
+__device__ __forceinline__ void sched_hints() {
+    if constexpr (Q < MF) {
+        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        if constexpr (READS && Q < NR) __builtin_amdgcn_sched_group_barrier(kDsRd, 1, 0);
+        constexpr int cnt = (N_OTHER * (Q + 1)) / MF - (N_OTHER * Q) / MF;
+        if constexpr (cnt > 0) __builtin_amdgcn_sched_group_barrier(OTHER, cnt, 0);
+        sched_hints<Q + 1, MF, NR, READS, OTHER, N_OTHER>();
+    } else {
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so the
 // ids of one XCD are made contiguous first, then walked in groups of kGroupM row
-// tiles (column-major inside a group) so concurrent workgroups share A and W panels.
+// tiles (column-major inside a group) so concurrent workgroups share X and W panels.
 __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, int* tn) {
     const int total = tiles_m * tiles_n;
     const int q = total / kNumXcd, r = total % kNumXcd;
@@ -56,11 +92,13 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
     *tn = in_group / gsize;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+// EVEN_K: K % 64 == 0 (no predicates in the K loop).  Ragged M / N tiles are handled
+// by clamping the loaded row index (extra rows are computed, never stored).
+template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(
-    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias, int32_t M,
-    int32_t N, int32_t K, int32_t tiles_m, int32_t tiles_n, bf16_t* __restrict__ out, float* __restrict__ resid,
-    RowVec gate) {
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, const float* __restrict__ bias, int32_t M,
+    int32_t N, int32_t K, int32_t tiles_m, int32_t tiles_n, int32_t vec_ok, bf16_t* __restrict__ out,
+    float* __restrict__ resid, RowVec gate) {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
     constexpr int LA = BM / 32, LB = BN / 32;          // 16-byte loads per thread per slice
@@ -75,56 +113,67 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(
 
     // ---- global -> register staging: chunk idx = i*256 + tid, row = idx/8, chunk = idx%8
     const int ld_row = tid >> 3, ld_chunk = tid & 7;
-    const char* a_src[LA];
-    const char* b_src[LB];
-    int a_dst[LA], b_dst[LB];
+    const char* xbase = reinterpret_cast<const char*>(X + static_cast<int64_t>(m0) * K);
+    const char* wbase = reinterpret_cast<const char*>(W + static_cast<int64_t>(n0) * K);
+    int a_off[LA], b_off[LB];                          // byte offsets from the tile bases
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
-        const int row = ld_row + 32 * i;
-        int gm = m0 + row;
-        if (gm >= M) gm = M - 1;                        // clamped rows are computed but never stored
-        a_src[i] = reinterpret_cast<const char*>(A + static_cast<int64_t>(gm) * K) + ld_chunk * 16;
-        a_dst[i] = row * kRowBytes + ((ld_chunk ^ (row & 7)) << 4);
+        int row = ld_row + 32 * i;
+        if (m0 + row >= M) row = M - 1 - m0;
+        a_off[i] = row * K * 2 + ld_chunk * 16;
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
-        const int row = ld_row + 32 * i;
-        int gn = n0 + row;
-        if (gn >= N) gn = N - 1;
-        b_src[i] = reinterpret_cast<const char*>(W + static_cast<int64_t>(gn) * K) + ld_chunk * 16;
-        b_dst[i] = BM * kRowBytes + row * kRowBytes + ((ld_chunk ^ (row & 7)) << 4);
+        int row = ld_row + 32 * i;
+        if (n0 + row >= N) row = N - 1 - n0;
+        b_off[i] = row * K * 2 + ld_chunk * 16;
     }
+    const int st_off = ld_row * kRowBytes + ((ld_chunk ^ (ld_row & 7)) << 4);   // + i*4096 per load
     u32x4_t sa[LA], sb[LB];
     const int nk = (K + BK - 1) / BK;
 
     auto fetch = [&](int kt) {
         const int kbyte = kt * kRowBytes;
-        const bool in_k = (kt * BK + ld_chunk * 8) < K;    // K % 8 == 0: a chunk is all in or all out
+        if (EVEN_K) {
 #pragma unroll
-        for (int i = 0; i < LA; ++i)
-            sa[i] = in_k ? *reinterpret_cast<const u32x4_t*>(a_src[i] + kbyte) : u32x4_t{0, 0, 0, 0};
+            for (int i = 0; i < LA; ++i) sa[i] = *reinterpret_cast<const u32x4_t*>(xbase + kbyte + a_off[i]);
 #pragma unroll
-        for (int i = 0; i < LB; ++i)
-            sb[i] = in_k ? *reinterpret_cast<const u32x4_t*>(b_src[i] + kbyte) : u32x4_t{0, 0, 0, 0};
+            for (int i = 0; i < LB; ++i) sb[i] = *reinterpret_cast<const u32x4_t*>(wbase + kbyte + b_off[i]);
+        } else {
+            const bool in_k = (kt * BK + ld_chunk * 8) < K;    // K % 8 == 0: a chunk is all in or all out
+#pragma unroll
+            for (int i = 0; i < LA; ++i)
+                sa[i] = in_k ? *reinterpret_cast<const u32x4_t*>(xbase + kbyte + a_off[i]) : u32x4_t{0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < LB; ++i)
+                sb[i] = in_k ? *reinterpret_cast<const u32x4_t*>(wbase + kbyte + b_off[i]) : u32x4_t{0, 0, 0, 0};
+        }
     };
     auto stash = [&](int stage) {
-        char* base = lds + stage * kStageBytes;
+        char* base = lds + stage * kStageBytes + st_off;
 #pragma unroll
-        for (int i = 0; i < LA; ++i) *reinterpret_cast<u32x4_t*>(base + a_dst[i]) = sa[i];
+        for (int i = 0; i < LA; ++i) *reinterpret_cast<u32x4_t*>(base + i * 32 * kRowBytes) = sa[i];
 #pragma unroll
-        for (int i = 0; i < LB; ++i) *reinterpret_cast<u32x4_t*>(base + b_dst[i]) = sb[i];
+        for (int i = 0; i < LB; ++i) *reinterpret_cast<u32x4_t*>(base + (BM + i * 32) * kRowBytes) = sb[i];
     };
 
-    // ---- MFMA operand addresses in LDS (row fixed per lane, chunk varies with the k step)
+    // ---- MFMA operand fragments: row fixed per lane, chunk varies with the k step
     const int l32 = lane & 31, lhi = lane >> 5;
-    int a_row_off[TM], b_row_off[TN];
+    const int sw = l32 & 7;                                // row % 8 (tile row offsets are multiples of 32)
+    const int x_row0 = (wm * TM * 32 + l32) * kRowBytes;           // + i*32 rows
+    const int w_row0 = (BM + wn * TN * 32 + l32) * kRowBytes;      // + j*32 rows
+    bf16x8_t fx[2][TM], fw[2][TN];
+    auto load_frags = [&](const char* base, int ks, int buf) {
+        const int choff = (((ks << 1) | lhi) ^ sw) << 4;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) a_row_off[i] = (wm * TM * 32 + i * 32 + l32) * kRowBytes;
+        for (int i = 0; i < TM; ++i)
+            fx[buf][i] = *reinterpret_cast<const bf16x8_t*>(base + x_row0 + i * 32 * kRowBytes + choff);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) b_row_off[j] = BM * kRowBytes + (wn * TN * 32 + j * 32 + l32) * kRowBytes;
-    const int sw = l32 & 7;                                // (row % 8): tile row offsets are multiples of 32
+        for (int j = 0; j < TN; ++j)
+            fw[buf][j] = *reinterpret_cast<const bf16x8_t*>(base + w_row0 + j * 32 * kRowBytes + choff);
+    };
 
-    f32x16_t acc[TM][TN];
+    f32x16_t acc[TM][TN];                                  // acc[i][j]: rows n (tile j), columns m (tile i)
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -132,48 +181,152 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const bool more = kt + 1 < nk;
-        if (more) fetch(kt + 1);
-        const char* base = lds + (kt & 1) * kStageBytes;
+    auto mma = [&](int buf) {
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            const int choff = (((ks << 1) | lhi) ^ sw) << 4;
-            bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8_t*>(base + a_row_off[i] + choff);
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8_t*>(base + b_row_off[j] + choff);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) stash((kt + 1) & 1);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][j], fx[buf][i], acc[i][j], 0, 0, 0);
+    };
+    // One K slice.  Precondition: fragments of k-step 0 are in buffer 0.
+    //   k-step 0: multiply | read fragments of step 1 | write slice kt+1 (in registers) to the other stage
+    //   k-step 1: multiply | read fragments of step 2 | start the global loads of slice kt+2
+    //   k-step 2: multiply | read fragments of step 3
+    //   barrier: the other stage is complete, this stage will not be read by a multiply again
+    //   k-step 3: multiply | read fragments of step 0 of slice kt+1 from the other stage
+    constexpr int MF = TM * TN, NR = TM + TN;
+    auto slice = [&](int kt, auto stash_next, auto fetch_next2) {
+        constexpr bool kStash = decltype(stash_next)::value, kFetch = decltype(fetch_next2)::value;
+        const char* base = lds + (kt & 1) * kStageBytes;
+        load_frags(base, 1, 1);
+        if (kStash) stash((kt + 1) & 1);
+        mma(0);
+        sched_hints<0, MF, NR, true, kDsWr, kStash ? LA + LB : 0>();
+        load_frags(base, 2, 0);
+        if (kFetch) fetch(kt + 2);
+        mma(1);
+        sched_hints<0, MF, NR, true, kVmemRd, kFetch ? LA + LB : 0>();
+        load_frags(base, 3, 1);
+        mma(0);
+        sched_hints<0, MF, NR, true, 0, 0>();
         __syncthreads();
-    }
+        if (kStash) load_frags(lds + ((kt + 1) & 1) * kStageBytes, 0, 0);
+        mma(1);
+        sched_hints<0, MF, NR, kStash, 0, 0>();
+    };
+    const std::true_type yes{};
+    const std::false_type no{};
 
-    // ---- epilogue.  Accumulator register e of lane l holds
-    //      row 8*(e/4) + 4*(l/32) + e%4, column l%32 of its 32x32 tile.
+    // ---- prologue
+    fetch(0);
+    stash(0);
+    if (nk > 1) fetch(1);
+    __syncthreads();
+    load_frags(lds, 0, 0);
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) slice(kt, yes, yes);
+    if (kt + 1 < nk) {
+        slice(kt, yes, no);
+        ++kt;
+    }
+    slice(kt, no, no);
+
+    // ---- epilogue.  Register e of acc[i][j] in lane l is
+    //      output row m = m0 + (wm TM + i) 32 + l%32, column n = n0 + (wn TN + j) 32 + 8 (e/4) + 4 (l/32) + e%4.
+    const int gm_lane = m0 + wm * TM * 32 + l32;
+    const int gn_wave = n0 + wn * TN * 32;
+    if (vec_ok) {
+        // N % 8 == 0 and 16-byte aligned rows: runs of 4 / 8 columns are all inside or all outside.
+        // Rows past M and runs past N (ragged edge tiles) are masked per lane.
+        if (EPI == FREE_EPI_GATE_RESID) {
+            // read-modify-write of the fp32 residual stream.  All loads of a column tile j are
+            // issued before its first store (a store would otherwise fence the following loads).
+            const float* __restrict__ gbase = gate.base;
+            int64_t g_off[TM], r_off[TM];
+            bool row_ok[TM];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int gn = n0 + wn * TN * 32 + j * 32 + l32;
-        if (gn >= N) continue;
-        const float bv = bias[gn];
+            for (int i = 0; i < TM; ++i) {
+                const int gm = gm_lane + i * 32;
+                row_ok[i] = gm < M;
+                g_off[i] = static_cast<int64_t>(gm / gate.rows_per_sample) * gate.stride;
+                r_off[i] = static_cast<int64_t>(gm) * N;
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int gn0 = gn_wave + j * 32 + 4 * lhi;
+                f32x4_t bv[4], g[TM][4], r[TM][4];
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4)
+                    if (gn0 + 8 * e4 < N) bv[e4] = *reinterpret_cast<const f32x4_t*>(bias + gn0 + 8 * e4);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4)
+                        if (row_ok[i] && gn0 + 8 * e4 < N) {
+                            g[i][e4] = *reinterpret_cast<const f32x4_t*>(gbase + g_off[i] + gn0 + 8 * e4);
+                            r[i][e4] = *reinterpret_cast<const f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4);
+                        }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4)
+                        if (row_ok[i] && gn0 + 8 * e4 < N) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                r[i][e4][c] = fmaf(g[i][e4][c], acc[i][j][4 * e4 + c] + bv[e4][c], r[i][e4][c]);
+                            *reinterpret_cast<f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4) = r[i][e4];
+                        }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e8 = 0; e8 < 2; ++e8) {
+                    // this lane's two runs: n = nb + 4 lhi + {0..3} (lo) and nb + 8 + 4 lhi + {0..3} (hi);
+                    // nb is a multiple of 16 and N of 8, so nb < N covers the lo run and nb + 8 < N the hi run
+                    const int nb = gn_wave + j * 32 + 16 * e8;
+                    f32x4_t blo = {0.f, 0.f, 0.f, 0.f}, bhi = {0.f, 0.f, 0.f, 0.f};
+                    if (nb < N) blo = *reinterpret_cast<const f32x4_t*>(bias + nb + 4 * lhi);
+                    if (nb + 8 < N) bhi = *reinterpret_cast<const f32x4_t*>(bias + nb + 8 + 4 * lhi);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        float v[8];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            v[c] = acc[i][j][8 * e8 + c] + blo[c];
+                            v[4 + c] = acc[i][j][8 * e8 + 4 + c] + bhi[c];
+                        }
+                        if (EPI == FREE_EPI_BIAS_GELU) {
+#pragma unroll
+                            for (int c = 0; c < 8; ++c) v[c] = gelu_fast(v[c]);
+                        }
+                        uint32_t lo0 = pack2(v[0], v[1]), lo1 = pack2(v[2], v[3]);
+                        uint32_t hi0 = pack2(v[4], v[5]), hi1 = pack2(v[6], v[7]);
+                        // lower half-wave keeps its lo run and receives the partner's lo run (n+4..7);
+                        // upper half-wave receives the partner's hi run (n+8..11) and keeps its own hi run
+                        const u32x2_t s0 = __builtin_amdgcn_permlane32_swap(lo0, hi0, false, false);
+                        const u32x2_t s1 = __builtin_amdgcn_permlane32_swap(lo1, hi1, false, false);
+                        const u32x4_t o = {s0[0], s1[0], s0[1], s1[1]};
+                        const int gm = gm_lane + i * 32;
+                        if (gm < M && nb + 8 * lhi < N)
+                            *reinterpret_cast<u32x4_t*>(out + static_cast<int64_t>(gm) * N + nb + 8 * lhi) = o;
+                    }
+                }
+        }
+        return;
+    }
+    // unaligned output: element-wise with bounds checks
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int row_base = m0 + wm * TM * 32 + i * 32 + 4 * lhi;
+            const int gm = gm_lane + i * 32;
+            if (gm >= M) continue;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int gm = row_base + 8 * (e >> 2) + (e & 3);
-                if (gm >= M) continue;
-                const float v = acc[i][j][e] + bv;
+                const int gn = gn_wave + j * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                if (gn >= N) continue;
+                const float v = acc[i][j][e] + bias[gn];
                 const int64_t o = static_cast<int64_t>(gm) * N + gn;
                 if (EPI == FREE_EPI_BIAS) {
                     out[o] = float_to_bf16(v);
@@ -185,35 +338,45 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(
                 }
             }
         }
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
+int32_t launch_one(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K, bf16_t* out,
+                   float* resid, RowVec gate, hipStream_t s) {
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const size_t lds = 2 * static_cast<size_t>(BM + BN) * kRowBytes;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, EVEN_K>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))))
+            return FREE_ERR_HIP;
+        attr_set = true;
     }
+    // the vector epilogue needs 16-byte aligned rows of out / resid / bias / gate
+    auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+    const int32_t vec_ok = ((N & 7) == 0) && al16(bias) && al16(out) && al16(resid) && al16(gate.base) &&
+                           ((gate.stride & 3) == 0);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(kThreads), lds, s, X, W, bias, M, N, K, tiles_m, tiles_n,
+                       vec_ok, out, resid, gate);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 
 template <int BM, int BN, int WGM, int WGN>
-int32_t launch_cfg(const bf16_t* A, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
+int32_t launch_cfg(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
                    int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s) {
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const size_t lds = 2 * static_cast<size_t>(BM + BN) * kRowBytes;
-    const dim3 grid(tiles_m * tiles_n), block(kThreads);
-#define FREE_GEMM_LAUNCH(E)                                                                                     \
-    do {                                                                                                        \
-        auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, E>;                                                      \
-        static bool attr_set = false;                                                                           \
-        if (!attr_set) {                                                                                        \
-            if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                \
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)))) \
-                return FREE_ERR_HIP;                                                                            \
-            attr_set = true;                                                                                    \
-        }                                                                                                       \
-        hipLaunchKernelGGL(kern, grid, block, lds, s, A, W, bias, M, N, K, tiles_m, tiles_n, out, resid, gate); \
-    } while (0)
+    const bool even = (K % BK) == 0;
+#define FREE_GEMM_CASE(E)                                                                                    \
+    case E:                                                                                                  \
+        return even ? launch_one<BM, BN, WGM, WGN, E, true>(X, W, bias, M, N, K, out, resid, gate, s)        \
+                    : launch_one<BM, BN, WGM, WGN, E, false>(X, W, bias, M, N, K, out, resid, gate, s)
     switch (epi) {
-        case FREE_EPI_BIAS: FREE_GEMM_LAUNCH(FREE_EPI_BIAS); break;
-        case FREE_EPI_BIAS_GELU: FREE_GEMM_LAUNCH(FREE_EPI_BIAS_GELU); break;
-        case FREE_EPI_GATE_RESID: FREE_GEMM_LAUNCH(FREE_EPI_GATE_RESID); break;
+        FREE_GEMM_CASE(FREE_EPI_BIAS);
+        FREE_GEMM_CASE(FREE_EPI_BIAS_GELU);
+        FREE_GEMM_CASE(FREE_EPI_GATE_RESID);
         default: return FREE_ERR_RANGE;
     }
-#undef FREE_GEMM_LAUNCH
-    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+#undef FREE_GEMM_CASE
 }
 
 // Fraction of the last wave of workgroups that is busy, times a per-shape efficiency guess.
@@ -227,20 +390,21 @@ double cfg_score(int M, int N, int bm, int bn, double shape_eff) {
 }  // namespace
 
 bool mfma_linear_supported(int32_t M, int32_t N, int32_t K) {
-    return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0;
+    // 32-bit byte offsets inside a tile: 256 rows of K bf16
+    return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && static_cast<int64_t>(K) * 2 * 256 < (1ll << 31);
 }
 
-int32_t launch_linear_mfma(const bf16_t* A, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
+int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
                            int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s) {
     if (!mfma_linear_supported(M, N, K)) return FREE_ERR_SHAPE;
-    if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(W)) & 15u) return FREE_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W)) & 15u) return FREE_ERR_SHAPE;
     const double s256 = cfg_score(M, N, 256, 256, 1.00);
     const double s2x1 = cfg_score(M, N, 256, 128, 0.90);
     const double s128 = cfg_score(M, N, 128, 128, 0.75);
     if (s256 >= s2x1 && s256 >= s128)
-        return launch_cfg<256, 256, 2, 2>(A, W, bias, M, N, K, epi, out, resid, gate, s);
-    if (s2x1 >= s128) return launch_cfg<256, 128, 2, 2>(A, W, bias, M, N, K, epi, out, resid, gate, s);
-    return launch_cfg<128, 128, 2, 2>(A, W, bias, M, N, K, epi, out, resid, gate, s);
+        return launch_cfg<256, 256, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    if (s2x1 >= s128) return launch_cfg<256, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    return launch_cfg<128, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
 }
 
 }  // namespace freemi
