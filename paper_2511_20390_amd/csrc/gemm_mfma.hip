@@ -24,6 +24,7 @@
 //  * workgroup ids are remapped so that each of the 8 XCDs (round-robin dispatch)
 //    works on a compact, L2-friendly group of tiles.
 #include <cmath>
+#include <cstdlib>
 #include <type_traits>
 
 #include "free_internal.h"
@@ -40,7 +41,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;
+static int g_variant = 0, g_wmap = 0;
 constexpr int BK = 64;                    // bf16 elements per K slice (128 bytes per row)
 constexpr int kRowBytes = BK * 2;
 constexpr int kNumXcd = 8;
@@ -58,18 +59,17 @@ __device__ inline uint32_t pack2(float lo, float hi) {
 }
 
 // Issue-order hints for one k-step of MF MFMAs: every MFMA is followed by at most one
-// fragment read (NR of them) and its share of N_OTHER instructions of class OTHER (LDS
-// writes or global loads), so the matrix pipe never waits behind a burst of memory
-// instructions.
+// fragment read (NR of them), one LDS write (NW) and one global load (NL), so the matrix
+// pipe never waits behind a burst of memory instructions.
 constexpr int kMfma = 0x008, kVmemRd = 0x020, kDsRd = 0x100, kDsWr = 0x200;
-template <int Q, int MF, int NR, bool READS, int OTHER, int N_OTHER>
+template <int Q, int MF, int NR, int NW, int NL>
 __device__ __forceinline__ void sched_hints() {
     if constexpr (Q < MF) {
         __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
-        if constexpr (READS && Q < NR) __builtin_amdgcn_sched_group_barrier(kDsRd, 1, 0);
-        constexpr int cnt = (N_OTHER * (Q + 1)) / MF - (N_OTHER * Q) / MF;
-        if constexpr (cnt > 0) __builtin_amdgcn_sched_group_barrier(OTHER, cnt, 0);
-        sched_hints<Q + 1, MF, NR, READS, OTHER, N_OTHER>();
+        if constexpr (Q < NR) __builtin_amdgcn_sched_group_barrier(kDsRd, 1, 0);
+        if constexpr (Q < NW) __builtin_amdgcn_sched_group_barrier(kDsWr, 1, 0);
+        if constexpr (Q < NL) __builtin_amdgcn_sched_group_barrier(kVmemRd, 1, 0);
+        sched_hints<Q + 1, MF, NR, NW, NL>();
     } else {
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -95,13 +95,15 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
 // EVEN_K: K % 64 == 0 (no predicates in the K loop).  Ragged M / N tiles are handled
 // by clamping the loaded row index (extra rows are computed, never stored).
 template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
-__global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, const float* __restrict__ bias, int32_t M,
     int32_t N, int32_t K, int32_t tiles_m, int32_t tiles_n, int32_t vec_ok, bf16_t* __restrict__ out,
     float* __restrict__ resid, RowVec gate) {
-    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    static_assert(WGM * WGN == 4 || WGM * WGN == 8, "four or eight wavefronts per workgroup");
+    constexpr int NT = WGM * WGN * 64;                 // threads per workgroup
+    constexpr int RP = NT / 8;                         // tile rows covered by one pass of 16-byte loads
     constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-    constexpr int LA = BM / 32, LB = BN / 32;          // 16-byte loads per thread per slice
+    constexpr int LA = BM / RP, LB = BN / RP;          // 16-byte loads per thread per slice
     constexpr int kStageBytes = (BM + BN) * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -111,51 +113,57 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // ---- global -> register staging: chunk idx = i*256 + tid, row = idx/8, chunk = idx%8
-    const int ld_row = tid >> 3, ld_chunk = tid & 7;
+    // ---- global -> register staging: chunk idx = i*NT + tid, row = idx/8, chunk = idx%8
+    const int ld_chunk = tid & 7;
+    const int ld_row = (vec_ok & 2) ? (wave * 8 + ((lane >> 3) & 3) * 2 + (lane >> 5)) : (tid >> 3);
     const char* xbase = reinterpret_cast<const char*>(X + static_cast<int64_t>(m0) * K);
     const char* wbase = reinterpret_cast<const char*>(W + static_cast<int64_t>(n0) * K);
     int a_off[LA], b_off[LB];                          // byte offsets from the tile bases
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
-        int row = ld_row + 32 * i;
+        int row = ld_row + RP * i;
         if (m0 + row >= M) row = M - 1 - m0;
         a_off[i] = row * K * 2 + ld_chunk * 16;
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
-        int row = ld_row + 32 * i;
+        int row = ld_row + RP * i;
         if (n0 + row >= N) row = N - 1 - n0;
         b_off[i] = row * K * 2 + ld_chunk * 16;
     }
-    const int st_off = ld_row * kRowBytes + ((ld_chunk ^ (ld_row & 7)) << 4);   // + i*4096 per load
+    const int st_off = ld_row * kRowBytes + ((ld_chunk ^ (ld_row & 7)) << 4);   // + i*RP rows per load
     u32x4_t sa[LA], sb[LB];
     const int nk = (K + BK - 1) / BK;
 
-    auto fetch = [&](int kt) {
+    // staging register idx in [0, LA + LB): the first LA hold X rows, the rest W rows
+    constexpr int NS = LA + LB;
+    auto fetch_range = [&](int kt, int lo, int hi) {
         const int kbyte = kt * kRowBytes;
-        if (EVEN_K) {
+        const bool in_k = EVEN_K || (kt * BK + ld_chunk * 8) < K;   // K % 8 == 0: a chunk is all in or all out
 #pragma unroll
-            for (int i = 0; i < LA; ++i) sa[i] = *reinterpret_cast<const u32x4_t*>(xbase + kbyte + a_off[i]);
-#pragma unroll
-            for (int i = 0; i < LB; ++i) sb[i] = *reinterpret_cast<const u32x4_t*>(wbase + kbyte + b_off[i]);
-        } else {
-            const bool in_k = (kt * BK + ld_chunk * 8) < K;    // K % 8 == 0: a chunk is all in or all out
-#pragma unroll
-            for (int i = 0; i < LA; ++i)
-                sa[i] = in_k ? *reinterpret_cast<const u32x4_t*>(xbase + kbyte + a_off[i]) : u32x4_t{0, 0, 0, 0};
-#pragma unroll
-            for (int i = 0; i < LB; ++i)
-                sb[i] = in_k ? *reinterpret_cast<const u32x4_t*>(wbase + kbyte + b_off[i]) : u32x4_t{0, 0, 0, 0};
+        for (int idx = 0; idx < NS; ++idx) {
+            if (idx < lo || idx >= hi) continue;
+            if (idx < LA) {
+                sa[idx] = in_k ? *reinterpret_cast<const u32x4_t*>(xbase + kbyte + a_off[idx]) : u32x4_t{0, 0, 0, 0};
+            } else {
+                sb[idx - LA] =
+                    in_k ? *reinterpret_cast<const u32x4_t*>(wbase + kbyte + b_off[idx - LA]) : u32x4_t{0, 0, 0, 0};
+            }
         }
     };
-    auto stash = [&](int stage) {
+    auto stash_range = [&](int stage, int lo, int hi) {
         char* base = lds + stage * kStageBytes + st_off;
 #pragma unroll
-        for (int i = 0; i < LA; ++i) *reinterpret_cast<u32x4_t*>(base + i * 32 * kRowBytes) = sa[i];
-#pragma unroll
-        for (int i = 0; i < LB; ++i) *reinterpret_cast<u32x4_t*>(base + (BM + i * 32) * kRowBytes) = sb[i];
+        for (int idx = 0; idx < NS; ++idx) {
+            if (idx < lo || idx >= hi) continue;
+            if (idx < LA)
+                *reinterpret_cast<u32x4_t*>(base + idx * RP * kRowBytes) = sa[idx];
+            else
+                *reinterpret_cast<u32x4_t*>(base + (BM + (idx - LA) * RP) * kRowBytes) = sb[idx - LA];
+        }
     };
+    auto fetch = [&](int kt) { fetch_range(kt, 0, NS); };
+    auto stash = [&](int stage) { stash_range(stage, 0, NS); };
 
     // ---- MFMA operand fragments: row fixed per lane, chunk varies with the k step
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -188,31 +196,39 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][j], fx[buf][i], acc[i][j], 0, 0, 0);
     };
-    // One K slice.  Precondition: fragments of k-step 0 are in buffer 0.
-    //   k-step 0: multiply | read fragments of step 1 | write slice kt+1 (in registers) to the other stage
-    //   k-step 1: multiply | read fragments of step 2 | start the global loads of slice kt+2
-    //   k-step 2: multiply | read fragments of step 3
-    //   barrier: the other stage is complete, this stage will not be read by a multiply again
+    // One K slice.  Precondition: fragments of k-step 0 are in buffer 0.  The staging
+    // registers hold slice kt+1; they are written to the other LDS stage in three
+    // portions (k-steps 0..2), and each freed portion is immediately refilled with the
+    // global loads of slice kt+2.  Spreading the LDS writes matters: the LDS write path
+    // is much narrower than the read path, a burst of 16 writes per lane stalls issue.
+    //   k-step 0..2: multiply | read fragments of the next step | write + refill a third
+    //   barrier: the other stage is complete, this stage will not be read again
     //   k-step 3: multiply | read fragments of step 0 of slice kt+1 from the other stage
     constexpr int MF = TM * TN, NR = TM + TN;
+    constexpr int C1 = (NS + 2) / 3, C2 = (2 * NS + 2) / 3;      // portion boundaries
     auto slice = [&](int kt, auto stash_next, auto fetch_next2) {
         constexpr bool kStash = decltype(stash_next)::value, kFetch = decltype(fetch_next2)::value;
         const char* base = lds + (kt & 1) * kStageBytes;
+        const int nst = (kt + 1) & 1;
         load_frags(base, 1, 1);
-        if (kStash) stash((kt + 1) & 1);
+        if (kStash) stash_range(nst, 0, C1);
+        if (kFetch) fetch_range(kt + 2, 0, C1);
         mma(0);
-        sched_hints<0, MF, NR, true, kDsWr, kStash ? LA + LB : 0>();
+        sched_hints<0, MF, NR, kStash ? C1 : 0, kFetch ? C1 : 0>();
         load_frags(base, 2, 0);
-        if (kFetch) fetch(kt + 2);
+        if (kStash) stash_range(nst, C1, C2);
+        if (kFetch) fetch_range(kt + 2, C1, C2);
         mma(1);
-        sched_hints<0, MF, NR, true, kVmemRd, kFetch ? LA + LB : 0>();
+        sched_hints<0, MF, NR, kStash ? C2 - C1 : 0, kFetch ? C2 - C1 : 0>();
         load_frags(base, 3, 1);
+        if (kStash) stash_range(nst, C2, NS);
+        if (kFetch) fetch_range(kt + 2, C2, NS);
         mma(0);
-        sched_hints<0, MF, NR, true, 0, 0>();
+        sched_hints<0, MF, NR, kStash ? NS - C2 : 0, kFetch ? NS - C2 : 0>();
         __syncthreads();
-        if (kStash) load_frags(lds + ((kt + 1) & 1) * kStageBytes, 0, 0);
+        if (kStash) load_frags(lds + nst * kStageBytes, 0, 0);
         mma(1);
-        sched_hints<0, MF, NR, kStash, 0, 0>();
+        sched_hints<0, MF, kStash ? NR : 0, 0, 0>();
     };
     const std::true_type yes{};
     const std::false_type no{};
@@ -235,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(
     //      output row m = m0 + (wm TM + i) 32 + l%32, column n = n0 + (wn TN + j) 32 + 8 (e/4) + 4 (l/32) + e%4.
     const int gm_lane = m0 + wm * TM * 32 + l32;
     const int gn_wave = n0 + wn * TN * 32;
-    if (vec_ok) {
+    if (vec_ok & 1) {
         // N % 8 == 0 and 16-byte aligned rows: runs of 4 / 8 columns are all inside or all outside.
         // Rows past M and runs past N (ragged edge tiles) are masked per lane.
         if (EPI == FREE_EPI_GATE_RESID) {
@@ -355,9 +371,10 @@ int32_t launch_one(const bf16_t* X, const bf16_t* W, const float* bias, int32_t 
     }
     // the vector epilogue needs 16-byte aligned rows of out / resid / bias / gate
     auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
-    const int32_t vec_ok = ((N & 7) == 0) && al16(bias) && al16(out) && al16(resid) && al16(gate.base) &&
-                           ((gate.stride & 3) == 0);
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(kThreads), lds, s, X, W, bias, M, N, K, tiles_m, tiles_n,
+    const bool vec = ((N & 7) == 0) && al16(bias) && al16(out) && al16(resid) && al16(gate.base) &&
+                     ((gate.stride & 3) == 0);
+    const int32_t vec_ok = (vec ? 1 : 0) | (g_wmap ? 2 : 0);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WGM * WGN * 64), lds, s, X, W, bias, M, N, K, tiles_m, tiles_n,
                        vec_ok, out, resid, gate);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
@@ -389,6 +406,14 @@ double cfg_score(int M, int N, int bm, int bn, double shape_eff) {
 
 }  // namespace
 
+static int g_variant_init = [] {
+    const char* e = std::getenv("FREE_GEMM_VARIANT");
+    const int v = e ? std::atoi(e) : 0;
+    g_variant = v % 10;
+    g_wmap = v / 10;
+    return v;
+}();
+
 bool mfma_linear_supported(int32_t M, int32_t N, int32_t K) {
     // 32-bit byte offsets inside a tile: 256 rows of K bf16
     return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && static_cast<int64_t>(K) * 2 * 256 < (1ll << 31);
@@ -399,10 +424,13 @@ int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, 
     if (!mfma_linear_supported(M, N, K)) return FREE_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W)) & 15u) return FREE_ERR_SHAPE;
     const double s256 = cfg_score(M, N, 256, 256, 1.00);
-    const double s2x1 = cfg_score(M, N, 256, 128, 0.90);
+    const double s2x1 = cfg_score(M, N, 256, 128, 0.80);
     const double s128 = cfg_score(M, N, 128, 128, 0.75);
-    if (s256 >= s2x1 && s256 >= s128)
+    if (s256 >= s2x1 && s256 >= s128) {
+        if (g_variant == 1) return launch_cfg<256, 256, 2, 4>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+        if (g_variant == 2) return launch_cfg<256, 256, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
         return launch_cfg<256, 256, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    }
     if (s2x1 >= s128) return launch_cfg<256, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
     return launch_cfg<128, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
 }
