@@ -1,0 +1,114 @@
+// adaLN modulation of every block and of the final layer in one launch, bf16 weights:
+//   mod[b, r] = sum_i SiLU(c)[b, i] W_r[i] + bias_r       (packed batch b, row r of the
+//   stacked modulation matrices; the conditioning vector c is constant across blocks,
+//   so the whole stack is one skinny GEMM that reads a third of all DiT parameters).
+// HBM-bound: every weight byte is needed exactly once per forward.  The packed batch
+// (<= 16 states per pass) is the N dimension of v_mfma_f32_16x16x32_bf16; weight rows are
+// the A operand and are loaded straight from global memory in the MFMA operand layout
+// (lane l: row l%16, 16 bytes at k = 8*(l/16)), so they never touch LDS.  The activation
+// operand lives in LDS, split into a bf16 high part and a bf16 remainder (two MFMAs per
+// k-step) so that the fp32 conditioning vector loses no precision.
+#include "free_internal.h"
+
+namespace freemi {
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kBatch = 16;
+
+__global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
+    const float* __restrict__ sc, int32_t B, int32_t D, const void* const* __restrict__ w_tab,
+    const float* const* __restrict__ b_tab, const int32_t* __restrict__ row_start, int32_t n_mats,
+    int32_t total_rows, int32_t blocks_per_wave, float* __restrict__ mod) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int row_bytes = D * 2 + 16;                       // odd number of 16-byte chunks per row
+    char* s_hi = lds;
+    char* s_lo = lds + kBatch * row_bytes;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // stage SiLU(c) as hi + lo bf16 parts; rows past B are zero
+    for (int i = tid; i < kBatch * (D / 2); i += kThreads) {
+        const int b = i / (D / 2), p = i % (D / 2);
+        float v0 = 0.f, v1 = 0.f;
+        if (b < B) {
+            const float2 v = reinterpret_cast<const float2*>(sc + static_cast<int64_t>(b) * D)[p];
+            v0 = v.x;
+            v1 = v.y;
+        }
+        const uint32_t hi = pack_bf16_pair(v0, v1);
+        const float r0 = v0 - __uint_as_float(hi << 16), r1 = v1 - __uint_as_float(hi & 0xffff0000u);
+        *reinterpret_cast<uint32_t*>(s_hi + b * row_bytes + p * 4) = hi;
+        *reinterpret_cast<uint32_t*>(s_lo + b * row_bytes + p * 4) = pack_bf16_pair(r0, r1);
+    }
+    __syncthreads();
+
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int nblocks = total_rows / 16;
+    const int first = (blockIdx.x * kWaves + wave) * blocks_per_wave;
+    const char* bh = s_hi + l16 * row_bytes + lq * 16;
+    const char* bl = s_lo + l16 * row_bytes + lq * 16;
+    const int steps = D / 32;
+    int mat = 0;
+    for (int blk = first; blk < first + blocks_per_wave && blk < nblocks; ++blk) {
+        const int r0 = blk * 16;
+        while (mat + 1 < n_mats && r0 >= row_start[mat + 1]) ++mat;
+        const int lr0 = r0 - row_start[mat];
+        const char* wrow = static_cast<const char*>(w_tab[mat]) + (static_cast<int64_t>(lr0 + l16) * D) * 2 + lq * 16;
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 6
+        for (int st = 0; st < steps; ++st) {
+            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(wrow + st * 64));
+            const bf16x8_t h = *reinterpret_cast<const bf16x8_t*>(bh + st * 64);
+            const bf16x8_t l = *reinterpret_cast<const bf16x8_t*>(bl + st * 64);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acc, 0, 0, 0);
+        }
+        // accumulator register i of lane l: weight row 4*(l/16) + i, batch column l%16
+        if (l16 < B) {
+            const f32x4_t bias = *reinterpret_cast<const f32x4_t*>(b_tab[mat] + lr0 + 4 * lq);
+            f32x4_t o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = acc[i] + bias[i];
+            *reinterpret_cast<f32x4_t*>(mod + static_cast<int64_t>(l16) * total_rows + r0 + 4 * lq) = o;
+        }
+    }
+}
+
+}  // namespace
+
+// Supported: bf16 weights, D % 32 == 0; every matrix has a multiple of 16 rows (true for
+// the 6D / 2D row stacks when D % 8 == 0).  16-byte aligned weight rows, biases and mod.
+bool adaln_mfma_supported(int32_t D, int32_t total_rows) { return D % 32 == 0 && total_rows % 16 == 0 && D <= 2048; }
+
+int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* const* w_tab,
+                          const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
+                          int32_t total_rows, float* mod, hipStream_t s) {
+    const int nblocks = total_rows / 16;
+    const int blocks_per_wave = nblocks >= 8192 ? 6 : 1;
+    const int waves = (nblocks + blocks_per_wave - 1) / blocks_per_wave;
+    const int grid = (waves + kWaves - 1) / kWaves;
+    const size_t lds = 2 * static_cast<size_t>(kBatch) * (D * 2 + 16);
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(adaln_mfma_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024)))
+            return FREE_ERR_HIP;
+        attr_set = true;
+    }
+    for (int b0 = 0; b0 < B; b0 += kBatch) {
+        const int nb = (B - b0 < kBatch) ? B - b0 : kBatch;
+        hipLaunchKernelGGL(adaln_mfma_kernel, dim3(grid), dim3(kThreads), lds, s, sc + static_cast<int64_t>(b0) * D,
+                           nb, D, w_tab, b_tab, row_start, n_mats, total_rows, blocks_per_wave,
+                           mod + static_cast<int64_t>(b0) * total_rows);
+        if (!launch_ok()) return FREE_ERR_HIP;
+    }
+    return FREE_OK;
+}
+
+}  // namespace freemi

@@ -199,6 +199,58 @@ __global__ __launch_bounds__(kThreads) void ln_modulate_kernel(
     }
 }
 
+// Same operation with the row held in registers: one 16-byte load per element group,
+// statistics from registers, one packed store.  HBM-bound (reads 4 B, writes 2 or 4 B per
+// element); needs D % 4 == 0, D <= 256 NV and 16-byte aligned rows.
+template <typename OT, int NV>
+__global__ __launch_bounds__(kThreads) void ln_modulate_vec_kernel(
+    const float* __restrict__ x, RowVec shift, RowVec scale, int32_t M, int32_t D, OT* __restrict__ out) {
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const int nvec = D >> 2;
+    const float4* xr = reinterpret_cast<const float4*>(x + row * D);
+    float4 xv[NV];
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = lane + 64 * k;
+        xv[k] = (v < nvec) ? xr[v] : make_float4(0.f, 0.f, 0.f, 0.f);
+        s += (xv[k].x + xv[k].y) + (xv[k].z + xv[k].w);
+    }
+    const float mean = wave_sum_f(s) / static_cast<float>(D);
+    float q = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        if (lane + 64 * k < nvec) {
+            const float a = xv[k].x - mean, b = xv[k].y - mean, c = xv[k].z - mean, d = xv[k].w - mean;
+            q += (a * a + b * b) + (c * c + d * d);
+        }
+    }
+    const float rstd = rsqrtf(wave_sum_f(q) / static_cast<float>(D) + kLnEps);
+    const float4* sh = reinterpret_cast<const float4*>(shift.base + (row / shift.rows_per_sample) * shift.stride);
+    const float4* sc = reinterpret_cast<const float4*>(scale.base + (row / scale.rows_per_sample) * scale.stride);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = lane + 64 * k;
+        if (v < nvec) {
+            const float4 h = sh[v], c = sc[v];
+            const float o0 = fmaf((xv[k].x - mean) * rstd, 1.0f + c.x, h.x);
+            const float o1 = fmaf((xv[k].y - mean) * rstd, 1.0f + c.y, h.y);
+            const float o2 = fmaf((xv[k].z - mean) * rstd, 1.0f + c.z, h.z);
+            const float o3 = fmaf((xv[k].w - mean) * rstd, 1.0f + c.w, h.w);
+            if constexpr (sizeof(OT) == 2) {
+                uint2 pk;
+                pk.x = pack_bf16_pair(o0, o1);
+                pk.y = pack_bf16_pair(o2, o3);
+                reinterpret_cast<uint2*>(out + row * D)[v] = pk;
+            } else {
+                reinterpret_cast<float4*>(out + row * D)[v] = make_float4(o0, o1, o2, o3);
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Plain tiled linear layer: out = epilogue(A[M,K] W[N,K]^T + bias), fp32 accumulate.
 // 64x64 tile, 16-deep K slices in LDS, 4x4 outputs per thread.
@@ -480,6 +532,28 @@ int32_t launch_patch_embed(const float* x, int32_t x_mod, int32_t B, int32_t C, 
 int32_t launch_ln_modulate(const float* x, RowVec shift, RowVec scale, int32_t M, int32_t D, int32_t dtype,
                            void* out, hipStream_t s) {
     const int blocks = (M + kWaves - 1) / kWaves;
+    auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+    const bool vec = (D % 4 == 0) && D <= 2048 && al16(x) && al16(out) && al16(shift.base) && al16(scale.base) &&
+                     (shift.stride % 4 == 0) && (scale.stride % 4 == 0);
+    if (vec) {
+        const int nv = (D / 4 + 63) / 64;
+#define FREE_LN_CASE(OT, NV)                                                                                   \
+    hipLaunchKernelGGL((ln_modulate_vec_kernel<OT, NV>), dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, D, \
+                       static_cast<OT*>(out))
+        if (dtype == FREE_BF16) {
+            if (nv <= 1) FREE_LN_CASE(bf16_t, 1);
+            else if (nv <= 2) FREE_LN_CASE(bf16_t, 2);
+            else if (nv <= 5) FREE_LN_CASE(bf16_t, 5);
+            else FREE_LN_CASE(bf16_t, 8);
+        } else {
+            if (nv <= 1) FREE_LN_CASE(float, 1);
+            else if (nv <= 2) FREE_LN_CASE(float, 2);
+            else if (nv <= 5) FREE_LN_CASE(float, 5);
+            else FREE_LN_CASE(float, 8);
+        }
+#undef FREE_LN_CASE
+        return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+    }
     if (dtype == FREE_BF16)
         hipLaunchKernelGGL(ln_modulate_kernel<bf16_t>, dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, D,
                            static_cast<bf16_t*>(out));

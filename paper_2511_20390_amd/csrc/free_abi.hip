@@ -181,8 +181,12 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     }
     {
     ProfScope prof(PROF_ADALN, s);
-    FREE_TRY(launch_adaln(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1, d.mod_rows,
-                          d.mode, mod, s));
+    if (d.mode == FREE_BF16 && adaln_mfma_supported(d.D, d.mod_rows))
+        FREE_TRY(launch_adaln_mfma(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1,
+                                   d.mod_rows, mod, s));
+    else
+        FREE_TRY(launch_adaln(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1, d.mod_rows,
+                              d.mode, mod, s));
     }
     {
     ProfScope prof(PROF_PATCH, s);

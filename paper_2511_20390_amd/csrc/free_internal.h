@@ -35,6 +35,16 @@ __host__ __device__ inline bf16_t float_to_bf16(float f) {
     return r;
 }
 
+#if defined(__HIPCC__)
+// two floats -> packed bf16 pair (low half = first), hardware round-to-nearest-even
+__device__ inline uint32_t pack_bf16_pair(float lo, float hi) {
+    typedef float f2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 b2_t __attribute__((ext_vector_type(2)));
+    const f2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
+}
+#endif
+
 __device__ inline float load_f(const float* p) { return *p; }
 __device__ inline float load_f(const bf16_t* p) { return bf16_to_float(*p); }
 __device__ inline void store_f(float* p, float v) { *p = v; }
@@ -124,6 +134,12 @@ int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const fl
                            int64_t hw, float* m_out, hipStream_t s);
 int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_t K, int32_t dup,
                          int32_t* t_out, int32_t* y_out, hipStream_t s);
+
+// ---- MFMA adaLN modulation GEMV, bf16 weights (adaln_mfma.hip)
+bool adaln_mfma_supported(int32_t D, int32_t total_rows);
+int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* const* w_tab,
+                          const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
+                          int32_t total_rows, float* mod, hipStream_t s);
 
 // ---- MFMA kernels, bf16 only (gemm_mfma.hip, attn_mfma.hip) ------------------------
 bool mfma_linear_supported(int32_t M, int32_t N, int32_t K);

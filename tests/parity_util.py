@@ -92,41 +92,55 @@ def round_case(name, mode, K, cfg_scale, seed, calibrated=True):
     return cfg, w, sched, ri
 
 
-def run_round_parity(name, mode="fp32", K=6, cfg_scale=4.0, seed=0, verbose=False, samples=None):
+def run_round_parity(name, mode="fp32", K=6, cfg_scale=4.0, seed=0, verbose=False, relaxed=False, sep=1.349):
     """spec_round on the GPU vs the oracle: (i) target means within the DiT tolerance,
     (ii) the GPU decisions equal the oracle's verification applied to the GPU means
-    (composition), (iii) information only: agreement with the all-oracle round."""
+    (composition), (iii) information only: agreement with the all-oracle round.
+
+    The round is a self-consistent drafting chain built with the ORACLE: for each k the
+    target mean m_k of the current state is computed, a draft mean is placed at distance
+    sep*sigma from it (sep = 1.349 gives a 50% acceptance rate), the next draft is a
+    sample of that proposal and becomes the next packed state - so outcomes are mixed."""
     import torch
     from paper_2511_20390_amd import binding
     cfg, w, sched, ri = round_case(name, mode, K, cfg_scale, seed)
     d = synth.latent_dim(cfg)
-    x_states = ri["x_states"].astype(np.float64)
-    # oracle means for the states as given
     cx64, ce64 = ri["coef_x"].astype(np.float64), ri["coef_eps"].astype(np.float64)
-    m_ref = fo.round_means(w, cfg, x_states, ri["t"], ri["y"], cfg_scale, cx64, ce64).reshape(K, d)
-    # calibrated draft means around the oracle means (mixed accept / reject)
-    rng = np.random.default_rng(seed + 1234)
     sig = ri["sigma"].astype(np.float64)
-    m_draft = (m_ref + (1.349 / math.sqrt(d)) * sig[:, None] * rng.standard_normal((K, d))).astype(np.float32)
+    rng = np.random.default_rng(seed + 1234)
+    shape = ri["x_states"].shape[1:]
+    states = [ri["x_states"][0].astype(np.float32)]
+    m_ref = np.empty((K, d))
+    m_draft = np.empty((K, d), np.float32)
+    for k in range(K):
+        m_ref[k] = fo.round_means(w, cfg, states[k][None].astype(np.float64), ri["t"][k:k + 1], ri["y"], cfg_scale,
+                                  cx64[k:k + 1], ce64[k:k + 1]).reshape(d)
+        m_draft[k] = (m_ref[k] + (sep / math.sqrt(d)) * sig[k] * rng.standard_normal(d)).astype(np.float32)
+        states.append((m_draft[k] + sig[k] * rng.standard_normal(d)).astype(np.float32).reshape(shape))
+    x_states = np.ascontiguousarray(np.stack(states[:K]))
+    x_last = np.ascontiguousarray(states[K])
+    # the oracle means above were computed state by state; the fp32 states fed to both sides are identical
     model = binding.FreeDit(cfg, w, mode)
-    lam = None
-    out = model.spec_round(to_dev(ri["x_states"]), to_dev(ri["x_last"]), to_dev(m_draft), to_dev(ri["t"]),
+    lam = ri["lam"] if relaxed else None
+    out = model.spec_round(to_dev(x_states), to_dev(x_last), to_dev(m_draft), to_dev(ri["t"]),
                            ri["y"], cfg_scale, to_dev(ri["coef_x"]), to_dev(ri["coef_eps"]), to_dev(ri["sigma"]),
-                           to_dev(ri["u"]), lam)
+                           to_dev(ri["u"]), None if lam is None else to_dev(lam))
     torch.cuda.synchronize()
     m_gpu = out["m_target"].cpu().numpy().astype(np.float64)
     # (i) means: the eps error is what the tolerance speaks of; means inherit it scaled
-    eps_ref = (m_ref - cx64[:, None] * x_states.reshape(K, d)) / ce64[:, None]
-    eps_gpu = (m_gpu - cx64[:, None] * x_states.reshape(K, d)) / ce64[:, None]
+    xs = x_states.reshape(K, d).astype(np.float64)
+    eps_ref = (m_ref - cx64[:, None] * xs) / ce64[:, None]
+    eps_gpu = (m_gpu - cx64[:, None] * xs) / ce64[:, None]
     err_eps = rel_l2(eps_gpu, eps_ref)
     err_m = rel_l2(m_gpu, m_ref)
     # (ii) composition: oracle verification on the GPU-produced means
-    xd = np.concatenate([ri["x_states"][1:], ri["x_last"][None]], 0).reshape(K, d)
-    ref = fo.spec_verify(m_gpu[None], m_draft[None], xd[None], ri["sigma"][None], ri["u"][None], lam)
+    xd = np.concatenate([x_states[1:], x_last[None]], 0).reshape(K, d)
+    lam_o = None if lam is None else lam[None]
+    ref = fo.spec_verify(m_gpu[None], m_draft[None], xd[None], ri["sigma"][None], ri["u"][None], lam_o)
     stats = compare_verify(dict(accept=out["accept"], n_accept=out["n_accept"], log_ratio=out["log_ratio"],
                                 x_out=out["x_out"]), ref, lam, ri["u"], f"round {name}/{mode}")
-    full = fo.spec_verify(m_ref[None], m_draft[None], xd[None], ri["sigma"][None], ri["u"][None], lam)
-    stats.update(err_eps=err_eps, err_m=err_m,
+    full = fo.spec_verify(m_ref[None], m_draft[None], xd[None], ri["sigma"][None], ri["u"][None], lam_o)
+    stats.update(err_eps=err_eps, err_m=err_m, n_accept=int(out["n_accept"].item()),
                  agree_full=int((full["accept"] == out["accept"].cpu().numpy().reshape(1, K)).sum()))
     if verbose:
         print(f"round {name}/{mode}: eps rel-L2 {err_eps:.3e}, mean rel-L2 {err_m:.3e}, "

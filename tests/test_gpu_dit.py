@@ -134,10 +134,71 @@ def test_forward_packing_invariance(mode):
 @pytest.mark.parametrize("mode", ["fp32", "bf16"])
 @pytest.mark.parametrize("name,cfg_scale", [("tiny", 4.0), ("tiny", 1.0), ("small", 4.0)])
 def test_round_parity(name, cfg_scale, mode):
-    st = pu.run_round_parity(name, mode=mode, K=6, cfg_scale=cfg_scale, seed=11, verbose=True)
-    assert st["ties"] == 0 or st["ties"] < 6
+    seen = set()
+    for seed in (11, 12, 13, 14):
+        st = pu.run_round_parity(name, mode=mode, K=6, cfg_scale=cfg_scale, seed=seed, verbose=True,
+                                 relaxed=(seed % 2 == 0))
+        seen.add(st["n_accept"])
+    assert len(seen) >= 2          # the rounds really end at different drafts
 
 
-def test_round_k1_and_relaxed():
+def test_round_k1_and_all_outcomes():
     pu.run_round_parity("tiny", mode="fp32", K=1, cfg_scale=4.0, seed=5, verbose=True)
     pu.run_round_parity("tiny", mode="fp32", K=3, cfg_scale=1.5, seed=6, verbose=True)
+    # far-away draft means: rejected at the first draft, reflection written
+    st = pu.run_round_parity("tiny", mode="fp32", K=4, cfg_scale=4.0, seed=7, verbose=True, sep=8.0)
+    assert st["n_accept"] == 0 and st["reflected"] == 1
+    # identical means up to rounding: everything accepted
+    st = pu.run_round_parity("tiny", mode="fp32", K=4, cfg_scale=4.0, seed=8, verbose=True, sep=1e-3)
+    assert st["n_accept"] == 4
+
+
+# ---- full DiT-XL/2 shapes, in the launch configuration bench.py times -------------
+def _xl_round(name, K, cfg_scale, mode, oracle_states):
+    """spec_round at a DiT-XL/2 shape.  The oracle (fp64, minutes for a whole pack) is run
+    on `oracle_states` of the K packed states only (each with its null-label twin): the
+    states of a pack are independent, so their means are comparable one by one; the
+    verification outputs are checked by composition on the GPU-produced means."""
+    import torch
+    from paper_2511_20390_amd import binding
+    cfg = synth.dit_config(name)
+    w = pu.weights_for(cfg, mode, seed=0)
+    sched = fo.ddpm_schedule()
+    ri = synth.make_round_inputs(cfg, K, 0, sched["sigma_clipped"], 0.1)
+    cx, ce = fo.mean_coefficients(ri["t"], sched)
+    d = synth.latent_dim(cfg)
+    # oracle means of the sampled states
+    m_ref = {}
+    for k in oracle_states:
+        m_ref[k] = fo.round_means(w, cfg, ri["x_states"][k:k + 1], ri["t"][k:k + 1], ri["y"], cfg_scale,
+                                  cx[k:k + 1], ce[k:k + 1]).reshape(d)
+    model = binding.FreeDit(cfg, w, mode)
+    out = model.spec_round(pu.to_dev(ri["x_states"]), pu.to_dev(ri["x_last"]), pu.to_dev(ri["m_draft"]),
+                           pu.to_dev(ri["t"]), ri["y"], cfg_scale, pu.to_dev(cx.astype(np.float32)),
+                           pu.to_dev(ce.astype(np.float32)), pu.to_dev(ri["sigma"]), pu.to_dev(ri["u"]), None)
+    torch.cuda.synchronize()
+    m_gpu = out["m_target"].cpu().numpy().astype(np.float64)
+    xs = ri["x_states"].reshape(K, d).astype(np.float64)
+    for k in oracle_states:
+        eps_ref = (m_ref[k] - cx[k] * xs[k]) / ce[k]
+        eps_gpu = (m_gpu[k] - np.float32(cx[k]).astype(np.float64) * xs[k]) / np.float32(ce[k]).astype(np.float64)
+        err = pu.rel_l2(eps_gpu, eps_ref)
+        print(f"{name}/{mode} state {k}: eps rel-L2 {err:.3e}")
+        assert err <= pu.DIT_REL_L2[mode]
+    xd = np.concatenate([ri["x_states"][1:], ri["x_last"][None]], 0).reshape(K, d)
+    ref = fo.spec_verify(m_gpu[None], ri["m_draft"][None], xd[None], ri["sigma"][None], ri["u"][None])
+    pu.compare_verify(dict(accept=out["accept"], n_accept=out["n_accept"], log_ratio=out["log_ratio"],
+                           x_out=out["x_out"]), ref, None, ri["u"], f"xl round {name}/{mode}")
+    model.close()
+
+
+def test_xl2_256_round_bf16():
+    _xl_round("xl2_256", 6, 1.0, "bf16", oracle_states=[0, 5])
+
+
+def test_xl2_512_cfg_round_bf16():
+    _xl_round("xl2_512", 6, 4.0, "bf16", oracle_states=[3])
+
+
+def test_xl2_256_round_fp32():
+    _xl_round("xl2_256", 6, 4.0, "fp32", oracle_states=[2])
