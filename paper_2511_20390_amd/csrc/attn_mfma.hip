@@ -35,13 +35,7 @@ constexpr int VROW = 144;                 // bytes per V^T row in LDS: 64 keys (
 
 __device__ inline int swap_bits_2_3(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
-__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
-    // round-to-nearest-even on both halves (inputs are finite and non-negative here)
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
-}
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) { return pack_bf16_pair(lo, hi); }   // v_cvt_pk_bf16_f32
 
 template <int DH, int QT>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __restrict__ qkv, int32_t N,
@@ -264,13 +258,10 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
 template <int DH>
 int32_t launch_dh(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, bf16_t* out, hipStream_t s) {
     const float scale_log2 = 1.4426950408889634f / std::sqrt(static_cast<float>(DH));
-    if (N >= 512) {
-        dim3 grid((N + 255) / 256, heads, B);
-        hipLaunchKernelGGL((attn_mfma_kernel<DH, 2>), grid, dim3(kThreads), 0, s, qkv, N, heads, scale_log2, out);
-    } else {
-        dim3 grid((N + 127) / 128, heads, B);
-        hipLaunchKernelGGL((attn_mfma_kernel<DH, 1>), grid, dim3(kThreads), 0, s, qkv, N, heads, scale_log2, out);
-    }
+    // one 32-query tile per wavefront: 128 queries per workgroup, two workgroups per CU
+    // (measured faster than two query tiles per wavefront at one workgroup per CU)
+    dim3 grid((N + 127) / 128, heads, B);
+    hipLaunchKernelGGL((attn_mfma_kernel<DH, 1>), grid, dim3(kThreads), 0, s, qkv, N, heads, scale_log2, out);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 

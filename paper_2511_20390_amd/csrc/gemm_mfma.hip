@@ -4,25 +4,35 @@
 // Both operands are K-contiguous, which is exactly the per-lane operand layout of
 // v_mfma_f32_32x32x16_bf16 (lane l: row/col l%32, 8 consecutive k at 8*(l/32)).
 //
-// Design for gfx950 (64-wide wavefronts, 160 KB LDS per CU, 512 VGPR+AGPR per lane):
-//  * workgroup = 256 threads = 4 wavefronts in a WGM x WGN grid, macro tile BM x BN,
-//    K slices of 64; each wavefront owns (BM/WGM) x (BN/WGN) as TM x TN MFMA tiles,
-//    accumulators stay in AGPRs for the whole K loop.
+// Design for gfx950 (64-wide wavefronts, 160 KB LDS per CU, 512 registers per lane):
+//  * workgroup = 4 or 8 wavefronts in a WGM x WGN grid, macro tile BM x BN (256x256 and
+//    384x192 with 8 wavefronts - two per SIMD, so one wavefront's memory instructions issue
+//    under the other's MFMAs - 256x128 / 128x128 with 4 for small problems), K slices of
+//    64; each wavefront owns (BM/WGM) x (BN/WGN) as TM x TN MFMA tiles of 32x32 and keeps
+//    the accumulators in registers for the whole K loop.
 //  * the MFMA takes the WEIGHT rows as its A operand and the activation rows as its
 //    B operand, i.e. it accumulates C^T tiles: a lane then owns one output ROW m
 //    (lane % 32) and runs of 4 consecutive output columns n per register group.  The
 //    epilogue therefore needs no transposition: one v_permlane32_swap pairs the two
 //    half-waves' runs into 8 consecutive bf16 (a 16-byte store), and the fp32
-//    residual update is a float4 read-modify-write.
+//    residual update is a float4 read-modify-write with all loads of a column tile
+//    issued before its first store.
 //  * LDS: two stages of [BM + BN rows][64 bf16]; the 16-byte chunk index of a row is
-//    XOR-swizzled with (row % 8): ds_read_b128 fragment reads are bank-conflict free
-//    and global loads stay 128-byte coalesced.
-//  * software pipeline: global loads run two slices ahead (slice kt+2 is in flight
-//    in registers while slice kt+1 is written to the other LDS stage and slice kt is
-//    multiplied); MFMA operand fragments are double-buffered in registers so every
-//    LDS read is issued one k-step before its use.  One barrier per slice.
+//    XOR-swizzled with (row % 8) for the ds_read_b128 fragment reads while global
+//    loads stay 128-byte coalesced.
+//  * global loads are buffer loads (descriptor + one per-lane offset + scalar offsets):
+//    no address registers, and rows past the end of a ragged edge tile read as zero.
+//  * software pipeline: global loads run two slices ahead (slice kt+2 is in flight in
+//    registers while slice kt+1 is written to the other LDS stage and slice kt is
+//    multiplied); the LDS writes and the refills are spread over three of the four
+//    k-steps; MFMA operand fragments are double-buffered in registers so every LDS read
+//    is issued one k-step before its use; issue order is pinned with
+//    sched_group_barrier.  One barrier per slice, placed before the last k-step so the
+//    first fragments of the next slice are read under that step's MFMAs.
 //  * workgroup ids are remapped so that each of the 8 XCDs (round-robin dispatch)
 //    works on a compact, L2-friendly group of tiles.
+//  * the tile configuration is chosen per problem from a measured time model (whole
+//    rounds of workgroups x (K slices x time per slice + per-tile fixed cost)).
 #include <cmath>
 #include <cstdlib>
 #include <type_traits>
@@ -41,7 +51,6 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-static int g_variant = 0, g_wmap = 0;
 constexpr int BK = 64;                    // bf16 elements per K slice (128 bytes per row)
 constexpr int kRowBytes = BK * 2;
 constexpr int kNumXcd = 8;
@@ -115,24 +124,21 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
 
     // ---- global -> register staging: chunk idx = i*NT + tid, row = idx/8, chunk = idx%8
     const int ld_chunk = tid & 7;
-    const int ld_row = (vec_ok & 2) ? (wave * 8 + ((lane >> 3) & 3) * 2 + (lane >> 5)) : (tid >> 3);
-    const char* xbase = reinterpret_cast<const char*>(X + static_cast<int64_t>(m0) * K);
-    const char* wbase = reinterpret_cast<const char*>(W + static_cast<int64_t>(n0) * K);
-    int a_off[LA], b_off[LB];                          // byte offsets from the tile bases
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        int row = ld_row + RP * i;
-        if (m0 + row >= M) row = M - 1 - m0;
-        a_off[i] = row * K * 2 + ld_chunk * 16;
-    }
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        int row = ld_row + RP * i;
-        if (n0 + row >= N) row = N - 1 - n0;
-        b_off[i] = row * K * 2 + ld_chunk * 16;
-    }
+    const int ld_row = tid >> 3;
+    // Buffer descriptors over the rows of this tile: a load past the end of the matrix (rows
+    // of a ragged edge tile) returns zeros, so no row clamping and no address registers -
+    // one per-lane byte offset plus wave-uniform (scalar) offsets per load and per slice.
+    const int64_t x_left = static_cast<int64_t>(M - m0) * K * 2, w_left = static_cast<int64_t>(N - n0) * K * 2;
+    const __amdgpu_buffer_rsrc_t xsrd = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(X + static_cast<int64_t>(m0) * K), 0,
+        static_cast<int>(x_left < 0x7fffffff ? x_left : 0x7fffffff), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wsrd = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(W + static_cast<int64_t>(n0) * K), 0,
+        static_cast<int>(w_left < 0x7fffffff ? w_left : 0x7fffffff), 0x00020000);
+    const int ld_voff = ld_row * K * 2 + ld_chunk * 16;       // per-lane byte offset inside the tile
+    const int pass_bytes = RP * K * 2;                        // RP rows further down per load index
     const int st_off = ld_row * kRowBytes + ((ld_chunk ^ (ld_row & 7)) << 4);   // + i*RP rows per load
-    u32x4_t sa[LA], sb[LB];
+    u32x4_t sreg[LA + LB];                              // staging registers: one K slice in flight
     const int nk = (K + BK - 1) / BK;
 
     // staging register idx in [0, LA + LB): the first LA hold X rows, the rest W rows
@@ -143,12 +149,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
 #pragma unroll
         for (int idx = 0; idx < NS; ++idx) {
             if (idx < lo || idx >= hi) continue;
-            if (idx < LA) {
-                sa[idx] = in_k ? *reinterpret_cast<const u32x4_t*>(xbase + kbyte + a_off[idx]) : u32x4_t{0, 0, 0, 0};
-            } else {
-                sb[idx - LA] =
-                    in_k ? *reinterpret_cast<const u32x4_t*>(wbase + kbyte + b_off[idx - LA]) : u32x4_t{0, 0, 0, 0};
-            }
+            const u32x4_t v = (idx < LA)
+                                  ? __builtin_amdgcn_raw_buffer_load_b128(xsrd, ld_voff, idx * pass_bytes + kbyte, 0)
+                                  : __builtin_amdgcn_raw_buffer_load_b128(wsrd, ld_voff, (idx - LA) * pass_bytes + kbyte, 0);
+            sreg[idx] = in_k ? v : u32x4_t{0, 0, 0, 0};
         }
     };
     auto stash_range = [&](int stage, int lo, int hi) {
@@ -156,14 +160,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
 #pragma unroll
         for (int idx = 0; idx < NS; ++idx) {
             if (idx < lo || idx >= hi) continue;
-            if (idx < LA)
-                *reinterpret_cast<u32x4_t*>(base + idx * RP * kRowBytes) = sa[idx];
-            else
-                *reinterpret_cast<u32x4_t*>(base + (BM + (idx - LA) * RP) * kRowBytes) = sb[idx - LA];
+            const int row = (idx < LA) ? idx * RP : BM + (idx - LA) * RP;
+            *reinterpret_cast<u32x4_t*>(base + row * kRowBytes) = sreg[idx];
         }
     };
-    auto fetch = [&](int kt) { fetch_range(kt, 0, NS); };
-    auto stash = [&](int stage) { stash_range(stage, 0, NS); };
 
     // ---- MFMA operand fragments: row fixed per lane, chunk varies with the k step
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -206,8 +206,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     //   k-step 3: multiply | read fragments of step 0 of slice kt+1 from the other stage
     constexpr int MF = TM * TN, NR = TM + TN;
     constexpr int C1 = (NS + 2) / 3, C2 = (2 * NS + 2) / 3;      // portion boundaries
-    auto slice = [&](int kt, auto stash_next, auto fetch_next2) {
-        constexpr bool kStash = decltype(stash_next)::value, kFetch = decltype(fetch_next2)::value;
+    auto slice = [&](int kt, auto stash_next, auto fetch_ahead) {
+        constexpr bool kStash = decltype(stash_next)::value, kFetch = decltype(fetch_ahead)::value;
         const char* base = lds + (kt & 1) * kStageBytes;
         const int nst = (kt + 1) & 1;
         load_frags(base, 1, 1);
@@ -233,12 +233,14 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     const std::true_type yes{};
     const std::false_type no{};
 
-    // ---- prologue
-    fetch(0);
-    stash(0);
-    if (nk > 1) fetch(1);
+    // ---- prologue: slice 0 through the registers into LDS stage 0, slice 1 into the registers
+    fetch_range(0, 0, NS);
+    stash_range(0, 0, NS);
+    if (nk > 1) fetch_range(1, 0, NS);
     __syncthreads();
     load_frags(lds, 0, 0);
+    // ---- steady state: slice kt multiplies while slice kt+1 moves registers -> LDS and
+    //      slice kt+2 is requested from global memory
     int kt = 0;
     for (; kt + 2 < nk; ++kt) slice(kt, yes, yes);
     if (kt + 1 < nk) {
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     //      output row m = m0 + (wm TM + i) 32 + l%32, column n = n0 + (wn TN + j) 32 + 8 (e/4) + 4 (l/32) + e%4.
     const int gm_lane = m0 + wm * TM * 32 + l32;
     const int gn_wave = n0 + wn * TN * 32;
-    if (vec_ok & 1) {
+    if (vec_ok) {
         // N % 8 == 0 and 16-byte aligned rows: runs of 4 / 8 columns are all inside or all outside.
         // Rows past M and runs past N (ragged edge tiles) are masked per lane.
         if (EPI == FREE_EPI_GATE_RESID) {
@@ -373,7 +375,7 @@ int32_t launch_one(const bf16_t* X, const bf16_t* W, const float* bias, int32_t 
     auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
     const bool vec = ((N & 7) == 0) && al16(bias) && al16(out) && al16(resid) && al16(gate.base) &&
                      ((gate.stride & 3) == 0);
-    const int32_t vec_ok = (vec ? 1 : 0) | (g_wmap ? 2 : 0);
+    const int32_t vec_ok = vec ? 1 : 0;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WGM * WGN * 64), lds, s, X, W, bias, M, N, K, tiles_m, tiles_n,
                        vec_ok, out, resid, gate);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
@@ -396,42 +398,45 @@ int32_t launch_cfg(const bf16_t* X, const bf16_t* W, const float* bias, int32_t 
 #undef FREE_GEMM_CASE
 }
 
-// Fraction of the last wave of workgroups that is busy, times a per-shape efficiency guess.
-double cfg_score(int M, int N, int bm, int bn, double shape_eff) {
+// Estimated time (us) of a tile configuration on `cus` compute units: workgroup rounds times
+// (K slices x measured time per slice + per-tile prologue/epilogue), measured on MI355X.
+double cfg_time(int M, int N, int K, int bm, int bn, double us_per_slice, double us_fixed, int cus) {
     const double tiles = static_cast<double>((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-    const double waves = std::ceil(tiles / 256.0);
-    const double useful = (static_cast<double>(M) * N) / (tiles * bm * bn);
-    return tiles / (waves * 256.0) * useful * shape_eff;
+    const double rounds = std::ceil(tiles / cus);
+    return rounds * (((K + BK - 1) / BK) * us_per_slice + us_fixed);
+}
+
+int device_cus() {
+    static int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return cus;
 }
 
 }  // namespace
 
-static int g_variant_init = [] {
-    const char* e = std::getenv("FREE_GEMM_VARIANT");
-    const int v = e ? std::atoi(e) : 0;
-    g_variant = v % 10;
-    g_wmap = v / 10;
-    return v;
-}();
-
 bool mfma_linear_supported(int32_t M, int32_t N, int32_t K) {
-    // 32-bit byte offsets inside a tile: 256 rows of K bf16
-    return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && static_cast<int64_t>(K) * 2 * 256 < (1ll << 31);
+    // 32-bit byte offsets inside a tile: up to 384 rows of K bf16
+    return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && static_cast<int64_t>(K) * 2 * 384 < (1ll << 31);
 }
 
 int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
                            int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s) {
     if (!mfma_linear_supported(M, N, K)) return FREE_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W)) & 15u) return FREE_ERR_SHAPE;
-    const double s256 = cfg_score(M, N, 256, 256, 1.00);
-    const double s2x1 = cfg_score(M, N, 256, 128, 0.80);
-    const double s128 = cfg_score(M, N, 128, 128, 0.75);
-    if (s256 >= s2x1 && s256 >= s128) {
-        if (g_variant == 1) return launch_cfg<256, 256, 2, 4>(X, W, bias, M, N, K, epi, out, resid, gate, s);
-        if (g_variant == 2) return launch_cfg<256, 256, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
-        return launch_cfg<256, 256, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
-    }
-    if (s2x1 >= s128) return launch_cfg<256, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    const int cus = device_cus();
+    const double t256 = cfg_time(M, N, K, 256, 256, 1.83, 9.0, cus);
+    const double t384 = cfg_time(M, N, K, 384, 192, 2.06, 10.0, cus);
+    const double t2x1 = cfg_time(M, N, K, 256, 128, 1.31, 6.0, cus);
+    const double t128 = cfg_time(M, N, K, 128, 128, 0.80, 4.0, cus);
+    const double best = std::fmin(std::fmin(t256, t384), std::fmin(t2x1, t128));
+    if (best == t384) return launch_cfg<384, 192, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    if (best == t256) return launch_cfg<256, 256, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    if (best == t2x1) return launch_cfg<256, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
     return launch_cfg<128, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
 }
 
