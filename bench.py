@@ -40,6 +40,29 @@ def forward_flops(cfg, B):
     return per, total
 
 
+# kernel symbol (as rocprofv3 prints it) behind each profiled category, to look its measured
+# HBM traffic up in the committed rocprofv3 --pmc summary
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "spec_round_xl2_512_hbm_traffic.md")
+CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<384, 192, 4, 2, 1, true>", "gemm_qkv": "gemm_bf16_kernel<256, 256, 4, 2, 0, true>",
+                   "attention": "attn_mfma_kernel<72, 1>", "verify_partial": "verify_partial_kernel<true>"}
+
+
+def measured_traffic(category):
+    """{'fetch_MB', 'write_MB'} per launch from the committed FETCH_SIZE / WRITE_SIZE summary, or None."""
+    sym = CATEGORY_SYMBOL.get(category)
+    if sym is None or not os.path.exists(TRAFFIC_FILE):
+        return None
+    for line in open(TRAFFIC_FILE):
+        if line.startswith("| `" + sym + "`"):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            try:
+                return {"fetch_MB": float(cells[2]), "write_MB": float(cells[3]), "unit": "MB per launch",
+                        "source": "profiles/spec_round_xl2_512_hbm_traffic.md (rocprofv3 --pmc, copy-kernel scaled)"}
+            except (ValueError, IndexError):
+                return None
+    return None
+
+
 def bench_round(args):
     import torch
     from paper_2511_20390_amd import binding, synth
@@ -90,7 +113,8 @@ def bench_round(args):
     dom = max((k for k in kernels if k in per), key=lambda k: kernels[k]["ms_per_step"])
     peak = PEAK_BF16_TFLOPS if mode == "bf16" else PEAK_FP32_TFLOPS
     roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": peak,
-                "unit": "TFLOP/s", "frac": kernels[dom]["tflops"] / peak, "traffic": None,
+                "unit": "TFLOP/s", "frac": kernels[dom]["tflops"] / peak,
+                "traffic": measured_traffic(dom) if args.config == "xl2_512" and mode == "bf16" else None,
                 "avg_launch_us": kernels[dom]["avg_us"],
                 "measured": "HIP events around every launch of this kernel, same steps repeated right after the timed region"}
     fwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if not k.startswith("verify") and k != "eps_to_mean")
@@ -144,7 +168,7 @@ def bench_verify(args, n_sets=6):
     wms, wn = warm["verify_partial"]
     nrej = int((out["n_accept"] < K).sum().item())
     return {"kernel": "verify_partial_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": gbs / PEAK_HBM_GBS, "traffic": None, "avg_launch_us": ms * 1e3 / n,
+            "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic("verify_partial"), "avg_launch_us": ms * 1e3 / n,
             "warm_cache_GBs": bytes_partial / (wms / wn * 1e-3) / 1e9,
             "finish_avg_us": prof["verify_finish"][0] * 1e3 / prof["verify_finish"][1],
             "call_us_back_to_back": call_us, "rounds_per_s_64traj": 64e6 / call_us,
@@ -185,6 +209,9 @@ def main():
     ap.add_argument("--relaxed", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify-bench", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run plain device copies of a known size (256 MiB) so that a rocprofv3 --pmc "
+                         "run of this command has a reference for scaling FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the packed states of a round share one device); "
@@ -195,6 +222,13 @@ def main():
     binding.load()          # fails loudly when the HIP library is missing
     torch.cuda.set_device(0)
 
+    if args.pmc_calibration:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            torch.mul(src, 1.0, out=dst)      # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     res, cfg, w, ri, sched = bench_round(args)
     rounds_per_s = 1e3 / res["ms_per_step"]
     line = {

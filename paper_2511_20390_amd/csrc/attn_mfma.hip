@@ -52,10 +52,24 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
-    const int h = blockIdx.y, b = blockIdx.z;
+    // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  All query
+    // tiles of one (sample, head) re-read the same K and V, so they are placed on ONE XCD,
+    // back to back: id L -> XCD L % 8; pair index = L % 8 + 8 * (L / (8 nq)), tile = (L / 8) % nq.
+    const int nq = (N + BQ - 1) / BQ;
+    const int n_pairs = static_cast<int>(gridDim.x) / nq;       // (sample, head) pairs
+    int pair_idx, q_tile;
+    if (n_pairs % 8 == 0) {
+        const int L = blockIdx.x;
+        pair_idx = (L & 7) + 8 * (L / (8 * nq));
+        q_tile = (L >> 3) % nq;
+    } else {
+        pair_idx = blockIdx.x / nq;
+        q_tile = blockIdx.x % nq;
+    }
+    const int h = pair_idx % heads, b = pair_idx / heads;
     const int D = heads * DH;
     const int64_t row0 = static_cast<int64_t>(b) * N;
-    const int q_base = blockIdx.x * BQ + wave * 32 * QT;
+    const int q_base = q_tile * BQ + wave * 32 * QT;
     const size_t row_bytes = static_cast<size_t>(3) * D * 2;
     const char* qkv_b = reinterpret_cast<const char*>(qkv);
 
@@ -260,7 +274,9 @@ int32_t launch_dh(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, bf16_t
     const float scale_log2 = 1.4426950408889634f / std::sqrt(static_cast<float>(DH));
     // one 32-query tile per wavefront: 128 queries per workgroup, two workgroups per CU
     // (measured faster than two query tiles per wavefront at one workgroup per CU)
-    dim3 grid((N + 127) / 128, heads, B);
+    const int64_t total = static_cast<int64_t>((N + 127) / 128) * heads * B;
+    if (total > 0x7fffffff) return FREE_ERR_SHAPE;
+    dim3 grid(static_cast<unsigned>(total));
     hipLaunchKernelGGL((attn_mfma_kernel<DH, 1>), grid, dim3(kThreads), 0, s, qkv, N, heads, scale_log2, out);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }

@@ -23,8 +23,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kChunkQuantum = 1024;       // elements; chunk sizes are multiples of this
-constexpr int kTargetBlocks = 2048;       // aim for ~8 workgroups per CU on 256 CUs
-constexpr int kReflectChunk = 4096;       // elements of x_out per workgroup in launch 2
+constexpr int kTargetBlocks = 1536;       // ~6 workgroups per CU on 256 CUs, 12 loads of 16 bytes in flight per lane
+constexpr int kReflectChunk = 1024;       // elements of x_out per workgroup in launch 2 (one float4 per lane)
 
 struct Plan {
     int64_t chunk;      // elements per workgroup in launch 1
@@ -188,6 +188,22 @@ __global__ __launch_bounds__(kThreads) void verify_finish_kernel(
     const int64_t lo = static_cast<int64_t>(blockIdx.x) * kReflectChunk;
     int64_t hi = lo + kReflectChunk;
     if (hi > d) hi = d;
+    const bool vec = ((d & 3) == 0) && ((reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(mh) |
+                                         reinterpret_cast<uintptr_t>(xh) | reinterpret_cast<uintptr_t>(xo)) & 15u) == 0;
+    if (vec) {
+        for (int64_t i = lo + 4 * threadIdx.x; i < hi; i += 4 * kThreads) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(m + i), b = *reinterpret_cast<const f32x4*>(mh + i),
+                        x = *reinterpret_cast<const f32x4*>(xh + i);
+            f32x4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double mm = a[j], mmh = b[j], xx = x[j];
+                o[j] = static_cast<float>(mm + (xx - mmh) - c * (mmh - mm));
+            }
+            *reinterpret_cast<f32x4*>(xo + i) = o;
+        }
+        return;
+    }
     for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) {
         const double mm = m[i], mmh = mh[i], xx = xh[i];
         xo[i] = static_cast<float>(mm + (xx - mmh) - c * (mmh - mm));
