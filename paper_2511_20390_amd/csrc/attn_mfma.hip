@@ -47,8 +47,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
     constexpr int KROW = ((2 * KSTEPS) | 1) * 16;     // bytes per K row in LDS (odd # of chunks)
     constexpr int BQ = 4 * 32 * QT;                   // queries per workgroup
     constexpr int NLD = (BKV * DCH + kThreads - 1) / kThreads;   // 16-byte loads per thread per tile
-    __shared__ __attribute__((aligned(16))) char sK[BKV * KROW];
-    __shared__ __attribute__((aligned(16))) char sV[DT * 32 * VROW];
+    constexpr int kKBytes = BKV * KROW, kVBytes = DT * 32 * VROW;
+    __shared__ __attribute__((aligned(16))) char sKbuf[2 * kKBytes];      // two stages: tile t is multiplied
+    __shared__ __attribute__((aligned(16))) char sVbuf[2 * kVBytes];      // while tile t+1 is written
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -74,12 +75,13 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
     const char* qkv_b = reinterpret_cast<const char*>(qkv);
 
     // zero the pad chunks of K (d in [DH, 16*KSTEPS)) and the pad rows of V^T once
-    for (int i = tid; i < BKV * (KROW / 16); i += kThreads) {
+    for (int i = tid; i < 2 * BKV * (KROW / 16); i += kThreads) {
         const int c = i % (KROW / 16);
-        if (c >= DCH) *reinterpret_cast<u32x4_t*>(sK + (i / (KROW / 16)) * KROW + c * 16) = u32x4_t{0, 0, 0, 0};
+        if (c >= DCH) *reinterpret_cast<u32x4_t*>(sKbuf + (i / (KROW / 16)) * KROW + c * 16) = u32x4_t{0, 0, 0, 0};
     }
-    for (int i = tid; i < (DT * 32 - DH) * (VROW / 16); i += kThreads)
-        *reinterpret_cast<u32x4_t*>(sV + DH * VROW + i * 16) = u32x4_t{0, 0, 0, 0};
+    for (int st = 0; st < 2; ++st)
+        for (int i = tid; i < (DT * 32 - DH) * (VROW / 16); i += kThreads)
+            *reinterpret_cast<u32x4_t*>(sVbuf + st * kVBytes + DH * VROW + i * 16) = u32x4_t{0, 0, 0, 0};
 
     // Q^T fragments (B operand of S^T): lane holds query column l32, k-slots d = 16 ks + 8 g + j
     bf16x8_t qf[QT][KSTEPS];
@@ -119,7 +121,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
             }
         }
     };
-    auto stash = [&]() {
+    auto stash = [&](int stage) {
+        char* sK = sKbuf + stage * kKBytes;
+        char* sV = sVbuf + stage * kVBytes;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int idx = tid + kThreads * i;
@@ -145,18 +149,25 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
         for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[dt][qt][e] = 0.f;
-    float m_run[QT], l_run[QT];
+    // m_ref: the reference maximum the exponentials of a query column are taken against.
+    // It follows the running maximum lazily: O^T and the running sum are rescaled only when the
+    // maximum has grown by more than kLazy (in log2 units) since the last rescale, so that
+    // probabilities stay below 2^kLazy (harmless in bf16/fp32) and the 3 x 16 accumulator
+    // registers are rarely touched by the VALU.
+    constexpr float kLazy = 8.0f;
+    float m_ref[QT], l_run[QT];
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
+    for (int qt = 0; qt < QT; ++qt) { m_ref[qt] = -INFINITY; l_run[qt] = 0.f; }
 
     const int ntiles = (N + BKV - 1) / BKV;
     fetch(0);
+    stash(0);
+    if (ntiles > 1) fetch(BKV);
+    __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
         const int kv0 = t * BKV;
-        __syncthreads();                       // previous tile fully consumed (and pad zeroing done)
-        stash();
-        __syncthreads();
-        if (t + 1 < ntiles) fetch(kv0 + BKV);
+        const char* sK = sKbuf + (t & 1) * kKBytes;
+        const char* sV = sVbuf + (t & 1) * kVBytes;
 
         // ---- S^T = K Q^T for the two 32-key blocks of the tile
         f32x16_t st[2][QT];
@@ -178,6 +189,11 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
                 for (int qt = 0; qt < QT; ++qt)
                     st[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[qt][ks], st[kb][qt], 0, 0, 0);
         }
+        // the next tile moves from registers to the other LDS stage while this one is processed;
+        // the tile after it is requested from global memory
+        if (t + 1 < ntiles) stash((t + 1) & 1);
+        if (t + 2 < ntiles) fetch(kv0 + 2 * BKV);
+
         // keys past N (last tile only): accumulator register e of block kb holds the key
         // kv0 + 32 kb + 16 (e/8) + 8 g + 4 ((e/4)%2) + e%4   (LDS rows were permuted on the way in)
         if (kv0 + BKV > N) {
@@ -202,10 +218,18 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[kb][qt][e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[qt], mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * scale_log2);
-            const float mb = m_new * scale_log2;
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                 // both half-waves of a column agree
+            if (__any((mx - m_ref[qt]) * scale_log2 > kLazy)) {     // also true for the first tile (m_ref = -inf)
+                const float m_new = fmaxf(m_ref[qt], mx);
+                const float alpha = __builtin_amdgcn_exp2f((m_ref[qt] - m_new) * scale_log2);
+                l_run[qt] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) o[dt][qt][e] *= alpha;
+                m_ref[qt] = m_new;
+            }
+            const float mb = m_ref[qt] * scale_log2;
             float sum = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -221,14 +245,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
                                   pack_bf16x2(p[6], p[7])};
                     pf[qt][kb][hh] = __builtin_bit_cast(bf16x8_t, pk);
                 }
-            l_run[qt] = l_run[qt] * alpha + sum;
-            if (__any(m_new > m_run[qt])) {
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) o[dt][qt][e] *= alpha;
-            }
-            m_run[qt] = m_new;
+            l_run[qt] += sum;
         }
 
         // ---- O^T += V^T P^T
@@ -245,6 +262,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
                         o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][kb][hh], o[dt][qt], 0, 0, 0);
                 }
             }
+        __syncthreads();          // stage (t+1)&1 is complete; stage t&1 may be overwritten next iteration
     }
 
     // ---- normalise and store: register e of O^T tile dt is row d = 32 dt + 8 (e/4) + 4 g + e%4, column l32

@@ -443,6 +443,89 @@ __global__ __launch_bounds__(kThreads) void final_layer_kernel(
     }
 }
 
+// Same operation with the token row read once: the normalised, modulated row stays in
+// registers (NV float4 per lane) and every output column is a dot product of registers
+// with a weight row streamed from cache.  Needs D % 4 == 0, D <= 256 NV, 16-byte rows.
+template <typename WT, int NV>
+__global__ __launch_bounds__(kThreads) void final_layer_vec_kernel(
+    const float* __restrict__ x, RowVec shift, RowVec scale, int32_t M, int32_t gh, int32_t gw, int32_t p,
+    int32_t c_out, int32_t D, const WT* __restrict__ w, const float* __restrict__ bias,
+    float* __restrict__ out) {
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const int nvec = D >> 2;
+    const float4* xr = reinterpret_cast<const float4*>(x + row * D);
+    float4 xv[NV];
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = lane + 64 * k;
+        xv[k] = (v < nvec) ? xr[v] : make_float4(0.f, 0.f, 0.f, 0.f);
+        s += (xv[k].x + xv[k].y) + (xv[k].z + xv[k].w);
+    }
+    const float mean = wave_sum_f(s) / static_cast<float>(D);
+    float q = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        if (lane + 64 * k < nvec) {
+            const float a = xv[k].x - mean, b = xv[k].y - mean, c = xv[k].z - mean, d = xv[k].w - mean;
+            q += (a * a + b * b) + (c * c + d * d);
+        }
+    }
+    const float rstd = rsqrtf(wave_sum_f(q) / static_cast<float>(D) + kLnEps);
+    const float4* sh = reinterpret_cast<const float4*>(shift.base + (row / shift.rows_per_sample) * shift.stride);
+    const float4* sc = reinterpret_cast<const float4*>(scale.base + (row / scale.rows_per_sample) * scale.stride);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = lane + 64 * k;
+        if (v < nvec) {
+            const float4 h = sh[v], c = sc[v];
+            xv[k].x = fmaf((xv[k].x - mean) * rstd, 1.0f + c.x, h.x);
+            xv[k].y = fmaf((xv[k].y - mean) * rstd, 1.0f + c.y, h.y);
+            xv[k].z = fmaf((xv[k].z - mean) * rstd, 1.0f + c.z, h.z);
+            xv[k].w = fmaf((xv[k].w - mean) * rstd, 1.0f + c.w, h.w);
+        } else {
+            xv[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    const int ntok = gh * gw;
+    const int b = static_cast<int>(row / ntok), n = static_cast<int>(row % ntok);
+    const int gi = n / gw, gj = n % gw;
+    const int P = p * p * c_out;
+    const int H = gh * p, Wd = gw * p;
+    for (int o = 0; o < P; ++o) {
+        const WT* wr = w + static_cast<int64_t>(o) * D;
+        float acc = 0.f;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int v = lane + 64 * k;
+            if (v < nvec) {
+                float w0, w1, w2, w3;
+                if constexpr (sizeof(WT) == 2) {
+                    const uint2 pk = reinterpret_cast<const uint2*>(wr)[v];
+                    w0 = __uint_as_float(pk.x << 16);
+                    w1 = __uint_as_float(pk.x & 0xffff0000u);
+                    w2 = __uint_as_float(pk.y << 16);
+                    w3 = __uint_as_float(pk.y & 0xffff0000u);
+                } else {
+                    const float4 f = reinterpret_cast<const float4*>(wr)[v];
+                    w0 = f.x; w1 = f.y; w2 = f.z; w3 = f.w;
+                }
+                acc = fmaf(xv[k].x, w0, acc);
+                acc = fmaf(xv[k].y, w1, acc);
+                acc = fmaf(xv[k].z, w2, acc);
+                acc = fmaf(xv[k].w, w3, acc);
+            }
+        }
+        acc = wave_sum_f(acc);
+        if (lane == 0) {
+            const int c = o % c_out, pq = (o / c_out) % p, ph = o / (c_out * p);
+            out[((static_cast<int64_t>(b) * c_out + c) * H + gi * p + ph) * Wd + gj * p + pq] = acc + bias[o];
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Guidance + eps -> mean (Eq. ddpm_update): m_k = coef_x[k] x_k + coef_eps[k] eps_k,
 // eps = eps_null + s (eps_cond - eps_null) when the batch carries both halves.
@@ -623,6 +706,28 @@ int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B
                            float* out, hipStream_t s) {
     const int M = B * gh * gw;
     const int blocks = (M + kWaves - 1) / kWaves;
+    auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    const bool vec = (D % 4 == 0) && D <= 2048 && al16(x) && al16(w) && al16(shift.base) && al16(scale.base) &&
+                     (shift.stride % 4 == 0) && (scale.stride % 4 == 0);
+    if (vec) {
+        const int nv = (D / 4 + 63) / 64;
+#define FREE_FIN_CASE(WT, NV)                                                                                  \
+    hipLaunchKernelGGL((final_layer_vec_kernel<WT, NV>), dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, gh, \
+                       gw, p, c_out, D, static_cast<const WT*>(w), bias, out)
+        if (dtype == FREE_BF16) {
+            if (nv <= 1) FREE_FIN_CASE(bf16_t, 1);
+            else if (nv <= 2) FREE_FIN_CASE(bf16_t, 2);
+            else if (nv <= 5) FREE_FIN_CASE(bf16_t, 5);
+            else FREE_FIN_CASE(bf16_t, 8);
+        } else {
+            if (nv <= 1) FREE_FIN_CASE(float, 1);
+            else if (nv <= 2) FREE_FIN_CASE(float, 2);
+            else if (nv <= 5) FREE_FIN_CASE(float, 5);
+            else FREE_FIN_CASE(float, 8);
+        }
+#undef FREE_FIN_CASE
+        return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+    }
     if (dtype == FREE_BF16)
         hipLaunchKernelGGL(final_layer_kernel<bf16_t>, dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, gh,
                            gw, p, c_out, D, static_cast<const bf16_t*>(w), bias, out);
