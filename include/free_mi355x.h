@@ -69,6 +69,18 @@ const char* free_status_string(int32_t status);
 /* hipError_t of the last failing HIP call seen by this thread (0 = none). */
 int32_t free_last_hip_error(void);
 
+/* Execution of the packed target forward (Alg. 1: the K states of a round are
+ * independent samples of one batch).  n = 2 (default): when a batch has at
+ * least 2 samples and each half at least 2048 token rows, the two halves of
+ * the batch run their transformer blocks concurrently on two streams owned by
+ * the model handle; the work is forked from and joined back into the caller's
+ * stream, so stream-ordered semantics towards the caller are unchanged and the
+ * results are the same as with n = 1 (one stream, kernels in sequence).
+ * Process-wide; not thread-safe against running calls.  FREE_ERR_RANGE for
+ * any other n. */
+int32_t free_set_batch_streams(int32_t n);
+int32_t free_get_batch_streams(void);
+
 /* Linear-beta DDPM schedule and the coefficients of the one-step update
  * (Eq. ddpm_update, App. C), 0-indexed by network timestep i in [0, T):
  *   coef_x[i]   = 1 / sqrt(alpha_i)

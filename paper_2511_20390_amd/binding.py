@@ -21,7 +21,8 @@ EPI_BIAS, EPI_BIAS_GELU, EPI_GATE_RESID = 0, 1, 2
 MODES = {"fp32": FREE_FP32, "bf16": FREE_BF16}
 
 EXPORTED_SYMBOLS = [
-    "free_version", "free_status_string", "free_last_hip_error", "free_ddpm_schedule",
+    "free_version", "free_status_string", "free_last_hip_error", "free_set_batch_streams",
+    "free_get_batch_streams", "free_ddpm_schedule",
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
     "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
@@ -60,6 +61,9 @@ def load():
     lib.free_status_string.restype = C.c_char_p
     lib.free_status_string.argtypes = [i32]
     lib.free_last_hip_error.restype = i32
+    lib.free_set_batch_streams.restype = i32
+    lib.free_set_batch_streams.argtypes = [i32]
+    lib.free_get_batch_streams.restype = i32
     lib.free_ddpm_schedule.restype = i32
     lib.free_ddpm_schedule.argtypes = [i32, C.c_double, C.c_double, vp, vp, vp]
     lib.free_weight_count.restype = i32
@@ -119,6 +123,15 @@ def free_ddpm_schedule(T: int = 1000, beta_start: float = 1e-4, beta_end: float 
     _check(load().free_ddpm_schedule(T, beta_start, beta_end, cx.ctypes.data, ce.ctypes.data, sg.ctypes.data),
            "free_ddpm_schedule")
     return cx, ce, sg
+
+
+def set_batch_streams(n: int) -> None:
+    """1: kernels of a forward in sequence on the caller's stream; 2 (default): halves of a large batch on two streams."""
+    _check(load().free_set_batch_streams(int(n)), "free_set_batch_streams")
+
+
+def get_batch_streams() -> int:
+    return int(load().free_get_batch_streams())
 
 
 def profile_begin():

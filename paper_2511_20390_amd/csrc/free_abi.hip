@@ -25,6 +25,8 @@ struct Profiler {
     size_t used = 0;
 };
 Profiler g_prof;
+int32_t g_batch_streams = 2;                  // 1: serial, 2: halves of a packed batch on two streams
+constexpr int64_t kMinSplitRows = 2048;       // token rows per half below which the split does not pay
 constexpr size_t kMaxProfSlots = 8192;
 }  // namespace
 
@@ -125,6 +127,10 @@ struct free_dit_s {
     const int32_t* ada_row_start = nullptr;
     const float* pos = nullptr;
     int device = 0;
+    // two side streams (default priority) on which the halves of a packed batch run concurrently
+    hipStream_t side[2] = {nullptr, nullptr};
+    hipEvent_t ev_fork = nullptr;
+    hipEvent_t ev_join[2] = {nullptr, nullptr};
 
     const void* blk(int l, int which) const { return w[7 + 10 * l + which]; }
     const void* fin(int which) const { return w[7 + 10 * dims.depth + which]; }
@@ -193,48 +199,80 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     FREE_TRY(launch_patch_embed(x, x_mod, B, d.C, d.H, d.W, d.p, d.D, static_cast<const float*>(h->w[W_PATCH_W]),
                                 static_cast<const float*>(h->w[W_PATCH_B]), h->pos, xres, s));
     }
-    auto vec = [&](int l, int which) {
-        RowVec r;
-        r.base = mod + static_cast<int64_t>(l) * 6 * d.D + static_cast<int64_t>(which) * d.D;
-        r.stride = d.mod_rows;
-        r.rows_per_sample = d.ntok;
-        return r;
-    };
-    for (int l = 0; l < d.depth; ++l) {
+    const size_t esz = d.mode == FREE_BF16 ? 2 : 4;
+    auto run_blocks = [&](int b0, int nb, hipStream_t s) -> int32_t {
+        const int32_t M = nb * d.ntok;
+        const int64_t r0 = static_cast<int64_t>(b0) * d.ntok;
+        float* xres_h = xres + r0 * d.D;
+        void* xn_h = static_cast<char*>(xn) + r0 * d.D * esz;
+        void* qkv_h = static_cast<char*>(qkv) + r0 * 3 * d.D * esz;
+        void* att_h = static_cast<char*>(att) + r0 * d.D * esz;
+        void* hmid_h = static_cast<char*>(hmid) + r0 * d.F * esz;
+        auto vec = [&](int l, int which) {
+            RowVec r;
+            r.base = mod + static_cast<int64_t>(b0) * d.mod_rows + static_cast<int64_t>(l) * 6 * d.D +
+                     static_cast<int64_t>(which) * d.D;
+            r.stride = d.mod_rows;
+            r.rows_per_sample = d.ntok;
+            return r;
+        };
+        for (int l = 0; l < d.depth; ++l) {
         // x += gate1 * Proj(Attn(LN(x)(1+scale1)+shift1))
         {
             ProfScope prof(PROF_LN_MOD, s);
-            FREE_TRY(launch_ln_modulate(xres, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn, s));
+            FREE_TRY(launch_ln_modulate(xres_h, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn_h, s));
         }
         {
             ProfScope prof(PROF_GEMM_QKV, s);
-            FREE_TRY(linear_dispatch(d, xn, h->blk(l, B_QKV_W), static_cast<const float*>(h->blk(l, B_QKV_B)), M,
-                                     3 * d.D, d.D, FREE_EPI_BIAS, qkv, nullptr, RowVec{nullptr, 0, 1}, s));
+            FREE_TRY(linear_dispatch(d, xn_h, h->blk(l, B_QKV_W), static_cast<const float*>(h->blk(l, B_QKV_B)), M,
+                                     3 * d.D, d.D, FREE_EPI_BIAS, qkv_h, nullptr, RowVec{nullptr, 0, 1}, s));
         }
         {
             ProfScope prof(PROF_ATTN, s);
-            FREE_TRY(attention_dispatch(d, qkv, B, att, s));
+            FREE_TRY(attention_dispatch(d, qkv_h, nb, att_h, s));
         }
         {
             ProfScope prof(PROF_GEMM_PROJ, s);
-            FREE_TRY(linear_dispatch(d, att, h->blk(l, B_PROJ_W), static_cast<const float*>(h->blk(l, B_PROJ_B)),
-                                     M, d.D, d.D, FREE_EPI_GATE_RESID, nullptr, xres, vec(l, 2), s));
+            FREE_TRY(linear_dispatch(d, att_h, h->blk(l, B_PROJ_W), static_cast<const float*>(h->blk(l, B_PROJ_B)),
+                                     M, d.D, d.D, FREE_EPI_GATE_RESID, nullptr, xres_h, vec(l, 2), s));
         }
         // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
         {
             ProfScope prof(PROF_LN_MOD, s);
-            FREE_TRY(launch_ln_modulate(xres, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn, s));
+            FREE_TRY(launch_ln_modulate(xres_h, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn_h, s));
         }
         {
             ProfScope prof(PROF_GEMM_FC1, s);
-            FREE_TRY(linear_dispatch(d, xn, h->blk(l, B_FC1_W), static_cast<const float*>(h->blk(l, B_FC1_B)), M,
-                                     d.F, d.D, FREE_EPI_BIAS_GELU, hmid, nullptr, RowVec{nullptr, 0, 1}, s));
+            FREE_TRY(linear_dispatch(d, xn_h, h->blk(l, B_FC1_W), static_cast<const float*>(h->blk(l, B_FC1_B)), M,
+                                     d.F, d.D, FREE_EPI_BIAS_GELU, hmid_h, nullptr, RowVec{nullptr, 0, 1}, s));
         }
         {
             ProfScope prof(PROF_GEMM_FC2, s);
-            FREE_TRY(linear_dispatch(d, hmid, h->blk(l, B_FC2_W), static_cast<const float*>(h->blk(l, B_FC2_B)),
-                                     M, d.D, d.F, FREE_EPI_GATE_RESID, nullptr, xres, vec(l, 5), s));
+            FREE_TRY(linear_dispatch(d, hmid_h, h->blk(l, B_FC2_W), static_cast<const float*>(h->blk(l, B_FC2_B)),
+                                     M, d.D, d.F, FREE_EPI_GATE_RESID, nullptr, xres_h, vec(l, 5), s));
         }
+    }
+        return FREE_OK;
+    };
+    // The samples of a packed batch are independent through all blocks, so the batch is cut in two
+    // halves that run on two streams forked from (and joined back into) the caller's stream: while
+    // one half is in a bandwidth-bound phase (layer norm, the residual read-modify-write at the end
+    // of a GEMM, the first and last wave of tiles) the other half's matrix kernels fill the idle
+    // compute units.  Per-kernel profiling needs serial execution, and small batches are launch
+    // bound, so both keep the single stream.
+    const bool split = g_batch_streams == 2 && !g_prof.on && B >= 2 &&
+                       static_cast<int64_t>(B / 2) * d.ntok >= kMinSplitRows;
+    if (split) {
+        if (!hip_ok(hipEventRecord(h->ev_fork, s))) return FREE_ERR_HIP;
+        for (int i = 0; i < 2; ++i) {
+            const int b0 = i == 0 ? 0 : B / 2, b1 = i == 0 ? B / 2 : B;
+            if (!hip_ok(hipStreamWaitEvent(h->side[i], h->ev_fork, 0))) return FREE_ERR_HIP;
+            FREE_TRY(run_blocks(b0, b1 - b0, h->side[i]));
+            if (!hip_ok(hipEventRecord(h->ev_join[i], h->side[i]))) return FREE_ERR_HIP;
+            if (!hip_ok(hipStreamWaitEvent(s, h->ev_join[i], 0))) return FREE_ERR_HIP;
+        }
+    } else {
+        FREE_TRY(run_blocks(0, B, s));
     }
     if (top_feat) {
         if (!hip_ok(hipMemcpyAsync(top_feat, xres, static_cast<size_t>(M) * d.D * 4, hipMemcpyDeviceToDevice, s)))
@@ -273,6 +311,14 @@ const char* free_status_string(int32_t st) {
 }
 
 int32_t free_last_hip_error(void) { return g_last_hip_error; }
+
+int32_t free_set_batch_streams(int32_t n) {
+    if (n != 1 && n != 2) return FREE_ERR_RANGE;
+    g_batch_streams = n;
+    return FREE_OK;
+}
+
+int32_t free_get_batch_streams(void) { return g_batch_streams; }
 
 int32_t free_profile_begin(void) {
     g_prof.used = 0;
@@ -391,6 +437,14 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
     h->ada_b_tab = reinterpret_cast<const float* const*>(db + off_b);
     h->ada_row_start = reinterpret_cast<const int32_t*>(db + off_r);
     h->pos = reinterpret_cast<const float*>(db + off_p);
+    bool ok = hip_ok(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
+    for (int i = 0; i < 2 && ok; ++i)
+        ok = hip_ok(hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking)) &&
+             hip_ok(hipEventCreateWithFlags(&h->ev_join[i], hipEventDisableTiming));
+    if (!ok) {
+        (void)free_dit_destroy(h);
+        return FREE_ERR_HIP;
+    }
     *out = h;
     return FREE_OK;
 }
@@ -398,6 +452,12 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
 int32_t free_dit_destroy(free_dit_t h) {
     if (!h) return FREE_ERR_NULL;
     int32_t st = FREE_OK;
+    for (int i = 0; i < 2; ++i) {
+        if (h->side[i] && !hip_ok(hipStreamSynchronize(h->side[i]))) st = FREE_ERR_HIP;
+        if (h->side[i] && !hip_ok(hipStreamDestroy(h->side[i]))) st = FREE_ERR_HIP;
+        if (h->ev_join[i] && !hip_ok(hipEventDestroy(h->ev_join[i]))) st = FREE_ERR_HIP;
+    }
+    if (h->ev_fork && !hip_ok(hipEventDestroy(h->ev_fork))) st = FREE_ERR_HIP;
     if (h->dev_block && !hip_ok(hipFree(h->dev_block))) st = FREE_ERR_HIP;
     delete h;
     return st;

@@ -13,13 +13,19 @@
 //  * the MFMA takes the WEIGHT rows as its A operand and the activation rows as its
 //    B operand, i.e. it accumulates C^T tiles: a lane then owns one output ROW m
 //    (lane % 32) and runs of 4 consecutive output columns n per register group.  The
-//    epilogue therefore needs no transposition: one v_permlane32_swap pairs the two
-//    half-waves' runs into 8 consecutive bf16 (a 16-byte store), and the fp32
-//    residual update is a float4 read-modify-write with all loads of a column tile
-//    issued before its first store.
+//    fp32 residual update is a float4 read-modify-write with all loads of a column tile
+//    issued before its first store.  For bf16 output one v_permlane32_swap pairs the two
+//    half-waves' runs into 8 consecutive bf16, and each 32-row block is transposed through a
+//    wave-private piece of the (by then idle) LDS tiles so that the global stores cover
+//    whole rows of the wave's tile with consecutive lanes - a row otherwise lives in two
+//    lanes, 32 bytes per row and instruction, and such partial-line writes cost up to 1.8x
+//    the algorithmic write traffic at the memory controller.
 //  * LDS: two stages of [BM + BN rows][64 bf16]; the 16-byte chunk index of a row is
-//    XOR-swizzled with (row % 8) for the ds_read_b128 fragment reads while global
-//    loads stay 128-byte coalesced.
+//    XOR-swizzled with (row / 2) % 8: a ds_read_b128 is served 16 lanes at a time over 64
+//    banks (256 bytes), and with this pattern the 16 rows of a pass hit 16 distinct 16-byte
+//    bank groups (the conflict counter reads zero; swizzling with row % 8 leaves rows r and
+//    r + 8 on the same banks, a 2-way conflict on every fragment read).  Global loads stay
+//    128-byte coalesced.
 //  * global loads are buffer loads (descriptor + one per-lane offset + scalar offsets):
 //    no address registers, and rows past the end of a ragged edge tile read as zero.
 //  * software pipeline: global loads run two slices ahead (slice kt+2 is in flight in
@@ -101,6 +107,143 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
     *tn = in_group / gsize;
 }
 
+// Epilogue shared by the GEMM kernels.  Register e of acc[i][j] in lane l is output row
+// m = gm_lane + 32 i (gm_lane already includes l % 32), column n = gn_wave + 32 j + 8 (e/4) + 4 lhi + e%4.
+template <int TM, int TN, int EPI>
+__device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm_lane, int gn_wave, int lane, int32_t M,
+                                           int32_t N, int32_t vec_ok, const float* __restrict__ bias,
+                                           bf16_t* __restrict__ out, float* __restrict__ resid, const RowVec& gate,
+                                           char* wave_lds) {
+    const int lhi = lane >> 5;
+    if (vec_ok) {
+        // N % 8 == 0 and 16-byte aligned rows: runs of 4 / 8 columns are all inside or all outside.
+        // Rows past M and runs past N (ragged edge tiles) are masked per lane.
+        if (EPI == FREE_EPI_GATE_RESID) {
+            // read-modify-write of the fp32 residual stream.  All loads of a column tile j are
+            // issued before its first store (a store would otherwise fence the following loads).
+            const float* __restrict__ gbase = gate.base;
+            int64_t g_off[TM], r_off[TM];
+            bool row_ok[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int gm = gm_lane + i * 32;
+                row_ok[i] = gm < M;
+                g_off[i] = static_cast<int64_t>(gm / gate.rows_per_sample) * gate.stride;
+                r_off[i] = static_cast<int64_t>(gm) * N;
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int gn0 = gn_wave + j * 32 + 4 * lhi;
+                f32x4_t bv[4], g[TM][4], r[TM][4];
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4)
+                    if (gn0 + 8 * e4 < N) bv[e4] = *reinterpret_cast<const f32x4_t*>(bias + gn0 + 8 * e4);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4)
+                        if (row_ok[i] && gn0 + 8 * e4 < N) {
+                            g[i][e4] = *reinterpret_cast<const f32x4_t*>(gbase + g_off[i] + gn0 + 8 * e4);
+                            r[i][e4] = *reinterpret_cast<const f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4);
+                        }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4)
+                        if (row_ok[i] && gn0 + 8 * e4 < N) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                r[i][e4][c] = fmaf(g[i][e4][c], acc[i][j][4 * e4 + c] + bv[e4][c], r[i][e4][c]);
+                            *reinterpret_cast<f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4) = r[i][e4];
+                        }
+            }
+        } else {
+            // bf16 output.  In the accumulator layout a row lives in two lanes only, so a direct store
+            // touches 32 rows x 32 bytes per instruction (partial cache lines).  Each 32-row block is
+            // instead packed to bf16, staged in a wave-private LDS region (rows padded by 16 bytes: the
+            // 16 lanes of a ds_write_b128 pass hit 16 distinct bank groups) and read back row-major, so
+            // that consecutive lanes store consecutive 16-byte chunks of whole output rows.
+            constexpr int CH = TN * 4;                         // 16-byte chunks per staged row
+            constexpr int kStageRow = (CH + 1) * 16;           // bytes per staged row
+            const int l32 = lane & 31;
+            f32x4_t blo[TN][2], bhi[TN][2];
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e8 = 0; e8 < 2; ++e8) {
+                    // this lane's two runs: n = nb + 4 lhi + {0..3} (lo) and nb + 8 + 4 lhi + {0..3} (hi);
+                    // nb is a multiple of 16 and N of 8, so nb < N covers the lo run and nb + 8 < N the hi run
+                    const int nb = gn_wave + j * 32 + 16 * e8;
+                    blo[j][e8] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    bhi[j][e8] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    if (nb < N) blo[j][e8] = *reinterpret_cast<const f32x4_t*>(bias + nb + 4 * lhi);
+                    if (nb + 8 < N) bhi[j][e8] = *reinterpret_cast<const f32x4_t*>(bias + nb + 8 + 4 * lhi);
+                }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e8 = 0; e8 < 2; ++e8) {
+                        float v[8];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            v[c] = acc[i][j][8 * e8 + c] + blo[j][e8][c];
+                            v[4 + c] = acc[i][j][8 * e8 + 4 + c] + bhi[j][e8][c];
+                        }
+                        if (EPI == FREE_EPI_BIAS_GELU) {
+#pragma unroll
+                            for (int c = 0; c < 8; ++c) v[c] = gelu_fast(v[c]);
+                        }
+                        uint32_t lo0 = pack2(v[0], v[1]), lo1 = pack2(v[2], v[3]);
+                        uint32_t hi0 = pack2(v[4], v[5]), hi1 = pack2(v[6], v[7]);
+                        // lower half-wave keeps its lo run and receives the partner's lo run (n+4..7);
+                        // upper half-wave receives the partner's hi run (n+8..11) and keeps its own hi run
+                        const u32x2_t s0 = __builtin_amdgcn_permlane32_swap(lo0, hi0, false, false);
+                        const u32x2_t s1 = __builtin_amdgcn_permlane32_swap(lo1, hi1, false, false);
+                        const u32x4_t o = {s0[0], s1[0], s0[1], s1[1]};
+                        // row l32 of the block, columns j*32 + 16*e8 + 8*lhi .. +7 -> chunk 4j + 2 e8 + lhi
+                        *reinterpret_cast<u32x4_t*>(wave_lds + l32 * kStageRow + ((4 * j + 2 * e8 + lhi) << 4)) = o;
+                    }
+                // read back: flat chunk f = q*64 + lane over 32 rows x CH chunks
+#pragma unroll
+                for (int q = 0; q < (32 * CH + 63) / 64; ++q) {
+                    const int f = q * 64 + lane;
+                    const int row = f / CH, ch = f % CH;
+                    if ((32 * CH) % 64 != 0 && f >= 32 * CH) continue;
+                    const u32x4_t o = *reinterpret_cast<const u32x4_t*>(wave_lds + row * kStageRow + (ch << 4));
+                    const int gm = gm_lane - l32 + i * 32 + row, gn = gn_wave + ch * 8;
+                    if (gm < M && gn < N) *reinterpret_cast<u32x4_t*>(out + static_cast<int64_t>(gm) * N + gn) = o;
+                }
+            }
+        }
+        return;
+    }
+    // unaligned output: element-wise with bounds checks
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int gm = gm_lane + i * 32;
+            if (gm >= M) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int gn = gn_wave + j * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                if (gn >= N) continue;
+                const float v = acc[i][j][e] + bias[gn];
+                const int64_t o = static_cast<int64_t>(gm) * N + gn;
+                if (EPI == FREE_EPI_BIAS) {
+                    out[o] = float_to_bf16(v);
+                } else if (EPI == FREE_EPI_BIAS_GELU) {
+                    out[o] = float_to_bf16(gelu_fast(v));
+                } else {
+                    const float g = gate.base[static_cast<int64_t>(gm / gate.rows_per_sample) * gate.stride + gn];
+                    resid[o] = fmaf(g, v, resid[o]);
+                }
+            }
+        }
+}
+
 // EVEN_K: K % 64 == 0 (no predicates in the K loop).  Ragged M / N tiles are handled
 // by clamping the loaded row index (extra rows are computed, never stored).
 template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
@@ -137,7 +280,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
         static_cast<int>(w_left < 0x7fffffff ? w_left : 0x7fffffff), 0x00020000);
     const int ld_voff = ld_row * K * 2 + ld_chunk * 16;       // per-lane byte offset inside the tile
     const int pass_bytes = RP * K * 2;                        // RP rows further down per load index
-    const int st_off = ld_row * kRowBytes + ((ld_chunk ^ (ld_row & 7)) << 4);   // + i*RP rows per load
+    const int st_off = ld_row * kRowBytes + ((ld_chunk ^ ((ld_row >> 1) & 7)) << 4);   // + i*RP rows per load
     u32x4_t sreg[LA + LB];                              // staging registers: one K slice in flight
     const int nk = (K + BK - 1) / BK;
 
@@ -167,7 +310,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
 
     // ---- MFMA operand fragments: row fixed per lane, chunk varies with the k step
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int sw = l32 & 7;                                // row % 8 (tile row offsets are multiples of 32)
+    const int sw = (l32 >> 1) & 7;                         // (row / 2) % 8 (tile row offsets are multiples of 32)
     const int x_row0 = (wm * TM * 32 + l32) * kRowBytes;           // + i*32 rows
     const int w_row0 = (BM + wn * TN * 32 + l32) * kRowBytes;      // + j*32 rows
     bf16x8_t fx[2][TM], fw[2][TN];
@@ -249,113 +392,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     }
     slice(kt, no, no);
 
-    // ---- epilogue.  Register e of acc[i][j] in lane l is
-    //      output row m = m0 + (wm TM + i) 32 + l%32, column n = n0 + (wn TN + j) 32 + 8 (e/4) + 4 (l/32) + e%4.
-    const int gm_lane = m0 + wm * TM * 32 + l32;
-    const int gn_wave = n0 + wn * TN * 32;
-    if (vec_ok) {
-        // N % 8 == 0 and 16-byte aligned rows: runs of 4 / 8 columns are all inside or all outside.
-        // Rows past M and runs past N (ragged edge tiles) are masked per lane.
-        if (EPI == FREE_EPI_GATE_RESID) {
-            // read-modify-write of the fp32 residual stream.  All loads of a column tile j are
-            // issued before its first store (a store would otherwise fence the following loads).
-            const float* __restrict__ gbase = gate.base;
-            int64_t g_off[TM], r_off[TM];
-            bool row_ok[TM];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int gm = gm_lane + i * 32;
-                row_ok[i] = gm < M;
-                g_off[i] = static_cast<int64_t>(gm / gate.rows_per_sample) * gate.stride;
-                r_off[i] = static_cast<int64_t>(gm) * N;
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int gn0 = gn_wave + j * 32 + 4 * lhi;
-                f32x4_t bv[4], g[TM][4], r[TM][4];
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4)
-                    if (gn0 + 8 * e4 < N) bv[e4] = *reinterpret_cast<const f32x4_t*>(bias + gn0 + 8 * e4);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int e4 = 0; e4 < 4; ++e4)
-                        if (row_ok[i] && gn0 + 8 * e4 < N) {
-                            g[i][e4] = *reinterpret_cast<const f32x4_t*>(gbase + g_off[i] + gn0 + 8 * e4);
-                            r[i][e4] = *reinterpret_cast<const f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4);
-                        }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int e4 = 0; e4 < 4; ++e4)
-                        if (row_ok[i] && gn0 + 8 * e4 < N) {
-#pragma unroll
-                            for (int c = 0; c < 4; ++c)
-                                r[i][e4][c] = fmaf(g[i][e4][c], acc[i][j][4 * e4 + c] + bv[e4][c], r[i][e4][c]);
-                            *reinterpret_cast<f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4) = r[i][e4];
-                        }
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int e8 = 0; e8 < 2; ++e8) {
-                    // this lane's two runs: n = nb + 4 lhi + {0..3} (lo) and nb + 8 + 4 lhi + {0..3} (hi);
-                    // nb is a multiple of 16 and N of 8, so nb < N covers the lo run and nb + 8 < N the hi run
-                    const int nb = gn_wave + j * 32 + 16 * e8;
-                    f32x4_t blo = {0.f, 0.f, 0.f, 0.f}, bhi = {0.f, 0.f, 0.f, 0.f};
-                    if (nb < N) blo = *reinterpret_cast<const f32x4_t*>(bias + nb + 4 * lhi);
-                    if (nb + 8 < N) bhi = *reinterpret_cast<const f32x4_t*>(bias + nb + 8 + 4 * lhi);
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) {
-                        float v[8];
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            v[c] = acc[i][j][8 * e8 + c] + blo[c];
-                            v[4 + c] = acc[i][j][8 * e8 + 4 + c] + bhi[c];
-                        }
-                        if (EPI == FREE_EPI_BIAS_GELU) {
-#pragma unroll
-                            for (int c = 0; c < 8; ++c) v[c] = gelu_fast(v[c]);
-                        }
-                        uint32_t lo0 = pack2(v[0], v[1]), lo1 = pack2(v[2], v[3]);
-                        uint32_t hi0 = pack2(v[4], v[5]), hi1 = pack2(v[6], v[7]);
-                        // lower half-wave keeps its lo run and receives the partner's lo run (n+4..7);
-                        // upper half-wave receives the partner's hi run (n+8..11) and keeps its own hi run
-                        const u32x2_t s0 = __builtin_amdgcn_permlane32_swap(lo0, hi0, false, false);
-                        const u32x2_t s1 = __builtin_amdgcn_permlane32_swap(lo1, hi1, false, false);
-                        const u32x4_t o = {s0[0], s1[0], s0[1], s1[1]};
-                        const int gm = gm_lane + i * 32;
-                        if (gm < M && nb + 8 * lhi < N)
-                            *reinterpret_cast<u32x4_t*>(out + static_cast<int64_t>(gm) * N + nb + 8 * lhi) = o;
-                    }
-                }
-        }
-        return;
-    }
-    // unaligned output: element-wise with bounds checks
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int gm = gm_lane + i * 32;
-            if (gm >= M) continue;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int gn = gn_wave + j * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
-                if (gn >= N) continue;
-                const float v = acc[i][j][e] + bias[gn];
-                const int64_t o = static_cast<int64_t>(gm) * N + gn;
-                if (EPI == FREE_EPI_BIAS) {
-                    out[o] = float_to_bf16(v);
-                } else if (EPI == FREE_EPI_BIAS_GELU) {
-                    out[o] = float_to_bf16(gelu_fast(v));
-                } else {
-                    const float g = gate.base[static_cast<int64_t>(gm / gate.rows_per_sample) * gate.stride + gn];
-                    resid[o] = fmaf(g, v, resid[o]);
-                }
-            }
-        }
+    // ---- epilogue
+    // after the barrier of the last slice no wavefront reads the LDS tiles any more: each wavefront
+    // may use a private 32 x (TN*64 + 16)-byte region of them to transpose its bf16 output
+    write_tile<TM, TN, EPI>(acc, m0 + wm * TM * 32 + l32, n0 + wn * TN * 32, lane, M, N, vec_ok, bias, out, resid, gate,
+                            lds + wave * (32 * (TN * 64 + 16)));
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>

@@ -202,3 +202,26 @@ def test_xl2_512_cfg_round_bf16():
 
 def test_xl2_256_round_fp32():
     _xl_round("xl2_256", 6, 4.0, "fp32", oracle_states=[2])
+
+
+def test_batch_streams_same_result():
+    """The two halves of a large batch run on two streams by default; the serial schedule
+    (one stream) must give the same numbers: every kernel reduces in the same order
+    whatever the number of rows it is launched on."""
+    import torch
+    from paper_2511_20390_amd import binding
+    assert binding.get_batch_streams() == 2
+    # B = 5 at 1024 tokens: halves of 2 and 3 samples, both at or above the split threshold
+    cfg, w, x, t, y, eps2, feat2, model = _forward_case("xl2_512", "bf16", 5, seed=0)
+    binding.set_batch_streams(1)
+    try:
+        eps1, feat1 = model.dit_forward_packed(pu.to_dev(x), pu.to_dev(t), pu.to_dev(y), want_feat=True)
+        torch.cuda.synchronize()
+    finally:
+        binding.set_batch_streams(2)
+    e, f = pu.rel_l2(eps2, eps1.cpu().numpy()), pu.rel_l2(feat2, feat1.cpu().numpy())
+    print(f"two streams vs one: eps rel-L2 {e:.3e}, top-feature rel-L2 {f:.3e}")
+    assert e < 1e-6 and f < 1e-6
+    with pytest.raises(binding.FreeError):
+        binding.set_batch_streams(3)
+    model.close()
