@@ -13,10 +13,11 @@
 // The key order inside each 32-key block is permuted when K is written to LDS
 // (bits 2 and 3 of the row index swapped) so that the 8 probabilities a lane feeds
 // to one MFMA belong to 8 CONSECUTIVE keys: the matching V^T operand is then a
-// single 16-byte LDS read.  V is transposed on its way into LDS.
+// pair of transposing LDS reads (ds_read_b64_tr_b16) of the row-major V tile.
 // Head dim 72 (DiT-XL): the contraction over d is padded 72 -> 80 with zero chunks
 // in LDS; the O^T rows are padded 72 -> 96 and the pad rows are never stored.
 #include <cmath>
+#include <type_traits>
 
 #include "free_internal.h"
 
@@ -28,17 +29,22 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef short v4s_t __attribute__((ext_vector_type(4)));
+typedef short v8s_t __attribute__((ext_vector_type(8)));
 
 constexpr int kThreads = 256;
 constexpr int BKV = 64;                   // keys per LDS tile
-constexpr int VROW = 144;                 // bytes per V^T row in LDS: 64 keys (128 B) + 16 B pad, odd # of 16-B chunks
 
 __device__ inline int swap_bits_2_3(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) { return pack_bf16_pair(lo, hi); }   // v_cvt_pk_bf16_f32
 
+// amdgpu_waves_per_eu(2): two workgroups per CU are wanted anyway (LDS and registers allow it), and
+// with at most 256 registers per lane the compiler uses the VGPR form of the MFMAs - with the
+// default budget of 512 it parks accumulators in AGPRs and moves them back and forth for the
+// softmax (several hundred v_accvgpr moves per key tile).
 template <int DH, int QT>
-__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __restrict__ qkv, int32_t N,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(const bf16_t* __restrict__ qkv, int32_t N,
                                                              int32_t heads, float scale_log2,
                                                              bf16_t* __restrict__ out) {
     constexpr int KSTEPS = (DH + 15) / 16;            // MFMA k-steps over the head dim (S^T)
@@ -47,7 +53,11 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
     constexpr int KROW = ((2 * KSTEPS) | 1) * 16;     // bytes per K row in LDS (odd # of chunks)
     constexpr int BQ = 4 * 32 * QT;                   // queries per workgroup
     constexpr int NLD = (BKV * DCH + kThreads - 1) / kThreads;   // 16-byte loads per thread per tile
-    constexpr int kKBytes = BKV * KROW, kVBytes = DT * 32 * VROW;
+    // V stays row-major in LDS ([key][d]) and is read with the transposing LDS load; a row stride of
+    // 64 or 192 (mod 256) bytes puts the 4 keys x 64 bytes that 32 lanes of such a load touch on
+    // disjoint banks
+    constexpr int VROW = DT == 1 ? 64 : (DT <= 3 ? 192 : 320);
+    constexpr int kKBytes = BKV * KROW, kVBytes = BKV * VROW;
     __shared__ __attribute__((aligned(16))) char sKbuf[2 * kKBytes];      // two stages: tile t is multiplied
     __shared__ __attribute__((aligned(16))) char sVbuf[2 * kVBytes];      // while tile t+1 is written
 
@@ -79,9 +89,10 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
         const int c = i % (KROW / 16);
         if (c >= DCH) *reinterpret_cast<u32x4_t*>(sKbuf + (i / (KROW / 16)) * KROW + c * 16) = u32x4_t{0, 0, 0, 0};
     }
-    for (int st = 0; st < 2; ++st)
-        for (int i = tid; i < (DT * 32 - DH) * (VROW / 16); i += kThreads)
-            *reinterpret_cast<u32x4_t*>(sVbuf + st * kVBytes + DH * VROW + i * 16) = u32x4_t{0, 0, 0, 0};
+    for (int i = tid; i < 2 * BKV * (VROW / 16); i += kThreads) {
+        const int c = i % (VROW / 16);
+        if (c >= DCH) *reinterpret_cast<u32x4_t*>(sVbuf + (i / (VROW / 16)) * VROW + c * 16) = u32x4_t{0, 0, 0, 0};
+    }
 
     // Q^T fragments (B operand of S^T): lane holds query column l32, k-slots d = 16 ks + 8 g + j
     bf16x8_t qf[QT][KSTEPS];
@@ -99,29 +110,35 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
         }
     }
 
-    // global -> register staging of one K/V tile
-    u32x4_t kreg[NLD], vreg[NLD];
-    auto fetch = [&](int kv0) {
+    // global -> register staging of one K/V tile: thread chunk idx = tid + 256 i -> key row idx / DCH,
+    // 16-byte chunk idx % DCH of that row, for K and for V alike (lanes walk the chunks of a row).
+    // Buffer loads over the rows of this sample: keys past N read as zero (on gfx950 the scalar offset
+    // takes part in the range check, measured), the tile and the K / V column offsets are wave-uniform
+    // scalar offsets, one per-lane byte offset per load.
+    const __amdgpu_buffer_rsrc_t srd = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(qkv_b) + row0 * row_bytes, 0, static_cast<int>(N * row_bytes), 0x00020000);
+    const int k_col = (D + h * DH) * 2, v_col = (2 * D + h * DH) * 2;
+    int ld_off[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int idx = tid + kThreads * i;
+        ld_off[i] = (idx / DCH) * static_cast<int>(row_bytes) + (idx % DCH) * 16;
+    }
+    // two register sets: the loads of tiles t+2 and t+3 are in flight while tile t is processed
+    u32x4_t kreg[2][NLD], vreg[2][NLD];
+    auto fetch = [&](int t, auto set) {
+        constexpr int S = decltype(set)::value;
+        const int tile_off = t * BKV * static_cast<int>(row_bytes);
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const int idx = tid + kThreads * i;
-            if (idx < BKV * DCH) {
-                {   // K: lanes walk the chunks of a row (coalesced)
-                    int kv = kv0 + idx / DCH;
-                    if (kv >= N) kv = N - 1;
-                    kreg[i] = *reinterpret_cast<const u32x4_t*>(qkv_b + (row0 + kv) * row_bytes +
-                                                                 static_cast<size_t>(D + h * DH) * 2 + (idx % DCH) * 16);
-                }
-                {   // V: lanes walk the keys of one chunk (conflict-free transposed LDS writes)
-                    int kv = kv0 + (idx & (BKV - 1));
-                    if (kv >= N) kv = N - 1;
-                    vreg[i] = *reinterpret_cast<const u32x4_t*>(qkv_b + (row0 + kv) * row_bytes +
-                                                                 static_cast<size_t>(2 * D + h * DH) * 2 + (idx / BKV) * 16);
-                }
+            if (tid + kThreads * i < BKV * DCH) {
+                kreg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(srd, ld_off[i], tile_off + k_col, 0);
+                vreg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(srd, ld_off[i], tile_off + v_col, 0);
             }
         }
     };
-    auto stash = [&](int stage) {
+    auto stash = [&](int stage, auto set) {
+        constexpr int S = decltype(set)::value;
         char* sK = sKbuf + stage * kKBytes;
         char* sV = sVbuf + stage * kVBytes;
 #pragma unroll
@@ -130,17 +147,17 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
             if (idx < BKV * DCH) {
                 const int r = idx / DCH;
                 const int lr = (r & ~31) | swap_bits_2_3(r & 31);
-                *reinterpret_cast<u32x4_t*>(sK + lr * KROW + (idx % DCH) * 16) = kreg[i];
-                const int kv = idx & (BKV - 1), c = idx / BKV;
-                const uint32_t w[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    *reinterpret_cast<uint16_t*>(sV + (8 * c + 2 * e) * VROW + kv * 2) = static_cast<uint16_t>(w[e] & 0xffffu);
-                    *reinterpret_cast<uint16_t*>(sV + (8 * c + 2 * e + 1) * VROW + kv * 2) = static_cast<uint16_t>(w[e] >> 16);
-                }
+                *reinterpret_cast<u32x4_t*>(sK + lr * KROW + (idx % DCH) * 16) = kreg[S][i];
+                *reinterpret_cast<u32x4_t*>(sV + r * VROW + (idx % DCH) * 16) = vreg[S][i];
             }
         }
     };
+    // Transposing read of V (ds_read_b64_tr_b16).  Within 16 lanes, lane i receives element i % 4 of
+    // the 8 bytes addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With source lane r of 16-lane
+    // group G pointing at V[8 (G/2) + r/4][16 (G%2) + 4 (r%4) ..+3], lane l gets 4 consecutive keys
+    // 8 (l/32) + 0..3 of head-dim column l % 32: half of the A operand of O^T += V^T P^T; the same
+    // read 4 rows further down gives the other half.
+    const int vtr_off = (8 * (lane >> 5) + ((lane & 15) >> 2)) * VROW + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
     f32x16_t o[DT][QT];
 #pragma unroll
@@ -160,11 +177,16 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
     for (int qt = 0; qt < QT; ++qt) { m_ref[qt] = -INFINITY; l_run[qt] = 0.f; }
 
     const int ntiles = (N + BKV - 1) / BKV;
-    fetch(0);
-    stash(0);
-    if (ntiles > 1) fetch(BKV);
+    const std::integral_constant<int, 0> set0{};
+    const std::integral_constant<int, 1> set1{};
+    fetch(0, set0);
+    stash(0, set0);
+    if (ntiles > 1) fetch(1, set1);
+    if (ntiles > 2) fetch(2, set0);
     __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
+    // tile t: its K/V are in LDS stage t % 2; tile t+1 sits in register set (t+1) % 2
+    auto tile = [&](int t, auto ragged, auto next_set) {
+        constexpr bool kRagged = decltype(ragged)::value;
         const int kv0 = t * BKV;
         const char* sK = sKbuf + (t & 1) * kKBytes;
         const char* sV = sVbuf + (t & 1) * kVBytes;
@@ -191,12 +213,12 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
         }
         // the next tile moves from registers to the other LDS stage while this one is processed;
         // the tile after it is requested from global memory
-        if (t + 1 < ntiles) stash((t + 1) & 1);
-        if (t + 2 < ntiles) fetch(kv0 + 2 * BKV);
+        if (t + 1 < ntiles) stash((t + 1) & 1, next_set);
+        if (t + 3 < ntiles) fetch(t + 3, next_set);
 
         // keys past N (last tile only): accumulator register e of block kb holds the key
         // kv0 + 32 kb + 16 (e/8) + 8 g + 4 ((e/4)%2) + e%4   (LDS rows were permuted on the way in)
-        if (kv0 + BKV > N) {
+        if (kRagged) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -219,7 +241,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
 #pragma unroll
                 for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[kb][qt][e]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                 // both half-waves of a column agree
-            if (__any((mx - m_ref[qt]) * scale_log2 > kLazy)) {     // also true for the first tile (m_ref = -inf)
+            if (__builtin_expect(__any((mx - m_ref[qt]) * scale_log2 > kLazy), 0)) {     // also true for the first tile (m_ref = -inf)
                 const float m_new = fmaxf(m_ref[qt], mx);
                 const float alpha = __builtin_amdgcn_exp2f((m_ref[qt] - m_new) * scale_log2);
                 l_run[qt] *= alpha;
@@ -255,14 +277,33 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t* __res
             for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
-                    const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sV + (dt * 32 + l32) * VROW +
-                                                                            (kb * 32 + hh * 16 + g * 8) * 2);
+                    using lds_v4 = __attribute__((address_space(3))) v4s_t*;
+                    const char* vp = sV + (kb * 32 + hh * 16) * VROW + dt * 64 + vtr_off;
+                    const v4s_t vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(vp));
+                    const v4s_t vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(vp + 4 * VROW));
+                    const v8s_t v8 = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt)
                         o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][kb][hh], o[dt][qt], 0, 0, 0);
                 }
             }
         __syncthreads();          // stage (t+1)&1 is complete; stage t&1 may be overwritten next iteration
+    };
+    // full tiles need no key masking; only a ragged last tile does
+    const int nfull = N / BKV;
+    int t = 0;
+    for (; t + 1 < nfull; t += 2) {
+        tile(t, std::false_type{}, set1);
+        tile(t + 1, std::false_type{}, set0);
+    }
+    if (t < nfull) {
+        tile(t, std::false_type{}, set1);
+        ++t;
+    }
+    if (t < ntiles) {
+        if (t & 1) tile(t, std::true_type{}, set0);
+        else tile(t, std::true_type{}, set1);
     }
 
     // ---- normalise and store: register e of O^T tile dt is row d = 32 dt + 8 (e/4) + 4 g + e%4, column l32
@@ -309,6 +350,8 @@ int32_t launch_attention_mfma(const bf16_t* qkv, int32_t B, int32_t N, int32_t h
                               hipStream_t s) {
     if (reinterpret_cast<uintptr_t>(qkv) & 15u) return FREE_ERR_SHAPE;
     if (B > 65535 || heads > 65535) return FREE_ERR_SHAPE;
+    // one sample's rows are addressed through a buffer descriptor with 32-bit byte offsets
+    if (static_cast<int64_t>(N) * 3 * heads * dh * 2 >= (1ll << 31)) return FREE_ERR_SHAPE;
     switch (dh) {
         case 16: return launch_dh<16>(qkv, B, N, heads, out, s);
         case 64: return launch_dh<64>(qkv, B, N, heads, out, s);
