@@ -60,7 +60,6 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 constexpr int BK = 64;                    // bf16 elements per K slice (128 bytes per row)
 constexpr int kRowBytes = BK * 2;
 constexpr int kNumXcd = 8;
-constexpr int kGroupM = 8;
 
 __device__ inline float gelu_fast(float v) {
     // tanh-form GELU: 0.5 v (1 + tanh(u)) = v / (1 + exp(-2u)), u = sqrt(2/pi)(v + 0.044715 v^3)
@@ -93,6 +92,7 @@ __device__ __forceinline__ void sched_hints() {
 // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so the
 // ids of one XCD are made contiguous first, then walked in groups of kGroupM row
 // tiles (column-major inside a group) so concurrent workgroups share X and W panels.
+template <int kGroupM>
 __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, int* tn) {
     const int total = tiles_m * tiles_n;
     const int q = total / kNumXcd, r = total % kNumXcd;
@@ -260,7 +260,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     int tile_m, tile_n;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, &tile_m, &tile_n);
+    // row tiles per group: the 32 workgroups that run together on an XCD then cover a x b tiles with
+    // a BM ~ b BN, the shape that needs the fewest distinct X and W panels (first-touch L2 misses)
+    tile_coords<(BM > BN ? 4 : 8)>(blockIdx.x, tiles_m, tiles_n, &tile_m, &tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
