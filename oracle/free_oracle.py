@@ -28,6 +28,16 @@ for the schedule, adaLN-Zero identity blocks, permutation/packing invariance,
 and agreement with an independent implementation built from library routines.
 The DiT forward has no published activations to compare against: beyond those
 invariants and the library-routine cross-check it is "parity unpinned".
+
+* The drafter and the drafting loop (Sec. 3.2, "Feature-Level Autoregressive
+  Drafting"; Alg. 1, inner drafting loop): shared embedding -> FC layer fusing
+  the embedding output with the propagated top-block feature -> DiT block(s)
+  -> output projection -> noise estimate -> transition mean -> sample.  Pins:
+  a drafter whose fusion passes the embedding through and whose block and
+  output weights are the target's reproduces the (depth-limited) target, such
+  a drafter is always accepted by the verification, the feature-only fusion
+  ignores the latent, and the drafted chain equals its step-by-step
+  composition.  Like the DiT forward it is otherwise "parity unpinned".
 """
 from __future__ import annotations
 
@@ -365,3 +375,75 @@ def spec_round(w: dict, cfg: dict, x_states, x_last, m_draft, t, y: int, cfg_sca
                       None if lam is None else np.asarray(lam).reshape(1, K))
     res["m_target"] = m.reshape(K, -1)
     return res
+
+
+# ----------------------------------------------------------------------------
+# Drafter and autoregressive drafting (Sec. 3.2; Alg. 1, drafting loop)
+# ----------------------------------------------------------------------------
+def drafter_forward(wd: dict, w: dict, cfg: dict, x, f_prev, t, y):
+    """One evaluation of the drafter p(. | x^_{t-1}, f_{t-1}) (Sec. 3.2).
+
+    The drafter reuses the target's embedding layers (patch embedding with the
+    positional table, timestep and label embedding: weights `w`), fuses the
+    embedded latent with the propagated feature by one fully connected layer on
+    their concatenation [embedding | feature] (`wd["fuse_w"]` is [D, 2D]), runs
+    its own DiT block(s) (`wd["blk{l}.*"]`, `cfg["drafter_depth"]` of them, one
+    in the paper's main setting) and a small output projection of the same form
+    as the target's final layer (`wd["fin_*"]`).
+
+    x [B, C, H, W], f_prev [B, N, D], t, y [B].  Returns (out [B, c_out, H, W],
+    f [B, N, D]): the noise estimate sits in channels [0, C) of `out`, `f` (the
+    output of the last drafter block) is the predicted next top-block feature.
+    """
+    x = np.asarray(x, F64)
+    B, C, H, W = x.shape
+    p, D, heads = cfg["patch"], cfg["hidden"], cfg["heads"]
+    ddepth = cfg.get("drafter_depth", 1)
+    gh, gw = H // p, W // p
+    sc = silu(conditioning(w, cfg, np.asarray(t), np.asarray(y)))
+    emb = linear(patchify(x, p), w["patch_w"], w["patch_b"]) + pos_embed_2d(gh, gw, D)
+    c_out = 2 * C if cfg.get("learn_sigma", 1) else C
+    out_tok = np.empty((B, gh * gw, p * p * c_out), F64)
+    feat = np.empty((B, gh * gw, D), F64)
+    for r in range(B):
+        z = linear(np.concatenate([emb[r], np.asarray(f_prev, F64)[r]], axis=1), wd["fuse_w"], wd["fuse_b"])
+        for l in range(ddepth):
+            z = dit_block(z, sc[r], wd, l, heads)
+        feat[r] = z
+        mod = linear(sc[r], wd["fin_ada_w"], wd["fin_ada_b"])
+        out_tok[r] = linear(layer_norm(z) * (1.0 + mod[D:]) + mod[:D], wd["fin_w"], wd["fin_b"])
+    return unpatchify(out_tok, p, c_out, gh, gw), feat
+
+
+def draft_steps(wd: dict, w: dict, cfg: dict, x_a, f_a, t, y: int, cfg_scale: float,
+                coef_x, coef_eps, sigma, xi) -> dict:
+    """The drafting loop of Alg. 1 for one trajectory.
+
+    Starting from the reference state x_a and the target's top-block feature
+    f_a, step k = 0..K-1 evaluates the drafter on (x^_k, f_{k-1}) at timestep
+    t[k] (x^_0 = x_a, f_{-1} = f_a), turns its noise estimate into the draft
+    mean m^_k = coef_x[k] x^_k + coef_eps[k] eps^_k and draws the next draft
+    x^_{k+1} = m^_k + sigma[k] xi[k] (xi: the standard normal draws, an input).
+    With guidance (cfg_scale > 1) the drafter runs on the label and on the null
+    label, each branch carrying its own feature (f_a is [2, N, D]: label branch
+    first), and the two noise estimates are combined as in the target.
+
+    Returns x_states [K, C, H, W] = (x_a, x^_1 .. x^_{K-1}), x_last = x^_K,
+    m_draft [K, d] and the final feature(s): exactly the inputs of spec_round.
+    """
+    x_a = np.asarray(x_a, F64)
+    C = x_a.shape[0]
+    K = len(t)
+    dup = 2 if cfg_scale > 1.0 else 1
+    f = np.asarray(f_a, F64).reshape((dup,) + np.asarray(f_a).shape[-2:])
+    yy = np.array([y, cfg["num_classes"]][:dup])
+    xs = [x_a]
+    m_draft = []
+    for k in range(K):
+        xk = xs[-1]
+        out, f = drafter_forward(wd, w, cfg, np.repeat(xk[None], dup, axis=0), f, np.full(dup, t[k]), yy)
+        eps = cfg_combine(out[0, :C], out[1, :C], cfg_scale) if dup == 2 else out[0, :C]
+        m = float(coef_x[k]) * xk + float(coef_eps[k]) * eps
+        m_draft.append(m.reshape(-1))
+        xs.append(m + float(sigma[k]) * np.asarray(xi, F64)[k].reshape(m.shape))
+    return dict(x_states=np.stack(xs[:K]), x_last=xs[K], m_draft=np.stack(m_draft), f_last=f)

@@ -30,7 +30,7 @@ CONFIGS = {
 }
 
 # names of the large matrices that are stored as bf16 buffers in bf16 mode
-BIG_MATRIX_SUFFIXES = ("ada_w", "qkv_w", "proj_w", "fc1_w", "fc2_w", "fin_ada_w", "fin_w")
+BIG_MATRIX_SUFFIXES = ("ada_w", "qkv_w", "proj_w", "fc1_w", "fc2_w", "fin_ada_w", "fin_w", "fuse_w")
 
 
 def dit_config(name: str, **over) -> dict:
@@ -66,6 +66,53 @@ def weight_spec(cfg: dict):
     spec += [("fin_ada_w", (2 * D, D)), ("fin_ada_b", (2 * D,)),
              ("fin_w", (pp * c_out, D)), ("fin_b", (pp * c_out,))]
     return spec
+
+
+def drafter_weight_spec(cfg: dict, drafter_depth: int = 1):
+    """Ordered (name, shape) list of the drafter's own weights (it shares the
+    embedding layers with the target): fusion layer on [embedding | feature],
+    `drafter_depth` blocks of the target's form, output projection of the form
+    of the target's final layer.  About 32 M parameters at DiT-XL/2 width."""
+    D, F = cfg["hidden"], cfg["mlp_hidden"]
+    pp = cfg["patch"] ** 2
+    c_out = cfg["in_ch"] * (2 if cfg["learn_sigma"] else 1)
+    spec = [("fuse_w", (D, 2 * D)), ("fuse_b", (D,))]
+    for l in range(drafter_depth):
+        spec += [(f"blk{l}.ada_w", (6 * D, D)), (f"blk{l}.ada_b", (6 * D,)),
+                 (f"blk{l}.qkv_w", (3 * D, D)), (f"blk{l}.qkv_b", (3 * D,)),
+                 (f"blk{l}.proj_w", (D, D)), (f"blk{l}.proj_b", (D,)),
+                 (f"blk{l}.fc1_w", (F, D)), (f"blk{l}.fc1_b", (F,)),
+                 (f"blk{l}.fc2_w", (D, F)), (f"blk{l}.fc2_b", (D,))]
+    spec += [("fin_ada_w", (2 * D, D)), ("fin_ada_b", (2 * D,)),
+             ("fin_w", (pp * c_out, D)), ("fin_b", (pp * c_out,))]
+    return spec
+
+
+def make_drafter_weights(cfg: dict, drafter_depth: int = 1, seed: int = 1, std: float = 0.02,
+                         bf16_values: bool = False) -> dict:
+    """Random-init drafter weights ~ N(0, std^2) (a stand-in for the trained drafter)."""
+    rng = np.random.default_rng(seed)
+    w = {}
+    for name, shape in drafter_weight_spec(cfg, drafter_depth):
+        a = rng.standard_normal(shape, dtype=np.float32) * np.float32(std)
+        w[name] = bf16_round(a) if bf16_values else a
+    return w
+
+
+def make_draft_inputs(cfg: dict, K: int, seed: int, cfg_scale: float, t0: int | None = None, T: int = 1000) -> dict:
+    """Inputs of one drafting loop: reference state ~ N(0, I), a top-block feature per guidance
+    branch ~ N(0, 1) (stand-in for the target's), consecutive timesteps, a label, standard normal draws."""
+    rng = np.random.default_rng(seed)
+    C, H, W = cfg["in_ch"], cfg["lat_h"], cfg["lat_w"]
+    dup = 2 if cfg_scale > 1.0 else 1
+    x_a = rng.standard_normal((C, H, W), dtype=np.float32)
+    f_a = rng.standard_normal((dup, n_tokens(cfg), cfg["hidden"]), dtype=np.float32)
+    if t0 is None:
+        t0 = int(rng.integers(K - 1, T))
+    t = (t0 - np.arange(K)).astype(np.int32)
+    y = int(rng.integers(0, cfg["num_classes"]))
+    xi = rng.standard_normal((K, C * H * W), dtype=np.float32)
+    return dict(x_a=x_a, f_a=f_a, t=t, y=y, xi=xi)
 
 
 def is_big_matrix(name: str) -> bool:
