@@ -179,6 +179,58 @@ int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, con
                    int32_t* n_accept, float* x_out,
                    void* workspace, size_t ws_bytes, void* stream);
 
+/* ---- drafter and drafting loop (Sec. 3.2 "Feature-Level Autoregressive Drafting";
+ *      Alg. 1, inner drafting loop) ------------------------------------------
+ * The drafter shares the target's embedding layers (patch embedding with the
+ * positional table, timestep and label embedding), fuses the embedded latent
+ * with the propagated top-block feature by one fully connected layer on their
+ * concatenation [embedding | feature], runs `drafter_depth` DiT blocks of its
+ * own (one in the paper's main setting) and an output projection of the form
+ * of the target's final layer.
+ *
+ * Weights [device], borrowed until free_drafter_destroy, in this order, the
+ * large matrices in the target's compute type, the rest fp32, all 16-byte
+ * aligned, matrices [out, in] row-major:
+ *   fuse_w [D, 2D], fuse_b [D],
+ *   per block: the 10 tensors of a target block (ada_w .. fc2_b),
+ *   fin_ada_w [2D, D], fin_ada_b [2D], fin_w [p*p*c_out, D], fin_b.
+ * free_drafter_weight_count(depth) = 2 + 10 depth + 4.  The target handle must
+ * outlive the drafter. */
+typedef struct free_drafter_s* free_drafter_t;
+int32_t free_drafter_weight_count(int32_t drafter_depth);
+int32_t free_drafter_create(free_dit_t target, int32_t drafter_depth, const void* const* weight_ptrs,
+                            int32_t n_ptrs, free_drafter_t* out);
+int32_t free_drafter_destroy(free_drafter_t dr);
+/* Workspace of drafter_forward on B samples; also sufficient for draft_round
+ * (which runs B = 1, or 2 with guidance).  0 on bad arguments. */
+size_t free_drafter_workspace_bytes(free_dit_t target, int32_t drafter_depth, int32_t B);
+
+/* One drafter evaluation p(. | x^_{t-1}, f_{t-1}) on B samples.
+ *   x [B, C, H, W], f_prev [B, N, D] fp32, t, y [B] int32  [device]
+ *   eps_out [B, c_out, H, W] fp32: noise estimate in channels [0, C)
+ *   f_out   [B, N, D] fp32: predicted next top-block feature; may alias f_prev
+ * Enqueues on `stream`; FREE_ERR_* as for dit_forward_packed. */
+int32_t drafter_forward(free_drafter_t dr, const float* x, const float* f_prev, const int32_t* t,
+                        const int32_t* y, int32_t B, float* eps_out, float* f_out,
+                        void* workspace, size_t ws_bytes, void* stream);
+
+/* The drafting loop of one trajectory: for k = 0..K-1 the drafter runs on
+ * (x^_k, f_{k-1}) at timestep t[k] (x^_0 = x_a, f_{-1} = f_a), its noise estimate
+ * gives the draft mean m^_k = coef_x[k] x^_k + coef_eps[k] eps^_k (Eq. ddpm_update)
+ * and the next draft is x^_{k+1} = m^_k + sigma[k] xi[k].  With cfg_scale > 1 the
+ * drafter runs on the label y and on the null label, each branch with its own
+ * feature, and the two estimates are combined as in spec_round.
+ *   x_a [C, H, W]; f_a [dup, N, D] (dup = 2 with guidance: label branch first);
+ *   t [K] int32; coef_x, coef_eps, sigma [K]; xi [K, d] standard normal draws
+ *   (an input: the library has no generator)                         [device]
+ *   outputs, the inputs of spec_round: x_states [K, C, H, W] (x_states[0] = x_a),
+ *   x_last [d], m_draft [K, d]; f_last [dup, N, D] (optional, may be NULL): the
+ *   feature after the last step. */
+int32_t draft_round(free_drafter_t dr, const float* x_a, const float* f_a, const int32_t* t, int32_t y,
+                    float cfg_scale, const float* coef_x, const float* coef_eps, const float* sigma,
+                    const float* xi, int32_t K, float* x_states, float* x_last, float* m_draft,
+                    float* f_last, void* workspace, size_t ws_bytes, void* stream);
+
 /* ---- per-kernel timing for benchmarks -------------------------------------
  * Between free_profile_begin and free_profile_end every kernel launch of the
  * hot-path calls is bracketed by two HIP events recorded on the launch stream.

@@ -25,6 +25,8 @@ EXPORTED_SYMBOLS = [
     "free_get_batch_streams", "free_ddpm_schedule",
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
     "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
+    "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
+    "drafter_forward", "draft_round",
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
     "free_profile_begin", "free_profile_end", "free_profile_category_name",
 ]
@@ -82,6 +84,18 @@ def load():
     lib.spec_verify.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp, sz, vp]
     lib.spec_round.restype = i32
     lib.spec_round.argtypes = [vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.free_drafter_weight_count.restype = i32
+    lib.free_drafter_weight_count.argtypes = [i32]
+    lib.free_drafter_create.restype = i32
+    lib.free_drafter_create.argtypes = [vp, i32, C.POINTER(vp), i32, C.POINTER(vp)]
+    lib.free_drafter_destroy.restype = i32
+    lib.free_drafter_destroy.argtypes = [vp]
+    lib.free_drafter_workspace_bytes.restype = sz
+    lib.free_drafter_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.drafter_forward.restype = i32
+    lib.drafter_forward.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.draft_round.restype = i32
+    lib.draft_round.argtypes = [vp, vp, vp, vp, i32, f32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.free_op_linear.restype = i32
     lib.free_op_linear.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, i32, vp]
     lib.free_op_attention.restype = i32
@@ -243,6 +257,81 @@ class FreeDit:
                                  K, _ptr(out["m_target"]), _ptr(out["log_ratio"]), _ptr(out["accept"]),
                                  _ptr(out["n_accept"]), _ptr(out["x_out"]), _ptr(ws), ws.numel(), _stream()),
                "spec_round")
+        return out
+
+
+class FreeDrafter:
+    """Drafter handle on top of a FreeDit target (shares its embedding layers); borrows the caller's
+    drafter weight tensors (kept alive here).  The target must outlive it."""
+
+    def __init__(self, target: FreeDit, weights: dict, drafter_depth: int = 1):
+        import torch
+        from . import synth
+        self.target, self.depth = target, int(drafter_depth)
+        self.device = target.device
+        self.tensors = []
+        for name, shape in synth.drafter_weight_spec(target.cfg, self.depth):
+            a = torch.from_numpy(np.ascontiguousarray(weights[name], dtype=np.float32)).reshape(shape).to(self.device)
+            if target.mode == "bf16" and synth.is_big_matrix(name):
+                a = a.to(torch.bfloat16)
+            self.tensors.append(a.contiguous())
+        n = load().free_drafter_weight_count(self.depth)
+        if n != len(self.tensors):
+            raise FreeError(FREE_ERR_SHAPE, "free_drafter_weight_count")
+        arr = (C.c_void_p * n)(*[t.data_ptr() for t in self.tensors])
+        self.handle = C.c_void_p()
+        _check(load().free_drafter_create(target.handle, self.depth, arr, n, C.byref(self.handle)), "free_drafter_create")
+        self._ws = {}
+
+    def close(self):
+        if getattr(self, "handle", None) is not None and self.handle.value:
+            load().free_drafter_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace(self, B: int):
+        import torch
+        if B not in self._ws:
+            n = load().free_drafter_workspace_bytes(self.target.handle, self.depth, B)
+            self._ws[B] = torch.empty(n, dtype=torch.uint8, device=self.device)
+        return self._ws[B]
+
+    def drafter_forward(self, x, f_prev, t, y):
+        """One drafter evaluation on B samples: returns (eps [B, c_out, H, W], f [B, N, D])."""
+        import torch
+        tg = self.target
+        B = x.shape[0]
+        eps = torch.empty(B, tg.c_out, tg.H, tg.W, dtype=torch.float32, device=self.device)
+        f = torch.empty(B, tg.ntok, tg.cfg["hidden"], dtype=torch.float32, device=self.device)
+        ws = self.workspace(B)
+        _check(load().drafter_forward(self.handle, _ptr(x), _ptr(f_prev), _ptr(t), _ptr(y), B, _ptr(eps), _ptr(f),
+                                      _ptr(ws), ws.numel(), _stream()), "drafter_forward")
+        return eps, f
+
+    def draft_round(self, x_a, f_a, t, y: int, cfg_scale: float, coef_x, coef_eps, sigma, xi, want_feat=False,
+                    out=None):
+        """K drafting steps: returns dict(x_states [K, C, H, W], x_last [d], m_draft [K, d], f_last)."""
+        import torch
+        tg = self.target
+        K = t.shape[0]
+        dup = 2 if cfg_scale > 1.0 else 1
+        dev = self.device
+        if out is None:
+            out = dict(x_states=torch.empty(K, tg.C, tg.H, tg.W, dtype=torch.float32, device=dev),
+                       x_last=torch.empty(tg.d, dtype=torch.float32, device=dev),
+                       m_draft=torch.empty(K, tg.d, dtype=torch.float32, device=dev),
+                       f_last=torch.empty(dup, tg.ntok, tg.cfg["hidden"], dtype=torch.float32, device=dev)
+                       if want_feat else None)
+        ws = self.workspace(dup)
+        _check(load().draft_round(self.handle, _ptr(x_a), _ptr(f_a), _ptr(t), int(y), float(cfg_scale), _ptr(coef_x),
+                                  _ptr(coef_eps), _ptr(sigma), _ptr(xi), K, _ptr(out["x_states"]), _ptr(out["x_last"]),
+                                  _ptr(out["m_draft"]), _ptr(out["f_last"]), _ptr(ws), ws.numel(), _stream()),
+               "draft_round")
         return out
 
 

@@ -737,6 +737,40 @@ int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 
+// ---- drafter helpers (Sec. 3.2: FC layer on [embedding | propagated feature]; Alg. 1 drafting loop) ----
+// fin[m, 0:D] = emb[m, :], fin[m, D:2D] = feat[m, :] in the compute type; 4 elements per thread (D % 4 == 0)
+template <typename OT>
+__global__ __launch_bounds__(256) void fuse_pack_kernel(const float* __restrict__ emb, const float* __restrict__ feat,
+                                                        int64_t M, int32_t D, OT* __restrict__ fin) {
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;       // group of 4 output elements
+    const int32_t per_row = 2 * D / 4;
+    if (q >= M * per_row) return;
+    const int64_t m = q / per_row;
+    const int32_t c = static_cast<int32_t>(q % per_row) * 4;
+    const float4 v = c < D ? *reinterpret_cast<const float4*>(emb + m * D + c)
+                           : *reinterpret_cast<const float4*>(feat + m * D + (c - D));
+    OT* o = fin + m * 2 * D + c;
+    if constexpr (sizeof(OT) == 2) {
+        uint2 pk = {pack_bf16_pair(v.x, v.y), pack_bf16_pair(v.z, v.w)};
+        *reinterpret_cast<uint2*>(o) = pk;
+    } else {
+        *reinterpret_cast<float4*>(o) = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, int64_t n4, float v) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n4) reinterpret_cast<float4*>(p)[i] = float4{v, v, v, v};
+}
+
+// x_next = m + sigma[k] * xi  (the draw of the next draft from its proposal, Alg. 1)
+__global__ __launch_bounds__(256) void gauss_step_kernel(const float* __restrict__ m, const float* __restrict__ sigma_k,
+                                                         const float* __restrict__ xi, int64_t n,
+                                                         float* __restrict__ out) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) out[i] = fmaf(sigma_k[0], xi[i], m[i]);
+}
+
 int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const float* coef_x,
                            const float* coef_eps, float cfg_scale, int32_t K, int32_t C, int32_t c_out,
                            int64_t hw, float* m_out, hipStream_t s) {
@@ -752,6 +786,33 @@ int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_
     const int n = K * dup;
     hipLaunchKernelGGL(pack_cond_kernel, dim3((n + 63) / 64), dim3(64), 0, s, t, y, null_label, K, dup, t_out,
                        y_out);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_fuse_pack(const float* emb, const float* feat, int64_t M, int32_t D, int32_t dtype, void* fin,
+                         hipStream_t s) {
+    if (D % 4) return FREE_ERR_SHAPE;
+    const int64_t groups = M * (2 * D / 4);
+    const unsigned blocks = static_cast<unsigned>((groups + 255) / 256);
+    if (dtype == FREE_BF16)
+        hipLaunchKernelGGL(fuse_pack_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, emb, feat, M, D,
+                           static_cast<bf16_t*>(fin));
+    else
+        hipLaunchKernelGGL(fuse_pack_kernel<float>, dim3(blocks), dim3(256), 0, s, emb, feat, M, D,
+                           static_cast<float*>(fin));
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t s) {
+    if (n % 4 || (reinterpret_cast<uintptr_t>(p) & 15u)) return FREE_ERR_SHAPE;
+    hipLaunchKernelGGL(fill_f32_kernel, dim3(static_cast<unsigned>((n / 4 + 255) / 256)), dim3(256), 0, s, p, n / 4, v);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_gauss_step(const float* m, const float* sigma_k, const float* xi, int64_t n, float* out,
+                          hipStream_t s) {
+    hipLaunchKernelGGL(gauss_step_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, m, sigma_k,
+                       xi, n, out);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 

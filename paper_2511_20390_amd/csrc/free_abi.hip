@@ -136,6 +136,21 @@ struct free_dit_s {
     const void* fin(int which) const { return w[7 + 10 * dims.depth + which]; }
 };
 
+struct free_drafter_s {
+    free_dit_t target = nullptr;
+    int depth = 1;
+    int32_t mod_rows = 0;                // depth*6D + 2D
+    std::vector<const void*> w;          // borrowed device pointers, in ABI order
+    void* dev_block = nullptr;           // adaLN pointer tables, row starts, a vector of ones
+    const void* const* ada_w_tab = nullptr;
+    const float* const* ada_b_tab = nullptr;
+    const int32_t* ada_row_start = nullptr;
+    const float* ones = nullptr;         // [D]
+
+    const void* const* blkw() const { return w.data() + 2; }
+    const void* fin(int which) const { return w[2 + 10 * depth + which]; }
+};
+
 namespace {
 
 enum { W_PATCH_W = 0, W_PATCH_B, W_T_W1, W_T_B1, W_T_W2, W_T_B2, W_Y_TABLE };
@@ -164,6 +179,76 @@ int32_t attention_dispatch(const Dims& d, const void* qkv, int32_t B, void* out,
     } while (0)
 
 // The packed forward.  x_mod: packed state b reads latent b % x_mod.
+// Activation buffers of a forward on B samples (token rows are sample-major).
+struct ActBufs {
+    float* xres;   // residual stream [B*ntok, D] fp32
+    void* xn;      // LN output       [B*ntok, D]   compute type
+    void* qkv;     //                 [B*ntok, 3D]
+    void* att;     //                 [B*ntok, D]
+    void* hmid;    //                 [B*ntok, F]
+};
+
+// `nblk` adaLN-Zero blocks on samples [b0, b0 + nb) of a batch.  blkw holds 10 pointers per block
+// (B_* order); block l's six modulation vectors of sample b are mod[b * mod_rows + l * 6D ..].
+int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const float* mod, int32_t mod_rows,
+                        const ActBufs& a, int b0, int nb, hipStream_t s) {
+    const size_t esz = d.mode == FREE_BF16 ? 2 : 4;
+    const int32_t M = nb * d.ntok;
+    const int64_t r0 = static_cast<int64_t>(b0) * d.ntok;
+    float* xres_h = a.xres + r0 * d.D;
+    void* xn_h = static_cast<char*>(a.xn) + r0 * d.D * esz;
+    void* qkv_h = static_cast<char*>(a.qkv) + r0 * 3 * d.D * esz;
+    void* att_h = static_cast<char*>(a.att) + r0 * d.D * esz;
+    void* hmid_h = static_cast<char*>(a.hmid) + r0 * d.F * esz;
+    auto vec = [&](int l, int which) {
+        RowVec r;
+        r.base = mod + static_cast<int64_t>(b0) * mod_rows + static_cast<int64_t>(l) * 6 * d.D +
+                 static_cast<int64_t>(which) * d.D;
+        r.stride = mod_rows;
+        r.rows_per_sample = d.ntok;
+        return r;
+    };
+    auto W = [&](int l, int which) { return blkw[10 * l + which]; };
+    auto Bv = [&](int l, int which) { return static_cast<const float*>(blkw[10 * l + which]); };
+    for (int l = 0; l < nblk; ++l) {
+        // x += gate1 * Proj(Attn(LN(x)(1+scale1)+shift1))
+        {
+            ProfScope prof(PROF_LN_MOD, s);
+            FREE_TRY(launch_ln_modulate(xres_h, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn_h, s));
+        }
+        {
+            ProfScope prof(PROF_GEMM_QKV, s);
+            FREE_TRY(linear_dispatch(d, xn_h, W(l, B_QKV_W), Bv(l, B_QKV_B), M, 3 * d.D, d.D, FREE_EPI_BIAS, qkv_h,
+                                     nullptr, RowVec{nullptr, 0, 1}, s));
+        }
+        {
+            ProfScope prof(PROF_ATTN, s);
+            FREE_TRY(attention_dispatch(d, qkv_h, nb, att_h, s));
+        }
+        {
+            ProfScope prof(PROF_GEMM_PROJ, s);
+            FREE_TRY(linear_dispatch(d, att_h, W(l, B_PROJ_W), Bv(l, B_PROJ_B), M, d.D, d.D, FREE_EPI_GATE_RESID,
+                                     nullptr, xres_h, vec(l, 2), s));
+        }
+        // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
+        {
+            ProfScope prof(PROF_LN_MOD, s);
+            FREE_TRY(launch_ln_modulate(xres_h, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn_h, s));
+        }
+        {
+            ProfScope prof(PROF_GEMM_FC1, s);
+            FREE_TRY(linear_dispatch(d, xn_h, W(l, B_FC1_W), Bv(l, B_FC1_B), M, d.F, d.D, FREE_EPI_BIAS_GELU, hmid_h,
+                                     nullptr, RowVec{nullptr, 0, 1}, s));
+        }
+        {
+            ProfScope prof(PROF_GEMM_FC2, s);
+            FREE_TRY(linear_dispatch(d, hmid_h, W(l, B_FC2_W), Bv(l, B_FC2_B), M, d.D, d.F, FREE_EPI_GATE_RESID,
+                                     nullptr, xres_h, vec(l, 5), s));
+        }
+    }
+    return FREE_OK;
+}
+
 int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t* t, const int32_t* y, int32_t B,
                      float* eps_out, float* top_feat, char* ws, hipStream_t s) {
     const Dims& d = h->dims;
@@ -199,60 +284,10 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     FREE_TRY(launch_patch_embed(x, x_mod, B, d.C, d.H, d.W, d.p, d.D, static_cast<const float*>(h->w[W_PATCH_W]),
                                 static_cast<const float*>(h->w[W_PATCH_B]), h->pos, xres, s));
     }
-    const size_t esz = d.mode == FREE_BF16 ? 2 : 4;
-    auto run_blocks = [&](int b0, int nb, hipStream_t s) -> int32_t {
-        const int32_t M = nb * d.ntok;
-        const int64_t r0 = static_cast<int64_t>(b0) * d.ntok;
-        float* xres_h = xres + r0 * d.D;
-        void* xn_h = static_cast<char*>(xn) + r0 * d.D * esz;
-        void* qkv_h = static_cast<char*>(qkv) + r0 * 3 * d.D * esz;
-        void* att_h = static_cast<char*>(att) + r0 * d.D * esz;
-        void* hmid_h = static_cast<char*>(hmid) + r0 * d.F * esz;
-        auto vec = [&](int l, int which) {
-            RowVec r;
-            r.base = mod + static_cast<int64_t>(b0) * d.mod_rows + static_cast<int64_t>(l) * 6 * d.D +
-                     static_cast<int64_t>(which) * d.D;
-            r.stride = d.mod_rows;
-            r.rows_per_sample = d.ntok;
-            return r;
-        };
-        for (int l = 0; l < d.depth; ++l) {
-        // x += gate1 * Proj(Attn(LN(x)(1+scale1)+shift1))
-        {
-            ProfScope prof(PROF_LN_MOD, s);
-            FREE_TRY(launch_ln_modulate(xres_h, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn_h, s));
-        }
-        {
-            ProfScope prof(PROF_GEMM_QKV, s);
-            FREE_TRY(linear_dispatch(d, xn_h, h->blk(l, B_QKV_W), static_cast<const float*>(h->blk(l, B_QKV_B)), M,
-                                     3 * d.D, d.D, FREE_EPI_BIAS, qkv_h, nullptr, RowVec{nullptr, 0, 1}, s));
-        }
-        {
-            ProfScope prof(PROF_ATTN, s);
-            FREE_TRY(attention_dispatch(d, qkv_h, nb, att_h, s));
-        }
-        {
-            ProfScope prof(PROF_GEMM_PROJ, s);
-            FREE_TRY(linear_dispatch(d, att_h, h->blk(l, B_PROJ_W), static_cast<const float*>(h->blk(l, B_PROJ_B)),
-                                     M, d.D, d.D, FREE_EPI_GATE_RESID, nullptr, xres_h, vec(l, 2), s));
-        }
-        // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
-        {
-            ProfScope prof(PROF_LN_MOD, s);
-            FREE_TRY(launch_ln_modulate(xres_h, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn_h, s));
-        }
-        {
-            ProfScope prof(PROF_GEMM_FC1, s);
-            FREE_TRY(linear_dispatch(d, xn_h, h->blk(l, B_FC1_W), static_cast<const float*>(h->blk(l, B_FC1_B)), M,
-                                     d.F, d.D, FREE_EPI_BIAS_GELU, hmid_h, nullptr, RowVec{nullptr, 0, 1}, s));
-        }
-        {
-            ProfScope prof(PROF_GEMM_FC2, s);
-            FREE_TRY(linear_dispatch(d, hmid_h, h->blk(l, B_FC2_W), static_cast<const float*>(h->blk(l, B_FC2_B)),
-                                     M, d.D, d.F, FREE_EPI_GATE_RESID, nullptr, xres_h, vec(l, 5), s));
-        }
-    }
-        return FREE_OK;
+    const ActBufs act{xres, xn, qkv, att, hmid};
+    const void* const* blkw = h->w.data() + 7;
+    auto run_blocks = [&](int b0, int nb, hipStream_t st) -> int32_t {
+        return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st);
     };
     // The samples of a packed batch are independent through all blocks, so the batch is cut in two
     // halves that run on two streams forked from (and joined back into) the caller's stream: while
@@ -570,6 +605,203 @@ int32_t free_op_ln_modulate(const float* x, const float* shift, const float* sca
     return launch_ln_modulate(x, RowVec{shift, mod_stride, rows_per_sample},
                               RowVec{scale, mod_stride, rows_per_sample}, M, D, dtype, out,
                               static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"
+
+namespace {
+
+// Workspace of the drafter on B samples.
+struct DraftLayout {
+    size_t cond_h, sc, mod, tpack, ypack, emb, fin, xn, qkv, att, hmid, eps, feat, total;
+};
+
+DraftLayout make_draft_layout(const Dims& d, int32_t mod_rows, int32_t B) {
+    DraftLayout L;
+    const size_t es = d.mode == FREE_BF16 ? 2 : 4;
+    const size_t M = static_cast<size_t>(B) * d.ntok;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    L.cond_h = take(static_cast<size_t>(B) * (d.tfreq + d.D) * 4);
+    L.sc = take(static_cast<size_t>(B) * d.D * 4);
+    L.mod = take(static_cast<size_t>(B) * mod_rows * 4);
+    L.tpack = take(static_cast<size_t>(B) * 4);
+    L.ypack = take(static_cast<size_t>(B) * 4);
+    L.emb = take(M * d.D * 4);
+    L.fin = take(M * 2 * d.D * es);
+    L.xn = take(M * d.D * es);
+    L.qkv = take(M * 3 * d.D * es);
+    L.att = take(M * d.D * es);
+    L.hmid = take(M * d.F * es);
+    L.eps = take(static_cast<size_t>(B) * d.c_out * d.H * d.W * 4);
+    L.feat = take(M * d.D * 4);
+    L.total = off;
+    return L;
+}
+
+// One drafter evaluation (Sec. 3.2).  Sample b reads the latent x[b % x_mod]; f_out doubles as the
+// residual stream of the drafter's blocks (it IS the predicted feature when they are done), and
+// f_prev is consumed before f_out is first written, so the two may alias.
+int32_t drafter_forward_impl(free_drafter_t dr, const float* x, int32_t x_mod, const float* f_prev, const int32_t* t,
+                             const int32_t* y, int32_t B, float* eps_out, float* f_out, char* ws, hipStream_t s) {
+    free_dit_t h = dr->target;
+    const Dims& d = h->dims;
+    const DraftLayout L = make_draft_layout(d, dr->mod_rows, B);
+    const int64_t M = static_cast<int64_t>(B) * d.ntok;
+    float* cond_h = reinterpret_cast<float*>(ws + L.cond_h);
+    float* sc = reinterpret_cast<float*>(ws + L.sc);
+    float* mod = reinterpret_cast<float*>(ws + L.mod);
+    float* emb = reinterpret_cast<float*>(ws + L.emb);
+    void* fin = ws + L.fin;
+    FREE_TRY(launch_conditioning(t, y, B, d.D, d.tfreq, static_cast<const float*>(h->w[W_T_W1]),
+                                 static_cast<const float*>(h->w[W_T_B1]), static_cast<const float*>(h->w[W_T_W2]),
+                                 static_cast<const float*>(h->w[W_T_B2]),
+                                 static_cast<const float*>(h->w[W_Y_TABLE]), cond_h, sc, s));
+    if (d.mode == FREE_BF16 && adaln_mfma_supported(d.D, dr->mod_rows))
+        FREE_TRY(launch_adaln_mfma(sc, B, d.D, dr->ada_w_tab, dr->ada_b_tab, dr->ada_row_start, dr->depth + 1,
+                                   dr->mod_rows, mod, s));
+    else
+        FREE_TRY(launch_adaln(sc, B, d.D, dr->ada_w_tab, dr->ada_b_tab, dr->ada_row_start, dr->depth + 1,
+                              dr->mod_rows, d.mode, mod, s));
+    FREE_TRY(launch_patch_embed(x, x_mod, B, d.C, d.H, d.W, d.p, d.D, static_cast<const float*>(h->w[W_PATCH_W]),
+                                static_cast<const float*>(h->w[W_PATCH_B]), h->pos, emb, s));
+    // z = fuse_w [emb | f_prev] + fuse_b, accumulated in fp32 straight into the residual stream:
+    // residual epilogue on a zeroed stream with a gate of ones
+    FREE_TRY(launch_fuse_pack(emb, f_prev, M, d.D, d.mode, fin, s));
+    FREE_TRY(launch_fill_f32(f_out, M * d.D, 0.0f, s));
+    FREE_TRY(linear_dispatch(d, fin, dr->w[0], static_cast<const float*>(dr->w[1]), static_cast<int32_t>(M), d.D,
+                             2 * d.D, FREE_EPI_GATE_RESID, nullptr, f_out, RowVec{dr->ones, 0, 1}, s));
+    const ActBufs act{f_out, ws + L.xn, ws + L.qkv, ws + L.att, ws + L.hmid};
+    FREE_TRY(run_block_stack(d, dr->blkw(), dr->depth, mod, dr->mod_rows, act, 0, B, s));
+    RowVec fsh{mod + static_cast<int64_t>(dr->depth) * 6 * d.D, dr->mod_rows, d.ntok};
+    RowVec fsc{mod + static_cast<int64_t>(dr->depth) * 6 * d.D + d.D, dr->mod_rows, d.ntok};
+    return launch_final_layer(f_out, fsh, fsc, B, d.gh, d.gw, d.p, d.c_out, d.D, dr->fin(F_W),
+                              static_cast<const float*>(dr->fin(F_B)), d.mode, eps_out, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t free_drafter_weight_count(int32_t drafter_depth) {
+    return drafter_depth < 1 ? -1 : 2 + 10 * drafter_depth + 4;
+}
+
+int32_t free_drafter_create(free_dit_t target, int32_t drafter_depth, const void* const* weight_ptrs,
+                            int32_t n_ptrs, free_drafter_t* out) {
+    if (!target || !weight_ptrs || !out) return FREE_ERR_NULL;
+    if (drafter_depth < 1 || drafter_depth > 64 || n_ptrs != free_drafter_weight_count(drafter_depth))
+        return FREE_ERR_SHAPE;
+    for (int i = 0; i < n_ptrs; ++i) {
+        if (!weight_ptrs[i]) return FREE_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(weight_ptrs[i]) & 15u) return FREE_ERR_SHAPE;
+    }
+    const Dims& d = target->dims;
+    free_drafter_s* dr = new (std::nothrow) free_drafter_s();
+    if (!dr) return FREE_ERR_HIP;
+    dr->target = target;
+    dr->depth = drafter_depth;
+    dr->mod_rows = drafter_depth * 6 * d.D + 2 * d.D;
+    dr->w.assign(weight_ptrs, weight_ptrs + n_ptrs);
+    // device block: [w_tab | b_tab | row_start | ones (D floats)]
+    const int n_mats = drafter_depth + 1;
+    const size_t off_w = 0;
+    const size_t off_b = align_up(off_w + n_mats * sizeof(void*));
+    const size_t off_r = align_up(off_b + n_mats * sizeof(void*));
+    const size_t off_o = align_up(off_r + (n_mats + 1) * sizeof(int32_t));
+    const size_t total = off_o + static_cast<size_t>(d.D) * sizeof(float);
+    std::vector<char> host(total, 0);
+    const void** wt = reinterpret_cast<const void**>(host.data() + off_w);
+    const void** bt = reinterpret_cast<const void**>(host.data() + off_b);
+    int32_t* rs = reinterpret_cast<int32_t*>(host.data() + off_r);
+    for (int l = 0; l < drafter_depth; ++l) {
+        wt[l] = dr->blkw()[10 * l + B_ADA_W];
+        bt[l] = dr->blkw()[10 * l + B_ADA_B];
+        rs[l] = l * 6 * d.D;
+    }
+    wt[drafter_depth] = dr->fin(F_ADA_W);
+    bt[drafter_depth] = dr->fin(F_ADA_B);
+    rs[drafter_depth] = drafter_depth * 6 * d.D;
+    rs[drafter_depth + 1] = dr->mod_rows;
+    float* ones = reinterpret_cast<float*>(host.data() + off_o);
+    for (int i = 0; i < d.D; ++i) ones[i] = 1.0f;
+    if (!hip_ok(hipMalloc(&dr->dev_block, total)) ||
+        !hip_ok(hipMemcpy(dr->dev_block, host.data(), total, hipMemcpyHostToDevice))) {
+        if (dr->dev_block) (void)hipFree(dr->dev_block);
+        delete dr;
+        return FREE_ERR_HIP;
+    }
+    char* db = static_cast<char*>(dr->dev_block);
+    dr->ada_w_tab = reinterpret_cast<const void* const*>(db + off_w);
+    dr->ada_b_tab = reinterpret_cast<const float* const*>(db + off_b);
+    dr->ada_row_start = reinterpret_cast<const int32_t*>(db + off_r);
+    dr->ones = reinterpret_cast<const float*>(db + off_o);
+    *out = dr;
+    return FREE_OK;
+}
+
+int32_t free_drafter_destroy(free_drafter_t dr) {
+    if (!dr) return FREE_ERR_NULL;
+    int32_t st = FREE_OK;
+    if (dr->dev_block && !hip_ok(hipFree(dr->dev_block))) st = FREE_ERR_HIP;
+    delete dr;
+    return st;
+}
+
+size_t free_drafter_workspace_bytes(free_dit_t target, int32_t drafter_depth, int32_t B) {
+    if (!target || drafter_depth < 1 || B < 1) return 0;
+    const Dims& d = target->dims;
+    return make_draft_layout(d, drafter_depth * 6 * d.D + 2 * d.D, B).total;
+}
+
+int32_t drafter_forward(free_drafter_t dr, const float* x, const float* f_prev, const int32_t* t,
+                        const int32_t* y, int32_t B, float* eps_out, float* f_out, void* workspace,
+                        size_t ws_bytes, void* stream) {
+    if (!dr || !x || !f_prev || !t || !y || !eps_out || !f_out) return FREE_ERR_NULL;
+    if (B < 1) return FREE_ERR_SHAPE;
+    const Dims& d = dr->target->dims;
+    FREE_TRY(check_ws(workspace, ws_bytes, make_draft_layout(d, dr->mod_rows, B).total));
+    if ((reinterpret_cast<uintptr_t>(f_prev) | reinterpret_cast<uintptr_t>(f_out)) & 15u) return FREE_ERR_SHAPE;
+    return drafter_forward_impl(dr, x, B, f_prev, t, y, B, eps_out, f_out, static_cast<char*>(workspace),
+                                static_cast<hipStream_t>(stream));
+}
+
+int32_t draft_round(free_drafter_t dr, const float* x_a, const float* f_a, const int32_t* t, int32_t y,
+                    float cfg_scale, const float* coef_x, const float* coef_eps, const float* sigma,
+                    const float* xi, int32_t K, float* x_states, float* x_last, float* m_draft,
+                    float* f_last, void* workspace, size_t ws_bytes, void* stream) {
+    if (!dr || !x_a || !f_a || !t || !coef_x || !coef_eps || !sigma || !xi || !x_states || !x_last || !m_draft)
+        return FREE_ERR_NULL;
+    const Dims& d = dr->target->dims;
+    if (K < 1 || K > FREE_MAX_DRAFTS) return FREE_ERR_SHAPE;
+    if (y < 0 || y > d.classes) return FREE_ERR_RANGE;
+    if (!(cfg_scale == cfg_scale)) return FREE_ERR_RANGE;
+    const int32_t dup = cfg_scale > 1.0f ? 2 : 1;
+    const DraftLayout L = make_draft_layout(d, dr->mod_rows, dup);
+    FREE_TRY(check_ws(workspace, ws_bytes, L.total));
+    if ((reinterpret_cast<uintptr_t>(f_a) | reinterpret_cast<uintptr_t>(f_last)) & 15u) return FREE_ERR_SHAPE;
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t* tp = reinterpret_cast<int32_t*>(ws + L.tpack);
+    int32_t* yp = reinterpret_cast<int32_t*>(ws + L.ypack);
+    float* eps = reinterpret_cast<float*>(ws + L.eps);
+    float* feat = f_last ? f_last : reinterpret_cast<float*>(ws + L.feat);
+    const size_t feat_bytes = static_cast<size_t>(dup) * d.ntok * d.D * 4;
+    const int64_t hw = static_cast<int64_t>(d.H) * d.W;
+    if (!hip_ok(hipMemcpyAsync(x_states, x_a, static_cast<size_t>(d.d) * 4, hipMemcpyDeviceToDevice, s)))
+        return FREE_ERR_HIP;
+    if (feat != f_a && !hip_ok(hipMemcpyAsync(feat, f_a, feat_bytes, hipMemcpyDeviceToDevice, s)))
+        return FREE_ERR_HIP;
+    for (int k = 0; k < K; ++k) {
+        const float* xk = x_states + static_cast<int64_t>(k) * d.d;
+        float* mk = m_draft + static_cast<int64_t>(k) * d.d;
+        float* xn = k + 1 < K ? x_states + static_cast<int64_t>(k + 1) * d.d : x_last;
+        FREE_TRY(launch_pack_cond(t + k, y, d.classes, 1, dup, tp, yp, s));
+        FREE_TRY(drafter_forward_impl(dr, xk, 1, feat, tp, yp, dup, eps, feat, ws, s));
+        FREE_TRY(launch_eps_to_mean(eps, xk, coef_x + k, coef_eps + k, cfg_scale, 1, d.C, d.c_out, hw, mk, s));
+        FREE_TRY(launch_gauss_step(mk, sigma + k, xi + static_cast<int64_t>(k) * d.d, d.d, xn, s));
+    }
+    return FREE_OK;
 }
 
 }  // extern "C"

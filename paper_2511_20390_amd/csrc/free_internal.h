@@ -135,6 +135,13 @@ int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const fl
 int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_t K, int32_t dup,
                          int32_t* t_out, int32_t* y_out, hipStream_t s);
 
+// drafter helpers: fin = [emb | feat] in the compute type; p[0:n] = v; out = m + sigma_k[0] * xi
+int32_t launch_fuse_pack(const float* emb, const float* feat, int64_t M, int32_t D, int32_t dtype, void* fin,
+                         hipStream_t s);
+int32_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t s);
+int32_t launch_gauss_step(const float* m, const float* sigma_k, const float* xi, int64_t n, float* out,
+                          hipStream_t s);
+
 // ---- MFMA adaLN modulation GEMV, bf16 weights (adaln_mfma.hip)
 bool adaln_mfma_supported(int32_t D, int32_t total_rows);
 int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* const* w_tab,

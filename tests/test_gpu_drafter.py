@@ -1,0 +1,144 @@
+"""GPU parity of the drafter forward and of the drafting loop (Sec. 3.2; Alg. 1, drafting loop)
+against the oracle, through the C ABI, and the chain drafting -> verification round."""
+import numpy as np
+import pytest
+
+from oracle import free_oracle as fo
+from paper_2511_20390_amd import synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _models(name, mode, depth, seed=0):
+    from paper_2511_20390_amd import binding
+    cfg = synth.dit_config(name)
+    w = pu.weights_for(cfg, mode, seed=seed)
+    wd = synth.make_drafter_weights(cfg, depth, seed=seed + 1, bf16_values=(mode == "bf16"))
+    target = binding.FreeDit(cfg, w, mode)
+    drafter = binding.FreeDrafter(target, wd, depth)
+    return cfg, w, wd, target, drafter
+
+
+@pytest.mark.parametrize("mode", ["fp32", "bf16"])
+@pytest.mark.parametrize("name,B,depth", [("tiny", 3, 1), ("small", 2, 1), ("small", 5, 2)])
+def test_drafter_forward_parity(name, B, depth, mode):
+    cfg, w, wd, target, drafter = _models(name, mode, depth)
+    rng = np.random.default_rng(B + depth)
+    x = rng.standard_normal((B, cfg["in_ch"], cfg["lat_h"], cfg["lat_w"])).astype(np.float32)
+    f = rng.standard_normal((B, synth.n_tokens(cfg), cfg["hidden"])).astype(np.float32)
+    t = rng.integers(0, 1000, B).astype(np.int32)
+    y = rng.integers(0, cfg["num_classes"] + 1, B).astype(np.int32)
+    eps, feat = drafter.drafter_forward(pu.to_dev(x), pu.to_dev(f), pu.to_dev(t), pu.to_dev(y))
+    ref_eps, ref_feat = fo.drafter_forward(wd, w, dict(cfg, drafter_depth=depth), x, f, t, y)
+    e1, e2 = pu.rel_l2(eps.cpu().numpy(), ref_eps), pu.rel_l2(feat.cpu().numpy(), ref_feat)
+    print(f"{name}/{mode} B={B} depth={depth}: eps rel-L2 {e1:.3e}, feature rel-L2 {e2:.3e}")
+    assert e1 <= pu.DIT_REL_L2[mode] and e2 <= pu.DIT_REL_L2[mode]
+    drafter.close()
+    target.close()
+
+
+def _draft_inputs(cfg, K, seed, cfg_scale):
+    sched = fo.ddpm_schedule()
+    di = synth.make_draft_inputs(cfg, K, seed, cfg_scale)
+    cx, ce = fo.mean_coefficients(di["t"], sched)
+    sigma = sched["sigma_clipped"][di["t"]]
+    return sched, di, cx, ce, sigma
+
+
+def _run_draft(drafter, di, cfg_scale, cx, ce, sigma, want_feat=True):
+    return drafter.draft_round(pu.to_dev(di["x_a"]), pu.to_dev(di["f_a"]), pu.to_dev(di["t"]), di["y"], cfg_scale,
+                               pu.to_dev(cx.astype(np.float32)), pu.to_dev(ce.astype(np.float32)),
+                               pu.to_dev(sigma.astype(np.float32)), pu.to_dev(di["xi"]), want_feat=want_feat)
+
+
+@pytest.mark.parametrize("mode", ["fp32", "bf16"])
+@pytest.mark.parametrize("name,K,cfg_scale,depth", [("tiny", 5, 4.0, 1), ("tiny", 1, 1.0, 1), ("small", 6, 4.0, 1),
+                                                    ("small", 3, 1.0, 2)])
+def test_draft_round_parity(name, K, cfg_scale, depth, mode):
+    """The whole autoregressive chain: errors compound over the K steps, so the last draft is the
+    strictest check.  The oracle is fed the float32-rounded coefficients the library receives."""
+    cfg, w, wd, target, drafter = _models(name, mode, depth, seed=2)
+    sched, di, cx, ce, sigma = _draft_inputs(cfg, K, 5, cfg_scale)
+    out = _run_draft(drafter, di, cfg_scale, cx, ce, sigma)
+    ref = fo.draft_steps(wd, w, dict(cfg, drafter_depth=depth), di["x_a"], di["f_a"], di["t"], di["y"], cfg_scale,
+                         cx.astype(np.float32), ce.astype(np.float32), sigma.astype(np.float32), di["xi"])
+    d = synth.latent_dim(cfg)
+    # the tolerance of the forward applies to the noise estimate; recover it from the mean: eps = (m - cx x) / ce
+    xs_g = out["x_states"].cpu().numpy().reshape(K, d).astype(np.float64)
+    m_g = out["m_draft"].cpu().numpy().astype(np.float64)
+    for k in range(K):
+        cxk, cek = np.float64(np.float32(cx[k])), np.float64(np.float32(ce[k]))
+        eps_g = (m_g[k] - cxk * xs_g[k]) / cek
+        eps_r = (ref["m_draft"][k] - cxk * ref["x_states"][k].reshape(-1)) / cek
+        err = pu.rel_l2(eps_g, eps_r)
+        print(f"{name}/{mode} K={K} step {k}: eps rel-L2 {err:.3e}")
+        assert err <= pu.DIT_REL_L2[mode] * (1 if mode == "fp32" else 2)
+    tol = 1e-4 if mode == "fp32" else 2e-2
+    assert pu.rel_l2(out["x_last"].cpu().numpy(), ref["x_last"].reshape(-1)) <= tol
+    assert pu.rel_l2(out["f_last"].cpu().numpy(), ref["f_last"]) <= tol * 2
+    assert np.array_equal(out["x_states"][0].cpu().numpy(), di["x_a"])
+    drafter.close()
+    target.close()
+
+
+def test_draft_then_verify_round_chain():
+    """Drafting loop -> verification round on the GPU, against the same chain in the oracle: the outputs
+    of draft_round are exactly the inputs of spec_round (Alg. 1)."""
+    import torch
+    mode, K, cfg_scale = "fp32", 4, 4.0
+    cfg, w, wd, target, drafter = _models("tiny", mode, 1, seed=3)
+    sched, di, cx, ce, sigma = _draft_inputs(cfg, K, 9, cfg_scale)
+    # the target's own top-block feature of the previous state starts the chain
+    rng = np.random.default_rng(4)
+    x_prev = rng.standard_normal((1,) + di["x_a"].shape).astype(np.float32)
+    tt = np.array([di["t"][0] + 1] * 2, np.int32) if di["t"][0] + 1 < 1000 else np.array([999, 999], np.int32)
+    yy = np.array([di["y"], cfg["num_classes"]], np.int32)
+    _, f_gpu = target.dit_forward_packed(pu.to_dev(np.repeat(x_prev, 2, 0)), pu.to_dev(tt), pu.to_dev(yy), want_feat=True)
+    _, f_ref = fo.dit_forward(w, cfg, np.repeat(x_prev, 2, 0), tt, yy)
+    di = dict(di, f_a=f_gpu.cpu().numpy())
+    out = _run_draft(drafter, di, cfg_scale, cx, ce, sigma, want_feat=False)
+    u = np.random.default_rng(5).random(K, dtype=np.float32)
+    dev = lambda a: pu.to_dev(np.asarray(a, np.float32))
+    res = target.spec_round(out["x_states"], out["x_last"], out["m_draft"], pu.to_dev(di["t"]), di["y"], cfg_scale,
+                            dev(cx), dev(ce), dev(sigma), dev(u), None)
+    torch.cuda.synchronize()
+    ref_d = fo.draft_steps(wd, w, cfg, di["x_a"], f_ref, di["t"], di["y"], cfg_scale, cx.astype(np.float32),
+                           ce.astype(np.float32), sigma.astype(np.float32), di["xi"])
+    assert pu.rel_l2(out["m_draft"].cpu().numpy(), ref_d["m_draft"]) < 1e-4
+    # verification is compared by composition on the GPU-produced chain (bit-exact decisions need identical inputs)
+    ref_v = fo.spec_round(w, cfg, out["x_states"].cpu().numpy(), out["x_last"].cpu().numpy().reshape(di["x_a"].shape),
+                          out["m_draft"].cpu().numpy(),
+                          di["t"], di["y"], cfg_scale, cx.astype(np.float32), ce.astype(np.float32),
+                          sigma.astype(np.float32), u)
+    m_gpu = res["m_target"].cpu().numpy().astype(np.float64)
+    assert pu.rel_l2(m_gpu, ref_v["m_target"]) < 1e-4
+    xd = np.concatenate([out["x_states"].cpu().numpy()[1:].reshape(K - 1, -1), out["x_last"].cpu().numpy()[None]], 0)
+    ref = fo.spec_verify(m_gpu[None], out["m_draft"].cpu().numpy()[None], xd[None], sigma.astype(np.float32)[None], u[None])
+    pu.compare_verify(dict(accept=res["accept"], n_accept=res["n_accept"], log_ratio=res["log_ratio"],
+                           x_out=res["x_out"]), ref, None, u, "draft -> verify chain")
+    print("chain: accepted", int(res["n_accept"].item()), "of", K, "log ratios", res["log_ratio"].cpu().numpy())
+    drafter.close()
+    target.close()
+
+
+def test_drafter_xl2_512_bf16():
+    """DiT-XL/2 width at 1024 tokens with guidance (the shape bench.py times): one block on two
+    samples is cheap enough for the oracle to check every output."""
+    cfg, w, wd, target, drafter = _models("xl2_512", "bf16", 1)
+    K, cfg_scale = 2, 4.0
+    sched, di, cx, ce, sigma = _draft_inputs(cfg, K, 1, cfg_scale)
+    out = _run_draft(drafter, di, cfg_scale, cx, ce, sigma)
+    ref = fo.draft_steps(wd, w, cfg, di["x_a"], di["f_a"], di["t"], di["y"], cfg_scale, cx.astype(np.float32),
+                         ce.astype(np.float32), sigma.astype(np.float32), di["xi"])
+    d = synth.latent_dim(cfg)
+    xs_g = out["x_states"].cpu().numpy().reshape(K, d).astype(np.float64)
+    m_g = out["m_draft"].cpu().numpy().astype(np.float64)
+    for k in range(K):
+        cxk, cek = np.float64(np.float32(cx[k])), np.float64(np.float32(ce[k]))
+        err = pu.rel_l2((m_g[k] - cxk * xs_g[k]) / cek, (ref["m_draft"][k] - cxk * ref["x_states"][k].reshape(-1)) / cek)
+        print(f"xl2_512/bf16 drafter step {k}: eps rel-L2 {err:.3e}")
+        assert err <= pu.DIT_REL_L2["bf16"]
+    assert pu.rel_l2(out["f_last"].cpu().numpy(), ref["f_last"]) <= pu.DIT_REL_L2["bf16"]
+    drafter.close()
+    target.close()
