@@ -142,8 +142,53 @@ def bench_round(args):
         "tokens_per_round": B * synth.n_tokens(cfg), "setup_s": setup_s,
         "n_accept": int(out["n_accept"].item()), "B": B,
     }
+    if not args.no_draft_bench:
+        res["drafting"] = bench_draft(args, cfg, model, ri, (cx, ce, sg), a, step)
     model.close()
     return res, cfg, w, ri, (cx, ce, sg)
+
+
+def bench_draft(args, cfg, model, ri, sched, a, verify_step):
+    """The step before the hot path (Alg. 1, drafting loop): K sequential drafter evaluations on the
+    reference state and the propagated feature (two samples with guidance), then the same followed
+    by the verification round that consumes the drafts."""
+    import torch
+    from paper_2511_20390_amd import binding, synth
+    K, scale = args.K, args.cfg_scale
+    dup = 2 if scale > 1 else 1
+    cx, ce, sg = sched
+    wd = synth.make_drafter_weights(cfg, 1, seed=1, bf16_values=(args.mode == "bf16"))
+    drafter = binding.FreeDrafter(model, wd, 1)
+    di = synth.make_draft_inputs(cfg, K, 0, scale, t0=int(ri["t"][0]))
+    dev = lambda v: torch.from_numpy(np.ascontiguousarray(v)).to("cuda:0")
+    x_a, f_a, xi = dev(di["x_a"]), dev(di["f_a"]), dev(di["xi"])
+    out = drafter.draft_round(x_a, f_a, a["t"], ri["y"], scale, a["coef_x"], a["coef_eps"], a["sigma"], xi)
+
+    def draft():
+        drafter.draft_round(x_a, f_a, a["t"], ri["y"], scale, a["coef_x"], a["coef_eps"], a["sigma"], xi, out=out)
+
+    def timed(fn, n):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    ms_draft = timed(draft, args.steps)
+    ms_both = timed(lambda: (draft(), verify_step()), args.steps)
+    N, D, F = synth.n_tokens(cfg), cfg["hidden"], cfg["mlp_hidden"]
+    M = dup * N
+    per, _ = forward_flops(cfg, dup)
+    flops_step = sum(per.values()) + 2.0 * M * D * 2 * D + 2.0 * dup * D * 8 * D
+    drafter.close()
+    return {"workload": f"draft_round: {K} sequential drafter steps (1 block, {dup} samples x {N} tokens)",
+            "ms_per_draft_round": ms_draft, "us_per_drafter_step": ms_draft * 1e3 / K,
+            "gflop_per_step": flops_step / 1e9, "tflops": flops_step * K / (ms_draft * 1e-3) / 1e12,
+            "ms_draft_plus_verify_round": ms_both,
+            "drafter_params_M": sum(int(np.prod(sh)) for _, sh in synth.drafter_weight_spec(cfg, 1)) / 1e6}
 
 
 def bench_verify(args, n_sets=6):
@@ -229,6 +274,7 @@ def main():
                          "that kernel durations are not inflated by overlap)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify-bench", action="store_true")
+    ap.add_argument("--no-draft-bench", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run plain device copies of a known size (256 MiB) so that a rocprofv3 --pmc "
                          "run of this command has a reference for scaling FETCH_SIZE / WRITE_SIZE")
@@ -265,6 +311,8 @@ def main():
         "batch_streams": res["batch_streams"], "ms_per_step_one_stream": res["ms_per_step_one_stream"],
         "roofline": res["roofline"], "forward": res["forward"], "kernels": res["kernels"],
     }
+    if "drafting" in res:
+        line["drafting"] = res["drafting"]
     if not args.no_verify_bench:
         line["roofline_verify"] = bench_verify(args)
     if not args.no_cpu_baseline:
