@@ -38,6 +38,12 @@ invariants and the library-routine cross-check it is "parity unpinned".
   a drafter is always accepted by the verification, the feature-only fusion
   ignores the latent, and the drafted chain equals its step-by-step
   composition.  Like the DiT forward it is otherwise "parity unpinned".
+* The whole sampler (Alg. 1): plain target step, drafting, one packed target
+  evaluation per round, sequential verification, advance.  Pins: with a drafter
+  equal to the target it is plain sequential ancestral sampling (checked on a
+  scalar chain and on the DiT), on a linear-Gaussian chain the distribution of
+  the result has the target's closed-form mean, variance and kurtosis whatever
+  the drafter proposes, and every step is taken exactly once.
 """
 from __future__ import annotations
 
@@ -447,3 +453,98 @@ def draft_steps(wd: dict, w: dict, cfg: dict, x_a, f_a, t, y: int, cfg_scale: fl
         m_draft.append(m.reshape(-1))
         xs.append(m + float(sigma[k]) * np.asarray(xi, F64)[k].reshape(m.shape))
     return dict(x_states=np.stack(xs[:K]), x_last=xs[K], m_draft=np.stack(m_draft), f_last=f)
+
+
+# ----------------------------------------------------------------------------
+# The whole sampler (Alg. 1): target step, drafting, packed verification, advance
+# ----------------------------------------------------------------------------
+def speculative_loop(x0, S: int, n_spec: int, L: int, sigma, xi, u, lam, target_means, draft_mean):
+    """Alg. 1 around two callables, so that the control flow can be checked on models with a known answer.
+
+    Steps are indexed i = 0..S-1: step i takes the state x_i and produces x_{i+1}; x_S is returned.
+      target_means(states, i0) -> (means, feats): the target's transition means of `states` (a list of
+          latents sitting at steps i0, i0+1, ...) and one opaque feature per state;
+      draft_mean(x, feat, i)   -> (mean, feat'): the drafter on (x, feature of the previous evaluation).
+    Reading of Alg. 1 used here (the listing's `a <- k` would re-draw an already verified state):
+      * a plain target step x_{i+1} = m_i + sigma_i xi_i is taken when no feature exists yet (i = 0) and for
+        the steps i >= n_spec that cannot be speculated (sigma = 0: the last, noise-free step);
+      * otherwise one round drafts K = min(L, n_spec - i) steps from (x_i, feature), draft j being
+        x^_{i+j+1} = m^_{i+j} + sigma_{i+j} xi_{i+j}, runs ONE packed target evaluation on
+        (x_i, x^_{i+1}, .., x^_{i+K-1}) and verifies draft j against (m^_{i+j}, m_{i+j}, sigma_{i+j}, u_{i+j});
+      * with n drafts accepted the sampler advances to x_{i+n} = x^_{i+n} if n = K, else to the reflected
+        x_{i+n+1}; the feature handed to the next round is the target's feature of the packed state that
+        produced the transition just taken (index K-1, or n).  Every round therefore costs one target call.
+    Returns (x_S, stats) with stats = dict(target_calls, rounds, accepted, drafter_steps, n_accept=[...]).
+    """
+    x = np.asarray(x0, F64)
+    d = x.size
+    sigma = np.asarray(sigma, F64)
+    xi = np.asarray(xi, F64).reshape(S, d)
+    u = np.asarray(u, F64)
+    lam = np.ones(S, F64) if lam is None else np.asarray(lam, F64)
+    stats = dict(target_calls=0, rounds=0, accepted=0, drafter_steps=0, n_accept=[])
+    feat = None
+    i = 0
+    while i < S:
+        if feat is None or i >= n_spec:
+            means, feats = target_means([x], i)
+            stats["target_calls"] += 1
+            x = np.asarray(means[0], F64) + sigma[i] * xi[i].reshape(x.shape)
+            feat = feats[0]
+            i += 1
+            continue
+        K = min(L, n_spec - i)
+        states, m_hat, f = [x], [], feat
+        for j in range(K):
+            m, f = draft_mean(states[-1], f, i + j)
+            m_hat.append(np.asarray(m, F64))
+            states.append(m_hat[-1] + sigma[i + j] * xi[i + j].reshape(x.shape))
+        stats["drafter_steps"] += K
+        means, feats = target_means(states[:K], i)
+        stats["target_calls"] += 1
+        stats["rounds"] += 1
+        n = K
+        for j in range(K):
+            xr, ok, _, _ = verification(m_hat[j].reshape(-1), np.asarray(means[j], F64).reshape(-1), sigma[i + j],
+                                        states[j + 1].reshape(-1), u[i + j], lam[i + j])
+            if not ok:
+                n = j
+                x = xr.reshape(x.shape)
+                break
+        stats["accepted"] += n
+        stats["n_accept"].append(n)
+        if n == K:
+            x, feat, i = states[K], feats[K - 1], i + K
+        else:
+            feat, i = feats[n], i + n + 1
+    return x, stats
+
+
+def free_sample(wd: dict, w: dict, cfg: dict, x0, y: int, cfg_scale: float, tmap, coef_x, coef_eps, sigma,
+                n_spec: int, L: int, xi, u, lam=None):
+    """Alg. 1 with the DiT target and the feature-level drafter: `tmap[i]` is the network timestep of
+    step i, (coef_x, coef_eps, sigma)[i] its transition coefficients (Eq. ddpm_update)."""
+    C = np.asarray(x0).shape[0]
+    dup = 2 if cfg_scale > 1.0 else 1
+    yy = np.array([y, cfg["num_classes"]][:dup])
+
+    def guided(out, K):
+        return cfg_combine(out[:K, :C], out[K:, :C], cfg_scale) if dup == 2 else out[:, :C]
+
+    def target_means(states, i0):
+        K = len(states)
+        xs = np.stack(states)
+        t = np.asarray([tmap[i0 + j] for j in range(K)])
+        out, feat = dit_forward(w, cfg, np.concatenate([xs] * dup), np.concatenate([t] * dup), np.repeat(yy, K))
+        eps = guided(out, K)
+        means = [float(coef_x[i0 + j]) * xs[j] + float(coef_eps[i0 + j]) * eps[j] for j in range(K)]
+        feats = [np.stack([feat[b * K + j] for b in range(dup)]) for j in range(K)]
+        return means, feats
+
+    def draft_mean(x, f, i):
+        out, f2 = drafter_forward(wd, w, cfg, np.stack([x] * dup), f, np.full(dup, tmap[i]), yy)
+        eps = guided(out, 1)[0]
+        return float(coef_x[i]) * np.asarray(x, F64) + float(coef_eps[i]) * eps, f2
+
+    S = len(tmap)
+    return speculative_loop(x0, S, n_spec, L, sigma, xi, u, lam, target_means, draft_mean)

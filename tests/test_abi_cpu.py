@@ -125,3 +125,16 @@ def test_synth_is_deterministic_and_bf16_rounding_is_exact():
     assert list(r1["t"]) == list(range(r1["t"][0], r1["t"][0] - 6, -1)) and r1["t"][-1] >= 0
     v = synth.make_verify_inputs(3, 6, 64, 0.1, 1, s["sigma_clipped"])
     assert v["m_target"].shape == (3, 6, 64) and (v["sigma"] > 0).all() and ((v["lam"] > 0) & (v["lam"] <= 1)).all()
+
+
+def test_drafter_argument_errors_are_status_codes(lib):
+    one = C.c_void_p(256)
+    assert lib.free_drafter_weight_count(1) == len(synth.drafter_weight_spec(synth.dit_config("tiny"), 1)) == 16
+    assert lib.free_drafter_weight_count(2) == 26 and lib.free_drafter_weight_count(0) < 0
+    h = C.c_void_p()
+    assert lib.free_drafter_create(None, 1, None, 16, C.byref(h)) == binding.FREE_ERR_NULL
+    assert lib.free_drafter_destroy(None) == binding.FREE_ERR_NULL
+    assert lib.free_drafter_workspace_bytes(None, 1, 2) == 0
+    assert lib.drafter_forward(None, one, one, one, one, 2, one, one, one, 4096, None) == binding.FREE_ERR_NULL
+    assert lib.draft_round(None, one, one, one, 0, 4.0, one, one, one, one, 6, one, one, one, None, one, 4096,
+                           None) == binding.FREE_ERR_NULL
