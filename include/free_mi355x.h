@@ -231,6 +231,31 @@ int32_t draft_round(free_drafter_t dr, const float* x_a, const float* f_a, const
                     const float* xi, int32_t K, float* x_states, float* x_last, float* m_draft,
                     float* f_last, void* workspace, size_t ws_bytes, void* stream);
 
+/* ---- the whole sampler (Alg. 1): target step, drafting, packed verification, advance
+ * Steps are indexed i = 0..S-1: step i takes the state x_i (network timestep tmap[i], transition
+ * coefficients coef_x[i], coef_eps[i], sigma[i]) and produces x_{i+1}; x_S is the result.
+ *   - a plain target step x_{i+1} = m_i + sigma[i] xi[i] is taken at i = 0 (no feature exists yet)
+ *     and for the steps i >= n_spec, which are never speculated (sigma = 0: the noise-free last step);
+ *   - otherwise one round drafts K = min(L, n_spec - i) steps from (x_i, feature) with draft_round
+ *     (noise xi[i .. i+K-1]), runs ONE packed target forward on (x_i, x^_{i+1}, .., x^_{i+K-1}) and
+ *     verifies the drafts in order with u[i .. i+K-1] (and lambda, when given), as spec_round does;
+ *   - with n drafts accepted the sampler moves to x^_{i+K} (n = K) or to the reflected sample
+ *     x_{i+n+1}; the feature handed to the next round is the target's top-block feature of the packed
+ *     state whose transition was just taken.  (The listing's last line would draw an already
+ *     verified state again; this reading does not, and every round costs one target call.)
+ * All arrays [device] unless marked: x_init [C, H, W]; tmap [S] int32; coef_x, coef_eps, sigma [S];
+ * xi [S, d]; u [S]; lambda [S] or NULL; x_result [C, H, W].
+ * stats [host, 4 x int32, may be NULL]: target calls, rounds, accepted drafts, drafter steps.
+ * n_accept_log [host, S x int32, may be NULL]: accepted drafts of round r in entry r.
+ * The call is SYNCHRONOUS: it reads the accepted count back after every round (4 bytes) and returns
+ * when x_result is complete.  Workspace: free_sample_workspace_bytes. */
+size_t free_sample_workspace_bytes(free_drafter_t dr, int32_t L, float cfg_scale);
+int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg_scale, int32_t S,
+                    int32_t n_spec, int32_t L, const int32_t* tmap, const float* coef_x,
+                    const float* coef_eps, const float* sigma, const float* xi, const float* u,
+                    const float* lambda, float* x_result, int32_t* stats, int32_t* n_accept_log,
+                    void* workspace, size_t ws_bytes, void* stream);
+
 /* ---- per-kernel timing for benchmarks -------------------------------------
  * Between free_profile_begin and free_profile_end every kernel launch of the
  * hot-path calls is bracketed by two HIP events recorded on the launch stream.

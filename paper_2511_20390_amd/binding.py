@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = [
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
     "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
     "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
-    "drafter_forward", "draft_round",
+    "drafter_forward", "draft_round", "free_sample_workspace_bytes", "free_sample",
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
     "free_profile_begin", "free_profile_end", "free_profile_category_name",
 ]
@@ -96,6 +96,10 @@ def load():
     lib.drafter_forward.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.draft_round.restype = i32
     lib.draft_round.argtypes = [vp, vp, vp, vp, i32, f32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.free_sample_workspace_bytes.restype = sz
+    lib.free_sample_workspace_bytes.argtypes = [vp, i32, f32]
+    lib.free_sample.restype = i32
+    lib.free_sample.argtypes = [vp, vp, i32, f32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.free_op_linear.restype = i32
     lib.free_op_linear.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, i32, vp]
     lib.free_op_attention.restype = i32
@@ -333,6 +337,26 @@ class FreeDrafter:
                                   _ptr(out["m_draft"]), _ptr(out["f_last"]), _ptr(ws), ws.numel(), _stream()),
                "draft_round")
         return out
+
+
+def free_sample(drafter: "FreeDrafter", x_init, y: int, cfg_scale: float, n_spec: int, L: int, tmap, coef_x,
+                coef_eps, sigma, xi, u, lam=None):
+    """The whole sampler (synchronous): returns (x_result, stats dict, per-round accepted counts)."""
+    import torch
+    S = tmap.shape[0]
+    n = load().free_sample_workspace_bytes(drafter.handle, L, float(cfg_scale))
+    key = ("loop", L, cfg_scale > 1.0)
+    if key not in drafter._ws:
+        drafter._ws[key] = torch.empty(n, dtype=torch.uint8, device=drafter.device)
+    ws = drafter._ws[key]
+    x_out = torch.empty_like(x_init)
+    stats = (C.c_int32 * 4)()
+    log = (C.c_int32 * S)()
+    _check(load().free_sample(drafter.handle, _ptr(x_init), int(y), float(cfg_scale), S, int(n_spec), int(L),
+                              _ptr(tmap), _ptr(coef_x), _ptr(coef_eps), _ptr(sigma), _ptr(xi), _ptr(u), _ptr(lam),
+                              _ptr(x_out), stats, log, _ptr(ws), ws.numel(), _stream()), "free_sample")
+    st = dict(target_calls=stats[0], rounds=stats[1], accepted=stats[2], drafter_steps=stats[3])
+    return x_out, st, [log[r] for r in range(stats[1])]
 
 
 def op_linear(A, W, bias, mode: str, epilogue: int = EPI_BIAS, resid=None, gate=None, rows_per_sample: int = 1):

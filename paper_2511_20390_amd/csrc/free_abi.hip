@@ -805,3 +805,131 @@ int32_t draft_round(free_drafter_t dr, const float* x_a, const float* f_a, const
 }
 
 }  // extern "C"
+
+namespace {
+
+// Workspace of the sampler: the target's and the drafter's own workspaces plus the round's buffers.
+struct LoopLayout {
+    size_t ws_target, ws_draft, x_cur, x_states, x_last, m_draft, m_target, log_ratio, accept, n_accept, x_refl,
+        top_feat, feat, tp, yp, eps, total;
+};
+
+LoopLayout make_loop_layout(const Dims& d, int32_t drafter_mod_rows, int32_t L, int32_t dup) {
+    LoopLayout o;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t r = off; off += align_up(bytes); return r; };
+    const size_t dd = static_cast<size_t>(d.d) * 4, fd = static_cast<size_t>(d.ntok) * d.D * 4;
+    o.ws_target = take(make_layout(d, L * dup).total);
+    o.ws_draft = take(make_draft_layout(d, drafter_mod_rows, dup).total);
+    o.x_cur = take(dd);
+    o.x_states = take(dd * L);
+    o.x_last = take(dd);
+    o.m_draft = take(dd * L);
+    o.m_target = take(dd * L);
+    o.log_ratio = take(static_cast<size_t>(L) * 4);
+    o.accept = take(static_cast<size_t>(L));
+    o.n_accept = take(4);
+    o.x_refl = take(dd);
+    o.top_feat = take(fd * L * dup);
+    o.feat = take(fd * dup);
+    o.tp = take(static_cast<size_t>(L) * dup * 4);
+    o.yp = take(static_cast<size_t>(L) * dup * 4);
+    o.eps = take(static_cast<size_t>(L) * dup * d.c_out * d.H * d.W * 4);
+    o.total = off;
+    return o;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t free_sample_workspace_bytes(free_drafter_t dr, int32_t L, float cfg_scale) {
+    if (!dr || L < 1 || L > FREE_MAX_DRAFTS || !(cfg_scale == cfg_scale)) return 0;
+    return make_loop_layout(dr->target->dims, dr->mod_rows, L, cfg_scale > 1.0f ? 2 : 1).total;
+}
+
+int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg_scale, int32_t S, int32_t n_spec,
+                    int32_t L, const int32_t* tmap, const float* coef_x, const float* coef_eps, const float* sigma,
+                    const float* xi, const float* u, const float* lambda, float* x_result, int32_t* stats,
+                    int32_t* n_accept_log, void* workspace, size_t ws_bytes, void* stream) {
+    if (!dr || !x_init || !tmap || !coef_x || !coef_eps || !sigma || !xi || !u || !x_result) return FREE_ERR_NULL;
+    free_dit_t h = dr->target;
+    const Dims& d = h->dims;
+    if (S < 1 || n_spec < 0 || n_spec > S || L < 1 || L > FREE_MAX_DRAFTS) return FREE_ERR_SHAPE;
+    if (y < 0 || y > d.classes) return FREE_ERR_RANGE;
+    if (!(cfg_scale == cfg_scale)) return FREE_ERR_RANGE;
+    const int32_t dup = cfg_scale > 1.0f ? 2 : 1;
+    const LoopLayout o = make_loop_layout(d, dr->mod_rows, L, dup);
+    FREE_TRY(check_ws(workspace, ws_bytes, o.total));
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    auto F = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+    float* x_cur = F(o.x_cur);
+    float* feat = F(o.feat);
+    float* top = F(o.top_feat);
+    int32_t* tp = reinterpret_cast<int32_t*>(ws + o.tp);
+    int32_t* yp = reinterpret_cast<int32_t*>(ws + o.yp);
+    int32_t* n_acc_dev = reinterpret_cast<int32_t*>(ws + o.n_accept);
+    const size_t dd = static_cast<size_t>(d.d) * 4, fd = static_cast<size_t>(d.ntok) * d.D * 4;
+    const int64_t hw = static_cast<int64_t>(d.H) * d.W;
+    auto copy = [&](void* dst, const void* src, size_t n) {
+        return hip_ok(hipMemcpyAsync(dst, src, n, hipMemcpyDeviceToDevice, s)) ? FREE_OK : FREE_ERR_HIP;
+    };
+    int32_t st[4] = {0, 0, 0, 0};       // target calls, rounds, accepted drafts, drafter steps
+    FREE_TRY(copy(x_cur, x_init, dd));
+    bool have_feat = false;
+    int i = 0, round = 0;
+    while (i < S) {
+        if (!have_feat || i >= n_spec) {
+            // plain target step: x_{i+1} = m_i + sigma_i xi_i; its top-block feature starts the next round
+            FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, 1, dup, tp, yp, s));
+            FREE_TRY(forward_impl(h, x_cur, 1, tp, yp, dup, F(o.eps), feat, ws + o.ws_target, s));
+            FREE_TRY(launch_eps_to_mean(F(o.eps), x_cur, coef_x + i, coef_eps + i, cfg_scale, 1, d.C, d.c_out, hw,
+                                        F(o.m_target), s));
+            FREE_TRY(launch_gauss_step(F(o.m_target), sigma + i, xi + static_cast<int64_t>(i) * d.d, d.d, x_cur, s));
+            have_feat = true;
+            ++st[0];
+            ++i;
+            continue;
+        }
+        const int K = L < n_spec - i ? L : n_spec - i;
+        const int B = K * dup;
+        FREE_TRY(draft_round(dr, x_cur, feat, tmap + i, y, cfg_scale, coef_x + i, coef_eps + i, sigma + i,
+                             xi + static_cast<int64_t>(i) * d.d, K, F(o.x_states), F(o.x_last), F(o.m_draft), feat,
+                             ws + o.ws_draft, make_draft_layout(d, dr->mod_rows, dup).total, s));
+        FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, K, dup, tp, yp, s));
+        FREE_TRY(forward_impl(h, F(o.x_states), K, tp, yp, B, F(o.eps), top, ws + o.ws_target, s));
+        FREE_TRY(launch_eps_to_mean(F(o.eps), F(o.x_states), coef_x + i, coef_eps + i, cfg_scale, K, d.C, d.c_out, hw,
+                                    F(o.m_target), s));
+        VerifyArgs a{F(o.m_target), F(o.m_draft), F(o.x_states), F(o.x_last), sigma + i, u + i,
+                     lambda ? lambda + i : nullptr, 1, K, d.d, F(o.log_ratio),
+                     reinterpret_cast<uint8_t*>(ws + o.accept), n_acc_dev, F(o.x_refl)};
+        const WsLayout TL = make_layout(d, B);
+        FREE_TRY(launch_verify(a, ws + o.ws_target + TL.vpart, verify_workspace_bytes(1, K, d.d), s));
+        int32_t n = 0;
+        if (!hip_ok(hipMemcpyAsync(&n, n_acc_dev, 4, hipMemcpyDeviceToHost, s)) || !hip_ok(hipStreamSynchronize(s)))
+            return FREE_ERR_HIP;
+        if (n < 0 || n > K) return FREE_ERR_HIP;
+        if (n_accept_log) n_accept_log[round] = n;
+        ++round;
+        ++st[0];
+        ++st[1];
+        st[2] += n;
+        st[3] += K;
+        // the feature of the packed state whose transition was taken: index K-1 (all accepted) or n,
+        // of the label branch (row j) and of the null branch (row K + j)
+        const int j = n == K ? K - 1 : n;
+        for (int b = 0; b < dup; ++b)
+            FREE_TRY(copy(reinterpret_cast<char*>(feat) + b * fd,
+                          reinterpret_cast<char*>(top) + (static_cast<size_t>(b) * K + j) * fd, fd));
+        FREE_TRY(copy(x_cur, n == K ? F(o.x_last) : F(o.x_refl), dd));
+        i += n == K ? K : n + 1;
+    }
+    FREE_TRY(copy(x_result, x_cur, dd));
+    if (!hip_ok(hipStreamSynchronize(s))) return FREE_ERR_HIP;
+    if (stats)
+        for (int k = 0; k < 4; ++k) stats[k] = st[k];
+    return FREE_OK;
+}
+
+}  // extern "C"

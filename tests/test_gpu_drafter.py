@@ -9,12 +9,16 @@ from tests import parity_util as pu
 
 pytestmark = pytest.mark.gpu
 
+GAIN = 4.0      # output gain of the test drafter in the sampler test: drafts are accepted and rejected
 
-def _models(name, mode, depth, seed=0):
+
+def _models(name, mode, depth, seed=0, out_gain=1.0):
     from paper_2511_20390_amd import binding
     cfg = synth.dit_config(name)
     w = pu.weights_for(cfg, mode, seed=seed)
     wd = synth.make_drafter_weights(cfg, depth, seed=seed + 1, bf16_values=(mode == "bf16"))
+    if out_gain != 1.0:       # a louder output projection: drafts far enough from the target to be rejected
+        wd["fin_w"] = synth.bf16_round(wd["fin_w"] * np.float32(out_gain)) if mode == "bf16" else wd["fin_w"] * np.float32(out_gain)
     target = binding.FreeDit(cfg, w, mode)
     drafter = binding.FreeDrafter(target, wd, depth)
     return cfg, w, wd, target, drafter
@@ -140,5 +144,48 @@ def test_drafter_xl2_512_bf16():
         print(f"xl2_512/bf16 drafter step {k}: eps rel-L2 {err:.3e}")
         assert err <= pu.DIT_REL_L2["bf16"]
     assert pu.rel_l2(out["f_last"].cpu().numpy(), ref["f_last"]) <= pu.DIT_REL_L2["bf16"]
+    drafter.close()
+    target.close()
+
+
+@pytest.mark.parametrize("mode,cfg_scale,L", [("fp32", 4.0, 4), ("fp32", 1.0, 3), ("bf16", 4.0, 5)])
+def test_free_sample_loop(mode, cfg_scale, L):
+    """The whole sampler (Alg. 1) on the GPU against the oracle's loop: same noise, same uniforms.
+    In fp32 mode the two chains take the same decisions (a flipped decision would need a log ratio
+    within rounding of log u) and end in the same sample; in bf16 mode the means differ by 1e-3, so
+    only the bookkeeping and the first round are compared."""
+    import torch
+    from paper_2511_20390_amd import binding
+    cfg, w, wd, target, drafter = _models("tiny", mode, 1, seed=6, out_gain=GAIN)
+    sched = fo.ddpm_schedule()
+    S = 14
+    tmap = (np.arange(S - 1, -1, -1) * 70 + 20).astype(np.int32)
+    cx, ce = fo.mean_coefficients(tmap, sched)
+    sigma = sched["sigma_clipped"][tmap].copy()
+    sigma[-1] = 0.0
+    rng = np.random.default_rng(12)
+    d = synth.latent_dim(cfg)
+    x0 = rng.standard_normal((cfg["in_ch"], cfg["lat_h"], cfg["lat_w"])).astype(np.float32)
+    xi = rng.standard_normal((S, d)).astype(np.float32)
+    u = rng.random(S).astype(np.float32)
+    y = 4
+    f32 = lambda a: pu.to_dev(np.asarray(a, np.float32))
+    x_gpu, st, log = binding.free_sample(drafter, pu.to_dev(x0), y, cfg_scale, S - 1, L, pu.to_dev(tmap), f32(cx), f32(ce),
+                                         f32(sigma), pu.to_dev(xi), pu.to_dev(u))
+    x_ref, st_ref = fo.free_sample(wd, w, cfg, x0, y, cfg_scale, tmap, cx.astype(np.float32), ce.astype(np.float32),
+                                   sigma.astype(np.float32), S - 1, L, xi, u)
+    print(f"{mode} scale {cfg_scale} L={L}: gpu {st} log {log}; oracle {st_ref}")
+    assert st["target_calls"] == st["rounds"] + 2 and st["drafter_steps"] >= st["accepted"]
+    assert len(log) == st["rounds"] and sum(log) == st["accepted"]
+    if mode == "fp32":
+        assert log == st_ref["n_accept"]
+        assert {k: st[k] for k in ("target_calls", "rounds", "accepted", "drafter_steps")} == \
+               {k: st_ref[k] for k in ("target_calls", "rounds", "accepted", "drafter_steps")}
+        assert pu.rel_l2(x_gpu.cpu().numpy(), x_ref) < 1e-4
+        assert 0 < st["accepted"] < st["drafter_steps"], "the case should exercise both outcomes"
+    else:
+        # bf16 means differ from the oracle's by ~1e-3: a decision may legitimately differ, after which the
+        # chains part; the first round starts from identical inputs and its outcome is compared
+        assert abs(log[0] - st_ref["n_accept"][0]) <= 1
     drafter.close()
     target.close()
