@@ -44,6 +44,12 @@ invariants and the library-routine cross-check it is "parity unpinned".
   scalar chain and on the DiT), on a linear-Gaussian chain the distribution of
   the result has the target's closed-form mean, variance and kurtosis whatever
   the drafter proposes, and every step is taken exactly once.
+* The relaxation profile (Sec. 3.4): self-speculative run with frozen-target
+  drafting recording the noise-estimate deviation per checked step, monotone
+  least-squares fit (pool adjacent violators), smoothing, inverse rescaled to
+  (0, 1].  Pins: the fit against brute force and a library isotonic regression,
+  the closed form of the frozen recurrence, exactness of frozen drafting for a
+  state-independent network, monotonicity and range of the profile.
 """
 from __future__ import annotations
 
@@ -458,7 +464,7 @@ def draft_steps(wd: dict, w: dict, cfg: dict, x_a, f_a, t, y: int, cfg_scale: fl
 # ----------------------------------------------------------------------------
 # The whole sampler (Alg. 1): target step, drafting, packed verification, advance
 # ----------------------------------------------------------------------------
-def speculative_loop(x0, S: int, n_spec: int, L: int, sigma, xi, u, lam, target_means, draft_mean):
+def speculative_loop(x0, S: int, n_spec: int, L: int, sigma, xi, u, lam, target_means, draft_mean, on_verify=None):
     """Alg. 1 around two callables, so that the control flow can be checked on models with a known answer.
 
     Steps are indexed i = 0..S-1: step i takes the state x_i and produces x_{i+1}; x_S is returned.
@@ -474,6 +480,7 @@ def speculative_loop(x0, S: int, n_spec: int, L: int, sigma, xi, u, lam, target_
       * with n drafts accepted the sampler advances to x_{i+n} = x^_{i+n} if n = K, else to the reflected
         x_{i+n+1}; the feature handed to the next round is the target's feature of the packed state that
         produced the transition just taken (index K-1, or n).  Every round therefore costs one target call.
+    `on_verify(i, m_hat, m, accepted)` is called for every draft that is checked (step index i).
     Returns (x_S, stats) with stats = dict(target_calls, rounds, accepted, drafter_steps, n_accept=[...]).
     """
     x = np.asarray(x0, F64)
@@ -507,6 +514,8 @@ def speculative_loop(x0, S: int, n_spec: int, L: int, sigma, xi, u, lam, target_
         for j in range(K):
             xr, ok, _, _ = verification(m_hat[j].reshape(-1), np.asarray(means[j], F64).reshape(-1), sigma[i + j],
                                         states[j + 1].reshape(-1), u[i + j], lam[i + j])
+            if on_verify is not None:
+                on_verify(i + j, m_hat[j], np.asarray(means[j], F64), bool(ok))
             if not ok:
                 n = j
                 x = xr.reshape(x.shape)
@@ -548,3 +557,92 @@ def free_sample(wd: dict, w: dict, cfg: dict, x0, y: int, cfg_scale: float, tmap
 
     S = len(tmap)
     return speculative_loop(x0, S, n_spec, L, sigma, xi, u, lam, target_means, draft_mean)
+
+
+# ----------------------------------------------------------------------------
+# Relaxation profile (Sec. 3.4): offline self-speculative run, monotone fit, inverse rescaled to [0, 1]
+# ----------------------------------------------------------------------------
+def frozen_draft_steps(x_a, eps_frozen, coef_x, coef_eps, sigma, xi) -> dict:
+    """Frozen-target drafting (Sec. 2: several future steps approximated by reusing a single noise estimate
+    of the target): m^_k = coef_x[k] x^_k + coef_eps[k] eps_frozen, x^_{k+1} = m^_k + sigma[k] xi[k]."""
+    x = np.asarray(x_a, F64)
+    e = np.asarray(eps_frozen, F64).reshape(x.shape)
+    K = len(sigma)
+    xs, ms = [x], []
+    for k in range(K):
+        m = float(coef_x[k]) * xs[-1] + float(coef_eps[k]) * e
+        ms.append(m.reshape(-1))
+        xs.append(m + float(sigma[k]) * np.asarray(xi, F64)[k].reshape(x.shape))
+    return dict(x_states=np.stack(xs[:K]), x_last=xs[K], m_draft=np.stack(ms))
+
+
+def self_speculative_run(w: dict, cfg: dict, x0, y: int, cfg_scale: float, tmap, coef_x, coef_eps, sigma,
+                         n_spec: int, L: int, xi, u, lam=None):
+    """The offline run of Sec. 3.4: the target DiT both proposes (frozen-target drafting: the guided noise
+    estimate of its latest evaluation is reused for the next K steps) and verifies (Alg. 2).  For every
+    checked draft at step i it records eps_delta[i] = || eps_pred - eps_ref ||_2 (the reused estimate
+    against the target's own at that state) and whether the draft passed; steps that were never checked
+    (plain target steps, drafts after a rejection) hold NaN / -1.
+    Returns (x_S, stats, eps_delta [S], accepted [S])."""
+    C = np.asarray(x0).shape[0]
+    S = len(tmap)
+    dup = 2 if cfg_scale > 1.0 else 1
+    yy = np.array([y, cfg["num_classes"]][:dup])
+    eps_delta = np.full(S, np.nan)
+    accepted = np.full(S, -1, np.int8)
+
+    def target_means(states, i0):
+        K = len(states)
+        xs = np.stack(states)
+        t = np.asarray([tmap[i0 + j] for j in range(K)])
+        out, _ = dit_forward(w, cfg, np.concatenate([xs] * dup), np.concatenate([t] * dup), np.repeat(yy, K))
+        eps = cfg_combine(out[:K, :C], out[K:, :C], cfg_scale) if dup == 2 else out[:, :C]
+        means = [float(coef_x[i0 + j]) * xs[j] + float(coef_eps[i0 + j]) * eps[j] for j in range(K)]
+        return means, [eps[j] for j in range(K)]          # the "feature" handed on is the noise estimate
+
+    def draft_mean(x, eps_frozen, i):
+        return float(coef_x[i]) * np.asarray(x, F64) + float(coef_eps[i]) * eps_frozen, eps_frozen
+
+    def on_verify(i, m_hat, m, ok):
+        eps_delta[i] = np.linalg.norm((m_hat - m).ravel()) / abs(float(coef_eps[i]))
+        accepted[i] = 1 if ok else 0
+
+    x, stats = speculative_loop(x0, S, n_spec, L, sigma, xi, u, lam, target_means, draft_mean, on_verify)
+    return x, stats, eps_delta, accepted
+
+
+def monotone_fit(v) -> np.ndarray:
+    """Least-squares non-decreasing fit of a sequence (pool adjacent violators); NaN entries carry no weight
+    and take the value of the fit at their position."""
+    v = np.asarray(v, F64)
+    ok = ~np.isnan(v)
+    if not ok.any():
+        raise ValueError("no measured value")
+    blocks = []                                   # [sum, weight, length]
+    for val, has in zip(v, ok):
+        blocks.append([val if has else 0.0, 1.0 if has else 0.0, 1])
+        while len(blocks) > 1:
+            a, b = blocks[-2], blocks[-1]
+            if a[1] == 0.0 or b[1] == 0.0 or a[0] / a[1] > b[0] / b[1]:
+                blocks[-2:] = [[a[0] + b[0], a[1] + b[1], a[2] + b[2]]]
+            else:
+                break
+    out = np.concatenate([np.full(n, s_ / w_) for s_, w_, n in blocks])
+    return out
+
+
+def relaxation_profile_from_deltas(eps_delta, window: int = 1) -> np.ndarray:
+    """lambda_i from the measured deviations (Sec. 3.4): a monotonically increasing curve g fitted to
+    eps_delta over the denoising steps (isotonic least squares, then a centred moving average of odd width
+    `window` with the ends held, which keeps it monotone and makes it smooth), inverted and rescaled to
+    (0, 1]: lambda_i = g_0 / g_i, so the rule is strict (lambda = 1) where the uncertainty is lowest and
+    relaxes as it grows."""
+    g = monotone_fit(eps_delta)
+    if window > 1:
+        if window % 2 == 0:
+            raise ValueError("window must be odd")
+        h = window // 2
+        gp = np.concatenate([np.full(h, g[0]), g, np.full(h, g[-1])])
+        g = np.convolve(gp, np.full(window, 1.0 / window), mode="valid")
+    g = np.maximum(g, 1e-300)
+    return g[0] / g
