@@ -256,6 +256,27 @@ int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg
                     const float* lambda, float* x_result, int32_t* stats, int32_t* n_accept_log,
                     void* workspace, size_t ws_bytes, void* stream);
 
+/* ---- relaxation profile (Sec. 3.4 "Uncertainty-Guided Verification Relaxation") ----
+ * free_self_speculative: the offline run in which the target both proposes and verifies.  Same loop
+ * and arguments as free_sample, with frozen-target drafting instead of a drafter: the guided noise
+ * estimate of the latest target evaluation is reused for the next K steps,
+ * m^_k = coef_x[k] x^_k + coef_eps[k] eps_frozen.  For every checked draft at step i it records
+ *   eps_delta[i] = || eps_frozen - eps_target(x^_i) ||_2   and   accepted[i] in {0, 1}
+ * [host arrays of S entries, either may be NULL]; steps that were never checked (plain target steps,
+ * drafts behind a rejection) hold NaN and -1.  Synchronous.
+ * free_lambda_profile [host only]: lambda from the measured deviations - a non-decreasing least-squares
+ * fit over the step index (NaN entries carry no weight), a centred moving average of odd width
+ * `window` (1 = none) with the ends held, then lambda_i = g_0 / g_i in (0, 1].  FREE_ERR_RANGE when no
+ * entry is measured, FREE_ERR_SHAPE for S < 1 or an even window. */
+size_t free_self_speculative_workspace_bytes(free_dit_t target, int32_t L, float cfg_scale);
+int32_t free_self_speculative(free_dit_t target, const float* x_init, int32_t y, float cfg_scale, int32_t S,
+                              int32_t n_spec, int32_t L, const int32_t* tmap, const float* coef_x,
+                              const float* coef_eps, const float* sigma, const float* xi, const float* u,
+                              const float* lambda, float* x_result, int32_t* stats, int32_t* n_accept_log,
+                              float* eps_delta, int8_t* accepted, void* workspace, size_t ws_bytes,
+                              void* stream);
+int32_t free_lambda_profile(const float* eps_delta, int32_t S, int32_t window, float* lambda_out);
+
 /* ---- per-kernel timing for benchmarks -------------------------------------
  * Between free_profile_begin and free_profile_end every kernel launch of the
  * hot-path calls is bracketed by two HIP events recorded on the launch stream.

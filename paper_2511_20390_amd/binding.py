@@ -27,6 +27,7 @@ EXPORTED_SYMBOLS = [
     "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
     "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
     "drafter_forward", "draft_round", "free_sample_workspace_bytes", "free_sample",
+    "free_self_speculative_workspace_bytes", "free_self_speculative", "free_lambda_profile",
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
     "free_profile_begin", "free_profile_end", "free_profile_category_name",
 ]
@@ -100,6 +101,12 @@ def load():
     lib.free_sample_workspace_bytes.argtypes = [vp, i32, f32]
     lib.free_sample.restype = i32
     lib.free_sample.argtypes = [vp, vp, i32, f32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.free_self_speculative_workspace_bytes.restype = sz
+    lib.free_self_speculative_workspace_bytes.argtypes = [vp, i32, f32]
+    lib.free_self_speculative.restype = i32
+    lib.free_self_speculative.argtypes = [vp, vp, i32, f32, i32, i32, i32] + [vp] * 12 + [vp, sz, vp]
+    lib.free_lambda_profile.restype = i32
+    lib.free_lambda_profile.argtypes = [vp, i32, i32, vp]
     lib.free_op_linear.restype = i32
     lib.free_op_linear.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, i32, vp]
     lib.free_op_attention.restype = i32
@@ -357,6 +364,38 @@ def free_sample(drafter: "FreeDrafter", x_init, y: int, cfg_scale: float, n_spec
                               _ptr(x_out), stats, log, _ptr(ws), ws.numel(), _stream()), "free_sample")
     st = dict(target_calls=stats[0], rounds=stats[1], accepted=stats[2], drafter_steps=stats[3])
     return x_out, st, [log[r] for r in range(stats[1])]
+
+
+def free_self_speculative(target: FreeDit, x_init, y: int, cfg_scale: float, n_spec: int, L: int, tmap, coef_x,
+                          coef_eps, sigma, xi, u, lam=None):
+    """The offline self-speculative run (synchronous): returns (x_result, stats, per-round accepted counts,
+    eps_delta [S] float32 with NaN where unchecked, accepted [S] int8 with -1 where unchecked)."""
+    import torch
+    S = tmap.shape[0]
+    n = load().free_self_speculative_workspace_bytes(target.handle, L, float(cfg_scale))
+    key = ("self", L, cfg_scale > 1.0)
+    if key not in target._ws:
+        target._ws[key] = torch.empty(n, dtype=torch.uint8, device=target.device)
+    ws = target._ws[key]
+    x_out = torch.empty_like(x_init)
+    stats = (C.c_int32 * 4)()
+    log = (C.c_int32 * S)()
+    delta = np.empty(S, np.float32)
+    acc = np.empty(S, np.int8)
+    _check(load().free_self_speculative(target.handle, _ptr(x_init), int(y), float(cfg_scale), S, int(n_spec), int(L),
+                                        _ptr(tmap), _ptr(coef_x), _ptr(coef_eps), _ptr(sigma), _ptr(xi), _ptr(u),
+                                        _ptr(lam), _ptr(x_out), stats, log, delta.ctypes.data, acc.ctypes.data,
+                                        _ptr(ws), ws.numel(), _stream()), "free_self_speculative")
+    st = dict(target_calls=stats[0], rounds=stats[1], accepted=stats[2], drafter_steps=stats[3])
+    return x_out, st, [log[r] for r in range(stats[1])], delta, acc
+
+
+def free_lambda_profile(eps_delta, window: int = 1) -> np.ndarray:
+    """Host only: the relaxation profile lambda [S] from measured deviations (NaN = not measured)."""
+    e = np.ascontiguousarray(eps_delta, np.float32)
+    out = np.empty(e.shape[0], np.float32)
+    _check(load().free_lambda_profile(e.ctypes.data, e.shape[0], int(window), out.ctypes.data), "free_lambda_profile")
+    return out
 
 
 def op_linear(A, W, bias, mode: str, epilogue: int = EPI_BIAS, resid=None, gate=None, rows_per_sample: int = 1):

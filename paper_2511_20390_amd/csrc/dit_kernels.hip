@@ -533,7 +533,7 @@ __global__ __launch_bounds__(kThreads) void final_layer_vec_kernel(
 __global__ void eps_to_mean_kernel(const float* __restrict__ eps_out, const float* __restrict__ x_states,
                                    const float* __restrict__ coef_x, const float* __restrict__ coef_eps,
                                    float cfg_scale, int32_t use_cfg, int32_t K, int32_t C, int32_t c_out,
-                                   int64_t hw, float* __restrict__ m_out) {
+                                   int64_t hw, float* __restrict__ m_out, float* __restrict__ eps_guided) {
     const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     const int64_t per = static_cast<int64_t>(C) * hw;
     if (idx >= per * K) return;
@@ -545,6 +545,7 @@ __global__ void eps_to_mean_kernel(const float* __restrict__ eps_out, const floa
         eps = fmaf(cfg_scale, eps - en, en);
     }
     m_out[idx] = fmaf(coef_x[k], x_states[idx], coef_eps[k] * eps);
+    if (eps_guided) eps_guided[idx] = eps;
 }
 
 __global__ void pack_cond_kernel(const int32_t* __restrict__ t, int32_t y, int32_t null_label, int32_t K,
@@ -771,13 +772,54 @@ __global__ __launch_bounds__(256) void gauss_step_kernel(const float* __restrict
     if (i < n) out[i] = fmaf(sigma_k[0], xi[i], m[i]);
 }
 
+// Frozen-target drafting (Sec. 2; used by the self-speculative run of Sec. 3.4): one noise estimate e is
+// reused for K steps, m^_k = coef_x[k] x^_k + coef_eps[k] e, x^_{k+1} = m^_k + sigma[k] xi[k]; every latent
+// element is an independent recurrence, so one thread walks all K steps of its element.
+__global__ __launch_bounds__(256) void frozen_draft_kernel(const float* __restrict__ x_a, const float* __restrict__ e,
+                                                           const float* __restrict__ coef_x,
+                                                           const float* __restrict__ coef_eps,
+                                                           const float* __restrict__ sigma, const float* __restrict__ xi,
+                                                           int32_t K, int64_t d, float* __restrict__ x_states,
+                                                           float* __restrict__ x_last, float* __restrict__ m_draft) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= d) return;
+    float x = x_a[i];
+    const float ev = e[i];
+    for (int k = 0; k < K; ++k) {
+        x_states[k * d + i] = x;
+        const float m = fmaf(coef_x[k], x, coef_eps[k] * ev);
+        m_draft[k * d + i] = m;
+        x = fmaf(sigma[k], xi[k * d + i], m);
+    }
+    x_last[i] = x;
+}
+
+// out[k] = || a_k - b_k ||_2^2 over d elements, fp64 accumulation, one workgroup per k (small K, d ~ 1e4..1e5)
+__global__ __launch_bounds__(256) void sqdist_kernel(const float* __restrict__ a, const float* __restrict__ b, int64_t d,
+                                                     double* __restrict__ out) {
+    __shared__ double part[256];
+    const int k = blockIdx.x;
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < d; i += 256) {
+        const double v = static_cast<double>(a[k * d + i]) - static_cast<double>(b[k * d + i]);
+        acc += v * v;
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[k] = part[0];
+}
+
 int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const float* coef_x,
                            const float* coef_eps, float cfg_scale, int32_t K, int32_t C, int32_t c_out,
-                           int64_t hw, float* m_out, hipStream_t s) {
+                           int64_t hw, float* m_out, hipStream_t s, float* eps_guided) {
     const int64_t n = static_cast<int64_t>(K) * C * hw;
     const int use_cfg = cfg_scale > 1.0f ? 1 : 0;
     hipLaunchKernelGGL(eps_to_mean_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, eps_out,
-                       x_states, coef_x, coef_eps, cfg_scale, use_cfg, K, C, c_out, hw, m_out);
+                       x_states, coef_x, coef_eps, cfg_scale, use_cfg, K, C, c_out, hw, m_out, eps_guided);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 
@@ -813,6 +855,19 @@ int32_t launch_gauss_step(const float* m, const float* sigma_k, const float* xi,
                           hipStream_t s) {
     hipLaunchKernelGGL(gauss_step_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, m, sigma_k,
                        xi, n, out);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_frozen_draft(const float* x_a, const float* e, const float* coef_x, const float* coef_eps,
+                            const float* sigma, const float* xi, int32_t K, int64_t d, float* x_states, float* x_last,
+                            float* m_draft, hipStream_t s) {
+    hipLaunchKernelGGL(frozen_draft_kernel, dim3(static_cast<unsigned>((d + 255) / 256)), dim3(256), 0, s, x_a, e, coef_x,
+                       coef_eps, sigma, xi, K, d, x_states, x_last, m_draft);
+    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t launch_sqdist(const float* a, const float* b, int32_t K, int64_t d, double* out, hipStream_t s) {
+    hipLaunchKernelGGL(sqdist_kernel, dim3(K), dim3(256), 0, s, a, b, d, out);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 

@@ -811,7 +811,7 @@ namespace {
 // Workspace of the sampler: the target's and the drafter's own workspaces plus the round's buffers.
 struct LoopLayout {
     size_t ws_target, ws_draft, x_cur, x_states, x_last, m_draft, m_target, log_ratio, accept, n_accept, x_refl,
-        top_feat, feat, tp, yp, eps, total;
+        top_feat, feat, tp, yp, eps, eps_guided, dist, total;
 };
 
 LoopLayout make_loop_layout(const Dims& d, int32_t drafter_mod_rows, int32_t L, int32_t dup) {
@@ -820,7 +820,7 @@ LoopLayout make_loop_layout(const Dims& d, int32_t drafter_mod_rows, int32_t L, 
     auto take = [&](size_t bytes) { size_t r = off; off += align_up(bytes); return r; };
     const size_t dd = static_cast<size_t>(d.d) * 4, fd = static_cast<size_t>(d.ntok) * d.D * 4;
     o.ws_target = take(make_layout(d, L * dup).total);
-    o.ws_draft = take(make_draft_layout(d, drafter_mod_rows, dup).total);
+    o.ws_draft = take(drafter_mod_rows > 0 ? make_draft_layout(d, drafter_mod_rows, dup).total : 0);
     o.x_cur = take(dd);
     o.x_states = take(dd * L);
     o.x_last = take(dd);
@@ -830,39 +830,45 @@ LoopLayout make_loop_layout(const Dims& d, int32_t drafter_mod_rows, int32_t L, 
     o.accept = take(static_cast<size_t>(L));
     o.n_accept = take(4);
     o.x_refl = take(dd);
-    o.top_feat = take(fd * L * dup);
-    o.feat = take(fd * dup);
+    o.top_feat = take(drafter_mod_rows > 0 ? fd * L * dup : 0);
+    o.feat = take(drafter_mod_rows > 0 ? fd * dup : dd);      // top-block features, or one frozen noise estimate
     o.tp = take(static_cast<size_t>(L) * dup * 4);
     o.yp = take(static_cast<size_t>(L) * dup * 4);
     o.eps = take(static_cast<size_t>(L) * dup * d.c_out * d.H * d.W * 4);
+    o.eps_guided = take(dd * L);
+    o.dist = take(sizeof(double) * FREE_MAX_DRAFTS);
     o.total = off;
     return o;
 }
 
-}  // namespace
+inline float* F0(char* ws, size_t off) { return reinterpret_cast<float*>(ws + off); }
 
-extern "C" {
+// The sampler of Alg. 1.  dr != nullptr: feature-level drafter; dr == nullptr: frozen-target drafting
+// (self-speculative run of Sec. 3.4: the guided noise estimate of the latest target evaluation is the
+// "feature"), with the deviation || eps_frozen - eps_target ||_2 and the outcome of every checked draft
+// logged to eps_delta / accepted (host arrays of S entries, NaN / -1 where nothing was checked).
+int32_t sample_loop(free_dit_t h, free_drafter_t dr, const float* x_init, int32_t y, float cfg_scale, int32_t S,
+                    int32_t n_spec, int32_t L, const int32_t* tmap, const float* coef_x, const float* coef_eps,
+                    const float* sigma, const float* xi, const float* u, const float* lambda, float* x_result,
+                    int32_t* stats, int32_t* n_accept_log, float* eps_delta, int8_t* accepted, void* workspace,
+                    size_t ws_bytes, hipStream_t s) {
+    if (!x_init || !tmap || !coef_x || !coef_eps || !sigma || !xi || !u || !x_result) return FREE_ERR_NULL;
 
-size_t free_sample_workspace_bytes(free_drafter_t dr, int32_t L, float cfg_scale) {
-    if (!dr || L < 1 || L > FREE_MAX_DRAFTS || !(cfg_scale == cfg_scale)) return 0;
-    return make_loop_layout(dr->target->dims, dr->mod_rows, L, cfg_scale > 1.0f ? 2 : 1).total;
-}
-
-int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg_scale, int32_t S, int32_t n_spec,
-                    int32_t L, const int32_t* tmap, const float* coef_x, const float* coef_eps, const float* sigma,
-                    const float* xi, const float* u, const float* lambda, float* x_result, int32_t* stats,
-                    int32_t* n_accept_log, void* workspace, size_t ws_bytes, void* stream) {
-    if (!dr || !x_init || !tmap || !coef_x || !coef_eps || !sigma || !xi || !u || !x_result) return FREE_ERR_NULL;
-    free_dit_t h = dr->target;
     const Dims& d = h->dims;
     if (S < 1 || n_spec < 0 || n_spec > S || L < 1 || L > FREE_MAX_DRAFTS) return FREE_ERR_SHAPE;
     if (y < 0 || y > d.classes) return FREE_ERR_RANGE;
     if (!(cfg_scale == cfg_scale)) return FREE_ERR_RANGE;
     const int32_t dup = cfg_scale > 1.0f ? 2 : 1;
-    const LoopLayout o = make_loop_layout(d, dr->mod_rows, L, dup);
+    const bool frozen = dr == nullptr;
+    const LoopLayout o = make_loop_layout(d, frozen ? 0 : dr->mod_rows, L, dup);
     FREE_TRY(check_ws(workspace, ws_bytes, o.total));
     char* ws = static_cast<char*>(workspace);
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (eps_delta)
+        for (int k = 0; k < S; ++k) eps_delta[k] = std::nanf("");
+    if (accepted)
+        for (int k = 0; k < S; ++k) accepted[k] = -1;
+    float* eps_g = F0(ws, o.eps_guided);          // guided noise estimates of the latest target call [L, d]
+    double* dist = reinterpret_cast<double*>(ws + o.dist);
     auto F = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
     float* x_cur = F(o.x_cur);
     float* feat = F(o.feat);
@@ -883,9 +889,9 @@ int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg
         if (!have_feat || i >= n_spec) {
             // plain target step: x_{i+1} = m_i + sigma_i xi_i; its top-block feature starts the next round
             FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, 1, dup, tp, yp, s));
-            FREE_TRY(forward_impl(h, x_cur, 1, tp, yp, dup, F(o.eps), feat, ws + o.ws_target, s));
+            FREE_TRY(forward_impl(h, x_cur, 1, tp, yp, dup, F(o.eps), frozen ? nullptr : feat, ws + o.ws_target, s));
             FREE_TRY(launch_eps_to_mean(F(o.eps), x_cur, coef_x + i, coef_eps + i, cfg_scale, 1, d.C, d.c_out, hw,
-                                        F(o.m_target), s));
+                                        F(o.m_target), s, frozen ? feat : nullptr));
             FREE_TRY(launch_gauss_step(F(o.m_target), sigma + i, xi + static_cast<int64_t>(i) * d.d, d.d, x_cur, s));
             have_feat = true;
             ++st[0];
@@ -894,13 +900,19 @@ int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg
         }
         const int K = L < n_spec - i ? L : n_spec - i;
         const int B = K * dup;
-        FREE_TRY(draft_round(dr, x_cur, feat, tmap + i, y, cfg_scale, coef_x + i, coef_eps + i, sigma + i,
-                             xi + static_cast<int64_t>(i) * d.d, K, F(o.x_states), F(o.x_last), F(o.m_draft), feat,
-                             ws + o.ws_draft, make_draft_layout(d, dr->mod_rows, dup).total, s));
+        if (frozen)
+            FREE_TRY(launch_frozen_draft(x_cur, feat, coef_x + i, coef_eps + i, sigma + i,
+                                         xi + static_cast<int64_t>(i) * d.d, K, d.d, F(o.x_states), F(o.x_last),
+                                         F(o.m_draft), s));
+        else
+            FREE_TRY(draft_round(dr, x_cur, feat, tmap + i, y, cfg_scale, coef_x + i, coef_eps + i, sigma + i,
+                                 xi + static_cast<int64_t>(i) * d.d, K, F(o.x_states), F(o.x_last), F(o.m_draft), feat,
+                                 ws + o.ws_draft, make_draft_layout(d, dr->mod_rows, dup).total, s));
         FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, K, dup, tp, yp, s));
-        FREE_TRY(forward_impl(h, F(o.x_states), K, tp, yp, B, F(o.eps), top, ws + o.ws_target, s));
+        FREE_TRY(forward_impl(h, F(o.x_states), K, tp, yp, B, F(o.eps), frozen ? nullptr : top, ws + o.ws_target, s));
         FREE_TRY(launch_eps_to_mean(F(o.eps), F(o.x_states), coef_x + i, coef_eps + i, cfg_scale, K, d.C, d.c_out, hw,
-                                    F(o.m_target), s));
+                                    F(o.m_target), s, frozen ? eps_g : nullptr));
+        if (eps_delta) FREE_TRY(launch_sqdist(F(o.m_draft), F(o.m_target), K, d.d, dist, s));
         VerifyArgs a{F(o.m_target), F(o.m_draft), F(o.x_states), F(o.x_last), sigma + i, u + i,
                      lambda ? lambda + i : nullptr, 1, K, d.d, F(o.log_ratio),
                      reinterpret_cast<uint8_t*>(ws + o.accept), n_acc_dev, F(o.x_refl)};
@@ -910,6 +922,20 @@ int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg
         if (!hip_ok(hipMemcpyAsync(&n, n_acc_dev, 4, hipMemcpyDeviceToHost, s)) || !hip_ok(hipStreamSynchronize(s)))
             return FREE_ERR_HIP;
         if (n < 0 || n > K) return FREE_ERR_HIP;
+        if (eps_delta || accepted) {
+            // the drafts 0 .. min(n, K-1) were checked: ||m^ - m|| / |coef_eps| = ||eps^ - eps|| (same state)
+            const int checked = n == K ? K : n + 1;
+            double hd[FREE_MAX_DRAFTS];
+            float hc[FREE_MAX_DRAFTS];
+            if (!hip_ok(hipMemcpyAsync(hd, dist, sizeof(double) * K, hipMemcpyDeviceToHost, s)) ||
+                !hip_ok(hipMemcpyAsync(hc, coef_eps + i, sizeof(float) * K, hipMemcpyDeviceToHost, s)) ||
+                !hip_ok(hipStreamSynchronize(s)))
+                return FREE_ERR_HIP;
+            for (int k = 0; k < checked; ++k) {
+                if (eps_delta) eps_delta[i + k] = static_cast<float>(std::sqrt(hd[k]) / std::fabs(hc[k]));
+                if (accepted) accepted[i + k] = k < n ? 1 : 0;
+            }
+        }
         if (n_accept_log) n_accept_log[round] = n;
         ++round;
         ++st[0];
@@ -919,9 +945,13 @@ int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg
         // the feature of the packed state whose transition was taken: index K-1 (all accepted) or n,
         // of the label branch (row j) and of the null branch (row K + j)
         const int j = n == K ? K - 1 : n;
-        for (int b = 0; b < dup; ++b)
-            FREE_TRY(copy(reinterpret_cast<char*>(feat) + b * fd,
-                          reinterpret_cast<char*>(top) + (static_cast<size_t>(b) * K + j) * fd, fd));
+        if (frozen) {
+            FREE_TRY(copy(feat, reinterpret_cast<char*>(eps_g) + static_cast<size_t>(j) * dd, dd));
+        } else {
+            for (int b = 0; b < dup; ++b)
+                FREE_TRY(copy(reinterpret_cast<char*>(feat) + b * fd,
+                              reinterpret_cast<char*>(top) + (static_cast<size_t>(b) * K + j) * fd, fd));
+        }
         FREE_TRY(copy(x_cur, n == K ? F(o.x_last) : F(o.x_refl), dd));
         i += n == K ? K : n + 1;
     }
@@ -929,6 +959,83 @@ int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg
     if (!hip_ok(hipStreamSynchronize(s))) return FREE_ERR_HIP;
     if (stats)
         for (int k = 0; k < 4; ++k) stats[k] = st[k];
+    return FREE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t free_sample_workspace_bytes(free_drafter_t dr, int32_t L, float cfg_scale) {
+    if (!dr || L < 1 || L > FREE_MAX_DRAFTS || !(cfg_scale == cfg_scale)) return 0;
+    return make_loop_layout(dr->target->dims, dr->mod_rows, L, cfg_scale > 1.0f ? 2 : 1).total;
+}
+
+int32_t free_sample(free_drafter_t dr, const float* x_init, int32_t y, float cfg_scale, int32_t S, int32_t n_spec,
+                    int32_t L, const int32_t* tmap, const float* coef_x, const float* coef_eps, const float* sigma,
+                    const float* xi, const float* u, const float* lambda, float* x_result, int32_t* stats,
+                    int32_t* n_accept_log, void* workspace, size_t ws_bytes, void* stream) {
+    if (!dr) return FREE_ERR_NULL;
+    return sample_loop(dr->target, dr, x_init, y, cfg_scale, S, n_spec, L, tmap, coef_x, coef_eps, sigma, xi, u, lambda,
+                       x_result, stats, n_accept_log, nullptr, nullptr, workspace, ws_bytes,
+                       static_cast<hipStream_t>(stream));
+}
+
+size_t free_self_speculative_workspace_bytes(free_dit_t target, int32_t L, float cfg_scale) {
+    if (!target || L < 1 || L > FREE_MAX_DRAFTS || !(cfg_scale == cfg_scale)) return 0;
+    return make_loop_layout(target->dims, 0, L, cfg_scale > 1.0f ? 2 : 1).total;
+}
+
+int32_t free_self_speculative(free_dit_t target, const float* x_init, int32_t y, float cfg_scale, int32_t S,
+                              int32_t n_spec, int32_t L, const int32_t* tmap, const float* coef_x,
+                              const float* coef_eps, const float* sigma, const float* xi, const float* u,
+                              const float* lambda, float* x_result, int32_t* stats, int32_t* n_accept_log,
+                              float* eps_delta, int8_t* accepted, void* workspace, size_t ws_bytes, void* stream) {
+    if (!target) return FREE_ERR_NULL;
+    return sample_loop(target, nullptr, x_init, y, cfg_scale, S, n_spec, L, tmap, coef_x, coef_eps, sigma, xi, u, lambda,
+                       x_result, stats, n_accept_log, eps_delta, accepted, workspace, ws_bytes,
+                       static_cast<hipStream_t>(stream));
+}
+
+int32_t free_lambda_profile(const float* eps_delta, int32_t S, int32_t window, float* lambda_out) {
+    if (!eps_delta || !lambda_out) return FREE_ERR_NULL;
+    if (S < 1 || window < 1 || window % 2 == 0) return FREE_ERR_SHAPE;
+    // isotonic least squares (pool adjacent violators); NaN entries carry no weight
+    struct Blk { double sum, w; int n; };
+    std::vector<Blk> blk;
+    blk.reserve(S);
+    bool any = false;
+    for (int i = 0; i < S; ++i) {
+        const bool has = eps_delta[i] == eps_delta[i];
+        any = any || has;
+        blk.push_back(Blk{has ? static_cast<double>(eps_delta[i]) : 0.0, has ? 1.0 : 0.0, 1});
+        while (blk.size() > 1) {
+            Blk& a = blk[blk.size() - 2];
+            const Blk& b = blk.back();
+            if (a.w == 0.0 || b.w == 0.0 || a.sum / a.w > b.sum / b.w) {
+                a.sum += b.sum; a.w += b.w; a.n += b.n;
+                blk.pop_back();
+            } else {
+                break;
+            }
+        }
+    }
+    if (!any) return FREE_ERR_RANGE;
+    std::vector<double> g;
+    g.reserve(S);
+    for (const Blk& b : blk) g.insert(g.end(), b.n, b.sum / b.w);
+    if (window > 1) {                     // centred moving average, ends held: keeps the fit monotone
+        const int hw = window / 2;
+        std::vector<double> sm(S);
+        for (int i = 0; i < S; ++i) {
+            double acc = 0.0;
+            for (int j = i - hw; j <= i + hw; ++j) acc += g[j < 0 ? 0 : (j >= S ? S - 1 : j)];
+            sm[i] = acc / window;
+        }
+        g.swap(sm);
+    }
+    const double g0 = g[0] > 1e-300 ? g[0] : 1e-300;
+    for (int i = 0; i < S; ++i) lambda_out[i] = static_cast<float>(g0 / (g[i] > 1e-300 ? g[i] : 1e-300));
     return FREE_OK;
 }
 

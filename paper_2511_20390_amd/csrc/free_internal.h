@@ -131,7 +131,7 @@ int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B
                            int32_t dtype, float* out, hipStream_t s);
 int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const float* coef_x,
                            const float* coef_eps, float cfg_scale, int32_t K, int32_t C, int32_t c_out,
-                           int64_t hw, float* m_out, hipStream_t s);
+                           int64_t hw, float* m_out, hipStream_t s, float* eps_guided = nullptr);
 int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_t K, int32_t dup,
                          int32_t* t_out, int32_t* y_out, hipStream_t s);
 
@@ -141,6 +141,12 @@ int32_t launch_fuse_pack(const float* emb, const float* feat, int64_t M, int32_t
 int32_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t s);
 int32_t launch_gauss_step(const float* m, const float* sigma_k, const float* xi, int64_t n, float* out,
                           hipStream_t s);
+
+// frozen-target drafting of K steps from one noise estimate e [d]; out[k] = ||a_k - b_k||^2 (fp64)
+int32_t launch_frozen_draft(const float* x_a, const float* e, const float* coef_x, const float* coef_eps,
+                            const float* sigma, const float* xi, int32_t K, int64_t d, float* x_states, float* x_last,
+                            float* m_draft, hipStream_t s);
+int32_t launch_sqdist(const float* a, const float* b, int32_t K, int64_t d, double* out, hipStream_t s);
 
 // ---- MFMA adaLN modulation GEMV, bf16 weights (adaln_mfma.hip)
 bool adaln_mfma_supported(int32_t D, int32_t total_rows);

@@ -138,3 +138,20 @@ def test_drafter_argument_errors_are_status_codes(lib):
     assert lib.drafter_forward(None, one, one, one, one, 2, one, one, one, 4096, None) == binding.FREE_ERR_NULL
     assert lib.draft_round(None, one, one, one, 0, 4.0, one, one, one, one, 6, one, one, one, None, one, 4096,
                            None) == binding.FREE_ERR_NULL
+
+
+def test_lambda_profile_host_helper_matches_oracle(lib):
+    rng = np.random.default_rng(0)
+    for S, window in ((5, 1), (60, 1), (60, 9), (250, 21)):
+        v = (np.linspace(1, 4, S) + 0.4 * rng.standard_normal(S)).astype(np.float32)
+        v[rng.random(S) < 0.3] = np.nan
+        v[0] = 1.0
+        ref = fo.relaxation_profile_from_deltas(v.astype(np.float64), window)
+        got = binding.free_lambda_profile(v, window)
+        np.testing.assert_allclose(got, ref, rtol=2e-6)
+    out = np.empty(4, np.float32)
+    nan = np.full(4, np.nan, np.float32)
+    assert lib.free_lambda_profile(nan.ctypes.data, 4, 1, out.ctypes.data) == binding.FREE_ERR_RANGE
+    assert lib.free_lambda_profile(nan.ctypes.data, 4, 2, out.ctypes.data) == binding.FREE_ERR_SHAPE
+    assert lib.free_lambda_profile(None, 4, 1, out.ctypes.data) == binding.FREE_ERR_NULL
+    assert lib.free_self_speculative_workspace_bytes(None, 4, 4.0) == 0

@@ -189,3 +189,40 @@ def test_free_sample_loop(mode, cfg_scale, L):
         assert abs(log[0] - st_ref["n_accept"][0]) <= 1
     drafter.close()
     target.close()
+
+
+@pytest.mark.parametrize("cfg_scale,L", [(4.0, 4), (1.0, 6)])
+def test_self_speculative_run_and_profile(cfg_scale, L):
+    """The offline run of Sec. 3.4 on the GPU (frozen-target drafting) against the oracle: same outcomes,
+    same recorded deviations, same final sample; then the profile built from them on both sides."""
+    from paper_2511_20390_amd import binding
+    cfg = synth.dit_config("tiny")
+    w = synth.make_weights(cfg, seed=1, std=0.12)          # state-dependent enough for some rejections
+    target = binding.FreeDit(cfg, w, "fp32")
+    sched = fo.ddpm_schedule()
+    S = 16
+    tmap = np.linspace(960, 30, S).round().astype(np.int32)
+    cx, ce = fo.mean_coefficients(tmap, sched)
+    sigma = sched["sigma_clipped"][tmap].copy()
+    sigma[-1] = 0.0
+    rng = np.random.default_rng(21)
+    d = synth.latent_dim(cfg)
+    x0 = rng.standard_normal((cfg["in_ch"], cfg["lat_h"], cfg["lat_w"])).astype(np.float32)
+    xi = rng.standard_normal((S, d)).astype(np.float32)
+    u = rng.random(S).astype(np.float32)
+    f32 = lambda a: pu.to_dev(np.asarray(a, np.float32))
+    x_gpu, st, log, delta, acc = binding.free_self_speculative(target, pu.to_dev(x0), 3, cfg_scale, S - 1, L, pu.to_dev(tmap),
+                                                               f32(cx), f32(ce), f32(sigma), pu.to_dev(xi), pu.to_dev(u))
+    x_ref, st_ref, delta_ref, acc_ref = fo.self_speculative_run(w, cfg, x0, 3, cfg_scale, tmap, cx.astype(np.float32),
+                                                                ce.astype(np.float32), sigma.astype(np.float32), S - 1, L, xi, u)
+    print(f"scale {cfg_scale} L={L}: gpu {st} log {log}; oracle n_accept {st_ref['n_accept']}")
+    print("eps_delta gpu", np.round(delta, 4), "\\n          ref", np.round(delta_ref, 4))
+    assert log == st_ref["n_accept"] and np.array_equal(acc, acc_ref)
+    chk = ~np.isnan(delta_ref)
+    assert np.array_equal(np.isnan(delta), ~chk)
+    assert np.allclose(delta[chk], delta_ref[chk], rtol=2e-3, atol=1e-5)
+    assert pu.rel_l2(x_gpu.cpu().numpy(), x_ref) < 1e-4
+    lam_gpu = binding.free_lambda_profile(delta, 3)
+    lam_ref = fo.relaxation_profile_from_deltas(delta_ref, 3)
+    assert np.allclose(lam_gpu, lam_ref, rtol=5e-3)
+    target.close()
