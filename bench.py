@@ -237,6 +237,12 @@ def bench_verify(args, n_sets=6):
             "workload": "64 traj x 6 drafts x 16384 fp32, 6 rotating input sets (453 MB)"}
 
 
+def _nanmean0(a):
+    """Column means ignoring NaN; NaN where a column has no value."""
+    cnt = (~np.isnan(a)).sum(axis=0)
+    return np.where(cnt > 0, np.nansum(a, axis=0) / np.maximum(cnt, 1), np.nan)
+
+
 def bench_loop(args):
     """The whole sampler (Alg. 1) at the DiT-XL/2 512^2 shape: 250 respaced DDPM steps, guidance 4.0,
     6 drafts per round, two-block drafter, random-init target and drafter, strict and relaxed rule,
@@ -284,10 +290,42 @@ def bench_loop(args):
                "mean_accepted_per_round": tot["accepted"] / max(1, tot["rounds"])}
         return out
 
+    def run_self(lam):
+        """Frozen-target drafting (the target's latest noise estimate reused for the next L steps)."""
+        tot = dict(target_calls=0, rounds=0, accepted=0, drafter_steps=0)
+        t_wall, deltas = 0.0, []
+        for img in range(args.loop_images):
+            x0 = dev(rng.standard_normal((cfg["in_ch"], cfg["lat_h"], cfg["lat_w"]), dtype=np.float32))
+            xi = dev(rng.standard_normal((S, d), dtype=np.float32))
+            u = dev(rng.random(S, dtype=np.float32))
+            y = int(rng.integers(0, cfg["num_classes"]))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            _, st, _, delta, acc = binding.free_self_speculative(model, x0, y, scale, S - 1, L, a["tmap"], a["cx"], a["ce"],
+                                                                 a["sigma"], xi, u, lam)
+            t_wall += time.perf_counter() - t0
+            deltas.append(delta)
+            for k in tot:
+                tot[k] += st[k]
+        n = args.loop_images
+        return {"wall_s_per_image": t_wall / n, "target_calls_per_image": tot["target_calls"] / n,
+                "rounds_per_image": tot["rounds"] / n,
+                "mean_accepted_per_round": tot["accepted"] / max(1, tot["rounds"])}, _nanmean0(np.stack(deltas))
+
     run(0, None)                                      # warm-up (also sizes the workspaces)
     res["modes"]["sequential"] = run(0, None)
     res["modes"]["free"] = run(S - 1, None)
     res["modes"]["free_relax"] = run(S - 1, a["lam"])
+    # Sec. 3.4: offline self-speculative run -> deviation curve -> relaxation profile -> relaxed run with it
+    with np.errstate(all="ignore"):
+        res["modes"]["self_speculative"], delta = run_self(None)
+        lam_fit = binding.free_lambda_profile(delta, 9)
+        res["modes"]["self_speculative_relax"], _ = run_self(dev(lam_fit))
+    q = np.linspace(0, S - 1, 6).round().astype(int)
+    res["fitted_profile"] = {"steps": q.tolist(), "lambda": [float(lam_fit[i]) for i in q],
+                             "eps_delta_measured": [None if np.isnan(delta[i]) else float(delta[i]) for i in q]}
+    for k in ("self_speculative", "self_speculative_relax"):
+        res["modes"][k]["speedup_vs_sequential"] = res["modes"]["sequential"]["wall_s_per_image"] / res["modes"][k]["wall_s_per_image"]
     seq = res["modes"]["sequential"]["wall_s_per_image"]
     for k in ("free", "free_relax"):
         res["modes"][k]["speedup_vs_sequential"] = seq / res["modes"][k]["wall_s_per_image"]
