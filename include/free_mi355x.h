@@ -92,6 +92,19 @@ int32_t free_get_batch_streams(void);
 int32_t free_ddpm_schedule(int32_t T, double beta_start, double beta_end,
                            double* coef_x, double* coef_eps, double* sigma);
 
+/* The family of reverse processes with a stochasticity parameter e >= 0 (App. on the
+ * stochasticity hyperparameter, Eq. mean_var_gamma): one Euler step of
+ *   dY = [ -f(Y) + (1 + e^2)/2 g^2 s(Y) ] dt + e g dW
+ * for the variance-preserving diffusion behind the linear-beta schedule (f(x) = -beta x / 2,
+ * g^2 = beta, one step = one of the T discrete betas, score s = -eps / sqrt(1 - alphabar)):
+ *   coef_x[i]   = 1 + beta_i / 2
+ *   coef_eps[i] = -(1 + e^2)/2 * beta_i / sqrt(1 - alphabar_i)
+ *   sigma[i]    = e * sqrt(beta_i)
+ * e = 1 is the reverse SDE (the DDPM update to first order in beta), e = 0 the probability-flow
+ * ODE (sigma = 0: such steps cannot be speculated).  [host] arrays of T doubles; any may be NULL. */
+int32_t free_sde_schedule(int32_t T, double beta_start, double beta_end, double stochasticity,
+                          double* coef_x, double* coef_eps, double* sigma);
+
 /* Number of weight pointers free_dit_create expects: 7 + 10*depth + 4. */
 int32_t free_weight_count(const free_dit_config* cfg);
 

@@ -90,6 +90,17 @@ def ddpm_schedule(T: int = 1000, beta_start: float = 1e-4, beta_end: float = 0.0
                 beta_tilde=beta_tilde, sigma=sigma, sigma_clipped=sigma_clipped)
 
 
+def sde_coefficients(stochasticity: float, T: int = 1000, beta_start: float = 1e-4, beta_end: float = 0.02):
+    """One Euler step of the reverse family with stochasticity parameter e (Eq. mean_var_gamma) for the
+    variance-preserving diffusion of the linear-beta schedule: forward drift f(x) = -beta x / 2, g^2 = beta,
+    score s = -eps / sqrt(1 - alphabar).  m = x + [beta x / 2 + (1 + e^2)/2 beta s], sigma^2 = e^2 beta,
+    i.e. m = coef_x x + coef_eps eps.  Returns (coef_x, coef_eps, sigma), each [T]."""
+    beta = np.linspace(beta_start, beta_end, T, dtype=F64)
+    alphabar = np.cumprod(1.0 - beta)
+    e2 = float(stochasticity) ** 2
+    return 1.0 + 0.5 * beta, -0.5 * (1.0 + e2) * beta / np.sqrt(1.0 - alphabar), float(stochasticity) * np.sqrt(beta)
+
+
 def eps_to_mean(x: np.ndarray, eps: np.ndarray, i: int, sched: dict) -> np.ndarray:
     """Transition mean of Eq. (ddpm_update) without the noise term:
     m = (x - (1 - alpha_i) / sqrt(1 - alphabar_i) * eps) / sqrt(alpha_i)."""

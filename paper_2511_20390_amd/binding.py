@@ -22,7 +22,7 @@ MODES = {"fp32": FREE_FP32, "bf16": FREE_BF16}
 
 EXPORTED_SYMBOLS = [
     "free_version", "free_status_string", "free_last_hip_error", "free_set_batch_streams",
-    "free_get_batch_streams", "free_ddpm_schedule",
+    "free_get_batch_streams", "free_ddpm_schedule", "free_sde_schedule",
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
     "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
     "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
@@ -69,6 +69,8 @@ def load():
     lib.free_get_batch_streams.restype = i32
     lib.free_ddpm_schedule.restype = i32
     lib.free_ddpm_schedule.argtypes = [i32, C.c_double, C.c_double, vp, vp, vp]
+    lib.free_sde_schedule.restype = i32
+    lib.free_sde_schedule.argtypes = [i32, C.c_double, C.c_double, C.c_double, vp, vp, vp]
     lib.free_weight_count.restype = i32
     lib.free_weight_count.argtypes = [C.POINTER(FreeDitConfig)]
     lib.free_dit_create.restype = i32
@@ -147,6 +149,14 @@ def free_ddpm_schedule(T: int = 1000, beta_start: float = 1e-4, beta_end: float 
     cx, ce, sg = (np.empty(T, np.float64) for _ in range(3))
     _check(load().free_ddpm_schedule(T, beta_start, beta_end, cx.ctypes.data, ce.ctypes.data, sg.ctypes.data),
            "free_ddpm_schedule")
+    return cx, ce, sg
+
+
+def free_sde_schedule(stochasticity: float, T: int = 1000, beta_start: float = 1e-4, beta_end: float = 0.02):
+    """Host-only: (coef_x, coef_eps, sigma) of the reverse process with the given stochasticity parameter."""
+    cx, ce, sg = (np.empty(T, np.float64) for _ in range(3))
+    _check(load().free_sde_schedule(T, beta_start, beta_end, float(stochasticity), cx.ctypes.data, ce.ctypes.data,
+                                    sg.ctypes.data), "free_sde_schedule")
     return cx, ce, sg
 
 

@@ -403,6 +403,22 @@ int32_t free_ddpm_schedule(int32_t T, double beta_start, double beta_end, double
     return FREE_OK;
 }
 
+int32_t free_sde_schedule(int32_t T, double beta_start, double beta_end, double stochasticity, double* coef_x,
+                          double* coef_eps, double* sigma) {
+    if (T < 2) return FREE_ERR_SHAPE;
+    if (!(beta_start > 0.0) || !(beta_end >= beta_start) || !(beta_end < 1.0) || !(stochasticity >= 0.0))
+        return FREE_ERR_RANGE;
+    double abar = 1.0;
+    for (int i = 0; i < T; ++i) {
+        const double beta = beta_start + (beta_end - beta_start) * static_cast<double>(i) / (T - 1);
+        abar *= 1.0 - beta;
+        if (coef_x) coef_x[i] = 1.0 + 0.5 * beta;
+        if (coef_eps) coef_eps[i] = -0.5 * (1.0 + stochasticity * stochasticity) * beta / std::sqrt(1.0 - abar);
+        if (sigma) sigma[i] = stochasticity * std::sqrt(beta);
+    }
+    return FREE_OK;
+}
+
 int32_t free_weight_count(const free_dit_config* cfg) {
     Dims d;
     if (!make_dims(cfg, &d)) return FREE_ERR_SHAPE;

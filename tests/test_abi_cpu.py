@@ -155,3 +155,14 @@ def test_lambda_profile_host_helper_matches_oracle(lib):
     assert lib.free_lambda_profile(nan.ctypes.data, 4, 2, out.ctypes.data) == binding.FREE_ERR_SHAPE
     assert lib.free_lambda_profile(None, 4, 1, out.ctypes.data) == binding.FREE_ERR_NULL
     assert lib.free_self_speculative_workspace_bytes(None, 4, 4.0) == 0
+
+
+def test_sde_schedule_helper_matches_oracle(lib):
+    for e in (0.0, 0.7, 1.0, 2.5):
+        cx, ce, sg = binding.free_sde_schedule(e)
+        ocx, oce, osg = fo.sde_coefficients(e)
+        np.testing.assert_allclose(cx, ocx, rtol=1e-14)
+        np.testing.assert_allclose(ce, oce, rtol=1e-12)
+        np.testing.assert_allclose(sg, osg, rtol=1e-14, atol=0)
+    assert lib.free_sde_schedule(10, 1e-4, 0.02, -1.0, None, None, None) == binding.FREE_ERR_RANGE
+    assert lib.free_sde_schedule(1, 1e-4, 0.02, 1.0, None, None, None) == binding.FREE_ERR_SHAPE

@@ -226,3 +226,31 @@ def test_self_speculative_run_and_profile(cfg_scale, L):
     lam_ref = fo.relaxation_profile_from_deltas(delta_ref, 3)
     assert np.allclose(lam_gpu, lam_ref, rtol=5e-3)
     target.close()
+
+
+def test_free_sample_on_the_stochasticity_family():
+    """The sampler with the transition coefficients of the reverse family with stochasticity 1.5
+    (Eq. mean_var_gamma) instead of the DDPM posterior: coefficients are inputs, so this only has to agree
+    with the oracle's loop on the same numbers; the larger sigma widens the acceptance region."""
+    from paper_2511_20390_amd import binding
+    cfg, w, wd, target, drafter = _models("tiny", "fp32", 1, seed=6, out_gain=GAIN)
+    S, L, scale = 12, 4, 4.0
+    tmap = np.linspace(950, 40, S).round().astype(np.int32)
+    cx_all, ce_all, sg_all = binding.free_sde_schedule(1.5)
+    ocx, oce, osg = fo.sde_coefficients(1.5)
+    assert np.allclose(cx_all, ocx) and np.allclose(sg_all, osg)
+    cx, ce, sigma = cx_all[tmap], ce_all[tmap], sg_all[tmap].copy()
+    sigma[-1] = 0.0
+    rng = np.random.default_rng(31)
+    d = synth.latent_dim(cfg)
+    x0 = rng.standard_normal((cfg["in_ch"], cfg["lat_h"], cfg["lat_w"])).astype(np.float32)
+    xi, u = rng.standard_normal((S, d)).astype(np.float32), rng.random(S).astype(np.float32)
+    f32 = lambda a: pu.to_dev(np.asarray(a, np.float32))
+    x_gpu, st, log = binding.free_sample(drafter, pu.to_dev(x0), 1, scale, S - 1, L, pu.to_dev(tmap), f32(cx), f32(ce),
+                                         f32(sigma), pu.to_dev(xi), pu.to_dev(u))
+    x_ref, st_ref = fo.free_sample(wd, w, cfg, x0, 1, scale, tmap, cx.astype(np.float32), ce.astype(np.float32),
+                                   sigma.astype(np.float32), S - 1, L, xi, u)
+    print("stochasticity 1.5:", st, log)
+    assert log == st_ref["n_accept"] and pu.rel_l2(x_gpu.cpu().numpy(), x_ref) < 1e-4
+    drafter.close()
+    target.close()

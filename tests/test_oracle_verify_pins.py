@@ -276,3 +276,33 @@ def test_tie_flag_window():
         assert fo.verification(m_hat, m, sigma, x_hat, math.exp(l + 5e-5))[3]
         assert fo.verification(m_hat, m, sigma, x_hat, math.exp(l - 5e-5))[3]
         assert not fo.verification(m_hat, m, sigma, x_hat, math.exp(l - 1e-2))[3]
+
+
+def test_stochasticity_family_shares_the_marginals_on_gaussian_data():
+    """Eq. mean_var_gamma: for every stochasticity e the reverse process has the forward marginals.
+    For data N(0, s0^2) the exact noise estimate is linear, eps(x) = x sqrt(1 - ab) / v with
+    v = ab s0^2 + 1 - ab the marginal variance, so the variance recursion of the discrete chain is closed
+    form: starting from v_T it must end near s0^2 for e = 0, 0.5, 1, 2 (first-order discretisation).
+    A wrong (1 + e^2)/2 factor or sigma = e sqrt(beta) scaling misses s0^2 by far more."""
+    T, s0 = 1000, 0.5
+    beta = np.linspace(1e-4, 0.02, T)
+    ab = np.cumprod(1 - beta)
+    v_marg = ab * s0 ** 2 + 1 - ab
+    for e in (0.0, 0.5, 1.0, 2.0):
+        cx, ce, sg = fo.sde_coefficients(e, T)
+        var = v_marg[-1]
+        for i in range(T - 1, -1, -1):
+            gain = cx[i] + ce[i] * np.sqrt(1 - ab[i]) / v_marg[i]       # x -> m is linear: m = gain x
+            var = gain ** 2 * var + sg[i] ** 2
+        assert abs(var - s0 ** 2) < 0.03 * s0 ** 2, (e, var)
+    # the two factors matter: dropping (1 + e^2)/2 or the e in sigma breaks it
+    cx, ce, sg = fo.sde_coefficients(2.0, T)
+    var = v_marg[-1]
+    for i in range(T - 1, -1, -1):
+        var = (cx[i] + ce[i] / 2.5 * np.sqrt(1 - ab[i]) / v_marg[i]) ** 2 * var + sg[i] ** 2
+    assert abs(var - s0 ** 2) > 0.5 * s0 ** 2
+    # e = 1 is the DDPM update to first order in beta
+    s = fo.ddpm_schedule()
+    cx1, ce1, sg1 = fo.sde_coefficients(1.0, T)
+    dcx, dce = fo.mean_coefficients(np.arange(T), s)
+    assert np.max(np.abs(cx1 - dcx)) < 2e-4 and np.max(np.abs(ce1 / dce - 1)) < 0.011
