@@ -225,3 +225,50 @@ def test_batch_streams_same_result():
     with pytest.raises(binding.FreeError):
         binding.set_batch_streams(3)
     model.close()
+
+
+@pytest.mark.parametrize("name,mode,cfg_scale", [("small", "fp32", 4.0), ("xl2_512", "bf16", 4.0)])
+def test_spec_round_in_a_captured_graph(name, mode, cfg_scale):
+    """spec_round enqueues kernels only (no allocation, no memset, no host synchronisation), so a caller can
+    capture it in a HIP graph - including the fork onto the handle's two side streams at the large shape.
+    Several replays with fresh inputs, eager work in between, each compared with the eager call."""
+    import torch
+    from paper_2511_20390_amd import binding
+    K = 6
+    cfg = synth.dit_config(name)
+    w = pu.weights_for(cfg, mode, seed=0)
+    model = binding.FreeDit(cfg, w, mode)
+    cx, ce, sg = binding.free_ddpm_schedule()
+
+    def inputs(seed):
+        ri = synth.make_round_inputs(cfg, K, seed, sg, 0.1)
+        return ri, [pu.to_dev(ri["x_states"]), pu.to_dev(ri["x_last"]), pu.to_dev(ri["m_draft"]), pu.to_dev(ri["t"]),
+                    pu.to_dev(cx[ri["t"]].astype(np.float32)), pu.to_dev(ce[ri["t"]].astype(np.float32)),
+                    pu.to_dev(ri["sigma"]), pu.to_dev(ri["u"])]
+
+    def call(bufs, y, out=None):
+        return model.spec_round(bufs[0], bufs[1], bufs[2], bufs[3], y, cfg_scale, bufs[4], bufs[5], bufs[6], bufs[7],
+                                None, out=out)
+    ri0, static = inputs(100)
+    y = ri0["y"]
+    out_g = call(static, y)                       # warm-up: sizes the workspace, loads the kernels
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call(static, y, out=out_g)
+    torch.cuda.synchronize()
+    for seed in (101, 102, 103):
+        ri, fresh = inputs(seed)
+        ref = call(fresh, y)                      # eager, own output buffers
+        torch.cuda.synchronize()
+        for dst, src in zip(static, fresh):
+            dst.copy_(src)
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ("m_target", "log_ratio", "accept", "n_accept"):
+            assert torch.equal(out_g[k], ref[k]), f"replay with seed {seed}: {k} differs from the eager call"
+        if int(ref["n_accept"].item()) < K:
+            assert torch.equal(out_g["x_out"], ref["x_out"])
+    model.close()
