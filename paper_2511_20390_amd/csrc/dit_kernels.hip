@@ -13,6 +13,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kMaxFinalLds = 160 * 1024;          // LDS of one CU: the final projection matrix must fit
 
 __device__ inline float wave_sum_f(float v) {
 #pragma unroll
@@ -443,11 +444,11 @@ __global__ __launch_bounds__(kThreads) void final_layer_kernel(
     }
 }
 
-// Same operation with the token row read once: the normalised, modulated row stays in
+// One wavefront per token row, read once: the normalised, modulated row stays in
 // registers (NV float4 per lane) and every output column is a dot product of registers
 // with a weight row streamed from cache.  Needs D % 4 == 0, D <= 256 NV, 16-byte rows.
 template <typename WT, int NV>
-__global__ __launch_bounds__(kThreads) void final_layer_vec_kernel(
+__global__ __launch_bounds__(kThreads) void final_layer_row_kernel(
     const float* __restrict__ x, RowVec shift, RowVec scale, int32_t M, int32_t gh, int32_t gw, int32_t p,
     int32_t c_out, int32_t D, const WT* __restrict__ w, const float* __restrict__ bias,
     float* __restrict__ out) {
@@ -523,6 +524,132 @@ __global__ __launch_bounds__(kThreads) void final_layer_vec_kernel(
             const int c = o % c_out, pq = (o / c_out) % p, ph = o / (c_out * p);
             out[((static_cast<int64_t>(b) * c_out + c) * H + gi * p + ph) * Wd + gj * p + pq] = acc + bias[o];
         }
+    }
+}
+
+// Few rows (e.g. the drafter's two samples): weights staged in LDS, all P dot products kept per lane.
+// Same operation with the token row read once: the normalised, modulated row stays in
+// registers (NV float4 per lane) and every output column is a dot product of registers
+// with a weight row streamed from cache.  Needs D % 4 == 0, D <= 256 NV, 16-byte rows.
+// The P <= 32 partial dot products of a lane are reduced over the wavefront together: five
+// halving exchanges (lane ^ 32, 16, 8, 4, 2: each lane keeps half of its values and adds the
+// partner's other half) leave one output per lane pair, one more exchange completes it - 32
+// cross-lane operations in independent groups instead of six dependent ones per output.
+template <typename WT, int NV, bool kStage>
+__global__ __launch_bounds__(kThreads) void final_layer_vec_kernel(
+    const float* __restrict__ x, RowVec shift, RowVec scale, int32_t M, int32_t gh, int32_t gw, int32_t p,
+    int32_t c_out, int32_t D, const WT* __restrict__ w, const float* __restrict__ bias,
+    float* __restrict__ out) {
+    // kStage (few rows, e.g. the drafter's two samples): the projection matrix (P x D, 74 KB in bf16 at
+    // DiT-XL/2) is staged in LDS once per workgroup and every wavefront walks token rows with a grid
+    // stride; read per row from L2 it costs P D bytes of cache traffic per token and that dominates when
+    // there are too few wavefronts to hide it.  With many rows one wavefront per row and weights
+    // from cache is faster (more wavefronts in flight).
+    extern __shared__ __attribute__((aligned(16))) char lds_w_raw[];
+    const WT* lw = kStage ? reinterpret_cast<const WT*>(lds_w_raw) : w;
+    if (kStage) {
+        const int n16 = (p * p * c_out * D * static_cast<int>(sizeof(WT))) / 16;
+        const uint4* src = reinterpret_cast<const uint4*>(w);
+        uint4* dst = reinterpret_cast<uint4*>(lds_w_raw);
+        for (int i = threadIdx.x; i < n16; i += kThreads) dst[i] = src[i];
+    }
+    if (kStage) __syncthreads();
+    const int lane = threadIdx.x & 63;
+    for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6); row < M;
+         row += static_cast<int64_t>(gridDim.x) * kWaves) {
+    const int nvec = D >> 2;
+    const float4* xr = reinterpret_cast<const float4*>(x + row * D);
+    float4 xv[NV];
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = lane + 64 * k;
+        xv[k] = (v < nvec) ? xr[v] : make_float4(0.f, 0.f, 0.f, 0.f);
+        s += (xv[k].x + xv[k].y) + (xv[k].z + xv[k].w);
+    }
+    const float mean = wave_sum_f(s) / static_cast<float>(D);
+    float q = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        if (lane + 64 * k < nvec) {
+            const float a = xv[k].x - mean, b = xv[k].y - mean, c = xv[k].z - mean, d = xv[k].w - mean;
+            q += (a * a + b * b) + (c * c + d * d);
+        }
+    }
+    const float rstd = rsqrtf(wave_sum_f(q) / static_cast<float>(D) + kLnEps);
+    const float4* sh = reinterpret_cast<const float4*>(shift.base + (row / shift.rows_per_sample) * shift.stride);
+    const float4* sc = reinterpret_cast<const float4*>(scale.base + (row / scale.rows_per_sample) * scale.stride);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = lane + 64 * k;
+        if (v < nvec) {
+            const float4 h = sh[v], c = sc[v];
+            xv[k].x = fmaf((xv[k].x - mean) * rstd, 1.0f + c.x, h.x);
+            xv[k].y = fmaf((xv[k].y - mean) * rstd, 1.0f + c.y, h.y);
+            xv[k].z = fmaf((xv[k].z - mean) * rstd, 1.0f + c.z, h.z);
+            xv[k].w = fmaf((xv[k].w - mean) * rstd, 1.0f + c.w, h.w);
+        } else {
+            xv[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    const int ntok = gh * gw;
+    const int b = static_cast<int>(row / ntok), n = static_cast<int>(row % ntok);
+    const int gi = n / gw, gj = n % gw;
+    const int P = p * p * c_out;
+    const int H = gh * p, Wd = gw * p;
+    for (int o0 = 0; o0 < P; o0 += 32) {
+        float acc[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            acc[j] = 0.f;
+            if (o0 + j < P) {
+                const WT* wr = lw + static_cast<int64_t>(o0 + j) * D;
+#pragma unroll
+                for (int k = 0; k < NV; ++k) {
+                    const int v = lane + 64 * k;
+                    if (v < nvec) {
+                        float w0, w1, w2, w3;
+                        if constexpr (sizeof(WT) == 2) {
+                            const uint2 pk = reinterpret_cast<const uint2*>(wr)[v];
+                            w0 = __uint_as_float(pk.x << 16);
+                            w1 = __uint_as_float(pk.x & 0xffff0000u);
+                            w2 = __uint_as_float(pk.y << 16);
+                            w3 = __uint_as_float(pk.y & 0xffff0000u);
+                        } else {
+                            const float4 f = reinterpret_cast<const float4*>(wr)[v];
+                            w0 = f.x; w1 = f.y; w2 = f.z; w3 = f.w;
+                        }
+                        acc[j] = fmaf(xv[k].x, w0, acc[j]);
+                        acc[j] = fmaf(xv[k].y, w1, acc[j]);
+                        acc[j] = fmaf(xv[k].z, w2, acc[j]);
+                        acc[j] = fmaf(xv[k].w, w3, acc[j]);
+                    }
+                }
+            }
+        }
+        // halving exchanges: after the step with offset 32 >> t a lane holds 16 >> t values
+#pragma unroll
+        for (int t = 0; t < 5; ++t) {
+            const int off = 32 >> t, half = 16 >> t;
+            const bool upper = (lane & off) != 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if (j < half) {
+                    const float send = upper ? acc[j] : acc[j + half];
+                    const float keep = upper ? acc[j + half] : acc[j];
+                    acc[j] = keep + __shfl_xor(send, off, 64);
+                }
+            }
+        }
+        const float total = acc[0] + __shfl_xor(acc[0], 1, 64);
+        // the value a lane ends with: bit 5 of the lane chose the upper 16 outputs, bit 4 the upper 8 of those, ...
+        const int o = o0 + ((lane >> 5) & 1) * 16 + ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 +
+                      ((lane >> 1) & 1);
+        if ((lane & 1) == 0 && o < P) {
+            const int c = o % c_out, pq = (o / c_out) % p, ph = o / (c_out * p);
+            out[((static_cast<int64_t>(b) * c_out + c) * H + gi * p + ph) * Wd + gj * p + pq] = total + bias[o];
+        }
+    }
     }
 }
 
@@ -708,13 +835,48 @@ int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B
     const int M = B * gh * gw;
     const int blocks = (M + kWaves - 1) / kWaves;
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-    const bool vec = (D % 4 == 0) && D <= 2048 && al16(x) && al16(w) && al16(shift.base) && al16(scale.base) &&
+    bool vec = (D % 4 == 0) && D <= 2048 && al16(x) && al16(w) && al16(shift.base) && al16(scale.base) &&
                      (shift.stride % 4 == 0) && (scale.stride % 4 == 0);
+    const size_t lds_bytes = static_cast<size_t>(p) * p * c_out * D * (dtype == FREE_BF16 ? 2 : 4);
     if (vec) {
         const int nv = (D / 4 + 63) / 64;
-#define FREE_FIN_CASE(WT, NV)                                                                                  \
-    hipLaunchKernelGGL((final_layer_vec_kernel<WT, NV>), dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, gh, \
+        // few rows: stage the weights in LDS, as many workgroups as fit on the chip at once (LDS-limited),
+        // each walking rows with a grid stride; many rows: one wavefront per row
+        const bool stage = M <= 4096 && lds_bytes <= static_cast<size_t>(kMaxFinalLds) && lds_bytes % 16 == 0;
+        const int per_cu = lds_bytes * 2 <= static_cast<size_t>(kMaxFinalLds) ? 2 : 1;
+        const int vblocks = blocks < 256 * per_cu ? blocks : 256 * per_cu;
+#define FREE_ROW_CASE(WT, NV)                                                                                  \
+    hipLaunchKernelGGL((final_layer_row_kernel<WT, NV>), dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, gh, \
                        gw, p, c_out, D, static_cast<const WT*>(w), bias, out)
+        if (!stage) {
+            if (dtype == FREE_BF16) {
+                if (nv <= 1) FREE_ROW_CASE(bf16_t, 1);
+                else if (nv <= 2) FREE_ROW_CASE(bf16_t, 2);
+                else if (nv <= 5) FREE_ROW_CASE(bf16_t, 5);
+                else FREE_ROW_CASE(bf16_t, 8);
+            } else {
+                if (nv <= 1) FREE_ROW_CASE(float, 1);
+                else if (nv <= 2) FREE_ROW_CASE(float, 2);
+                else if (nv <= 5) FREE_ROW_CASE(float, 5);
+                else FREE_ROW_CASE(float, 8);
+            }
+            return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+        }
+#undef FREE_ROW_CASE
+#define FREE_FIN_CASE(WT, NV)                                                                                  \
+    do {                                                                                                       \
+        auto kern = final_layer_vec_kernel<WT, NV, true>;                                                      \
+        static bool attr_set = false;                                                                          \
+        if (stage && !attr_set) {                                                                              \
+            if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                               \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxFinalLds)))        \
+                return FREE_ERR_HIP;                                                                           \
+            attr_set = true;                                                                                   \
+        }                                                                                                      \
+        hipLaunchKernelGGL(kern, dim3(vblocks), dim3(kThreads), stage ? lds_bytes : 0, s, x, shift, scale, M,  \
+                           gh, gw, p,                                                                          \
+                           c_out, D, static_cast<const WT*>(w), bias, out);                                    \
+    } while (0)
         if (dtype == FREE_BF16) {
             if (nv <= 1) FREE_FIN_CASE(bf16_t, 1);
             else if (nv <= 2) FREE_FIN_CASE(bf16_t, 2);
