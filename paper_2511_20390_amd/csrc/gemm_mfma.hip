@@ -449,6 +449,19 @@ double cfg_time(int M, int N, int K, int bm, int bn, double us_per_slice, double
     return rounds * (((K + BK - 1) / BK) * us_per_slice + us_fixed);
 }
 
+// The 128x128 configuration is small enough for two workgroups per CU: measured 0.6 us per slice for a
+// workgroup that has its CU to itself and 1.05 us each for two that share one.  Used for problems of
+// few rows (the drafter, single-state steps), where it decides between half-empty rounds of large
+// tiles and fuller rounds of small ones.
+double small_tile_time(int M, int N, int K, int cus) {
+    const double tiles = static_cast<double>((M + 127) / 128) * ((N + 127) / 128);
+    const int nk = (K + BK - 1) / BK;
+    const double shared = nk * 1.05 + 4.0, alone = nk * 0.6 + 4.0;
+    const double full = std::floor(tiles / (2.0 * cus));
+    const double rest = tiles - full * 2.0 * cus;
+    return full * shared + (rest == 0.0 ? 0.0 : (rest <= cus ? alone : shared));
+}
+
 int device_cus() {
     static int cus = [] {
         int dev = 0, n = 0;
@@ -475,7 +488,7 @@ int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, 
     const double t256 = cfg_time(M, N, K, 256, 256, 1.83, 9.0, cus);
     const double t384 = cfg_time(M, N, K, 384, 192, 2.06, 10.0, cus);
     const double t2x1 = cfg_time(M, N, K, 256, 128, 1.31, 6.0, cus);
-    const double t128 = cfg_time(M, N, K, 128, 128, 0.80, 4.0, cus);
+    const double t128 = M <= 4096 ? small_tile_time(M, N, K, cus) : cfg_time(M, N, K, 128, 128, 0.80, 4.0, cus);
     const double best = std::fmin(std::fmin(t256, t384), std::fmin(t2x1, t128));
     if (best == t384) return launch_cfg<384, 192, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
     if (best == t256) return launch_cfg<256, 256, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
