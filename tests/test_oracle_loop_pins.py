@@ -53,11 +53,13 @@ def test_every_step_is_taken_exactly_once_whatever_is_rejected():
         return b * np.asarray(x), 0.0
     x, st = fo.speculative_loop(np.array([2.0]), S, S - 1, L, sigma, rng.standard_normal((S, 1)), rng.random(S), None, tm, dm)
     assert st["target_calls"] == len(tm_calls) and 0 < st["accepted"] < st["drafter_steps"]
-    covered = 0
-    for (i0, k), n in zip(tm_calls[1:1 + st["rounds"]], st["n_accept"]):
-        assert i0 == 1 + covered
-        covered += k if n == k else n + 1
-    assert 1 + covered + 1 == S or tm_calls[-1][0] == S - 1
+    # call 0 is the plain step at i = 0, then the rounds, then the plain noise-free step at i = S - 1
+    assert tm_calls[0] == (0, 1) and tm_calls[-1] == (S - 1, 1) and len(tm_calls) == st["rounds"] + 2
+    pos = 1
+    for (i0, k), n in zip(tm_calls[1:-1], st["n_accept"]):
+        assert i0 == pos and k == min(L, S - 1 - pos) and 0 <= n <= k
+        pos += k if n == k else n + 1
+    assert pos == S - 1
 
 
 def test_loop_preserves_the_target_distribution_on_a_linear_gaussian_chain():
