@@ -223,6 +223,18 @@ def bench_verify(args, n_sets=6):
     for r in range(reps * n_sets):
         binding.spec_verify(*sets[0], out=out, workspace=ws)
     warm = binding.profile_end()
+    # the same kernel on a problem large enough to leave the launch ramp behind: 384 trajectories (453 MB)
+    nl = 384
+    vl = synth.make_verify_inputs(nl, K, d, 0.01, 200, sg)
+    big = [torch.from_numpy(vl[k]).to("cuda:0") for k in ("m_target", "m_draft", "x_draft", "sigma", "u")]
+    out_l = binding.spec_verify(*big)
+    ws_l = torch.empty(binding.spec_verify_workspace_bytes(nl, K, d), dtype=torch.uint8, device="cuda:0")
+    binding.profile_begin()
+    for r in range(8):
+        binding.spec_verify(*big, out=out_l, workspace=ws_l)
+    lprof = binding.profile_end()
+    large_gbs = nl * K * 3 * d * 4 / (lprof["verify_partial"][0] / lprof["verify_partial"][1] * 1e-3) / 1e9
+    del big, out_l, ws_l
     ms, n = prof["verify_partial"]
     bytes_partial = n_traj * K * 3 * d * 4
     gbs = bytes_partial / (ms / n * 1e-3) / 1e9
@@ -231,6 +243,7 @@ def bench_verify(args, n_sets=6):
     return {"kernel": "verify_partial_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic("verify_partial"), "avg_launch_us": ms * 1e3 / n,
             "warm_cache_GBs": bytes_partial / (wms / wn * 1e-3) / 1e9,
+            "GBs_at_384_trajectories_453MB": large_gbs,
             "finish_avg_us": prof["verify_finish"][0] * 1e3 / prof["verify_finish"][1],
             "call_us_back_to_back": call_us, "rounds_per_s_64traj": 64e6 / call_us,
             "algorithmic_bytes": bytes_partial, "reflected_rows": nrej,
