@@ -141,7 +141,12 @@ size_t free_workspace_bytes(const free_dit_config* cfg, int32_t B);
  *   eps_out  [B, c_out, H, W] fp32, c_out = 2C with learn_sigma: channels
  *            [0, C) are the noise prediction, [C, 2C) the unused variance.
  *   top_feat [B, N, hidden] fp32 or NULL: output of the last block (the
- *            feature f of Alg. 1). */
+ *            feature f of Alg. 1).
+ * Enqueues on `stream` and returns; results are ordered after the call on that
+ * stream.  A handle owns two internal side streams (see free_set_batch_streams),
+ * so two calls on the SAME handle must not be in flight from different streams at
+ * the same time; calls on different handles are independent.  The call allocates
+ * nothing and can be captured in a HIP graph. */
 int32_t dit_forward_packed(free_dit_t h, const float* x, const int32_t* t, const int32_t* y,
                            int32_t B, float* eps_out, float* top_feat,
                            void* workspace, size_t ws_bytes, void* stream);
