@@ -63,8 +63,14 @@ constexpr int kNumXcd = 8;
 
 __device__ inline float gelu_fast(float v) {
     // tanh-form GELU: 0.5 v (1 + tanh(u)) = v / (1 + exp(-2u)), u = sqrt(2/pi)(v + 0.044715 v^3)
-    const float u = 0.7978845608028654f * (v + 0.044715f * v * v * v);
-    return v * __frcp_rn(1.0f + __expf(-2.0f * u));
+    // exp(-2u) = 2^(v (a + b v^2)) with the constants folded; v_exp_f32 and v_rcp_f32 directly (1 ulp each,
+    // far below the bf16 rounding of the result).  The correctly rounded reciprocal is a ten-instruction
+    // division sequence per element, and this runs on every element of the MLP's hidden layer while the
+    // matrix cores wait.  2^t overflows to +inf for very negative v: 1 / inf = 0, the right limit.
+    constexpr float a = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
+    constexpr float b = a * 0.044715f;
+    const float t = v * fmaf(v * v, b, a);
+    return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
 __device__ inline uint32_t pack2(float lo, float hi) {
