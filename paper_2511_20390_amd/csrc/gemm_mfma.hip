@@ -12,14 +12,14 @@
 //    the accumulators in registers for the whole K loop.
 //  * the MFMA takes the WEIGHT rows as its A operand and the activation rows as its
 //    B operand, i.e. it accumulates C^T tiles: a lane then owns one output ROW m
-//    (lane % 32) and runs of 4 consecutive output columns n per register group.  The
-//    fp32 residual update is a float4 read-modify-write with all loads of a column tile
-//    issued before its first store.  For bf16 output one v_permlane32_swap pairs the two
-//    half-waves' runs into 8 consecutive bf16, and each 32-row block is transposed through a
-//    wave-private piece of the (by then idle) LDS tiles so that the global stores cover
-//    whole rows of the wave's tile with consecutive lanes - a row otherwise lives in two
-//    lanes, 32 bytes per row and instruction, and such partial-line writes cost up to 1.8x
-//    the algorithmic write traffic at the memory controller.
+//    (lane % 32) and runs of 4 consecutive output columns n per register group.  Each
+//    32-row block of output is transposed through a wave-private piece of the (by then idle)
+//    LDS tiles so that global accesses cover whole rows of the wave's tile with consecutive
+//    lanes - a row otherwise lives in two lanes, 32 bytes per row and instruction, and such
+//    partial-line writes cost up to 1.8x the algorithmic write traffic at the memory
+//    controller.  For bf16 output one v_permlane32_swap first pairs the two half-waves' runs
+//    into 8 consecutive bf16; the fp32 residual update is a float4 read-modify-write on the
+//    transposed block with all loads of a group issued before its first store.
 //  * LDS: two stages of [BM + BN rows][64 bf16]; the 16-byte chunk index of a row is
 //    XOR-swizzled with (row / 2) % 8: a ds_read_b128 is served 16 lanes at a time over 64
 //    banks (256 bytes), and with this pattern the 16 rows of a pass hit 16 distinct 16-byte
@@ -115,7 +115,9 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
 
 // Epilogue shared by the GEMM kernels.  Register e of acc[i][j] in lane l is output row
 // m = gm_lane + 32 i (gm_lane already includes l % 32), column n = gn_wave + 32 j + 8 (e/4) + 4 lhi + e%4.
-template <int TM, int TN, int EPI>
+// QB: for the residual update, chunks per lane whose loads are in flight together in the LDS-staged form; 0
+// selects the direct form.
+template <int TM, int TN, int EPI, int QB>
 __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm_lane, int gn_wave, int lane, int32_t M,
                                            int32_t N, int32_t vec_ok, const float* __restrict__ bias,
                                            bf16_t* __restrict__ out, float* __restrict__ resid, const RowVec& gate,
@@ -124,9 +126,11 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
     if (vec_ok) {
         // N % 8 == 0 and 16-byte aligned rows: runs of 4 / 8 columns are all inside or all outside.
         // Rows past M and runs past N (ragged edge tiles) are masked per lane.
-        if (EPI == FREE_EPI_GATE_RESID) {
-            // read-modify-write of the fp32 residual stream.  All loads of a column tile j are
-            // issued before its first store (a store would otherwise fence the following loads).
+        if constexpr (EPI == FREE_EPI_GATE_RESID && QB == 0) {
+            // read-modify-write of the fp32 residual stream straight from the accumulator layout (32 rows x
+            // 32 bytes per instruction).  All loads of a column tile j are issued before its first store (a
+            // store would otherwise fence the following loads).  Faster than the staged form below for the
+            // four-wavefront configurations: with one wavefront per SIMD the LDS round trip is not hidden.
             const float* __restrict__ gbase = gate.base;
             int64_t g_off[TM], r_off[TM];
             bool row_ok[TM];
@@ -162,6 +166,69 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                                 r[i][e4][c] = fmaf(g[i][e4][c], acc[i][j][4 * e4 + c] + bv[e4][c], r[i][e4][c]);
                             *reinterpret_cast<f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4) = r[i][e4];
                         }
+            }
+        } else if constexpr (EPI == FREE_EPI_GATE_RESID) {
+            // read-modify-write of the fp32 residual stream.  As for the bf16 output below, the accumulator
+            // layout would touch 32 rows x 32 bytes per instruction; each 32-row block is staged in the
+            // wave-private LDS region CG column tiles at a time (rows padded by 16 bytes) and read back
+            // row-major, so that the loads and stores of the residual cover whole 128-byte lines.
+            constexpr int CG = (TN % 2 == 0) ? 2 : 1;          // column tiles per staged group (rows of 256 / 128 bytes)
+            constexpr int CH = CG * 8;                         // 16-byte chunks (4 floats) per staged row
+            constexpr int kStageRow = (CH + 1) * 16;
+            constexpr int NQ = 32 * CH / 64;                   // chunks per lane per group
+            const int l32 = lane & 31;
+            const float* __restrict__ gbase = gate.base;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int gm_blk = gm_lane - l32 + i * 32;     // first row of the block (wave-uniform)
+                // one sample for the whole block (the usual case: rows per sample a multiple of 32)?
+                const int s_first = gm_blk / gate.rows_per_sample;
+                const bool one_sample = (gm_blk + 31) / gate.rows_per_sample == s_first;
+#pragma unroll
+                for (int jg = 0; jg < TN; jg += CG) {
+#pragma unroll
+                    for (int jj = 0; jj < CG; ++jj)
+#pragma unroll
+                        for (int e4 = 0; e4 < 4; ++e4) {
+                            const f32x4_t v = {acc[i][jg + jj][4 * e4], acc[i][jg + jj][4 * e4 + 1],
+                                               acc[i][jg + jj][4 * e4 + 2], acc[i][jg + jj][4 * e4 + 3]};
+                            // columns jj*32 + 8 e4 + 4 lhi .. +3 -> chunk 8 jj + 2 e4 + lhi
+                            *reinterpret_cast<f32x4_t*>(wave_lds + l32 * kStageRow + ((8 * jj + 2 * e4 + lhi) << 4)) = v;
+                        }
+                    // batches of 4 chunks per lane: all loads of a batch before its first store, and few
+                    // enough registers beside the accumulators
+                    constexpr int QN = QB < NQ ? QB : NQ;
+                    static_assert(NQ % QN == 0, "whole batches");
+#pragma unroll
+                    for (int q0 = 0; q0 < NQ; q0 += QN) {
+                        f32x4_t r[QN], g[QN], bv[QN];
+                        int64_t off[QN];
+                        bool ok[QN];
+#pragma unroll
+                        for (int q = 0; q < QN; ++q) {
+                            const int f = (q0 + q) * 64 + lane;
+                            const int row = f / CH, ch = f % CH;
+                            const int gm = gm_blk + row, gn = gn_wave + jg * 32 + ch * 4;
+                            ok[q] = gm < M && gn < N;
+                            off[q] = static_cast<int64_t>(gm) * N + gn;
+                            if (ok[q]) {
+                                const int smp = one_sample ? s_first : gm / gate.rows_per_sample;
+                                r[q] = *reinterpret_cast<const f32x4_t*>(resid + off[q]);
+                                g[q] = *reinterpret_cast<const f32x4_t*>(gbase + static_cast<int64_t>(smp) * gate.stride + gn);
+                                bv[q] = *reinterpret_cast<const f32x4_t*>(bias + gn);
+                            }
+                        }
+#pragma unroll
+                        for (int q = 0; q < QN; ++q)
+                            if (ok[q]) {
+                                const int f = (q0 + q) * 64 + lane;
+                                const f32x4_t v = *reinterpret_cast<const f32x4_t*>(wave_lds + (f / CH) * kStageRow + ((f % CH) << 4));
+#pragma unroll
+                                for (int c = 0; c < 4; ++c) r[q][c] = fmaf(g[q][c], v[c] + bv[q][c], r[q][c]);
+                                *reinterpret_cast<f32x4_t*>(resid + off[q]) = r[q];
+                            }
+                    }
+                }
             }
         } else {
             // bf16 output.  In the accumulator layout a row lives in two lanes only, so a direct store
@@ -402,9 +469,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
 
     // ---- epilogue
     // after the barrier of the last slice no wavefront reads the LDS tiles any more: each wavefront
-    // may use a private 32 x (TN*64 + 16)-byte region of them to transpose its bf16 output
-    write_tile<TM, TN, EPI>(acc, m0 + wm * TM * 32 + l32, n0 + wn * TN * 32, lane, M, N, vec_ok, bias, out, resid, gate,
-                            lds + wave * (32 * (TN * 64 + 16)));
+    // may use a private region of them to transpose its output
+    constexpr int kWaveStage = EPI == FREE_EPI_GATE_RESID ? 32 * (((TN % 2 == 0 ? 2 : 1) * 8 + 1) * 16)   // fp32 groups
+                                                          : 32 * (TN * 64 + 16);                            // bf16 rows
+    static_assert(WGM * WGN * kWaveStage <= 2 * kStageBytes, "output staging must fit in the K-loop tiles");
+    constexpr int kResidBatch = (WGM * WGN == 8) ? 4 : 0;
+    write_tile<TM, TN, EPI, kResidBatch>(acc, m0 + wm * TM * 32 + l32, n0 + wn * TN * 32, lane, M, N, vec_ok, bias, out, resid, gate,
+                            lds + wave * kWaveStage);
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
