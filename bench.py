@@ -132,6 +132,13 @@ def bench_round(args):
                 "avg_launch_us": kernels[dom]["avg_us"],
                 "measured": "HIP events around every launch of this kernel, same steps repeated right after the "
                             "timed region with all kernels in sequence on one stream"}
+    if mode == "bf16" and not args.no_mfma_calibration:
+        # what a register-only MFMA loop sustains on this device right now, and at which shader clock: the
+        # published peak assumes the 2.4 GHz peak clock, which a chip under matrix load does not hold
+        cal = binding.mfma_ceiling(200000)
+        roofline["mfma_calibration"] = {"register_only_loop_tflops": cal["tflops"],
+                                        "shader_clock_mhz": cal["shader_clock_mhz"],
+                                        "frac_of_calibrated": kernels[dom]["tflops"] / cal["tflops"]}
     fwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if not k.startswith("verify") and k != "eps_to_mean")
     res = {
         "ms_per_step": ms_per_step, "ms_per_step_one_stream": ms_one_stream,
@@ -393,6 +400,8 @@ def main():
                          "that kernel durations are not inflated by overlap)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify-bench", action="store_true")
+    ap.add_argument("--no-mfma-calibration", action="store_true",
+                    help="skip the register-only MFMA loop that reports the device's sustained matrix rate and clock")
     ap.add_argument("--no-draft-bench", action="store_true")
     ap.add_argument("--loop", action="store_true", help="time the whole sampler (Alg. 1) instead of the verification round")
     ap.add_argument("--loop-steps", type=int, default=250)

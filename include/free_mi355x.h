@@ -310,6 +310,16 @@ int32_t free_profile_begin(void);
 int32_t free_profile_end(float* ms, int32_t* launches);
 const char* free_profile_category_name(int32_t category);
 
+/* Matrix-core calibration for the "mfma" roofline of the benchmark: runs a
+ * register-only loop of `iters` x 4 v_mfma_f32_32x32x16_bf16 per wavefront on
+ * every compute unit (8 wavefronts each, no memory traffic), once untimed and
+ * once timed with HIP events on `stream`, and returns [host] the sustained
+ * TFLOP/s and the shader clock in MHz observed meanwhile (shader cycles over
+ * the constant-rate wall clock, mean over workgroups).  Blocking; allocates
+ * and frees two small device buffers.  iters in [1, 2^24]; about 75 ns per
+ * iteration.  FREE_ERR_NULL / FREE_ERR_RANGE / FREE_ERR_HIP on failure. */
+int32_t free_mfma_ceiling(int32_t iters, double* tflops, double* mhz, void* stream);
+
 /* ---- single DiT operators, exported for per-kernel parity tests -----------
  * (the pieces of the adaLN-Zero block that dit_forward_packed chains).
  * dtype = FREE_FP32 (A, W, out fp32) or FREE_BF16 (A, W, out bf16). */

@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = [
     "drafter_forward", "draft_round", "free_sample_workspace_bytes", "free_sample",
     "free_self_speculative_workspace_bytes", "free_self_speculative", "free_lambda_profile",
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
-    "free_profile_begin", "free_profile_end", "free_profile_category_name",
+    "free_profile_begin", "free_profile_end", "free_profile_category_name", "free_mfma_ceiling",
 ]
 PROF_NCAT = 13
 
@@ -118,6 +118,8 @@ def load():
     lib.free_profile_begin.restype = i32
     lib.free_profile_end.restype = i32
     lib.free_profile_end.argtypes = [vp, vp]
+    lib.free_mfma_ceiling.restype = i32
+    lib.free_mfma_ceiling.argtypes = [i32, vp, vp, vp]
     lib.free_profile_category_name.restype = C.c_char_p
     lib.free_profile_category_name.argtypes = [i32]
     _lib = lib
@@ -179,6 +181,15 @@ def profile_end() -> dict:
     cnt = np.zeros(PROF_NCAT, np.int32)
     _check(load().free_profile_end(ms.ctypes.data, cnt.ctypes.data), "free_profile_end")
     return {load().free_profile_category_name(c).decode(): (float(ms[c]), int(cnt[c])) for c in range(PROF_NCAT)}
+
+
+def mfma_ceiling(iters: int = 200000) -> dict:
+    """Sustained TFLOP/s of a register-only bf16 MFMA loop on every CU and the shader clock meanwhile."""
+    import torch
+    tf, mhz = C.c_double(0.0), C.c_double(0.0)
+    _check(load().free_mfma_ceiling(int(iters), C.addressof(tf), C.addressof(mhz), _stream()),
+           "free_mfma_ceiling")
+    return {"tflops": tf.value, "shader_clock_mhz": mhz.value}
 
 
 def spec_verify_workspace_bytes(n_traj: int, K: int, d: int) -> int:

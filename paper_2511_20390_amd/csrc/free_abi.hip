@@ -376,6 +376,12 @@ int32_t free_profile_end(float* ms, int32_t* launches) {
     return FREE_OK;
 }
 
+int32_t free_mfma_ceiling(int32_t iters, double* tflops, double* mhz, void* stream) {
+    if (!tflops || !mhz) return FREE_ERR_NULL;
+    if (iters < 1 || iters > (1 << 24)) return FREE_ERR_RANGE;
+    return run_mfma_ceiling(iters, tflops, mhz, static_cast<hipStream_t>(stream));
+}
+
 const char* free_profile_category_name(int32_t c) {
     static const char* names[FREE_PROF_NCAT] = {"conditioning", "adaln", "patch_embed", "ln_modulate", "gemm_qkv",
                                                 "attention", "gemm_proj", "gemm_fc1", "gemm_fc2", "final_layer",

@@ -74,6 +74,10 @@ def test_weight_count_and_workspace(lib):
 
 def test_argument_errors_are_status_codes(lib):
     one = C.c_void_p(256)            # never dereferenced: the checks fail first
+    # calibration loop: null outputs and iteration counts outside [1, 2^24] fail before any device call
+    assert lib.free_mfma_ceiling(1000, None, one, None) == binding.FREE_ERR_NULL
+    assert lib.free_mfma_ceiling(0, one, one, None) == binding.FREE_ERR_RANGE
+    assert lib.free_mfma_ceiling((1 << 24) + 1, one, one, None) == binding.FREE_ERR_RANGE
     # spec_verify: null pointer, bad shape
     assert lib.spec_verify(None, one, one, one, one, None, 1, 6, 64, one, one, one, one, one, 4096, None) == binding.FREE_ERR_NULL
     assert lib.spec_verify(one, one, one, one, one, None, 1, 0, 64, one, one, one, one, one, 4096, None) == binding.FREE_ERR_SHAPE

@@ -204,6 +204,21 @@ def test_xl2_256_round_fp32():
     _xl_round("xl2_256", 6, 4.0, "fp32", oracle_states=[2])
 
 
+def test_mfma_calibration_is_sane():
+    """The register-only MFMA loop of the benchmark's calibration: its rate equals workgroups x
+    wavefronts x MFMAs x flops over the measured time by construction; what can be checked is that
+    the two outputs are consistent with each other - 4 SIMDs x 1024 flop per clock per compute
+    unit at the reported clock bounds the reported rate - and inside the chip's envelope."""
+    import torch
+    from paper_2511_20390_amd import binding
+    torch.zeros(1, device="cuda:0")
+    cal = binding.mfma_ceiling(50000)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert 500.0 < cal["shader_clock_mhz"] < 2500.0
+    at_clock = cus * 4 * 1024 * cal["shader_clock_mhz"] * 1e6 / 1e12     # TFLOP/s if every SIMD issues back to back
+    assert 0.5 * at_clock < cal["tflops"] <= 1.02 * at_clock
+
+
 def test_batch_streams_same_result():
     """The two halves of a large batch run on two streams by default; the serial schedule
     (one stream) must give the same numbers: every kernel reduces in the same order
