@@ -50,6 +50,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     constexpr int KSTEPS = (DH + 15) / 16;            // MFMA k-steps over the head dim (S^T)
     constexpr int DCH = DH / 8;                       // 16-byte chunks per Q/K/V row
     constexpr int DT = (DH + 31) / 32;                // 32-row tiles of O^T
+    constexpr bool kSumByMfma = (DH % 32) != 0;       // a spare row of O^T can carry the softmax denominator
     constexpr int KROW = ((2 * KSTEPS) | 1) * 16;     // bytes per K row in LDS (odd # of chunks)
     constexpr int BQ = 4 * 32 * QT;                   // queries per workgroup
     constexpr int NLD = (BKV * DCH + kThreads - 1) / kThreads;   // 16-byte loads per thread per tile
@@ -89,9 +90,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int c = i % (KROW / 16);
         if (c >= DCH) *reinterpret_cast<u32x4_t*>(sKbuf + (i / (KROW / 16)) * KROW + c * 16) = u32x4_t{0, 0, 0, 0};
     }
+    // ... except, when the head dimension leaves pad columns (kSumByMfma), column DH of V, which is one
+    // (bf16 0x3F80) for every key: row DH of O^T then accumulates the sum of the probabilities in the matrix
+    // pipe, rescaled together with O^T, instead of one VALU addition per score
     for (int i = tid; i < 2 * BKV * (VROW / 16); i += kThreads) {
         const int c = i % (VROW / 16);
-        if (c >= DCH) *reinterpret_cast<u32x4_t*>(sVbuf + (i / (VROW / 16)) * VROW + c * 16) = u32x4_t{0, 0, 0, 0};
+        if (c >= DCH)
+            *reinterpret_cast<u32x4_t*>(sVbuf + (i / (VROW / 16)) * VROW + c * 16) =
+                u32x4_t{(kSumByMfma && c == DCH) ? 0x3F80u : 0u, 0, 0, 0};
     }
 
     // Q^T fragments (B operand of S^T): lane holds query column l32, k-slots d = 16 ks + 8 g + j
@@ -172,6 +178,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     // probabilities stay below 2^kLazy (harmless in bf16/fp32) and the 3 x 16 accumulator
     // registers are rarely touched by the VALU.
     constexpr float kLazy = 8.0f;
+    constexpr int kPrioMfma = 2;       // wave priority while issuing the MFMA blocks (0 in the softmax): measured 2.5 %
     float m_ref[QT], l_run[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) { m_ref[qt] = -INFINITY; l_run[qt] = 0.f; }
@@ -192,6 +199,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const char* sV = sVbuf + (t & 1) * kVBytes;
 
         // ---- S^T = K Q^T for the two 32-key blocks of the tile
+        __builtin_amdgcn_s_setprio(kPrioMfma);
         f32x16_t st[2][QT];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -211,6 +219,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int qt = 0; qt < QT; ++qt)
                     st[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[qt][ks], st[kb][qt], 0, 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
         // the next tile moves from registers to the other LDS stage while this one is processed;
         // the tile after it is requested from global memory
         if (t + 1 < ntiles) stash((t + 1) & 1, next_set);
@@ -240,11 +249,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[kb][qt][e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                 // both half-waves of a column agree
+            {   // both half-waves of a column agree: v_permlane32_swap leaves {own, partner} in the two
+                // results (in either order), without the LDS round trip of a bpermute
+                const uint32_t mb32 = __builtin_bit_cast(uint32_t, mx);
+                const u32x2_t sw = __builtin_amdgcn_permlane32_swap(mb32, mb32, false, false);
+                const uint32_t s0 = sw[0], s1 = sw[1];
+                mx = fmaxf(__builtin_bit_cast(float, s0), __builtin_bit_cast(float, s1));
+            }
             if (__builtin_expect(__any((mx - m_ref[qt]) * scale_log2 > kLazy), 0)) {     // also true for the first tile (m_ref = -inf)
                 const float m_new = fmaxf(m_ref[qt], mx);
                 const float alpha = __builtin_amdgcn_exp2f((m_ref[qt] - m_new) * scale_log2);
-                l_run[qt] *= alpha;
+                if constexpr (!kSumByMfma) l_run[qt] *= alpha;
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -252,7 +267,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
                 m_ref[qt] = m_new;
             }
             const float mb = m_ref[qt] * scale_log2;
-            float sum = 0.f;
+            [[maybe_unused]] float sum = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -261,16 +276,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         p[j] = __builtin_amdgcn_exp2f(fmaf(st[kb][qt][8 * hh + j], scale_log2, -mb));
-                        sum += p[j];
+                        if constexpr (!kSumByMfma) sum += p[j];
                     }
                     u32x4_t pk = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
                                   pack_bf16x2(p[6], p[7])};
                     pf[qt][kb][hh] = __builtin_bit_cast(bf16x8_t, pk);
                 }
-            l_run[qt] += sum;
+            if constexpr (!kSumByMfma) l_run[qt] += sum;
         }
 
         // ---- O^T += V^T P^T
+        __builtin_amdgcn_s_setprio(kPrioMfma);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -288,6 +304,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
                         o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][kb][hh], o[dt][qt], 0, 0, 0);
                 }
             }
+        __builtin_amdgcn_s_setprio(0);
         __syncthreads();          // stage (t+1)&1 is complete; stage t&1 may be overwritten next iteration
     };
     // full tiles need no key masking; only a ragged last tile does
@@ -310,7 +327,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         const int q = q_base + qt * 32 + l32;
-        const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
+        float l_tot;
+        if constexpr (kSumByMfma) {
+            // row DH of O^T: tile DH / 32, register 4 (r / 8) + r % 4 of the half-wave (r % 8) / 4, r = DH % 32
+            constexpr int r = DH % 32;
+            const float mine = o[DH / 32][qt][4 * (r / 8) + r % 4];
+            const float other = __shfl_xor(mine, 32, 64);
+            l_tot = (g == (r % 8) / 4) ? mine : other;
+        } else {
+            l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
+        }
         if (q >= N) continue;
         const float inv = 1.0f / l_tot;
         char* dst = reinterpret_cast<char*>(out) + ((row0 + q) * D + static_cast<size_t>(h) * DH) * 2;
