@@ -39,17 +39,21 @@ __device__ inline int swap_bits_2_3(int r) { return (r & ~12) | ((r & 4) << 1) |
 
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) { return pack_bf16_pair(lo, hi); }   // v_cvt_pk_bf16_f32
 
-// amdgpu_waves_per_eu(2): two workgroups per CU are wanted anyway (LDS and registers allow it), and
-// with at most 256 registers per lane the compiler uses the VGPR form of the MFMAs - with the
-// default budget of 512 it parks accumulators in AGPRs and moves them back and forth for the
-// softmax (several hundred v_accvgpr moves per key tile).
+// amdgpu_waves_per_eu: with at most 256 registers per lane the compiler uses the VGPR form of the MFMAs -
+// with the default budget of 512 it parks accumulators in AGPRs and moves them back and forth for the
+// softmax (several hundred v_accvgpr moves per key tile).  Head dims up to 72 run three workgroups per CU
+// (168 registers, 47 KB of LDS each): the phases of a tile - S^T on the matrix pipe, softmax on the VALU,
+// O^T on the matrix pipe - are serial inside a wavefront, so what overlaps them is the number of
+// wavefronts per SIMD; the third one is worth more (measured 4.5 %) than the second set of K/V staging
+// registers it costs.
 template <int DH, int QT>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(const bf16_t* __restrict__ qkv, int32_t N,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH <= 72 ? 3 : 2, DH <= 72 ? 3 : 2))) void attn_mfma_kernel(const bf16_t* __restrict__ qkv, int32_t N,
                                                              int32_t heads, float scale_log2,
                                                              bf16_t* __restrict__ out) {
     constexpr int KSTEPS = (DH + 15) / 16;            // MFMA k-steps over the head dim (S^T)
     constexpr int DCH = DH / 8;                       // 16-byte chunks per Q/K/V row
     constexpr int DT = (DH + 31) / 32;                // 32-row tiles of O^T
+    constexpr int kSets = DH <= 72 ? 1 : 2;           // K/V register sets: tiles in flight from global memory
     constexpr bool kSumByMfma = (DH % 32) != 0;       // a spare row of O^T can carry the softmax denominator
     constexpr int KROW = ((2 * KSTEPS) | 1) * 16;     // bytes per K row in LDS (odd # of chunks)
     constexpr int BQ = 4 * 32 * QT;                   // queries per workgroup
@@ -130,8 +134,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int idx = tid + kThreads * i;
         ld_off[i] = (idx / DCH) * static_cast<int>(row_bytes) + (idx % DCH) * 16;
     }
-    // two register sets: the loads of tiles t+2 and t+3 are in flight while tile t is processed
-    u32x4_t kreg[2][NLD], vreg[2][NLD];
+    // kSets register sets: the loads of tiles t+2 .. t+1+kSets are in flight while tile t is processed
+    u32x4_t kreg[kSets][NLD], vreg[kSets][NLD];
     auto fetch = [&](int t, auto set) {
         constexpr int S = decltype(set)::value;
         const int tile_off = t * BKV * static_cast<int>(row_bytes);
@@ -185,11 +189,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     const int ntiles = (N + BKV - 1) / BKV;
     const std::integral_constant<int, 0> set0{};
-    const std::integral_constant<int, 1> set1{};
+    const std::integral_constant<int, kSets - 1> set1{};
     fetch(0, set0);
     stash(0, set0);
     if (ntiles > 1) fetch(1, set1);
-    if (ntiles > 2) fetch(2, set0);
+    if (kSets == 2 && ntiles > 2) fetch(2, set0);
     __syncthreads();
     // tile t: its K/V are in LDS stage t % 2; tile t+1 sits in register set (t+1) % 2
     auto tile = [&](int t, auto ragged, auto next_set) {
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         // the next tile moves from registers to the other LDS stage while this one is processed;
         // the tile after it is requested from global memory
         if (t + 1 < ntiles) stash((t + 1) & 1, next_set);
-        if (t + 3 < ntiles) fetch(t + 3, next_set);
+        if (t + 1 + kSets < ntiles) fetch(t + 1 + kSets, next_set);
 
         // keys past N (last tile only): accumulator register e of block kb holds the key
         // kv0 + 32 kb + 16 (e/8) + 8 g + 4 ((e/4)%2) + e%4   (LDS rows were permuted on the way in)
