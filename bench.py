@@ -96,18 +96,18 @@ def bench_round(args):
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # the same steps with all kernels in sequence on one stream (what the per-kernel figures refer to)
-    ms_one_stream = ms_per_step
-    if binding.get_batch_streams() != 1:
-        binding.set_batch_streams(1)
+    # the same steps in the other stream mode (the per-kernel figures below refer to one stream)
+    other = 2 if binding.get_batch_streams() == 1 else 1
+    binding.set_batch_streams(other)
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
         step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        ms_one_stream = (time.perf_counter() - t0) * 1e3 / args.steps
-        binding.set_batch_streams(args.streams)
+    torch.cuda.synchronize()
+    ms_other = (time.perf_counter() - t0) * 1e3 / args.steps
+    binding.set_batch_streams(args.streams)
+    ms_one_stream, ms_two_streams = (ms_per_step, ms_other) if other == 2 else (ms_other, ms_per_step)
 
     # per-kernel durations: the same steps again, every launch bracketed by HIP events on its stream
     # (the library runs them in sequence on one stream while it profiles)
@@ -141,7 +141,7 @@ def bench_round(args):
                                         "frac_of_calibrated": kernels[dom]["tflops"] / cal["tflops"]}
     fwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if not k.startswith("verify") and k != "eps_to_mean")
     res = {
-        "ms_per_step": ms_per_step, "ms_per_step_one_stream": ms_one_stream,
+        "ms_per_step": ms_per_step, "ms_per_step_one_stream": ms_one_stream, "ms_per_step_two_streams": ms_two_streams,
         "batch_streams": binding.get_batch_streams(), "kernels": kernels, "roofline": roofline,
         "forward": {"algorithmic_tflop": total_flops / 1e12, "ms_sum_of_kernels": fwd_ms,
                     "tflops_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12,
@@ -444,6 +444,7 @@ def main():
                                f"{'relaxed' if args.relaxed else 'strict'} rule",
                    "packed_batch": res["B"], "tokens": res["tokens_per_round"]},
         "batch_streams": res["batch_streams"], "ms_per_step_one_stream": res["ms_per_step_one_stream"],
+        "ms_per_step_two_streams": res["ms_per_step_two_streams"],
         "roofline": res["roofline"], "forward": res["forward"], "kernels": res["kernels"],
     }
     if "drafting" in res:

@@ -18,8 +18,9 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;                  // per workgroup: they share one staged copy of the activations
+constexpr int kThreads = 64 * kWaves;
+constexpr int kChunk = 6;                  // k-steps (1 KB of weights per wavefront each) per register set
 constexpr int kBatch = 16;
 
 __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
@@ -54,24 +55,59 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
     const char* bh = s_hi + l16 * row_bytes + lq * 16;
     const char* bl = s_lo + l16 * row_bytes + lq * 16;
     const int steps = D / 32;
+    // Weight rows stream through two register sets of kChunk k-steps each: the loads of one set are in
+    // flight while the other is multiplied, across row blocks too (the first chunk of the next block is
+    // requested before the last chunk of this one is multiplied).  The pointers come from a table in
+    // memory, so they are cast to the global address space explicitly - as generic pointers every load
+    // would be a flat load that the compiler must order against the LDS reads, one load in flight per
+    // wavefront.
+    using gvec = const __attribute__((address_space(1))) u32x4_t*;
+    u32x4_t wa[kChunk], wb[kChunk];
+    auto load = [&](u32x4_t (&dst)[kChunk], const char* wrow, int st0) {
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u)
+            if (st0 + u < steps) dst[u] = *(gvec)(wrow + (st0 + u) * 64);
+    };
     int mat = 0;
-    for (int blk = first; blk < first + blocks_per_wave && blk < nblocks; ++blk) {
+    auto row_ptr = [&](int blk) {          // advances `mat` to the matrix that holds row block blk
         const int r0 = blk * 16;
         while (mat + 1 < n_mats && r0 >= row_start[mat + 1]) ++mat;
-        const int lr0 = r0 - row_start[mat];
-        const char* wrow = static_cast<const char*>(w_tab[mat]) + (static_cast<int64_t>(lr0 + l16) * D) * 2 + lq * 16;
+        return static_cast<const char*>(w_tab[mat]) + (static_cast<int64_t>(r0 - row_start[mat] + l16) * D) * 2 + lq * 16;
+    };
+    const int last = (first + blocks_per_wave < nblocks) ? first + blocks_per_wave : nblocks;
+    const char* wrow = nullptr;
+    if (first < last) {
+        wrow = row_ptr(first);
+        load(wa, wrow, 0);
+    }
+    for (int blk = first; blk < last; ++blk) {
+        const int r0 = blk * 16;
+        const int cur_mat = mat;
+        const int lr0 = r0 - row_start[cur_mat];
+        const char* wnext = (blk + 1 < last) ? row_ptr(blk + 1) : nullptr;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 6
-        for (int st = 0; st < steps; ++st) {
-            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(wrow + st * 64));
-            const bf16x8_t h = *reinterpret_cast<const bf16x8_t*>(bh + st * 64);
-            const bf16x8_t l = *reinterpret_cast<const bf16x8_t*>(bl + st * 64);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acc, 0, 0, 0);
+        auto multiply = [&](const u32x4_t (&src)[kChunk], int st0) {
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u)
+                if (st0 + u < steps) {
+                    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, src[u]);
+                    const bf16x8_t h = *reinterpret_cast<const bf16x8_t*>(bh + (st0 + u) * 64);
+                    const bf16x8_t l = *reinterpret_cast<const bf16x8_t*>(bl + (st0 + u) * 64);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acc, 0, 0, 0);
+                }
+        };
+        for (int st0 = 0; st0 < steps; st0 += 2 * kChunk) {
+            load(wb, wrow, st0 + kChunk);
+            multiply(wa, st0);
+            if (st0 + 2 * kChunk < steps) load(wa, wrow, st0 + 2 * kChunk);
+            else if (wnext) load(wa, wnext, 0);
+            multiply(wb, st0 + kChunk);
         }
+        wrow = wnext;
         // accumulator register i of lane l: weight row 4*(l/16) + i, batch column l%16
         if (l16 < B) {
-            const f32x4_t bias = *reinterpret_cast<const f32x4_t*>(b_tab[mat] + lr0 + 4 * lq);
+            const f32x4_t bias = *reinterpret_cast<const f32x4_t*>(b_tab[cur_mat] + lr0 + 4 * lq);
             f32x4_t o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = acc[i] + bias[i];
@@ -90,7 +126,8 @@ int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* con
                           const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
                           int32_t total_rows, float* mod, hipStream_t s) {
     const int nblocks = total_rows / 16;
-    const int blocks_per_wave = nblocks >= 8192 ? 6 : 1;
+    // about 16 wavefronts per CU at the DiT-XL size (12096 row blocks): measured best among 2, 3, 6, 12
+    const int blocks_per_wave = nblocks >= 8192 ? 3 : 1;
     const int waves = (nblocks + blocks_per_wave - 1) / blocks_per_wave;
     const int grid = (waves + kWaves - 1) / kWaves;
     const size_t lds = 2 * static_cast<size_t>(kBatch) * (D * 2 + 16);
