@@ -915,6 +915,9 @@ int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B
     bool vec = (D % 4 == 0) && D <= 2048 && al16(x) && al16(w) && al16(shift.base) && al16(scale.base) &&
                      (shift.stride % 4 == 0) && (scale.stride % 4 == 0);
     const size_t lds_bytes = static_cast<size_t>(p) * p * c_out * D * (dtype == FREE_BF16 ? 2 : 4);
+    if (vec && dtype == FREE_BF16 && final_mfma_supported(D, p * p * c_out))
+        return launch_final_layer_mfma(x, shift, scale, M, gh, gw, p, c_out, D, static_cast<const bf16_t*>(w), bias,
+                                       out, s);
     if (vec) {
         const int nv = (D / 4 + 63) / 64;
         // few rows: stage the weights in LDS, as many workgroups as fit on the chip at once (LDS-limited),

@@ -152,6 +152,11 @@ int32_t launch_sqdist(const float* a, const float* b, int32_t K, int64_t d, doub
 
 // ---- MFMA adaLN modulation GEMV, bf16 weights (adaln_mfma.hip)
 bool adaln_mfma_supported(int32_t D, int32_t total_rows);
+// final_mfma.hip: final layer on the matrix cores (bf16 weights, DiT-S/B/L/XL widths)
+bool final_mfma_supported(int32_t D, int32_t P);
+int32_t launch_final_layer_mfma(const float* x, RowVec shift, RowVec scale, int32_t M, int32_t gh, int32_t gw,
+                                int32_t p, int32_t c_out, int32_t D, const bf16_t* w, const float* bias, float* out,
+                                hipStream_t s);
 int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* const* w_tab,
                           const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
                           int32_t total_rows, float* mod, hipStream_t s);
