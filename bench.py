@@ -43,8 +43,10 @@ def forward_flops(cfg, B):
 # kernel symbol (as rocprofv3 prints it) behind each profiled category, to look its measured
 # HBM traffic up in the committed rocprofv3 --pmc summary
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "spec_round_xl2_512_hbm_traffic.md")
-CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<384, 192, 4, 2, 1, true>", "gemm_qkv": "gemm_bf16_kernel<256, 256, 4, 2, 0, true>",
-                   "attention": "attn_mfma_kernel<72, 1>", "verify_partial": "verify_partial_kernel<true>"}
+CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<384, 192, 4, 2, 1, true>`", "gemm_qkv": "gemm_bf16_kernel<256, 256, 4, 2, 0, true>`",
+                   "gemm_fc2": "gemm_bf16_kernel<256, 256, 4, 2, 2, true>` FC2",
+                   "gemm_proj": "gemm_bf16_kernel<256, 256, 4, 2, 2, true>` out-projection",
+                   "attention": "attn_mfma_kernel<72, 1>`", "verify_partial": "verify_partial_kernel<true>`"}
 
 
 def measured_traffic(category):
@@ -53,7 +55,7 @@ def measured_traffic(category):
     if sym is None or not os.path.exists(TRAFFIC_FILE):
         return None
     for line in open(TRAFFIC_FILE):
-        if line.startswith("| `" + sym + "`"):
+        if line.startswith("| `" + sym + " ("):
             cells = [c.strip() for c in line.strip().strip("|").split("|")]
             try:
                 return {"fetch_MB": float(cells[2]), "write_MB": float(cells[3]), "unit": "MB per launch",
