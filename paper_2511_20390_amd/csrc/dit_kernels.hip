@@ -174,6 +174,7 @@ __global__ __launch_bounds__(kThreads) void patch_embed_kernel(
 // registers over a run of kPatchTok tokens: read per token from cache the D x 16 matrix costs 74 KB per
 // token at D = 1152, two orders of magnitude more than the token's 4.6 KB of output.
 constexpr int kPatchTok = 16;
+constexpr int kPatchUnroll = 4;
 template <int NR>
 __global__ __launch_bounds__(kThreads) void patch_embed16_kernel(
     const float* __restrict__ x, int32_t x_mod, int32_t C, int32_t H, int32_t W, int32_t p, int32_t D,
@@ -209,26 +210,40 @@ __global__ __launch_bounds__(kThreads) void patch_embed16_kernel(
         }
     }
     __syncthreads();
-    for (int tk = 0; tk < kPatchTok; ++tk) {
-        const int n = n0 + tk;
-        if (n >= ntok) break;
-        float4 pv[4];
+    // groups of kPatchUnroll tokens: the position-table loads of a whole group are issued together, so their
+    // latency is paid once per group and not once per token (a block has nothing else to hide it behind)
+    for (int tk0 = 0; tk0 < kPatchTok; tk0 += kPatchUnroll) {
+        if (n0 + tk0 >= ntok) break;
+        float pe[kPatchUnroll][NR];
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) pv[q4] = reinterpret_cast<const float4*>(patch[tk])[q4];
-        const int64_t row = static_cast<int64_t>(b) * ntok + n;
+        for (int u = 0; u < kPatchUnroll; ++u)
 #pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            const int j = threadIdx.x + kThreads * r;
-            if (j < D) {
-                float acc = bias[r];
+            for (int r = 0; r < NR; ++r) {
+                const int n = n0 + tk0 + u, j = threadIdx.x + kThreads * r;
+                pe[u][r] = (n < ntok && j < D) ? pos[static_cast<int64_t>(n) * D + j] : 0.f;
+            }
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {           // same summation order as the generic kernel
-                    acc = fmaf(pv[q4].x, w[r][q4].x, acc);
-                    acc = fmaf(pv[q4].y, w[r][q4].y, acc);
-                    acc = fmaf(pv[q4].z, w[r][q4].z, acc);
-                    acc = fmaf(pv[q4].w, w[r][q4].w, acc);
+        for (int u = 0; u < kPatchUnroll; ++u) {
+            const int n = n0 + tk0 + u;
+            if (n >= ntok) break;
+            float4 pv[4];
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) pv[q4] = reinterpret_cast<const float4*>(patch[tk0 + u])[q4];
+            const int64_t row = static_cast<int64_t>(b) * ntok + n;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int j = threadIdx.x + kThreads * r;
+                if (j < D) {
+                    float acc = bias[r];
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {           // same summation order as the generic kernel
+                        acc = fmaf(pv[q4].x, w[r][q4].x, acc);
+                        acc = fmaf(pv[q4].y, w[r][q4].y, acc);
+                        acc = fmaf(pv[q4].z, w[r][q4].z, acc);
+                        acc = fmaf(pv[q4].w, w[r][q4].w, acc);
+                    }
+                    out[row * D + j] = acc + pe[u][r];
                 }
-                out[row * D + j] = acc + pos[static_cast<int64_t>(n) * D + j];
             }
         }
     }
