@@ -39,6 +39,7 @@
 //    works on a compact, L2-friendly group of tiles.
 //  * the tile configuration is chosen per problem from a measured time model (whole
 //    rounds of workgroups x (K slices x time per slice + per-tile fixed cost)).
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <type_traits>
@@ -98,8 +99,7 @@ __device__ __forceinline__ void sched_hints() {
 // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so the
 // ids of one XCD are made contiguous first, then walked in groups of kGroupM row
 // tiles (column-major inside a group) so concurrent workgroups share X and W panels.
-template <int kGroupM>
-__device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, int* tn) {
+__device__ inline void tile_coords(int kGroupM, int pid, int tiles_m, int tiles_n, int* tm, int* tn) {
     const int total = tiles_m * tiles_n;
     const int q = total / kNumXcd, r = total % kNumXcd;
     const int x = pid % kNumXcd, j = pid / kNumXcd;
@@ -322,8 +322,8 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
 template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, const float* __restrict__ bias, int32_t M,
-    int32_t N, int32_t K, int32_t tiles_m, int32_t tiles_n, int32_t vec_ok, bf16_t* __restrict__ out,
-    float* __restrict__ resid, RowVec gate) {
+    int32_t N, int32_t K, int32_t tiles_m, int32_t tiles_n, int32_t group_m, int32_t vec_ok,
+    bf16_t* __restrict__ out, float* __restrict__ resid, RowVec gate) {
     static_assert(WGM * WGN == 4 || WGM * WGN == 8, "four or eight wavefronts per workgroup");
     constexpr int NT = WGM * WGN * 64;                 // threads per workgroup
     constexpr int RP = NT / 8;                         // tile rows covered by one pass of 16-byte loads
@@ -333,9 +333,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     int tile_m, tile_n;
-    // row tiles per group: the 32 workgroups that run together on an XCD then cover a x b tiles with
-    // a BM ~ b BN, the shape that needs the fewest distinct X and W panels (first-touch L2 misses)
-    tile_coords<(BM > BN ? 4 : 8)>(blockIdx.x, tiles_m, tiles_n, &tile_m, &tile_n);
+    tile_coords(group_m, blockIdx.x, tiles_m, tiles_n, &tile_m, &tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -478,6 +476,17 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
                             lds + wave * kWaveStage);
 }
 
+int device_cus() {
+    static int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return cus;
+}
+
 template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
 int32_t launch_one(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K, bf16_t* out,
                    float* resid, RowVec gate, hipStream_t s) {
@@ -496,7 +505,19 @@ int32_t launch_one(const bf16_t* X, const bf16_t* W, const float* bias, int32_t 
     const bool vec = ((N & 7) == 0) && al16(bias) && al16(out) && al16(resid) && al16(gate.base) &&
                      ((gate.stride & 3) == 0);
     const int32_t vec_ok = vec ? 1 : 0;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WGM * WGN * 64), lds, s, X, W, bias, M, N, K, tiles_m, tiles_n,
+    // Row tiles per group of the tile order.  Several rounds of workgroups: the 32 that run together on an
+    // XCD should cover a x b tiles with a BM ~ b BN, the shape that needs the fewest distinct X and W panels
+    // (first-touch misses of that XCD's L2).  A single round: every XCD holds total / 8 tiles for the whole
+    // kernel, and a group of exactly that many tiles - whole tile rows - keeps each X panel in one L2
+    // (FC2 at 12288 rows: 361 MB fetched with groups of 8 row tiles, X read by two or three XCDs each).
+    // This is about traffic, not time: the Infinity Cache served the repeats at no measurable cost.
+    const int total = tiles_m * tiles_n;
+    int group_m = BM > BN ? 4 : 8;
+    if (total <= device_cus()) {
+        const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+        group_m = std::max(1, (per_xcd + tiles_n / 2) / tiles_n);
+    }
+    hipLaunchKernelGGL(kern, dim3(total), dim3(WGM * WGN * 64), lds, s, X, W, bias, M, N, K, tiles_m, tiles_n, group_m,
                        vec_ok, out, resid, gate);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
@@ -539,16 +560,6 @@ double small_tile_time(int M, int N, int K, int cus) {
     return full * shared + (rest == 0.0 ? 0.0 : (rest <= cus ? alone : shared));
 }
 
-int device_cus() {
-    static int cus = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-            n = 256;
-        return n;
-    }();
-    return cus;
-}
 
 }  // namespace
 
