@@ -15,7 +15,8 @@
 // to one MFMA belong to 8 CONSECUTIVE keys: the matching V^T operand is then a
 // pair of transposing LDS reads (ds_read_b64_tr_b16) of the row-major V tile.
 // Head dim 72 (DiT-XL): the contraction over d is padded 72 -> 80 with zero chunks
-// in LDS; the O^T rows are padded 72 -> 96 and the pad rows are never stored.
+// in LDS; the O^T rows are padded 72 -> 96 and the pad rows are never stored (row 72 carries the
+// softmax denominator: column 72 of the V tile is set to one).
 #include <cmath>
 #include <type_traits>
 
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(DH <= 
 template <int DH>
 int32_t launch_dh(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, bf16_t* out, hipStream_t s) {
     const float scale_log2 = 1.4426950408889634f / std::sqrt(static_cast<float>(DH));
-    // one 32-query tile per wavefront: 128 queries per workgroup, two workgroups per CU
+    // one 32-query tile per wavefront: 128 queries per workgroup, two or three workgroups per CU
     // (measured faster than two query tiles per wavefront at one workgroup per CU)
     const int64_t total = static_cast<int64_t>((N + 127) / 128) * heads * B;
     if (total > 0x7fffffff) return FREE_ERR_SHAPE;

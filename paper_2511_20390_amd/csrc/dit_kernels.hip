@@ -282,52 +282,80 @@ __global__ __launch_bounds__(kThreads) void ln_modulate_kernel(
 // Same operation with the row held in registers: one 16-byte load per element group,
 // statistics from registers, one packed store.  HBM-bound (reads 4 B, writes 2 or 4 B per
 // element); needs D % 4 == 0, D <= 256 NV and 16-byte aligned rows.
-template <typename OT, int NV>
+// A wavefront walks kLnRows consecutive rows (4 when there are enough rows to fill the chip that way, else 1): the shift / scale vectors of a sample (as many bytes as the row
+// itself, each) stay in registers while the sample does not change - read per row they triple the traffic
+// through the L1 - and the next row is requested before the current one is reduced.
+template <typename OT, int NV, int kLnRows>
 __global__ __launch_bounds__(kThreads) void ln_modulate_vec_kernel(
     const float* __restrict__ x, RowVec shift, RowVec scale, int32_t M, int32_t D, OT* __restrict__ out) {
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6)) * kLnRows;
     const int lane = threadIdx.x & 63;
-    if (row >= M) return;
+    if (row0 >= M) return;
+    const int nrows = M - row0 < kLnRows ? static_cast<int>(M - row0) : kLnRows;
     const int nvec = D >> 2;
-    const float4* xr = reinterpret_cast<const float4*>(x + row * D);
-    float4 xv[NV];
-    float s = 0.f;
+    auto load_row = [&](float4 (&dst)[NV], int64_t row) {
+        const float4* xr = reinterpret_cast<const float4*>(x + row * D);
 #pragma unroll
-    for (int k = 0; k < NV; ++k) {
-        const int v = lane + 64 * k;
-        xv[k] = (v < nvec) ? xr[v] : make_float4(0.f, 0.f, 0.f, 0.f);
-        s += (xv[k].x + xv[k].y) + (xv[k].z + xv[k].w);
-    }
-    const float mean = wave_sum_f(s) / static_cast<float>(D);
-    float q = 0.f;
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-        if (lane + 64 * k < nvec) {
-            const float a = xv[k].x - mean, b = xv[k].y - mean, c = xv[k].z - mean, d = xv[k].w - mean;
-            q += (a * a + b * b) + (c * c + d * d);
+        for (int k = 0; k < NV; ++k) {
+            const int v = lane + 64 * k;
+            dst[k] = (v < nvec) ? xr[v] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-    }
-    const float rstd = rsqrtf(wave_sum_f(q) / static_cast<float>(D) + kLnEps);
-    const float4* sh = reinterpret_cast<const float4*>(shift.base + (row / shift.rows_per_sample) * shift.stride);
-    const float4* sc = reinterpret_cast<const float4*>(scale.base + (row / scale.rows_per_sample) * scale.stride);
+    };
+    float4 xv[NV], xn[NV], shv[NV], scv[NV];
+    int64_t sh_smp = -1, sc_smp = -1;
+    load_row(xv, row0);
+    for (int r = 0; r < nrows; ++r) {
+        const int64_t row = row0 + r;
+        if (r + 1 < nrows) load_row(xn, row + 1);
+        const int64_t s_sh = row / shift.rows_per_sample, s_sc = row / scale.rows_per_sample;
+        if (s_sh != sh_smp) {                                  // wave-uniform
+            const float4* sh = reinterpret_cast<const float4*>(shift.base + s_sh * shift.stride);
 #pragma unroll
-    for (int k = 0; k < NV; ++k) {
-        const int v = lane + 64 * k;
-        if (v < nvec) {
-            const float4 h = sh[v], c = sc[v];
-            const float o0 = fmaf((xv[k].x - mean) * rstd, 1.0f + c.x, h.x);
-            const float o1 = fmaf((xv[k].y - mean) * rstd, 1.0f + c.y, h.y);
-            const float o2 = fmaf((xv[k].z - mean) * rstd, 1.0f + c.z, h.z);
-            const float o3 = fmaf((xv[k].w - mean) * rstd, 1.0f + c.w, h.w);
-            if constexpr (sizeof(OT) == 2) {
-                uint2 pk;
-                pk.x = pack_bf16_pair(o0, o1);
-                pk.y = pack_bf16_pair(o2, o3);
-                reinterpret_cast<uint2*>(out + row * D)[v] = pk;
-            } else {
-                reinterpret_cast<float4*>(out + row * D)[v] = make_float4(o0, o1, o2, o3);
+            for (int k = 0; k < NV; ++k)
+                if (lane + 64 * k < nvec) shv[k] = sh[lane + 64 * k];
+            sh_smp = s_sh;
+        }
+        if (s_sc != sc_smp) {
+            const float4* sc = reinterpret_cast<const float4*>(scale.base + s_sc * scale.stride);
+#pragma unroll
+            for (int k = 0; k < NV; ++k)
+                if (lane + 64 * k < nvec) scv[k] = sc[lane + 64 * k];
+            sc_smp = s_sc;
+        }
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) s += (xv[k].x + xv[k].y) + (xv[k].z + xv[k].w);
+        const float mean = wave_sum_f(s) / static_cast<float>(D);
+        float q = 0.f;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            if (lane + 64 * k < nvec) {
+                const float a = xv[k].x - mean, b = xv[k].y - mean, c = xv[k].z - mean, d = xv[k].w - mean;
+                q += (a * a + b * b) + (c * c + d * d);
             }
         }
+        const float rstd = rsqrtf(wave_sum_f(q) / static_cast<float>(D) + kLnEps);
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int v = lane + 64 * k;
+            if (v < nvec) {
+                const float4 h = shv[k], c = scv[k];
+                const float o0 = fmaf((xv[k].x - mean) * rstd, 1.0f + c.x, h.x);
+                const float o1 = fmaf((xv[k].y - mean) * rstd, 1.0f + c.y, h.y);
+                const float o2 = fmaf((xv[k].z - mean) * rstd, 1.0f + c.z, h.z);
+                const float o3 = fmaf((xv[k].w - mean) * rstd, 1.0f + c.w, h.w);
+                if constexpr (sizeof(OT) == 2) {
+                    uint2 pk;
+                    pk.x = pack_bf16_pair(o0, o1);
+                    pk.y = pack_bf16_pair(o2, o3);
+                    reinterpret_cast<uint2*>(out + row * D)[v] = pk;
+                } else {
+                    reinterpret_cast<float4*>(out + row * D)[v] = make_float4(o0, o1, o2, o3);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < NV; ++k) xv[k] = xn[k];
     }
 }
 
@@ -841,8 +869,20 @@ int32_t launch_ln_modulate(const float* x, RowVec shift, RowVec scale, int32_t M
     if (vec) {
         const int nv = (D / 4 + 63) / 64;
 #define FREE_LN_CASE(OT, NV)                                                                                   \
-    hipLaunchKernelGGL((ln_modulate_vec_kernel<OT, NV>), dim3(blocks), dim3(kThreads), 0, s, x, shift, scale, M, D, \
-                       static_cast<OT*>(out))
+    do {                                                                                                       \
+        if (rows_per_wave == 4)                                                                                \
+            hipLaunchKernelGGL((ln_modulate_vec_kernel<OT, NV, 4>), dim3((blocks + 3) / 4), dim3(kThreads), 0, s, x, \
+                               shift, scale, M, D, static_cast<OT*>(out));                                     \
+        else if (rows_per_wave == 2)                                                                           \
+            hipLaunchKernelGGL((ln_modulate_vec_kernel<OT, NV, 2>), dim3((blocks + 1) / 2), dim3(kThreads), 0, s, x, \
+                               shift, scale, M, D, static_cast<OT*>(out));                                     \
+        else                                                                                                   \
+            hipLaunchKernelGGL((ln_modulate_vec_kernel<OT, NV, 1>), dim3(blocks), dim3(kThreads), 0, s, x, shift, \
+                               scale, M, D, static_cast<OT*>(out));                                            \
+    } while (0)
+        // measured at D = 1152: 12288 rows 19.3 / 16.2 / 15.8 us with 1 / 2 / 4 rows per wavefront, 6144 rows
+        // 10.4 / 9.1 / 10.0 us; with few rows the chain of one row's latencies is what counts
+        const int rows_per_wave = M >= 8192 ? 4 : (M >= 4096 ? 2 : 1);
         if (dtype == FREE_BF16) {
             if (nv <= 1) FREE_LN_CASE(bf16_t, 1);
             else if (nv <= 2) FREE_LN_CASE(bf16_t, 2);
