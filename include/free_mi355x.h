@@ -92,6 +92,17 @@ int32_t free_get_batch_streams(void);
 int32_t free_ddpm_schedule(int32_t T, double beta_start, double beta_end,
                            double* coef_x, double* coef_eps, double* sigma);
 
+/* Opt-in range check of device-resident inputs of spec_verify / spec_round / the samplers (the hot-path
+ * calls do not look at device values: that would force a synchronisation).  t: [device] n_t timesteps,
+ * each must lie in [0, T); sigma, u, lambda: [device] n values each; sigma must be positive and finite
+ * (Alg. 2 divides by sigma^2), u and lambda in [0, 1] (Alg. 2; Eq. acc_relax); NaN fails.  Any pointer
+ * may be NULL (that check is skipped).  Blocking: enqueues one kernel on `stream`, waits, and allocates and
+ * frees four bytes of device memory.  violations (nullable, [host]): bit 0 t, bit 1 sigma, bit 2 u,
+ * bit 3 lambda.  Returns FREE_OK, FREE_ERR_RANGE if any value is out of range, FREE_ERR_SHAPE for negative
+ * counts or T < 1, FREE_ERR_HIP. */
+int32_t free_validate_inputs(const int32_t* t, int64_t n_t, int32_t T, const float* sigma, const float* u,
+                             const float* lambda, int64_t n, uint32_t* violations, void* stream);
+
 /* The family of reverse processes with a stochasticity parameter e >= 0 (App. on the
  * stochasticity hyperparameter, Eq. mean_var_gamma): one Euler step of
  *   dY = [ -f(Y) + (1 + e^2)/2 g^2 s(Y) ] dt + e g dW

@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = [
     "drafter_forward", "draft_round", "free_sample_workspace_bytes", "free_sample",
     "free_self_speculative_workspace_bytes", "free_self_speculative", "free_lambda_profile",
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
-    "free_profile_begin", "free_profile_end", "free_profile_category_name", "free_mfma_ceiling",
+    "free_profile_begin", "free_profile_end", "free_profile_category_name", "free_mfma_ceiling", "free_validate_inputs",
 ]
 PROF_NCAT = 13
 
@@ -118,6 +118,8 @@ def load():
     lib.free_profile_begin.restype = i32
     lib.free_profile_end.restype = i32
     lib.free_profile_end.argtypes = [vp, vp]
+    lib.free_validate_inputs.restype = i32
+    lib.free_validate_inputs.argtypes = [vp, i64, i32, vp, vp, vp, i64, vp, vp]
     lib.free_mfma_ceiling.restype = i32
     lib.free_mfma_ceiling.argtypes = [i32, vp, vp, vp]
     lib.free_profile_category_name.restype = C.c_char_p
@@ -181,6 +183,21 @@ def profile_end() -> dict:
     cnt = np.zeros(PROF_NCAT, np.int32)
     _check(load().free_profile_end(ms.ctypes.data, cnt.ctypes.data), "free_profile_end")
     return {load().free_profile_category_name(c).decode(): (float(ms[c]), int(cnt[c])) for c in range(PROF_NCAT)}
+
+
+def validate_inputs(t=None, T: int = 1000, sigma=None, u=None, lam=None) -> int:
+    """Blocking range check of device tensors (any may be None); returns the bit mask of violations
+    (0 = all in range; bit 0 t, bit 1 sigma, bit 2 u, bit 3 lambda)."""
+    n = max([x.numel() for x in (sigma, u, lam) if x is not None], default=0)
+    for x in (sigma, u, lam):
+        if x is not None and x.numel() != n:
+            raise ValueError("sigma, u and lambda must have the same number of elements")
+    mask = C.c_uint32(0)
+    st = load().free_validate_inputs(_ptr(t), 0 if t is None else t.numel(), int(T), _ptr(sigma), _ptr(u), _ptr(lam),
+                                     n, C.addressof(mask), _stream())
+    if st not in (FREE_OK, FREE_ERR_RANGE):
+        _check(st, "free_validate_inputs")
+    return int(mask.value)
 
 
 def mfma_ceiling(iters: int = 200000) -> dict:

@@ -1061,6 +1061,24 @@ __global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, in
     if (i < n4) reinterpret_cast<float4*>(p)[i] = float4{v, v, v, v};
 }
 
+// Range checks of device-resident inputs (opt-in, never on the hot path): bit 0 a timestep outside [0, T),
+// bit 1 a sigma that is not positive and finite, bit 2 a uniform outside [0, 1], bit 3 a lambda outside
+// [0, 1] (NaN fails every check).  Violations are OR-ed into *flags.
+__global__ __launch_bounds__(256) void validate_kernel(const int32_t* __restrict__ t, int64_t n_t, int32_t T,
+                                                       const float* __restrict__ sigma, const float* __restrict__ u,
+                                                       const float* __restrict__ lambda, int64_t n,
+                                                       unsigned int* __restrict__ flags) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    unsigned int bad = 0;
+    if (t && i < n_t && (t[i] < 0 || t[i] >= T)) bad |= 1u;
+    if (i < n) {
+        if (sigma && !(sigma[i] > 0.f && sigma[i] < INFINITY)) bad |= 2u;
+        if (u && !(u[i] >= 0.f && u[i] <= 1.f)) bad |= 4u;
+        if (lambda && !(lambda[i] >= 0.f && lambda[i] <= 1.f)) bad |= 8u;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
 // x_next = m + sigma[k] * xi  (the draw of the next draft from its proposal, Alg. 1)
 __global__ __launch_bounds__(256) void gauss_step_kernel(const float* __restrict__ m, const float* __restrict__ sigma_k,
                                                          const float* __restrict__ xi, int64_t n,
@@ -1146,6 +1164,30 @@ int32_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t s) {
     if (n % 4 || (reinterpret_cast<uintptr_t>(p) & 15u)) return FREE_ERR_SHAPE;
     hipLaunchKernelGGL(fill_f32_kernel, dim3(static_cast<unsigned>((n / 4 + 255) / 256)), dim3(256), 0, s, p, n / 4, v);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+}
+
+int32_t run_validate(const int32_t* t, int64_t n_t, int32_t T, const float* sigma, const float* u,
+                     const float* lambda, int64_t n, uint32_t* violations, hipStream_t s) {
+    unsigned int* flags = nullptr;
+    if (!hip_ok(hipMalloc(&flags, sizeof(unsigned int)))) return FREE_ERR_HIP;
+    unsigned int host = 0;
+    int32_t rc = FREE_ERR_HIP;
+    do {
+        if (!hip_ok(hipMemcpyAsync(flags, &host, sizeof(host), hipMemcpyHostToDevice, s))) break;
+        const int64_t most = n_t > n ? n_t : n;
+        if (most > 0) {
+            hipLaunchKernelGGL(validate_kernel, dim3(static_cast<unsigned>((most + 255) / 256)), dim3(256), 0, s, t, n_t,
+                               T, sigma, u, lambda, n, flags);
+            if (!launch_ok()) break;
+        }
+        if (!hip_ok(hipMemcpyAsync(&host, flags, sizeof(host), hipMemcpyDeviceToHost, s))) break;
+        if (!hip_ok(hipStreamSynchronize(s))) break;
+        rc = FREE_OK;
+    } while (false);
+    (void)hipFree(flags);
+    if (rc != FREE_OK) return rc;
+    if (violations) *violations = host;
+    return host ? FREE_ERR_RANGE : FREE_OK;
 }
 
 int32_t launch_gauss_step(const float* m, const float* sigma_k, const float* xi, int64_t n, float* out,

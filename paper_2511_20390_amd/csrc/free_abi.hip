@@ -378,6 +378,14 @@ int32_t free_profile_end(float* ms, int32_t* launches) {
     return FREE_OK;
 }
 
+int32_t free_validate_inputs(const int32_t* t, int64_t n_t, int32_t T, const float* sigma, const float* u,
+                             const float* lambda, int64_t n, uint32_t* violations, void* stream) {
+    if (n_t < 0 || n < 0 || (t && T < 1)) return FREE_ERR_SHAPE;
+    if (n_t > (1ll << 38) || n > (1ll << 38)) return FREE_ERR_SHAPE;
+    return run_validate(t, t ? n_t : 0, T, sigma, u, lambda, (sigma || u || lambda) ? n : 0, violations,
+                        static_cast<hipStream_t>(stream));
+}
+
 int32_t free_mfma_ceiling(int32_t iters, double* tflops, double* mhz, void* stream) {
     if (!tflops || !mhz) return FREE_ERR_NULL;
     if (iters < 1 || iters > (1 << 24)) return FREE_ERR_RANGE;

@@ -139,6 +139,9 @@ int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_
 int32_t launch_fuse_pack(const float* emb, const float* feat, int64_t M, int32_t D, int32_t dtype, void* fin,
                          hipStream_t s);
 int32_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t s);
+// blocking range check of device-resident inputs (any pointer may be null); bit mask of violations
+int32_t run_validate(const int32_t* t, int64_t n_t, int32_t T, const float* sigma, const float* u,
+                     const float* lambda, int64_t n, uint32_t* violations, hipStream_t s);
 // calib.hip: register-only MFMA loop on every CU; sustained TFLOP/s and shader clock (MHz) while it runs
 int32_t run_mfma_ceiling(int32_t iters, double* tflops, double* mhz, hipStream_t s);
 int32_t launch_gauss_step(const float* m, const float* sigma_k, const float* xi, int64_t n, float* out,

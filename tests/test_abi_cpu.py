@@ -78,6 +78,10 @@ def test_argument_errors_are_status_codes(lib):
     assert lib.free_mfma_ceiling(1000, None, one, None) == binding.FREE_ERR_NULL
     assert lib.free_mfma_ceiling(0, one, one, None) == binding.FREE_ERR_RANGE
     assert lib.free_mfma_ceiling((1 << 24) + 1, one, one, None) == binding.FREE_ERR_RANGE
+    # validation helper: negative counts and T < 1 fail before any device call
+    assert lib.free_validate_inputs(one, -1, 1000, None, None, None, 0, None, None) == binding.FREE_ERR_SHAPE
+    assert lib.free_validate_inputs(one, 4, 0, None, None, None, 0, None, None) == binding.FREE_ERR_SHAPE
+    assert lib.free_validate_inputs(None, 0, 1000, one, None, None, -5, None, None) == binding.FREE_ERR_SHAPE
     # spec_verify: null pointer, bad shape
     assert lib.spec_verify(None, one, one, one, one, None, 1, 6, 64, one, one, one, one, one, 4096, None) == binding.FREE_ERR_NULL
     assert lib.spec_verify(one, one, one, one, one, None, 1, 0, 64, one, one, one, one, one, 4096, None) == binding.FREE_ERR_SHAPE

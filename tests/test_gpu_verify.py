@@ -84,3 +84,35 @@ def test_verify_full_size_config(delta):
 
 def test_verify_full_size_relaxed():
     pu.run_verify_parity(n_traj=64, K=6, d=16384, delta=0.01, seed=77, relaxed=True)
+
+
+def test_validate_inputs_flags_each_kind_of_violation():
+    """The opt-in range check of device-resident inputs: clean inputs pass; a timestep outside [0, T), a
+    sigma that is zero / negative / NaN, a uniform above one and a lambda below zero each set their own bit
+    (bit 0 t, 1 sigma, 2 u, 3 lambda), wherever in the arrays they sit."""
+    import torch
+    from paper_2511_20390_amd import binding
+    n_traj, K = 37, 6
+    rng = np.random.default_rng(5)
+    t = torch.from_numpy(rng.integers(0, 1000, 300).astype(np.int32)).cuda()
+    sigma = torch.from_numpy(rng.uniform(0.01, 1.0, (n_traj, K)).astype(np.float32)).cuda()
+    u = torch.from_numpy(rng.uniform(0.0, 1.0, (n_traj, K)).astype(np.float32)).cuda()
+    u[0, 0], u[1, 1] = 0.0, 1.0                      # both ends are allowed
+    lam = torch.from_numpy(rng.uniform(0.0, 1.0, (n_traj, K)).astype(np.float32)).cuda()
+    assert binding.validate_inputs(t, 1000, sigma, u, lam) == 0
+    assert binding.validate_inputs(None, 1000, sigma, None, None) == 0
+    for bit, make in [(1, lambda: t.index_put_((torch.tensor([299]).cuda(),), torch.tensor([1000], dtype=torch.int32).cuda())),
+                      (1, lambda: t.index_put_((torch.tensor([0]).cuda(),), torch.tensor([-1], dtype=torch.int32).cuda())),
+                      (2, lambda: sigma.__setitem__((36, 5), 0.0)),
+                      (2, lambda: sigma.__setitem__((3, 2), float("nan"))),
+                      (2, lambda: sigma.__setitem__((3, 2), float("inf"))),
+                      (4, lambda: u.__setitem__((20, 3), 1.0001)),
+                      (8, lambda: lam.__setitem__((0, 0), -1e-6))]:
+        tc, sc, uc, lc = t.clone(), sigma.clone(), u.clone(), lam.clone()
+        make()
+        assert binding.validate_inputs(t, 1000, sigma, u, lam) == bit
+        t, sigma, u, lam = tc, sc, uc, lc
+    u[5, 5] = 2.0
+    lam[6, 0] = 7.0
+    assert binding.validate_inputs(t, 1000, sigma, u, lam) == 4 | 8
+    assert binding.validate_inputs(t, 500, None, None, None) == 1     # the same timesteps against a shorter schedule
