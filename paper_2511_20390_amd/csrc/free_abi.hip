@@ -644,6 +644,8 @@ int32_t free_op_ln_modulate(const float* x, const float* shift, const float* sca
 namespace {
 
 // Workspace of the drafter on B samples.
+constexpr int kHoistRows = 16;          // samples of one adaLN pass
+
 struct DraftLayout {
     size_t cond_h, sc, mod, tpack, ypack, emb, fin, xn, qkv, att, hmid, eps, feat, total;
 };
@@ -654,11 +656,14 @@ DraftLayout make_draft_layout(const Dims& d, int32_t mod_rows, int32_t B) {
     const size_t M = static_cast<size_t>(B) * d.ntok;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
-    L.cond_h = take(static_cast<size_t>(B) * (d.tfreq + d.D) * 4);
-    L.sc = take(static_cast<size_t>(B) * d.D * 4);
-    L.mod = take(static_cast<size_t>(B) * mod_rows * 4);
-    L.tpack = take(static_cast<size_t>(B) * 4);
-    L.ypack = take(static_cast<size_t>(B) * 4);
+    // conditioning buffers hold at least kHoistRows samples: draft_round computes the conditioning and the
+    // modulation vectors of all its K steps (their timesteps are known up front) in one go
+    const size_t CB = static_cast<size_t>(B > kHoistRows ? B : kHoistRows);
+    L.cond_h = take(CB * (d.tfreq + d.D) * 4);
+    L.sc = take(CB * d.D * 4);
+    L.mod = take(CB * mod_rows * 4);
+    L.tpack = take(CB * 4);
+    L.ypack = take(CB * 4);
     L.emb = take(M * d.D * 4);
     L.fin = take(M * 2 * d.D * es);
     L.xn = take(M * d.D * es);
@@ -674,27 +679,41 @@ DraftLayout make_draft_layout(const Dims& d, int32_t mod_rows, int32_t B) {
 // One drafter evaluation (Sec. 3.2).  Sample b reads the latent x[b % x_mod]; f_out doubles as the
 // residual stream of the drafter's blocks (it IS the predicted feature when they are done), and
 // f_prev is consumed before f_out is first written, so the two may alias.
+// Conditioning (shared embedding layers of the target) and the drafter's modulation vectors for B samples.
+int32_t drafter_modulation(free_drafter_t dr, const int32_t* t, const int32_t* y, int32_t B, float* cond_h, float* sc,
+                           float* mod, hipStream_t s) {
+    free_dit_t h = dr->target;
+    const Dims& d = h->dims;
+    FREE_TRY(launch_conditioning(t, y, B, d.D, d.tfreq, static_cast<const float*>(h->w[W_T_W1]),
+                                 static_cast<const float*>(h->w[W_T_B1]), static_cast<const float*>(h->w[W_T_W2]),
+                                 static_cast<const float*>(h->w[W_T_B2]),
+                                 static_cast<const float*>(h->w[W_Y_TABLE]), cond_h, sc, s));
+    if (d.mode == FREE_BF16 && adaln_mfma_supported(d.D, dr->mod_rows))
+        return launch_adaln_mfma(sc, B, d.D, dr->ada_w_tab, dr->ada_b_tab, dr->ada_row_start, dr->depth + 1,
+                                 dr->mod_rows, mod, s);
+    return launch_adaln(sc, B, d.D, dr->ada_w_tab, dr->ada_b_tab, dr->ada_row_start, dr->depth + 1, dr->mod_rows,
+                        d.mode, mod, s);
+}
+
+// mod_pre (nullable): modulation vectors computed by the caller, sample b at mod_pre + b * mod_stride; then t
+// and y are not read.
 int32_t drafter_forward_impl(free_drafter_t dr, const float* x, int32_t x_mod, const float* f_prev, const int32_t* t,
-                             const int32_t* y, int32_t B, float* eps_out, float* f_out, char* ws, hipStream_t s) {
+                             const int32_t* y, int32_t B, float* eps_out, float* f_out, char* ws, hipStream_t s,
+                             const float* mod_pre = nullptr, int32_t mod_stride = 0) {
     free_dit_t h = dr->target;
     const Dims& d = h->dims;
     const DraftLayout L = make_draft_layout(d, dr->mod_rows, B);
     const int64_t M = static_cast<int64_t>(B) * d.ntok;
     float* cond_h = reinterpret_cast<float*>(ws + L.cond_h);
     float* sc = reinterpret_cast<float*>(ws + L.sc);
-    float* mod = reinterpret_cast<float*>(ws + L.mod);
+    const float* mod = mod_pre;
+    if (!mod_pre) {
+        FREE_TRY(drafter_modulation(dr, t, y, B, cond_h, sc, reinterpret_cast<float*>(ws + L.mod), s));
+        mod = reinterpret_cast<float*>(ws + L.mod);
+        mod_stride = dr->mod_rows;
+    }
     float* emb = reinterpret_cast<float*>(ws + L.emb);
     void* fin = ws + L.fin;
-    FREE_TRY(launch_conditioning(t, y, B, d.D, d.tfreq, static_cast<const float*>(h->w[W_T_W1]),
-                                 static_cast<const float*>(h->w[W_T_B1]), static_cast<const float*>(h->w[W_T_W2]),
-                                 static_cast<const float*>(h->w[W_T_B2]),
-                                 static_cast<const float*>(h->w[W_Y_TABLE]), cond_h, sc, s));
-    if (d.mode == FREE_BF16 && adaln_mfma_supported(d.D, dr->mod_rows))
-        FREE_TRY(launch_adaln_mfma(sc, B, d.D, dr->ada_w_tab, dr->ada_b_tab, dr->ada_row_start, dr->depth + 1,
-                                   dr->mod_rows, mod, s));
-    else
-        FREE_TRY(launch_adaln(sc, B, d.D, dr->ada_w_tab, dr->ada_b_tab, dr->ada_row_start, dr->depth + 1,
-                              dr->mod_rows, d.mode, mod, s));
     FREE_TRY(launch_patch_embed(x, x_mod, B, d.C, d.H, d.W, d.p, d.D, static_cast<const float*>(h->w[W_PATCH_W]),
                                 static_cast<const float*>(h->w[W_PATCH_B]), h->pos, emb, s));
     // z = fuse_w [emb | f_prev] + fuse_b, accumulated in fp32 straight into the residual stream:
@@ -704,9 +723,9 @@ int32_t drafter_forward_impl(free_drafter_t dr, const float* x, int32_t x_mod, c
     FREE_TRY(linear_dispatch(d, fin, dr->w[0], static_cast<const float*>(dr->w[1]), static_cast<int32_t>(M), d.D,
                              2 * d.D, FREE_EPI_GATE_RESID, nullptr, f_out, RowVec{dr->ones, 0, 1}, s));
     const ActBufs act{f_out, ws + L.xn, ws + L.qkv, ws + L.att, ws + L.hmid};
-    FREE_TRY(run_block_stack(d, dr->blkw(), dr->depth, mod, dr->mod_rows, act, 0, B, s));
-    RowVec fsh{mod + static_cast<int64_t>(dr->depth) * 6 * d.D, dr->mod_rows, d.ntok};
-    RowVec fsc{mod + static_cast<int64_t>(dr->depth) * 6 * d.D + d.D, dr->mod_rows, d.ntok};
+    FREE_TRY(run_block_stack(d, dr->blkw(), dr->depth, mod, mod_stride, act, 0, B, s));
+    RowVec fsh{mod + static_cast<int64_t>(dr->depth) * 6 * d.D, mod_stride, d.ntok};
+    RowVec fsc{mod + static_cast<int64_t>(dr->depth) * 6 * d.D + d.D, mod_stride, d.ntok};
     return launch_final_layer(f_out, fsh, fsc, B, d.gh, d.gw, d.p, d.c_out, d.D, dr->fin(F_W),
                               static_cast<const float*>(dr->fin(F_B)), d.mode, eps_out, s);
 }
@@ -824,12 +843,27 @@ int32_t draft_round(free_drafter_t dr, const float* x_a, const float* f_a, const
         return FREE_ERR_HIP;
     if (feat != f_a && !hip_ok(hipMemcpyAsync(feat, f_a, feat_bytes, hipMemcpyDeviceToDevice, s)))
         return FREE_ERR_HIP;
+    // The timesteps of all K steps are known: their conditioning and modulation vectors are computed in one
+    // pass (packed as [cond x K | null x K], so step k reads samples k and K + k), not once per step.
+    const bool hoist = K * dup <= kHoistRows;
+    const float* mod_all = nullptr;
+    if (hoist) {
+        FREE_TRY(launch_pack_cond(t, y, d.classes, K, dup, tp, yp, s));
+        FREE_TRY(drafter_modulation(dr, tp, yp, K * dup, reinterpret_cast<float*>(ws + L.cond_h),
+                                    reinterpret_cast<float*>(ws + L.sc), reinterpret_cast<float*>(ws + L.mod), s));
+        mod_all = reinterpret_cast<const float*>(ws + L.mod);
+    }
     for (int k = 0; k < K; ++k) {
         const float* xk = x_states + static_cast<int64_t>(k) * d.d;
         float* mk = m_draft + static_cast<int64_t>(k) * d.d;
         float* xn = k + 1 < K ? x_states + static_cast<int64_t>(k + 1) * d.d : x_last;
-        FREE_TRY(launch_pack_cond(t + k, y, d.classes, 1, dup, tp, yp, s));
-        FREE_TRY(drafter_forward_impl(dr, xk, 1, feat, tp, yp, dup, eps, feat, ws, s));
+        if (hoist) {
+            FREE_TRY(drafter_forward_impl(dr, xk, 1, feat, nullptr, nullptr, dup, eps, feat, ws, s,
+                                          mod_all + static_cast<int64_t>(k) * dr->mod_rows, K * dr->mod_rows));
+        } else {
+            FREE_TRY(launch_pack_cond(t + k, y, d.classes, 1, dup, tp, yp, s));
+            FREE_TRY(drafter_forward_impl(dr, xk, 1, feat, tp, yp, dup, eps, feat, ws, s));
+        }
         FREE_TRY(launch_eps_to_mean(eps, xk, coef_x + k, coef_eps + k, cfg_scale, 1, d.C, d.c_out, hw, mk, s));
         FREE_TRY(launch_gauss_step(mk, sigma + k, xi + static_cast<int64_t>(k) * d.d, d.d, xn, s));
     }
