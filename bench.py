@@ -89,6 +89,11 @@ def bench_round(args):
         model.spec_round(a["x_states"], a["x_last"], a["m_draft"], a["t"], ri["y"], scale, a["coef_x"],
                          a["coef_eps"], a["sigma"], a["u"], a["lam"] if args.relaxed else None, out=out)
 
+    if args.draft_only:
+        res = {"drafting": bench_draft(args, cfg, model, ri, (cx, ce, sg), a, step)}
+        model.close()
+        return res, cfg, w, ri, (cx, ce, sg)
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -405,6 +410,8 @@ def main():
     ap.add_argument("--no-mfma-calibration", action="store_true",
                     help="skip the register-only MFMA loop that reports the device's sustained matrix rate and clock")
     ap.add_argument("--no-draft-bench", action="store_true")
+    ap.add_argument("--draft-only", action="store_true",
+                    help="time only the drafting round (the step before the hot path), e.g. under rocprofv3")
     ap.add_argument("--loop", action="store_true", help="time the whole sampler (Alg. 1) instead of the verification round")
     ap.add_argument("--loop-steps", type=int, default=250)
     ap.add_argument("--loop-images", type=int, default=1)
@@ -434,6 +441,11 @@ def main():
                           "dtype": args.mode, "data": "synthetic", "higher_is_better": False, **bench_loop(args)}))
         return
     res, cfg, w, ri, sched = bench_round(args)
+    if args.draft_only:
+        print(json.dumps({"metric": "drafting round (K sequential drafter steps)", "unit": "ms", "n_gpus": 1,
+                          "dtype": args.mode, "data": "synthetic", "higher_is_better": False,
+                          "value": res["drafting"]["ms_per_draft_round"], **res["drafting"]}))
+        return
     rounds_per_s = 1e3 / res["ms_per_step"]
     line = {
         "metric": "packed DiT-XL/2 verify rounds/s at 512^2 (K=6)", "value": rounds_per_s, "unit": "rounds/s",
