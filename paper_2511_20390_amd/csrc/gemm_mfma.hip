@@ -584,7 +584,18 @@ int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, 
         const double tiles = static_cast<double>((M + 95) / 96) * ((N + 127) / 128);
         if (tiles <= cus && M <= 4096) t96 = ((K + BK - 1) / BK) * 0.47 + 4.0;      // measured 0.47 us per slice
     }
-    const double best = std::fmin(std::fmin(std::fmin(t256, t384), std::fmin(t2x1, t128)), t96);
+    // 160 x 128 (same shape of workgroup, 160 x 32 per wavefront): for few rows and many columns, where 128 x 128
+    // tiles spill into a second round (2048 x 4608: 576 tiles on 512 slots; 468 of 160 x 128).  Measured about
+    // 1.25 x the slice time of 128 x 128, alone and shared.
+    double t160 = 1e30;
+    if (M <= 4096) {
+        const double tiles = static_cast<double>((M + 159) / 160) * ((N + 127) / 128);
+        const int nk = (K + BK - 1) / BK;
+        if (tiles <= cus) t160 = nk * 0.80 + 4.0;
+        else if (tiles <= 2.0 * cus) t160 = nk * 1.40 + 4.0;
+    }
+    const double best = std::fmin(std::fmin(std::fmin(t256, t384), std::fmin(t2x1, t128)), std::fmin(t96, t160));
+    if (best == t160) return launch_cfg<160, 128, 1, 4>(X, W, bias, M, N, K, epi, out, resid, gate, s);
     if (best == t96) return launch_cfg<96, 128, 1, 4>(X, W, bias, M, N, K, epi, out, resid, gate, s);
     if (best == t384) return launch_cfg<384, 192, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
     if (best == t256) return launch_cfg<256, 256, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
