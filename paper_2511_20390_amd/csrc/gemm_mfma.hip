@@ -7,7 +7,7 @@
 // Design for gfx950 (64-wide wavefronts, 160 KB LDS per CU, 512 registers per lane):
 //  * workgroup = 4 or 8 wavefronts in a WGM x WGN grid, macro tile BM x BN (256x256 and
 //    384x192 with 8 wavefronts - two per SIMD, so one wavefront's memory instructions issue
-//    under the other's MFMAs - 256x128 / 128x128 with 4 for small problems), K slices of
+//    under the other's MFMAs - 256x128 / 128x128 / 96x128 / 160x128 with 4 for small problems), K slices of
 //    64; each wavefront owns (BM/WGM) x (BN/WGN) as TM x TN MFMA tiles of 32x32 and keeps
 //    the accumulators in registers for the whole K loop.
 //  * the MFMA takes the WEIGHT rows as its A operand and the activation rows as its
