@@ -764,10 +764,14 @@ __global__ __launch_bounds__(kThreads) void final_layer_vec_kernel(
 // Guidance + eps -> mean (Eq. ddpm_update): m_k = coef_x[k] x_k + coef_eps[k] eps_k,
 // eps = eps_null + s (eps_cond - eps_null) when the batch carries both halves.
 // ---------------------------------------------------------------------------
-__global__ void eps_to_mean_kernel(const float* __restrict__ eps_out, const float* __restrict__ x_states,
+// Optionally also the draw of the next state, x_next = m + sigma_step[k] * xi (Alg. 1: next draft, or the
+// plain target step); x_next may be x_states itself (each thread reads its element before it writes it).
+__global__ void eps_to_mean_kernel(const float* __restrict__ eps_out, const float* x_states,
                                    const float* __restrict__ coef_x, const float* __restrict__ coef_eps,
                                    float cfg_scale, int32_t use_cfg, int32_t K, int32_t C, int32_t c_out,
-                                   int64_t hw, float* __restrict__ m_out, float* __restrict__ eps_guided) {
+                                   int64_t hw, float* __restrict__ m_out, float* __restrict__ eps_guided,
+                                   const float* __restrict__ sigma_step, const float* __restrict__ xi,
+                                   float* x_next) {
     const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     const int64_t per = static_cast<int64_t>(C) * hw;
     if (idx >= per * K) return;
@@ -778,8 +782,10 @@ __global__ void eps_to_mean_kernel(const float* __restrict__ eps_out, const floa
         const float en = eps_out[static_cast<int64_t>(K + k) * c_out * hw + rem];
         eps = fmaf(cfg_scale, eps - en, en);
     }
-    m_out[idx] = fmaf(coef_x[k], x_states[idx], coef_eps[k] * eps);
+    const float m = fmaf(coef_x[k], x_states[idx], coef_eps[k] * eps);
+    m_out[idx] = m;
     if (eps_guided) eps_guided[idx] = eps;
+    if (x_next) x_next[idx] = fmaf(sigma_step[k], xi[idx], m);
 }
 
 __global__ void pack_cond_kernel(const int32_t* __restrict__ t, int32_t y, int32_t null_label, int32_t K,
@@ -1036,10 +1042,12 @@ int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B
 }
 
 // ---- drafter helpers (Sec. 3.2: FC layer on [embedding | propagated feature]; Alg. 1 drafting loop) ----
-// fin[m, 0:D] = emb[m, :], fin[m, D:2D] = feat[m, :] in the compute type; 4 elements per thread (D % 4 == 0)
+// fin[m, 0:D] = emb[m, :], fin[m, D:2D] = feat[m, :] in the compute type; 4 elements per thread (D % 4 == 0).
+// zero_out (nullable, [M, D], may be feat itself): cleared on the way - the stream the fusion GEMM then
+// accumulates into; the thread that clears an element of feat is the one that has just read it.
 template <typename OT>
-__global__ __launch_bounds__(256) void fuse_pack_kernel(const float* __restrict__ emb, const float* __restrict__ feat,
-                                                        int64_t M, int32_t D, OT* __restrict__ fin) {
+__global__ __launch_bounds__(256) void fuse_pack_kernel(const float* __restrict__ emb, const float* feat, int64_t M,
+                                                        int32_t D, OT* __restrict__ fin, float* zero_out) {
     const int64_t q = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;       // group of 4 output elements
     const int32_t per_row = 2 * D / 4;
     if (q >= M * per_row) return;
@@ -1047,6 +1055,7 @@ __global__ __launch_bounds__(256) void fuse_pack_kernel(const float* __restrict_
     const int32_t c = static_cast<int32_t>(q % per_row) * 4;
     const float4 v = c < D ? *reinterpret_cast<const float4*>(emb + m * D + c)
                            : *reinterpret_cast<const float4*>(feat + m * D + (c - D));
+    if (zero_out && c >= D) *reinterpret_cast<float4*>(zero_out + m * D + (c - D)) = float4{0.f, 0.f, 0.f, 0.f};
     OT* o = fin + m * 2 * D + c;
     if constexpr (sizeof(OT) == 2) {
         uint2 pk = {pack_bf16_pair(v.x, v.y), pack_bf16_pair(v.z, v.w)};
@@ -1054,11 +1063,6 @@ __global__ __launch_bounds__(256) void fuse_pack_kernel(const float* __restrict_
     } else {
         *reinterpret_cast<float4*>(o) = v;
     }
-}
-
-__global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, int64_t n4, float v) {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (i < n4) reinterpret_cast<float4*>(p)[i] = float4{v, v, v, v};
 }
 
 // Range checks of device-resident inputs (opt-in, never on the hot path): bit 0 a timestep outside [0, T),
@@ -1079,13 +1083,6 @@ __global__ __launch_bounds__(256) void validate_kernel(const int32_t* __restrict
     if (bad) atomicOr(flags, bad);
 }
 
-// x_next = m + sigma[k] * xi  (the draw of the next draft from its proposal, Alg. 1)
-__global__ __launch_bounds__(256) void gauss_step_kernel(const float* __restrict__ m, const float* __restrict__ sigma_k,
-                                                         const float* __restrict__ xi, int64_t n,
-                                                         float* __restrict__ out) {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (i < n) out[i] = fmaf(sigma_k[0], xi[i], m[i]);
-}
 
 // Frozen-target drafting (Sec. 2; used by the self-speculative run of Sec. 3.4): one noise estimate e is
 // reused for K steps, m^_k = coef_x[k] x^_k + coef_eps[k] e, x^_{k+1} = m^_k + sigma[k] xi[k]; every latent
@@ -1130,11 +1127,14 @@ __global__ __launch_bounds__(256) void sqdist_kernel(const float* __restrict__ a
 
 int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const float* coef_x,
                            const float* coef_eps, float cfg_scale, int32_t K, int32_t C, int32_t c_out,
-                           int64_t hw, float* m_out, hipStream_t s, float* eps_guided) {
+                           int64_t hw, float* m_out, hipStream_t s, float* eps_guided, const float* sigma_step,
+                           const float* xi, float* x_next) {
     const int64_t n = static_cast<int64_t>(K) * C * hw;
     const int use_cfg = cfg_scale > 1.0f ? 1 : 0;
+    if (x_next && (!sigma_step || !xi)) return FREE_ERR_NULL;
     hipLaunchKernelGGL(eps_to_mean_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, eps_out,
-                       x_states, coef_x, coef_eps, cfg_scale, use_cfg, K, C, c_out, hw, m_out, eps_guided);
+                       x_states, coef_x, coef_eps, cfg_scale, use_cfg, K, C, c_out, hw, m_out, eps_guided, sigma_step,
+                       xi, x_next);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 
@@ -1147,22 +1147,16 @@ int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_
 }
 
 int32_t launch_fuse_pack(const float* emb, const float* feat, int64_t M, int32_t D, int32_t dtype, void* fin,
-                         hipStream_t s) {
+                         float* zero_out, hipStream_t s) {
     if (D % 4) return FREE_ERR_SHAPE;
     const int64_t groups = M * (2 * D / 4);
     const unsigned blocks = static_cast<unsigned>((groups + 255) / 256);
     if (dtype == FREE_BF16)
         hipLaunchKernelGGL(fuse_pack_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, emb, feat, M, D,
-                           static_cast<bf16_t*>(fin));
+                           static_cast<bf16_t*>(fin), zero_out);
     else
         hipLaunchKernelGGL(fuse_pack_kernel<float>, dim3(blocks), dim3(256), 0, s, emb, feat, M, D,
-                           static_cast<float*>(fin));
-    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
-}
-
-int32_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t s) {
-    if (n % 4 || (reinterpret_cast<uintptr_t>(p) & 15u)) return FREE_ERR_SHAPE;
-    hipLaunchKernelGGL(fill_f32_kernel, dim3(static_cast<unsigned>((n / 4 + 255) / 256)), dim3(256), 0, s, p, n / 4, v);
+                           static_cast<float*>(fin), zero_out);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 
@@ -1188,13 +1182,6 @@ int32_t run_validate(const int32_t* t, int64_t n_t, int32_t T, const float* sigm
     if (rc != FREE_OK) return rc;
     if (violations) *violations = host;
     return host ? FREE_ERR_RANGE : FREE_OK;
-}
-
-int32_t launch_gauss_step(const float* m, const float* sigma_k, const float* xi, int64_t n, float* out,
-                          hipStream_t s) {
-    hipLaunchKernelGGL(gauss_step_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, s, m, sigma_k,
-                       xi, n, out);
-    return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 
 int32_t launch_frozen_draft(const float* x_a, const float* e, const float* coef_x, const float* coef_eps,

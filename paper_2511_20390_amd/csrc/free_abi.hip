@@ -718,8 +718,7 @@ int32_t drafter_forward_impl(free_drafter_t dr, const float* x, int32_t x_mod, c
                                 static_cast<const float*>(h->w[W_PATCH_B]), h->pos, emb, s));
     // z = fuse_w [emb | f_prev] + fuse_b, accumulated in fp32 straight into the residual stream:
     // residual epilogue on a zeroed stream with a gate of ones
-    FREE_TRY(launch_fuse_pack(emb, f_prev, M, d.D, d.mode, fin, s));
-    FREE_TRY(launch_fill_f32(f_out, M * d.D, 0.0f, s));
+    FREE_TRY(launch_fuse_pack(emb, f_prev, M, d.D, d.mode, fin, f_out, s));
     FREE_TRY(linear_dispatch(d, fin, dr->w[0], static_cast<const float*>(dr->w[1]), static_cast<int32_t>(M), d.D,
                              2 * d.D, FREE_EPI_GATE_RESID, nullptr, f_out, RowVec{dr->ones, 0, 1}, s));
     const ActBufs act{f_out, ws + L.xn, ws + L.qkv, ws + L.att, ws + L.hmid};
@@ -864,8 +863,8 @@ int32_t draft_round(free_drafter_t dr, const float* x_a, const float* f_a, const
             FREE_TRY(launch_pack_cond(t + k, y, d.classes, 1, dup, tp, yp, s));
             FREE_TRY(drafter_forward_impl(dr, xk, 1, feat, tp, yp, dup, eps, feat, ws, s));
         }
-        FREE_TRY(launch_eps_to_mean(eps, xk, coef_x + k, coef_eps + k, cfg_scale, 1, d.C, d.c_out, hw, mk, s));
-        FREE_TRY(launch_gauss_step(mk, sigma + k, xi + static_cast<int64_t>(k) * d.d, d.d, xn, s));
+        FREE_TRY(launch_eps_to_mean(eps, xk, coef_x + k, coef_eps + k, cfg_scale, 1, d.C, d.c_out, hw, mk, s, nullptr,
+                                    sigma + k, xi + static_cast<int64_t>(k) * d.d, xn));
     }
     return FREE_OK;
 }
@@ -957,8 +956,8 @@ int32_t sample_loop(free_dit_t h, free_drafter_t dr, const float* x_init, int32_
             FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, 1, dup, tp, yp, s));
             FREE_TRY(forward_impl(h, x_cur, 1, tp, yp, dup, F(o.eps), frozen ? nullptr : feat, ws + o.ws_target, s));
             FREE_TRY(launch_eps_to_mean(F(o.eps), x_cur, coef_x + i, coef_eps + i, cfg_scale, 1, d.C, d.c_out, hw,
-                                        F(o.m_target), s, frozen ? feat : nullptr));
-            FREE_TRY(launch_gauss_step(F(o.m_target), sigma + i, xi + static_cast<int64_t>(i) * d.d, d.d, x_cur, s));
+                                        F(o.m_target), s, frozen ? feat : nullptr, sigma + i,
+                                        xi + static_cast<int64_t>(i) * d.d, x_cur));
             have_feat = true;
             ++st[0];
             ++i;

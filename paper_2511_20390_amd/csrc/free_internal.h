@@ -131,21 +131,19 @@ int32_t launch_final_layer(const float* x, RowVec shift, RowVec scale, int32_t B
                            int32_t dtype, float* out, hipStream_t s);
 int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const float* coef_x,
                            const float* coef_eps, float cfg_scale, int32_t K, int32_t C, int32_t c_out,
-                           int64_t hw, float* m_out, hipStream_t s, float* eps_guided = nullptr);
+                           int64_t hw, float* m_out, hipStream_t s, float* eps_guided = nullptr,
+                           const float* sigma_step = nullptr, const float* xi = nullptr, float* x_next = nullptr);
 int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_t K, int32_t dup,
                          int32_t* t_out, int32_t* y_out, hipStream_t s);
 
-// drafter helpers: fin = [emb | feat] in the compute type; p[0:n] = v; out = m + sigma_k[0] * xi
+// drafter helper: fin = [emb | feat] in the compute type, zero_out (nullable) cleared
 int32_t launch_fuse_pack(const float* emb, const float* feat, int64_t M, int32_t D, int32_t dtype, void* fin,
-                         hipStream_t s);
-int32_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t s);
+                         float* zero_out, hipStream_t s);
 // blocking range check of device-resident inputs (any pointer may be null); bit mask of violations
 int32_t run_validate(const int32_t* t, int64_t n_t, int32_t T, const float* sigma, const float* u,
                      const float* lambda, int64_t n, uint32_t* violations, hipStream_t s);
 // calib.hip: register-only MFMA loop on every CU; sustained TFLOP/s and shader clock (MHz) while it runs
 int32_t run_mfma_ceiling(int32_t iters, double* tflops, double* mhz, hipStream_t s);
-int32_t launch_gauss_step(const float* m, const float* sigma_k, const float* xi, int64_t n, float* out,
-                          hipStream_t s);
 
 // frozen-target drafting of K steps from one noise estimate e [d]; out[k] = ||a_k - b_k||^2 (fp64)
 int32_t launch_frozen_draft(const float* x_a, const float* e, const float* coef_x, const float* coef_eps,
