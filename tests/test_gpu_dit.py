@@ -26,7 +26,8 @@ def _vals(a, mode):
 
 @pytest.mark.parametrize("mode", ["fp32", "bf16"])
 @pytest.mark.parametrize("M,N,K", [(96, 192, 64), (576, 432, 144), (300, 1152, 1152), (1536, 3456, 1152),
-                                   (257, 136, 328), (1024, 1152, 4608)])
+                                   (257, 136, 328), (1024, 1152, 4608), (1000, 1152, 2304),
+                                   (2048, 1152, 4608), (200, 136, 2176)])
 def test_op_linear(mode, M, N, K):
     import torch
     from paper_2511_20390_amd import binding
