@@ -391,6 +391,39 @@ def cpu_baseline(cfg, w, ri, sched, args):
                       f"{dt:.1f} s, scaled x{args.K}", "seconds_per_round_scaled": per_round}
 
 
+def bench_gemm(args):
+    """One linear layer of the given shape on seeded normal data (weights scaled by K^-1/2), timed with
+    events on the launch stream."""
+    import torch
+    from paper_2511_20390_amd import binding
+    M, N, K, epi = (int(v) for v in args.gemm_only.split(","))
+    g = torch.Generator(device="cuda").manual_seed(0)
+    dt = torch.bfloat16 if args.mode == "bf16" else torch.float32
+    X = torch.randn(M, K, device="cuda", generator=g).to(dt)
+    W = (torch.randn(N, K, device="cuda", generator=g) / K ** 0.5).to(dt)
+    bias = torch.randn(N, device="cuda", generator=g)
+    resid = torch.zeros(M, N, device="cuda") if epi == 2 else None
+    gate = torch.randn(1, N, device="cuda", generator=g) if epi == 2 else None
+
+    def run():
+        binding.op_linear(X, W, bias, args.mode, epi, resid=resid, gate=gate, rows_per_sample=M)
+
+    for _ in range(args.warmup):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / args.steps
+    return {"metric": "one linear layer", "unit": "us", "value": us, "higher_is_better": False, "n_gpus": 1,
+            "dtype": args.mode, "data": "synthetic", "steps": args.steps, "warmup": args.warmup,
+            "config": {"workload": f"linear {M} x {N} x {K}, epilogue {epi}"},
+            "tflops": 2.0 * M * N * K / us / 1e6}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -412,6 +445,9 @@ def main():
     ap.add_argument("--no-draft-bench", action="store_true")
     ap.add_argument("--draft-only", action="store_true",
                     help="time only the drafting round (the step before the hot path), e.g. under rocprofv3")
+    ap.add_argument("--gemm-only", default=None, metavar="M,N,K,EPI",
+                    help="time one linear layer out = epilogue(X W^T + b) of the given shape through the C ABI "
+                         "(EPI 0: bias, 1: bias + GELU, 2: gated fp32 residual update), e.g. under rocprofv3")
     ap.add_argument("--loop", action="store_true", help="time the whole sampler (Alg. 1) instead of the verification round")
     ap.add_argument("--loop-steps", type=int, default=250)
     ap.add_argument("--loop-images", type=int, default=1)
@@ -436,6 +472,9 @@ def main():
             torch.mul(src, 1.0, out=dst)      # one elementwise kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
+    if args.gemm_only:
+        print(json.dumps(bench_gemm(args)))
+        return
     if args.loop:
         print(json.dumps({"metric": "whole sampler (Alg. 1), wall time per image", "unit": "s", "n_gpus": 1,
                           "dtype": args.mode, "data": "synthetic", "higher_is_better": False, **bench_loop(args)}))
