@@ -94,6 +94,12 @@ def bench_round(args):
         model.close()
         return res, cfg, w, ri, (cx, ce, sg)
 
+    # set-up, untimed: with the default --streams 0 the library tries one and two streams in turn over its
+    # first six forwards at this batch size and decides at the seventh (one was made above)
+    if args.streams == 0:
+        for _ in range(6):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -102,19 +108,21 @@ def bench_round(args):
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    stream_choice = model.stream_choice() if args.streams == 0 else args.streams
 
-    # the same steps in the other stream mode (the per-kernel figures below refer to one stream)
-    other = 2 if binding.get_batch_streams() == 1 else 1
-    binding.set_batch_streams(other)
-    step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
+    # the same steps with each schedule forced (the per-kernel figures below refer to one stream)
+    forced = {}
+    for n in (1, 2):
+        binding.set_batch_streams(n)
         step()
-    torch.cuda.synchronize()
-    ms_other = (time.perf_counter() - t0) * 1e3 / args.steps
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        forced[n] = (time.perf_counter() - t0) * 1e3 / args.steps
     binding.set_batch_streams(args.streams)
-    ms_one_stream, ms_two_streams = (ms_per_step, ms_other) if other == 2 else (ms_other, ms_per_step)
+    ms_one_stream, ms_two_streams = forced[1], forced[2]
 
     # per-kernel durations: the same steps again, every launch bracketed by HIP events on its stream
     # (the library runs them in sequence on one stream while it profiles)
@@ -149,7 +157,7 @@ def bench_round(args):
     fwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if not k.startswith("verify") and k != "eps_to_mean")
     res = {
         "ms_per_step": ms_per_step, "ms_per_step_one_stream": ms_one_stream, "ms_per_step_two_streams": ms_two_streams,
-        "batch_streams": binding.get_batch_streams(), "kernels": kernels, "roofline": roofline,
+        "batch_streams": binding.get_batch_streams(), "stream_choice": stream_choice, "kernels": kernels, "roofline": roofline,
         "forward": {"algorithmic_tflop": total_flops / 1e12, "ms_sum_of_kernels": fwd_ms,
                     "tflops_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12,
                     "frac_of_peak_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12 / peak},
@@ -434,8 +442,9 @@ def main():
     ap.add_argument("--K", type=int, default=6)
     ap.add_argument("--cfg-scale", type=float, default=4.0)
     ap.add_argument("--relaxed", action="store_true")
-    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
-                    help="2: the halves of the packed batch run concurrently on two streams (library default); "
+    ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
+                    help="0 (library default): the library times one and two streams over its first forwards and "
+                         "keeps the faster; 2: the halves of the packed batch run concurrently on two streams; "
                          "1: every kernel in sequence on one stream (use this under rocprofv3 --kernel-trace so "
                          "that kernel durations are not inflated by overlap)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -496,7 +505,7 @@ def main():
                                f"guidance {args.cfg_scale} (packed batch {res['B']}, {res['tokens_per_round']} tokens), "
                                f"{'relaxed' if args.relaxed else 'strict'} rule",
                    "packed_batch": res["B"], "tokens": res["tokens_per_round"]},
-        "batch_streams": res["batch_streams"], "ms_per_step_one_stream": res["ms_per_step_one_stream"],
+        "batch_streams": res["batch_streams"], "stream_choice": res["stream_choice"], "ms_per_step_one_stream": res["ms_per_step_one_stream"],
         "ms_per_step_two_streams": res["ms_per_step_two_streams"],
         "roofline": res["roofline"], "forward": res["forward"], "kernels": res["kernels"],
     }

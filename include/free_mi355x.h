@@ -70,16 +70,24 @@ const char* free_status_string(int32_t status);
 int32_t free_last_hip_error(void);
 
 /* Execution of the packed target forward (Alg. 1: the K states of a round are
- * independent samples of one batch).  n = 2 (default): when a batch has at
- * least 2 samples and each half at least 2048 token rows, the two halves of
- * the batch run their transformer blocks concurrently on two streams owned by
- * the model handle; the work is forked from and joined back into the caller's
- * stream, so stream-ordered semantics towards the caller are unchanged and the
- * results are the same as with n = 1 (one stream, kernels in sequence).
- * Process-wide; not thread-safe against running calls.  FREE_ERR_RANGE for
- * any other n. */
+ * independent samples of one batch).  n = 2: when a batch has at least 2
+ * samples and each half at least 2048 token rows, the two halves of the batch
+ * run their transformer blocks concurrently on two streams owned by the model
+ * handle; the work is forked from and joined back into the caller's stream, so
+ * stream-ordered semantics towards the caller are unchanged and the results
+ * are the same as with n = 1 (one stream, kernels in sequence).  n = 0
+ * (default): which of the two is faster differs from machine to machine, so
+ * the first six eager forwards of a handle at a batch size of that kind use
+ * the two schedules in turn, timed with events on the caller's stream; the
+ * seventh waits for those six to finish and keeps the faster schedule for that
+ * batch size (a new batch size starts over).  Calls under stream capture never
+ * time anything: they use the schedule already chosen for their batch size,
+ * else two streams.  free_dit_stream_choice returns the handle's choice (0 while
+ * undecided, else 1 or 2; FREE_ERR_NULL).  The setting is process-wide and not
+ * thread-safe against running calls.  FREE_ERR_RANGE for any other n. */
 int32_t free_set_batch_streams(int32_t n);
 int32_t free_get_batch_streams(void);
+int32_t free_dit_stream_choice(free_dit_t h);
 
 /* Linear-beta DDPM schedule and the coefficients of the one-step update
  * (Eq. ddpm_update, App. C), 0-indexed by network timestep i in [0, T):

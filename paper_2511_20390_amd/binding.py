@@ -22,7 +22,7 @@ MODES = {"fp32": FREE_FP32, "bf16": FREE_BF16}
 
 EXPORTED_SYMBOLS = [
     "free_version", "free_status_string", "free_last_hip_error", "free_set_batch_streams",
-    "free_get_batch_streams", "free_ddpm_schedule", "free_sde_schedule",
+    "free_get_batch_streams", "free_dit_stream_choice", "free_ddpm_schedule", "free_sde_schedule",
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
     "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
     "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
@@ -67,6 +67,8 @@ def load():
     lib.free_set_batch_streams.restype = i32
     lib.free_set_batch_streams.argtypes = [i32]
     lib.free_get_batch_streams.restype = i32
+    lib.free_dit_stream_choice.restype = i32
+    lib.free_dit_stream_choice.argtypes = [vp]
     lib.free_ddpm_schedule.restype = i32
     lib.free_ddpm_schedule.argtypes = [i32, C.c_double, C.c_double, vp, vp, vp]
     lib.free_sde_schedule.restype = i32
@@ -165,7 +167,8 @@ def free_sde_schedule(stochasticity: float, T: int = 1000, beta_start: float = 1
 
 
 def set_batch_streams(n: int) -> None:
-    """1: kernels of a forward in sequence on the caller's stream; 2 (default): halves of a large batch on two streams."""
+    """1: kernels of a forward in sequence on the caller's stream; 2: halves of a large batch on two streams;
+    0 (default): the first forwards at a batch size time both and the faster one is kept."""
     _check(load().free_set_batch_streams(int(n)), "free_set_batch_streams")
 
 
@@ -257,6 +260,12 @@ class FreeDit:
         self.c_out = self.C * (2 if cfg["learn_sigma"] else 1)
         self.ntok = (self.H // cfg["patch"]) * (self.W // cfg["patch"])
         self.d = self.C * self.H * self.W
+
+    def stream_choice(self) -> int:
+        """What the timed choice between one and two streams has settled on (0 while undecided)."""
+        st = int(load().free_dit_stream_choice(self.handle))
+        _check(min(st, 0), "free_dit_stream_choice")
+        return st
 
     def close(self):
         if getattr(self, "handle", None) is not None and self.handle.value:

@@ -25,7 +25,8 @@ struct Profiler {
     size_t used = 0;
 };
 Profiler g_prof;
-int32_t g_batch_streams = 2;                  // 1: serial, 2: halves of a packed batch on two streams
+int32_t g_batch_streams = 0;                  // 1: serial, 2: halves of a packed batch on two streams, 0: timed choice
+constexpr int kTuneTrials = 6;                // calls that try the two modes in turn; the first two are not counted
 constexpr int64_t kMinSplitRows = 2048;       // token rows per half below which the split does not pay
 constexpr size_t kMaxProfSlots = 8192;
 }  // namespace
@@ -131,6 +132,14 @@ struct free_dit_s {
     hipStream_t side[2] = {nullptr, nullptr};
     hipEvent_t ev_fork = nullptr;
     hipEvent_t ev_join[2] = {nullptr, nullptr};
+    // Timed choice between one and two streams: the first kTuneTrials forwards at a batch size use the two
+    // modes in turn, bracketed by events on the caller's stream; the faster one is kept for that batch size.
+    struct StreamTune {
+        int32_t batch = 0;                    // batch size the trials refer to
+        int32_t trial = 0;                    // trials enqueued so far
+        int32_t choice = 0;                   // 0: undecided, else 1 or 2
+        hipEvent_t ev[kTuneTrials][2] = {};   // [trial][start, stop], created with the handle
+    } tune;
 
     const void* blk(int l, int which) const { return w[7 + 10 * l + which]; }
     const void* fin(int which) const { return w[7 + 10 * dims.depth + which]; }
@@ -249,6 +258,19 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
     return FREE_OK;
 }
 
+// Ends the trial phase: the shorter of the counted trials of each mode decides (ties go to one stream).
+int32_t choose_streams(free_dit_s::StreamTune* tn) {
+    float best[2] = {1e30f, 1e30f};
+    for (int i = 2; i < kTuneTrials; ++i) {
+        float ms = 0.f;
+        if (!hip_ok(hipEventSynchronize(tn->ev[i][1])) || !hip_ok(hipEventElapsedTime(&ms, tn->ev[i][0], tn->ev[i][1])))
+            return FREE_ERR_HIP;
+        if (ms < best[i & 1]) best[i & 1] = ms;
+    }
+    tn->choice = best[0] <= best[1] ? 1 : 2;
+    return FREE_OK;
+}
+
 int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t* t, const int32_t* y, int32_t B,
                      float* eps_out, float* top_feat, char* ws, hipStream_t s) {
     const Dims& d = h->dims;
@@ -293,12 +315,38 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     // halves that run on two streams forked from (and joined back into) the caller's stream: while
     // one half is in a bandwidth-bound phase (layer norm, the residual read-modify-write at the end
     // of a GEMM, the first and last wave of tiles) the other half's matrix kernels fill the idle
-    // compute units.  Measured at 12 x 1024 tokens on two machines of the same type: 15.0 ms per round on
-    // both with two streams; 14.6 ms on one and 15.4 ms on the other with one stream - the split is kept as
-    // the default for the steadier figure.  Per-kernel profiling needs serial execution, and small batches
-    // are launch bound, so both keep the single stream.
-    const bool split = g_batch_streams == 2 && !g_prof.on && B >= 2 &&
-                       static_cast<int64_t>(B / 2) * d.ntok >= kMinSplitRows;
+    // compute units.  Which schedule is faster differs between machines of the same type (12 x 1024 tokens,
+    // two streams / one stream: 15.0 / 14.6 ms, 15.0 / 15.4, 14.7 / 14.5, 14.8 / 14.2), so by default the
+    // first forwards at a batch size time both and the faster one is kept.  Both give the same numbers.
+    // Per-kernel profiling needs serial execution, and small batches are launch bound, so both keep the
+    // single stream.
+    const bool eligible = !g_prof.on && B >= 2 && static_cast<int64_t>(B / 2) * d.ntok >= kMinSplitRows;
+    int mode = g_batch_streams, trial = -1;
+    if (mode == 0) {
+        mode = 2;
+        free_dit_s::StreamTune& tn = h->tune;
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        if (eligible && !hip_ok(hipStreamIsCapturing(s, &capturing))) return FREE_ERR_HIP;
+        if (eligible && capturing != hipStreamCaptureStatusNone) {
+            // no timing inside a capture: what an earlier eager call at this batch size decided, else two streams
+            if (tn.batch == B && tn.choice) mode = tn.choice;
+        } else if (eligible) {
+            if (tn.batch != B) {
+                tn.batch = B;
+                tn.trial = 0;
+                tn.choice = 0;
+            }
+            if (!tn.choice && tn.trial == kTuneTrials) FREE_TRY(choose_streams(&tn));
+            if (tn.choice) {
+                mode = tn.choice;
+            } else {
+                trial = tn.trial++;
+                mode = 1 + (trial & 1);
+            }
+        }
+    }
+    const bool split = mode == 2 && eligible;
+    if (trial >= 0 && !hip_ok(hipEventRecord(h->tune.ev[trial][0], s))) return FREE_ERR_HIP;
     if (split) {
         if (!hip_ok(hipEventRecord(h->ev_fork, s))) return FREE_ERR_HIP;
         for (int i = 0; i < 2; ++i) {
@@ -311,6 +359,7 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     } else {
         FREE_TRY(run_blocks(0, B, s));
     }
+    if (trial >= 0 && !hip_ok(hipEventRecord(h->tune.ev[trial][1], s))) return FREE_ERR_HIP;
     if (top_feat) {
         if (!hip_ok(hipMemcpyAsync(top_feat, xres, static_cast<size_t>(M) * d.D * 4, hipMemcpyDeviceToDevice, s)))
             return FREE_ERR_HIP;
@@ -350,12 +399,17 @@ const char* free_status_string(int32_t st) {
 int32_t free_last_hip_error(void) { return g_last_hip_error; }
 
 int32_t free_set_batch_streams(int32_t n) {
-    if (n != 1 && n != 2) return FREE_ERR_RANGE;
+    if (n < 0 || n > 2) return FREE_ERR_RANGE;
     g_batch_streams = n;
     return FREE_OK;
 }
 
 int32_t free_get_batch_streams(void) { return g_batch_streams; }
+
+int32_t free_dit_stream_choice(free_dit_t h) {
+    if (!h) return FREE_ERR_NULL;
+    return h->tune.choice;
+}
 
 int32_t free_profile_begin(void) {
     g_prof.used = 0;
@@ -508,6 +562,8 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
     for (int i = 0; i < 2 && ok; ++i)
         ok = hip_ok(hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking)) &&
              hip_ok(hipEventCreateWithFlags(&h->ev_join[i], hipEventDisableTiming));
+    for (int i = 0; i < kTuneTrials && ok; ++i)
+        ok = hip_ok(hipEventCreate(&h->tune.ev[i][0])) && hip_ok(hipEventCreate(&h->tune.ev[i][1]));
     if (!ok) {
         (void)free_dit_destroy(h);
         return FREE_ERR_HIP;
@@ -525,6 +581,9 @@ int32_t free_dit_destroy(free_dit_t h) {
         if (h->ev_join[i] && !hip_ok(hipEventDestroy(h->ev_join[i]))) st = FREE_ERR_HIP;
     }
     if (h->ev_fork && !hip_ok(hipEventDestroy(h->ev_fork))) st = FREE_ERR_HIP;
+    for (int i = 0; i < kTuneTrials; ++i)
+        for (int j = 0; j < 2; ++j)
+            if (h->tune.ev[i][j] && !hip_ok(hipEventDestroy(h->tune.ev[i][j]))) st = FREE_ERR_HIP;
     if (h->dev_block && !hip_ok(hipFree(h->dev_block))) st = FREE_ERR_HIP;
     delete h;
     return st;

@@ -106,6 +106,13 @@ def test_argument_errors_are_status_codes(lib):
     cc.mode = 5
     assert lib.free_dit_create(C.byref(cc), arr, 31, C.byref(h)) == binding.FREE_ERR_DTYPE
     assert lib.free_dit_destroy(None) == binding.FREE_ERR_NULL
+    # schedule of the packed forward: 0 (timed choice, the default), 1 or 2 streams
+    assert lib.free_get_batch_streams() == 0
+    assert lib.free_set_batch_streams(3) == binding.FREE_ERR_RANGE
+    assert lib.free_set_batch_streams(-1) == binding.FREE_ERR_RANGE
+    assert lib.free_set_batch_streams(2) == binding.FREE_OK and lib.free_get_batch_streams() == 2
+    assert lib.free_set_batch_streams(0) == binding.FREE_OK
+    assert lib.free_dit_stream_choice(None) == binding.FREE_ERR_NULL
     assert lib.dit_forward_packed(None, one, one, one, 6, one, None, one, 1 << 20, None) == binding.FREE_ERR_NULL
     assert lib.spec_round(None, one, one, one, one, 0, 4.0, one, one, one, one, None, 6, None, one, one, one, one,
                           one, 1 << 20, None) == binding.FREE_ERR_NULL
