@@ -95,9 +95,11 @@ def bench_round(args):
         return res, cfg, w, ri, (cx, ce, sg)
 
     # set-up, untimed: with the default --streams 0 the library tries one and two streams in turn over its
-    # first six forwards at this batch size and decides at the seventh (one was made above)
+    # first 24 forwards at this batch size and decides at the next (one was made above)
     if args.streams == 0:
-        for _ in range(6):
+        for _ in range(64):
+            if model.stream_choice() != 0:
+                break
             step()
         torch.cuda.synchronize()
     for _ in range(args.warmup):

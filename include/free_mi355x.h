@@ -77,13 +77,15 @@ int32_t free_last_hip_error(void);
  * stream-ordered semantics towards the caller are unchanged and the results
  * are the same as with n = 1 (one stream, kernels in sequence).  n = 0
  * (default): which of the two is faster differs from machine to machine, so
- * the first six eager forwards of a handle at a batch size of that kind use
+ * the first 24 eager forwards of a handle at a batch size of that kind use
  * the two schedules in turn, timed with events on the caller's stream; the
- * seventh waits for those six to finish and keeps the faster schedule for that
- * batch size (a new batch size starts over).  Calls under stream capture never
+ * next one waits for them to finish, compares the medians of the last 8 of
+ * each and keeps the faster schedule for that batch size (a new batch size
+ * starts over; after every 1000 further forwards the 16 counted trials are
+ * repeated, since machines drift).  Calls under stream capture never
  * time anything: they use the schedule already chosen for their batch size,
- * else two streams.  free_dit_stream_choice returns the handle's choice (0 while
- * undecided, else 1 or 2; FREE_ERR_NULL).  The setting is process-wide and not
+ * else two streams.  free_dit_stream_choice returns the handle's latest choice (0
+ * while there is none, else 1 or 2; FREE_ERR_NULL).  The setting is process-wide and not
  * thread-safe against running calls.  FREE_ERR_RANGE for any other n. */
 int32_t free_set_batch_streams(int32_t n);
 int32_t free_get_batch_streams(void);

@@ -4,6 +4,7 @@
 // Alg. 1) and a whole round.  All arithmetic runs in the HIP kernels; the only
 // host-side mathematics is the diffusion schedule helper (Eq. ddpm_update) and the
 // fixed positional table computed once at handle creation.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -26,7 +27,9 @@ struct Profiler {
 };
 Profiler g_prof;
 int32_t g_batch_streams = 0;                  // 1: serial, 2: halves of a packed batch on two streams, 0: timed choice
-constexpr int kTuneTrials = 6;                // calls that try the two modes in turn; the first two are not counted
+constexpr int kTuneTrials = 24;               // calls that try the two modes in turn ...
+constexpr int kTuneSkip = 8;                  // ... of which the first ones (clocks and caches settling) are not counted
+constexpr int kTuneAgain = 1000;              // forwards after which the counted trials are repeated (machines drift)
 constexpr int64_t kMinSplitRows = 2048;       // token rows per half below which the split does not pay
 constexpr size_t kMaxProfSlots = 8192;
 }  // namespace
@@ -137,7 +140,9 @@ struct free_dit_s {
     struct StreamTune {
         int32_t batch = 0;                    // batch size the trials refer to
         int32_t trial = 0;                    // trials enqueued so far
-        int32_t choice = 0;                   // 0: undecided, else 1 or 2
+        int32_t choice = 0;                   // 0: trying, else 1 or 2
+        int32_t last = 0;                     // the previous choice while trying again (0: none yet)
+        int32_t since = 0;                    // forwards since the choice was made
         hipEvent_t ev[kTuneTrials][2] = {};   // [trial][start, stop], created with the handle
     } tune;
 
@@ -258,16 +263,22 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
     return FREE_OK;
 }
 
-// Ends the trial phase: the shorter of the counted trials of each mode decides (ties go to one stream).
+// Ends the trial phase: the median of the counted trials of each mode decides (ties go to one stream).
 int32_t choose_streams(free_dit_s::StreamTune* tn) {
-    float best[2] = {1e30f, 1e30f};
-    for (int i = 2; i < kTuneTrials; ++i) {
-        float ms = 0.f;
-        if (!hip_ok(hipEventSynchronize(tn->ev[i][1])) || !hip_ok(hipEventElapsedTime(&ms, tn->ev[i][0], tn->ev[i][1])))
+    float ms[2][kTuneTrials];
+    int n[2] = {0, 0};
+    for (int i = kTuneSkip; i < kTuneTrials; ++i) {
+        float t = 0.f;
+        if (!hip_ok(hipEventSynchronize(tn->ev[i][1])) || !hip_ok(hipEventElapsedTime(&t, tn->ev[i][0], tn->ev[i][1])))
             return FREE_ERR_HIP;
-        if (ms < best[i & 1]) best[i & 1] = ms;
+        ms[i & 1][n[i & 1]++] = t;
     }
-    tn->choice = best[0] <= best[1] ? 1 : 2;
+    float med[2];
+    for (int m = 0; m < 2; ++m) {
+        std::sort(ms[m], ms[m] + n[m]);
+        med[m] = 0.5f * (ms[m][(n[m] - 1) / 2] + ms[m][n[m] / 2]);
+    }
+    tn->choice = med[0] <= med[1] ? 1 : 2;
     return FREE_OK;
 }
 
@@ -317,7 +328,7 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     // of a GEMM, the first and last wave of tiles) the other half's matrix kernels fill the idle
     // compute units.  Which schedule is faster differs between machines of the same type (12 x 1024 tokens,
     // two streams / one stream: 15.0 / 14.6 ms, 15.0 / 15.4, 14.7 / 14.5, 14.8 / 14.2), so by default the
-    // first forwards at a batch size time both and the faster one is kept.  Both give the same numbers.
+    // first 24 forwards at a batch size time both in turn and the faster one is kept.  Both give the same numbers.
     // Per-kernel profiling needs serial execution, and small batches are launch bound, so both keep the
     // single stream.
     const bool eligible = !g_prof.on && B >= 2 && static_cast<int64_t>(B / 2) * d.ntok >= kMinSplitRows;
@@ -329,12 +340,16 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
         if (eligible && !hip_ok(hipStreamIsCapturing(s, &capturing))) return FREE_ERR_HIP;
         if (eligible && capturing != hipStreamCaptureStatusNone) {
             // no timing inside a capture: what an earlier eager call at this batch size decided, else two streams
-            if (tn.batch == B && tn.choice) mode = tn.choice;
+            if (tn.batch == B && (tn.choice || tn.last)) mode = tn.choice ? tn.choice : tn.last;
         } else if (eligible) {
             if (tn.batch != B) {
                 tn.batch = B;
                 tn.trial = 0;
-                tn.choice = 0;
+                tn.choice = tn.last = tn.since = 0;
+            } else if (tn.choice && ++tn.since >= kTuneAgain) {
+                tn.last = tn.choice;
+                tn.choice = tn.since = 0;
+                tn.trial = kTuneSkip;             // warm already: counted trials only
             }
             if (!tn.choice && tn.trial == kTuneTrials) FREE_TRY(choose_streams(&tn));
             if (tn.choice) {
@@ -408,7 +423,7 @@ int32_t free_get_batch_streams(void) { return g_batch_streams; }
 
 int32_t free_dit_stream_choice(free_dit_t h) {
     if (!h) return FREE_ERR_NULL;
-    return h->tune.choice;
+    return h->tune.choice ? h->tune.choice : h->tune.last;
 }
 
 int32_t free_profile_begin(void) {

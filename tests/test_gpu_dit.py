@@ -238,7 +238,7 @@ def test_mfma_calibration_is_sane():
 def test_batch_streams_same_result():
     """The two halves of a large batch can run on two streams; the serial schedule (one stream) must give
     the same numbers: every kernel reduces in the same order whatever the number of rows it is launched on.
-    By default the library times both schedules over the first six forwards at a batch size and keeps one."""
+    By default the library times both schedules over the first 24 forwards at a batch size and keeps one."""
     import torch
     from paper_2511_20390_amd import binding
     assert binding.get_batch_streams() == 0
@@ -256,8 +256,10 @@ def test_batch_streams_same_result():
     finally:
         binding.set_batch_streams(0)
     assert model.stream_choice() == 0                    # forced schedules are not trials
-    for _ in range(6):                                   # trials 2..6, then the call that decides
+    for _ in range(23):                                  # the remaining trials
         eps, feat = model.dit_forward_packed(dx, dt, dy, want_feat=True)
+    assert model.stream_choice() == 0
+    eps, feat = model.dit_forward_packed(dx, dt, dy, want_feat=True)    # the call that decides
     torch.cuda.synchronize()
     assert model.stream_choice() in (1, 2)
     results[0] = (eps.cpu().numpy(), feat.cpu().numpy())
@@ -272,6 +274,24 @@ def test_batch_streams_same_result():
     assert model.stream_choice() == choice
     with pytest.raises(binding.FreeError):
         binding.set_batch_streams(3)
+    model.close()
+
+
+def test_stream_choice_is_made_again_after_many_forwards():
+    """The timed choice between one and two streams is repeated after every 1000 forwards at a batch size;
+    while the 16 counted trials run again the previous choice stays reported, and the output never changes.
+    A narrow model with 1024 tokens keeps the 1100 forwards short."""
+    over = dict(lat_h=64, lat_w=64, hidden=64, heads=2, mlp_hidden=128, depth=2)
+    cfg, w, x, t, y, eps0, feat0, model = _forward_case("tiny", "bf16", 4, seed=3, cfg_over=over)
+    dx, dt, dy = pu.to_dev(x), pu.to_dev(t), pu.to_dev(y)
+    for _ in range(24):
+        model.dit_forward_packed(dx, dt, dy)
+    assert model.stream_choice() in (1, 2)               # 24 trials, decided at the 25th forward
+    for i in range(1000 + 17):
+        eps = model.dit_forward_packed(dx, dt, dy)
+        assert model.stream_choice() in (1, 2), i
+        if i % 100 == 0 or i >= 995:
+            assert np.array_equal(eps.cpu().numpy(), eps0), i
     model.close()
 
 
