@@ -172,10 +172,10 @@ enum { B_ADA_W = 0, B_ADA_B, B_QKV_W, B_QKV_B, B_PROJ_W, B_PROJ_B, B_FC1_W, B_FC
 enum { F_ADA_W = 0, F_ADA_B, F_W, F_B };
 
 int32_t linear_dispatch(const Dims& d, const void* A, const void* W, const float* bias, int32_t M, int32_t N,
-                        int32_t K, int32_t epi, void* out, float* resid, RowVec gate, hipStream_t s) {
+                        int32_t K, int32_t epi, void* out, float* resid, RowVec gate, hipStream_t s, int cu_share = 1) {
     if (d.mode == FREE_BF16 && mfma_linear_supported(M, N, K))
         return launch_linear_mfma(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, M, N, K, epi,
-                                  static_cast<bf16_t*>(out), resid, gate, s);
+                                  static_cast<bf16_t*>(out), resid, gate, s, cu_share);
     return launch_linear_simple(A, W, bias, M, N, K, d.mode, epi, out, resid, gate, s);
 }
 
@@ -204,8 +204,9 @@ struct ActBufs {
 
 // `nblk` adaLN-Zero blocks on samples [b0, b0 + nb) of a batch.  blkw holds 10 pointers per block
 // (B_* order); block l's six modulation vectors of sample b are mod[b * mod_rows + l * 6D ..].
+// cu_share: number of such stacks running side by side on different streams (tile choice of the GEMMs).
 int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const float* mod, int32_t mod_rows,
-                        const ActBufs& a, int b0, int nb, hipStream_t s) {
+                        const ActBufs& a, int b0, int nb, hipStream_t s, int cu_share = 1) {
     const size_t esz = d.mode == FREE_BF16 ? 2 : 4;
     const int32_t M = nb * d.ntok;
     const int64_t r0 = static_cast<int64_t>(b0) * d.ntok;
@@ -233,7 +234,7 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
         {
             ProfScope prof(PROF_GEMM_QKV, s);
             FREE_TRY(linear_dispatch(d, xn_h, W(l, B_QKV_W), Bv(l, B_QKV_B), M, 3 * d.D, d.D, FREE_EPI_BIAS, qkv_h,
-                                     nullptr, RowVec{nullptr, 0, 1}, s));
+                                     nullptr, RowVec{nullptr, 0, 1}, s, cu_share));
         }
         {
             ProfScope prof(PROF_ATTN, s);
@@ -242,7 +243,7 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
         {
             ProfScope prof(PROF_GEMM_PROJ, s);
             FREE_TRY(linear_dispatch(d, att_h, W(l, B_PROJ_W), Bv(l, B_PROJ_B), M, d.D, d.D, FREE_EPI_GATE_RESID,
-                                     nullptr, xres_h, vec(l, 2), s));
+                                     nullptr, xres_h, vec(l, 2), s, cu_share));
         }
         // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
         {
@@ -252,12 +253,12 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
         {
             ProfScope prof(PROF_GEMM_FC1, s);
             FREE_TRY(linear_dispatch(d, xn_h, W(l, B_FC1_W), Bv(l, B_FC1_B), M, d.F, d.D, FREE_EPI_BIAS_GELU, hmid_h,
-                                     nullptr, RowVec{nullptr, 0, 1}, s));
+                                     nullptr, RowVec{nullptr, 0, 1}, s, cu_share));
         }
         {
             ProfScope prof(PROF_GEMM_FC2, s);
             FREE_TRY(linear_dispatch(d, hmid_h, W(l, B_FC2_W), Bv(l, B_FC2_B), M, d.D, d.F, FREE_EPI_GATE_RESID,
-                                     nullptr, xres_h, vec(l, 5), s));
+                                     nullptr, xres_h, vec(l, 5), s, cu_share));
         }
     }
     return FREE_OK;
@@ -319,8 +320,8 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     }
     const ActBufs act{xres, xn, qkv, att, hmid};
     const void* const* blkw = h->w.data() + 7;
-    auto run_blocks = [&](int b0, int nb, hipStream_t st) -> int32_t {
-        return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st);
+    auto run_blocks = [&](int b0, int nb, hipStream_t st, int cu_share) -> int32_t {
+        return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st, cu_share);
     };
     // The samples of a packed batch are independent through all blocks, so the batch is cut in two
     // halves that run on two streams forked from (and joined back into) the caller's stream: while
@@ -367,12 +368,12 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
         for (int i = 0; i < 2; ++i) {
             const int b0 = i == 0 ? 0 : B / 2, b1 = i == 0 ? B / 2 : B;
             if (!hip_ok(hipStreamWaitEvent(h->side[i], h->ev_fork, 0))) return FREE_ERR_HIP;
-            FREE_TRY(run_blocks(b0, b1 - b0, h->side[i]));
+            FREE_TRY(run_blocks(b0, b1 - b0, h->side[i], 2));
             if (!hip_ok(hipEventRecord(h->ev_join[i], h->side[i]))) return FREE_ERR_HIP;
             if (!hip_ok(hipStreamWaitEvent(s, h->ev_join[i], 0))) return FREE_ERR_HIP;
         }
     } else {
-        FREE_TRY(run_blocks(0, B, s));
+        FREE_TRY(run_blocks(0, B, s, 1));
     }
     if (trial >= 0 && !hip_ok(hipEventRecord(h->tune.ev[trial][1], s))) return FREE_ERR_HIP;
     if (top_feat) {

@@ -568,11 +568,14 @@ bool mfma_linear_supported(int32_t M, int32_t N, int32_t K) {
     return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && static_cast<int64_t>(K) * 2 * 384 < (1ll << 31);
 }
 
+// cu_share: how many launches of this size are expected to run side by side (the halves of a packed batch on two
+// streams); the tile configuration is chosen for that share of the compute units.  Tiles change how the output
+// is cut, never the order in which a dot product is summed, so the result does not depend on it.
 int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
-                           int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s) {
+                           int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s, int cu_share) {
     if (!mfma_linear_supported(M, N, K)) return FREE_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W)) & 15u) return FREE_ERR_SHAPE;
-    const int cus = device_cus();
+    const int cus = std::max(1, device_cus() / std::max(1, cu_share));
     const double t256 = cfg_time(M, N, K, 256, 256, 1.83, 9.0, cus);
     const double t384 = cfg_time(M, N, K, 384, 192, 2.06, 10.0, cus);
     const double t2x1 = cfg_time(M, N, K, 256, 128, 1.31, 6.0, cus);
