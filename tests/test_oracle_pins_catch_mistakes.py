@@ -11,6 +11,7 @@ import pytest
 from oracle import free_oracle as fo
 
 import test_oracle_dit_pins as dit_pins
+import test_oracle_drafter_pins as drafter_pins
 import test_oracle_loop_pins as loop_pins
 import test_oracle_profile_pins as profile_pins
 import test_oracle_verify_pins as verify_pins
@@ -215,6 +216,28 @@ SOURCE_MUTANTS = [
                      "x, feat, i = states[K - 1], feats[K - 1], i + K"),
      [loop_pins.test_perfect_drafter_is_sequential_sampling_and_all_drafts_pass,
       loop_pins.test_loop_preserves_the_target_distribution_on_a_linear_gaussian_chain]),
+    # the fusion layer fed [feature | embedding] instead of [embedding | feature]
+    ("fusion_inputs_swapped", "drafter_forward",
+     lambda: _edited(fo.drafter_forward, "np.concatenate([emb[r], np.asarray(f_prev, F64)[r]], axis=1)",
+                     "np.concatenate([np.asarray(f_prev, F64)[r], emb[r]], axis=1)"),
+     [drafter_pins.test_embedding_passthrough_drafter_is_the_depth_limited_target,
+      drafter_pins.test_feature_only_fusion_ignores_the_latent_and_batch_rows_are_independent]),
+    # the propagated feature taken before the drafter's blocks instead of after them
+    ("feature_taken_before_the_blocks", "drafter_forward",
+     lambda: _edited(fo.drafter_forward, "        for l in range(ddepth):\n            z = dit_block(z, sc[r], wd, l, heads)\n        feat[r] = z\n",
+                     "        feat[r] = z\n        for l in range(ddepth):\n            z = dit_block(z, sc[r], wd, l, heads)\n"),
+     [drafter_pins.test_embedding_passthrough_drafter_is_the_depth_limited_target,
+      drafter_pins.test_draft_chain_equals_its_step_by_step_composition,
+      drafter_pins.test_a_drafter_that_reproduces_the_target_is_always_accepted]),
+    # every drafting step reuses the feature of the reference state
+    ("feature_not_propagated", "draft_steps",
+     lambda: _edited(fo.draft_steps, "out, f = drafter_forward(", "out, _ = drafter_forward("),
+     [drafter_pins.test_draft_chain_equals_its_step_by_step_composition]),
+    # draft k + 1 drawn around the state instead of around the draft mean
+    ("next_draft_around_the_state", "draft_steps",
+     lambda: _edited(fo.draft_steps, "xs.append(m + float(sigma[k])", "xs.append(xk + float(sigma[k])"),
+     [drafter_pins.test_zero_noise_drafts_sit_on_their_means,
+      drafter_pins.test_draft_chain_equals_its_step_by_step_composition]),
     ("monotone_fit_is_a_running_maximum", "monotone_fit", lambda: _cumulative_maximum,
      [profile_pins.test_monotone_fit_against_brute_force_and_library]),
     ("profile_not_inverted", "relaxation_profile_from_deltas",
