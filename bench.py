@@ -46,7 +46,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "spec_round_xl2_512_hbm_traffic.md
 CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<384, 192, 4, 2, 1, true>`", "gemm_qkv": "gemm_bf16_kernel<256, 256, 4, 2, 0, true>`",
                    "gemm_fc2": "gemm_bf16_kernel<256, 256, 4, 2, 2, true>` FC2",
                    "gemm_proj": "gemm_bf16_kernel<256, 256, 4, 2, 2, true>` out-projection",
-                   "attention": "attn_mfma_kernel<72, 1>`", "verify_partial": "verify_partial_kernel<true>`"}
+                   "attention": "attn_mfma_kernel<72, 1>`", "verify": "verify_fused_kernel<true>`"}
 
 
 def measured_traffic(category):
@@ -94,14 +94,15 @@ def bench_round(args):
         model.close()
         return res, cfg, w, ri, (cx, ce, sg)
 
-    # set-up, untimed: with the default --streams 0 the library tries one and two streams in turn over its
-    # first 24 forwards at this batch size and decides at the next (one was made above)
+    # set-up, untimed: --streams 0 asks the library to time both schedules of the block stack on these inputs
+    # (free_dit_tune, a blocking call outside the hot path) and to keep the faster one for this batch size
+    tp = torch.cat([a["t"], a["t"]]) if B == 2 * K else a["t"]
+    yp = torch.tensor([ri["y"]] * K + [cfg["num_classes"]] * (B - K), dtype=torch.int32, device="cuda:0")
+    xp = torch.cat([a["x_states"], a["x_states"]]) if B == 2 * K else a["x_states"]
+    model.set_streams(args.streams)
     if args.streams == 0:
-        for _ in range(64):
-            if model.stream_choice() != 0:
-                break
-            step()
-        torch.cuda.synchronize()
+        model.tune(xp, tp, yp)
+    stream_choice = model.stream_choice(B)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -110,12 +111,11 @@ def bench_round(args):
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    stream_choice = model.stream_choice() if args.streams == 0 else args.streams
 
     # the same steps with each schedule forced (the per-kernel figures below refer to one stream)
     forced = {}
     for n in (1, 2):
-        binding.set_batch_streams(n)
+        model.set_streams(n)
         step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -123,15 +123,15 @@ def bench_round(args):
             step()
         torch.cuda.synchronize()
         forced[n] = (time.perf_counter() - t0) * 1e3 / args.steps
-    binding.set_batch_streams(args.streams)
+    model.set_streams(args.streams)
     ms_one_stream, ms_two_streams = forced[1], forced[2]
 
     # per-kernel durations: the same steps again, every launch bracketed by HIP events on its stream
     # (the library runs them in sequence on one stream while it profiles)
-    binding.profile_begin()
+    model.profile_begin()
     for _ in range(args.steps):
         step()
-    prof = binding.profile_end()
+    prof = model.profile_end()
     per, total_flops = forward_flops(cfg, B)
     kernels = {}
     for name, (ms, n) in prof.items():
@@ -159,7 +159,7 @@ def bench_round(args):
     fwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if not k.startswith("verify") and k != "eps_to_mean")
     res = {
         "ms_per_step": ms_per_step, "ms_per_step_one_stream": ms_one_stream, "ms_per_step_two_streams": ms_two_streams,
-        "batch_streams": binding.get_batch_streams(), "stream_choice": stream_choice, "kernels": kernels, "roofline": roofline,
+        "batch_streams": args.streams, "stream_choice": stream_choice, "kernels": kernels, "roofline": roofline,
         "forward": {"algorithmic_tflop": total_flops / 1e12, "ms_sum_of_kernels": fwd_ms,
                     "tflops_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12,
                     "frac_of_peak_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12 / peak},
@@ -217,60 +217,76 @@ def bench_draft(args, cfg, model, ri, sched, a, verify_step):
 
 def bench_verify(args, n_sets=6):
     """spec_verify alone at 64 x 6 x 16384 fp32, rotating over n_sets distinct input sets
-    (> 256 MB in total) so that the Infinity Cache cannot stand in for HBM."""
+    (> 256 MB in total) so that the Infinity Cache cannot stand in for HBM.  A call is one small fill
+    kernel (the arrival counters) and ONE streaming kernel that also takes the decisions and writes the
+    reflected samples; every call is bracketed by HIP events on the launch stream (torch's current stream
+    is the stream the binding hands to the library)."""
     import torch
     from paper_2511_20390_amd import binding, synth
     n_traj, K, d = 64, 6, 16384
     _, _, sg = binding.free_ddpm_schedule()
+
+    def event_us(calls):
+        """Average time per call from events recorded before the first and after every call."""
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
+        torch.cuda.synchronize()
+        # a few milliseconds of unrelated device work first: the host then enqueues all the calls while the
+        # device is still busy, so the events measure the device, not the time Python takes between calls
+        for _ in range(6):
+            torch.mul(blocker, 1.0, out=blocker_out)
+        ev[0].record()
+        for i, c in enumerate(calls):
+            c()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        return sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(len(calls)))
+
+    blocker = torch.ones(256 << 20, device="cuda:0", dtype=torch.float32)       # 1 GiB: a copy takes ~0.4 ms
+    blocker_out = torch.empty_like(blocker)
     sets = []
     for i in range(n_sets):
         vi = synth.make_verify_inputs(n_traj, K, d, 0.01, 100 + i, sg)
         sets.append([torch.from_numpy(vi[k]).to("cuda:0") for k in ("m_target", "m_draft", "x_draft", "sigma", "u")])
     out = binding.spec_verify(*sets[0])
     ws = torch.empty(binding.spec_verify_workspace_bytes(n_traj, K, d), dtype=torch.uint8, device="cuda:0")
-    reps = 5
-    for i in range(n_sets):
-        binding.spec_verify(*sets[i], out=out, workspace=ws)
+    reps = 8
+    rot = [lambda i=i: binding.spec_verify(*sets[i], out=out, workspace=ws) for _ in range(reps) for i in range(n_sets)]
+    for c in rot[:n_sets]:
+        c()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for r in range(reps):
-        for i in range(n_sets):
-            binding.spec_verify(*sets[i], out=out, workspace=ws)
+    for c in rot:
+        c()
     torch.cuda.synchronize()
-    call_us = (time.perf_counter() - t0) * 1e6 / (reps * n_sets)
-    binding.profile_begin()
-    for r in range(reps):
-        for i in range(n_sets):
-            binding.spec_verify(*sets[i], out=out, workspace=ws)
-    prof = binding.profile_end()
-    binding.profile_begin()
-    for r in range(reps * n_sets):
-        binding.spec_verify(*sets[0], out=out, workspace=ws)
-    warm = binding.profile_end()
+    call_us = (time.perf_counter() - t0) * 1e6 / len(rot)
+    us = event_us(rot)
+    launch_us = sum(us) / len(us)
+    warm = event_us([lambda: binding.spec_verify(*sets[0], out=out, workspace=ws) for _ in range(reps * n_sets)])
+    nrej = int((out["n_accept"] < K).sum().item())
     # the same kernel on a problem large enough to leave the launch ramp behind: 384 trajectories (453 MB)
     nl = 384
     vl = synth.make_verify_inputs(nl, K, d, 0.01, 200, sg)
     big = [torch.from_numpy(vl[k]).to("cuda:0") for k in ("m_target", "m_draft", "x_draft", "sigma", "u")]
     out_l = binding.spec_verify(*big)
     ws_l = torch.empty(binding.spec_verify_workspace_bytes(nl, K, d), dtype=torch.uint8, device="cuda:0")
-    binding.profile_begin()
-    for r in range(8):
-        binding.spec_verify(*big, out=out_l, workspace=ws_l)
-    lprof = binding.profile_end()
-    large_gbs = nl * K * 3 * d * 4 / (lprof["verify_partial"][0] / lprof["verify_partial"][1] * 1e-3) / 1e9
+    lus = event_us([lambda: binding.spec_verify(*big, out=out_l, workspace=ws_l) for _ in range(8)])
+    nrej_l = int((out_l["n_accept"] < K).sum().item())
+    large_gbs = (nl * K * 3 * d * 4 + nrej_l * 4 * d * 4) / (sum(lus) / len(lus) * 1e-6) / 1e9
     del big, out_l, ws_l
-    ms, n = prof["verify_partial"]
-    bytes_partial = n_traj * K * 3 * d * 4
-    gbs = bytes_partial / (ms / n * 1e-3) / 1e9
-    wms, wn = warm["verify_partial"]
-    nrej = int((out["n_accept"] < K).sum().item())
-    return {"kernel": "verify_partial_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic("verify_partial"), "avg_launch_us": ms * 1e3 / n,
-            "warm_cache_GBs": bytes_partial / (wms / wn * 1e-3) / 1e9,
+    bytes_stream = n_traj * K * 3 * d * 4            # 12 bytes per latent element and draft
+    bytes_reflect = nrej * 4 * d * 4                 # + 16 bytes per element of a rejected draft
+    gbs = (bytes_stream + bytes_reflect) / (launch_us * 1e-6) / 1e9
+    return {"kernel": "verify_fused_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic("verify"), "avg_launch_us": launch_us,
+            "median_launch_us": us[len(us) // 2],
+            "measured": "HIP events on the launch stream before and after every call (fill kernel + streaming kernel, "
+                        "launch gaps included), 6 rotating input sets",
+            "streaming_only_GBs": bytes_stream / (launch_us * 1e-6) / 1e9,
+            "warm_cache_GBs": (bytes_stream + bytes_reflect) / (sum(warm) / len(warm) * 1e-6) / 1e9,
             "GBs_at_384_trajectories_453MB": large_gbs,
-            "finish_avg_us": prof["verify_finish"][0] * 1e3 / prof["verify_finish"][1],
             "call_us_back_to_back": call_us, "rounds_per_s_64traj": 64e6 / call_us,
-            "algorithmic_bytes": bytes_partial, "reflected_rows": nrej,
+            "algorithmic_bytes": bytes_stream + bytes_reflect, "algorithmic_bytes_streaming": bytes_stream,
+            "reflected_rows": nrej,
             "workload": "64 traj x 6 drafts x 16384 fp32, 6 rotating input sets (453 MB)"}
 
 
@@ -474,7 +490,6 @@ def main():
     from paper_2511_20390_amd import binding
     binding.load()          # fails loudly when the HIP library is missing
     torch.cuda.set_device(0)
-    binding.set_batch_streams(args.streams)
 
     if args.pmc_calibration:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")

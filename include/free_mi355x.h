@@ -14,9 +14,10 @@
  *    from a caller-provided device workspace whose size is given by the
  *    *_workspace_bytes functions.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Hot-path calls only enqueue work and return; outputs are valid after the
- *    caller synchronises the stream.  Calls that share a workspace must be
- *    ordered on one stream.
+ *    Hot-path calls only enqueue work and return: none of them waits for the
+ *    device, times itself or reads device memory on the host.  Outputs are valid
+ *    after the caller synchronises the stream.  Calls that share a workspace
+ *    must be ordered on one stream.
  *  - Argument checks are host-side (null pointers, shapes).  Values that live
  *    in device memory (timesteps, labels, sigma, u, lambda) are NOT range
  *    checked: a timestep is any int, a label must lie in [0, num_classes]
@@ -68,28 +69,6 @@ const char* free_version(void);
 const char* free_status_string(int32_t status);
 /* hipError_t of the last failing HIP call seen by this thread (0 = none). */
 int32_t free_last_hip_error(void);
-
-/* Execution of the packed target forward (Alg. 1: the K states of a round are
- * independent samples of one batch).  n = 2: when a batch has at least 2
- * samples and each half at least 2048 token rows, the two halves of the batch
- * run their transformer blocks concurrently on two streams owned by the model
- * handle; the work is forked from and joined back into the caller's stream, so
- * stream-ordered semantics towards the caller are unchanged and the results
- * are the same as with n = 1 (one stream, kernels in sequence).  n = 0
- * (default): which of the two is faster differs from machine to machine, so
- * the first 24 eager forwards of a handle at a batch size of that kind use
- * the two schedules in turn, timed with events on the caller's stream; the
- * next one waits for them to finish, compares the medians of the last 8 of
- * each and keeps the faster schedule for that batch size (a new batch size
- * starts over; after every 1000 further forwards the 16 counted trials are
- * repeated, since machines drift).  Calls under stream capture never
- * time anything: they use the schedule already chosen for their batch size,
- * else two streams.  free_dit_stream_choice returns the handle's latest choice (0
- * while there is none, else 1 or 2; FREE_ERR_NULL).  The setting is process-wide and not
- * thread-safe against running calls.  FREE_ERR_RANGE for any other n. */
-int32_t free_set_batch_streams(int32_t n);
-int32_t free_get_batch_streams(void);
-int32_t free_dit_stream_choice(free_dit_t h);
 
 /* Linear-beta DDPM schedule and the coefficients of the one-step update
  * (Eq. ddpm_update, App. C), 0-indexed by network timestep i in [0, T):
@@ -155,6 +134,34 @@ int32_t free_dit_destroy(free_dit_t h);
  * also sufficient for spec_round with the same B.  0 on a bad configuration. */
 size_t free_workspace_bytes(const free_dit_config* cfg, int32_t B);
 
+/* ---- schedule of the packed forward (Alg. 1: the K states of a round are
+ *      independent samples of one batch) -------------------------------------
+ * One stream (the default): the kernels of a forward run in sequence on the
+ * caller's stream.  Two streams: when a batch has at least 2 samples and each
+ * half at least 2048 token rows, the two halves of the batch run their
+ * transformer blocks concurrently on two side streams owned by the handle; the
+ * work is forked from and joined back into the caller's stream by events, so
+ * stream-ordered semantics towards the caller are unchanged, and the results are
+ * bit-identical to those of one stream.  Which of the two is faster differs by
+ * a few per cent either way between machines of the same type.
+ *   free_dit_set_streams(h, n): n = 1 or 2 forces that schedule for every batch
+ *     size of the handle; n = 0 (initial state) uses, per batch size, what
+ *     free_dit_tune measured, and one stream where nothing was measured.
+ *   free_dit_tune: NOT a hot-path call - it blocks.  Runs 16 forwards on the given
+ *     inputs (arguments as for dit_forward_packed, no top_feat), the two schedules
+ *     in turn, each bracketed by events on `stream`, waits for them, compares the
+ *     medians of the last 6 of each and remembers the faster schedule for this
+ *     batch size (the handle keeps the 8 most recently tuned batch sizes).  A
+ *     batch that can never split returns FREE_OK at once.  eps_out holds a valid
+ *     forward result afterwards.
+ *   free_dit_stream_choice(h, B): the schedule (1 or 2) a forward on B packed
+ *     states would use now.
+ * Settings belong to the handle; calls on one handle must not race. */
+int32_t free_dit_set_streams(free_dit_t h, int32_t n);
+int32_t free_dit_tune(free_dit_t h, const float* x, const int32_t* t, const int32_t* y, int32_t B,
+                      float* eps_out, void* workspace, size_t ws_bytes, void* stream);
+int32_t free_dit_stream_choice(free_dit_t h, int32_t B);
+
 /* ---- the packed target forward (Alg. 1, "in parallel"; Sec. 3.3) ----------
  * One forward of the class-conditional DiT on B packed states, each with its
  * own timestep t[b] and label y[b] (int32, device).
@@ -163,11 +170,12 @@ size_t free_workspace_bytes(const free_dit_config* cfg, int32_t B);
  *            [0, C) are the noise prediction, [C, 2C) the unused variance.
  *   top_feat [B, N, hidden] fp32 or NULL: output of the last block (the
  *            feature f of Alg. 1).
- * Enqueues on `stream` and returns; results are ordered after the call on that
- * stream.  A handle owns two internal side streams (see free_set_batch_streams),
- * so two calls on the SAME handle must not be in flight from different streams at
- * the same time; calls on different handles are independent.  The call allocates
- * nothing and can be captured in a HIP graph. */
+ * Enqueues on `stream` and returns without waiting for the device; results are
+ * ordered after the call on that stream.  A handle owns two internal side
+ * streams (see free_dit_set_streams), so two calls on the SAME handle must not
+ * be in flight from different streams at the same time; calls on different
+ * handles are independent.  The call allocates nothing and can be captured in a
+ * HIP graph. */
 int32_t dit_forward_packed(free_dit_t h, const float* x, const int32_t* t, const int32_t* y,
                            int32_t B, float* eps_out, float* top_feat,
                            void* workspace, size_t ws_bytes, void* stream);
@@ -190,7 +198,15 @@ int32_t dit_forward_packed(free_dit_t h, const float* x, const int32_t* t, const
  *                               x = m + (I - 2 e e^T)(x^ - m^), e = (m^ - m)/||m^ - m||;
  *                               rows with n_accept == K are left untouched.
  * Sums over d are accumulated in fp64 in a fixed order: results are
- * deterministic run to run. */
+ * deterministic run to run.
+ * Workspace: spec_verify_workspace_bytes(n_traj, K, d) bytes of device memory,
+ * 8-byte aligned, contents arbitrary (one arrival counter per trajectory, which
+ * the call clears itself, and the partial sums); FREE_ERR_WORKSPACE if missing
+ * or too small.  Limits: 1 <= K <= FREE_MAX_DRAFTS; n_traj * K * ceil(d / chunk)
+ * workgroups must fit a one-dimensional grid (2^31 - 1; chunk >= 1024 elements);
+ * states of more than 2^18 elements are reflected by a second launch, which
+ * needs n_traj <= 65535; FREE_ERR_SHAPE otherwise.  Enqueues one small fill
+ * kernel and ONE streaming kernel; no host synchronisation. */
 size_t spec_verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d);
 int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_draft,
                     const float* sigma, const float* u, const float* lambda,
@@ -317,18 +333,20 @@ int32_t free_self_speculative(free_dit_t target, const float* x_init, int32_t y,
 int32_t free_lambda_profile(const float* eps_delta, int32_t S, int32_t window, float* lambda_out);
 
 /* ---- per-kernel timing for benchmarks -------------------------------------
- * Between free_profile_begin and free_profile_end every kernel launch of the
- * hot-path calls is bracketed by two HIP events recorded on the launch stream.
+ * Between free_profile_begin(h) and free_profile_end(h) every kernel launch that
+ * a hot-path call makes on behalf of handle h (dit_forward_packed, spec_round,
+ * the drafter and the samplers built on it) is bracketed by two HIP events
+ * recorded on the launch stream, and the forward uses one stream.
  * free_profile_end waits for the last event and returns, per category, the
  * summed elapsed milliseconds and the number of bracketed launches ([host]
- * arrays of FREE_PROF_NCAT entries).  Process-global and not thread-safe;
- * the events are created on first use and reused.  Categories, in order:
+ * arrays of FREE_PROF_NCAT entries).  The state belongs to the handle (events
+ * are created on first use and released with it); off by default, and a handle
+ * that never profiles records nothing.  Categories, in order:
  * conditioning, adaln, patch_embed, ln_modulate, gemm_qkv, attention,
- * gemm_proj, gemm_fc1, gemm_fc2, final_layer, eps_to_mean, verify_partial,
- * verify_finish. */
-#define FREE_PROF_NCAT 13
-int32_t free_profile_begin(void);
-int32_t free_profile_end(float* ms, int32_t* launches);
+ * gemm_proj, gemm_fc1, gemm_fc2, final_layer, eps_to_mean, verify. */
+#define FREE_PROF_NCAT 12
+int32_t free_profile_begin(free_dit_t h);
+int32_t free_profile_end(free_dit_t h, float* ms, int32_t* launches);
 const char* free_profile_category_name(int32_t category);
 
 /* Matrix-core calibration for the "mfma" roofline of the benchmark: runs a

@@ -21,8 +21,8 @@ EPI_BIAS, EPI_BIAS_GELU, EPI_GATE_RESID = 0, 1, 2
 MODES = {"fp32": FREE_FP32, "bf16": FREE_BF16}
 
 EXPORTED_SYMBOLS = [
-    "free_version", "free_status_string", "free_last_hip_error", "free_set_batch_streams",
-    "free_get_batch_streams", "free_dit_stream_choice", "free_ddpm_schedule", "free_sde_schedule",
+    "free_version", "free_status_string", "free_last_hip_error", "free_dit_set_streams",
+    "free_dit_tune", "free_dit_stream_choice", "free_ddpm_schedule", "free_sde_schedule",
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
     "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
     "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
@@ -31,7 +31,7 @@ EXPORTED_SYMBOLS = [
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
     "free_profile_begin", "free_profile_end", "free_profile_category_name", "free_mfma_ceiling", "free_validate_inputs",
 ]
-PROF_NCAT = 13
+PROF_NCAT = 12
 
 
 class FreeError(RuntimeError):
@@ -64,11 +64,12 @@ def load():
     lib.free_status_string.restype = C.c_char_p
     lib.free_status_string.argtypes = [i32]
     lib.free_last_hip_error.restype = i32
-    lib.free_set_batch_streams.restype = i32
-    lib.free_set_batch_streams.argtypes = [i32]
-    lib.free_get_batch_streams.restype = i32
+    lib.free_dit_set_streams.restype = i32
+    lib.free_dit_set_streams.argtypes = [vp, i32]
+    lib.free_dit_tune.restype = i32
+    lib.free_dit_tune.argtypes = [vp, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.free_dit_stream_choice.restype = i32
-    lib.free_dit_stream_choice.argtypes = [vp]
+    lib.free_dit_stream_choice.argtypes = [vp, i32]
     lib.free_ddpm_schedule.restype = i32
     lib.free_ddpm_schedule.argtypes = [i32, C.c_double, C.c_double, vp, vp, vp]
     lib.free_sde_schedule.restype = i32
@@ -118,8 +119,9 @@ def load():
     lib.free_op_ln_modulate.restype = i32
     lib.free_op_ln_modulate.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     lib.free_profile_begin.restype = i32
+    lib.free_profile_begin.argtypes = [vp]
     lib.free_profile_end.restype = i32
-    lib.free_profile_end.argtypes = [vp, vp]
+    lib.free_profile_end.argtypes = [vp, vp, vp]
     lib.free_validate_inputs.restype = i32
     lib.free_validate_inputs.argtypes = [vp, i64, i32, vp, vp, vp, i64, vp, vp]
     lib.free_mfma_ceiling.restype = i32
@@ -137,6 +139,26 @@ def _check(status, where):
 
 def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _dev(t, dtype, name, shape=None, optional=False):
+    """Pointer of a device tensor handed to the library, after the checks the C side cannot make: the
+    library reads raw memory, so a tensor of another element type (torch integers default to int64), a
+    strided view or a host tensor would give wrong results or out-of-bounds device reads, not an error."""
+    import torch
+    if t is None:
+        if optional:
+            return None
+        raise FreeError(FREE_ERR_NULL, name)
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise FreeError(FREE_ERR_NULL, f"{name}: not a device tensor")
+    if t.dtype != dtype:
+        raise FreeError(FREE_ERR_DTYPE, f"{name}: element type {t.dtype}, expected {dtype}")
+    if not t.is_contiguous():
+        raise FreeError(FREE_ERR_SHAPE, f"{name}: not contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise FreeError(FREE_ERR_SHAPE, f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return C.c_void_p(t.data_ptr())
 
 
 def _stream():
@@ -166,28 +188,6 @@ def free_sde_schedule(stochasticity: float, T: int = 1000, beta_start: float = 1
     return cx, ce, sg
 
 
-def set_batch_streams(n: int) -> None:
-    """1: kernels of a forward in sequence on the caller's stream; 2: halves of a large batch on two streams;
-    0 (default): the first forwards at a batch size time both and the faster one is kept."""
-    _check(load().free_set_batch_streams(int(n)), "free_set_batch_streams")
-
-
-def get_batch_streams() -> int:
-    return int(load().free_get_batch_streams())
-
-
-def profile_begin():
-    _check(load().free_profile_begin(), "free_profile_begin")
-
-
-def profile_end() -> dict:
-    """{category: (total_ms, launches)} for the launches since profile_begin."""
-    ms = np.zeros(PROF_NCAT, np.float32)
-    cnt = np.zeros(PROF_NCAT, np.int32)
-    _check(load().free_profile_end(ms.ctypes.data, cnt.ctypes.data), "free_profile_end")
-    return {load().free_profile_category_name(c).decode(): (float(ms[c]), int(cnt[c])) for c in range(PROF_NCAT)}
-
-
 def validate_inputs(t=None, T: int = 1000, sigma=None, u=None, lam=None) -> int:
     """Blocking range check of device tensors (any may be None); returns the bit mask of violations
     (0 = all in range; bit 0 t, bit 1 sigma, bit 2 u, bit 3 lambda)."""
@@ -196,8 +196,11 @@ def validate_inputs(t=None, T: int = 1000, sigma=None, u=None, lam=None) -> int:
         if x is not None and x.numel() != n:
             raise ValueError("sigma, u and lambda must have the same number of elements")
     mask = C.c_uint32(0)
-    st = load().free_validate_inputs(_ptr(t), 0 if t is None else t.numel(), int(T), _ptr(sigma), _ptr(u), _ptr(lam),
-                                     n, C.addressof(mask), _stream())
+    import torch
+    f32, i32 = torch.float32, torch.int32
+    st = load().free_validate_inputs(_dev(t, i32, "t", optional=True), 0 if t is None else t.numel(), int(T),
+                                     _dev(sigma, f32, "sigma", optional=True), _dev(u, f32, "u", optional=True),
+                                     _dev(lam, f32, "lambda", optional=True), n, C.addressof(mask), _stream())
     if st not in (FREE_OK, FREE_ERR_RANGE):
         _check(st, "free_validate_inputs")
     return int(mask.value)
@@ -216,21 +219,33 @@ def spec_verify_workspace_bytes(n_traj: int, K: int, d: int) -> int:
     return load().spec_verify_workspace_bytes(n_traj, K, d)
 
 
-def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None, out=None, workspace=None):
-    """Device tensors in, dict of device tensors out.  m_*, x_draft: [n_traj, K, d] fp32."""
+def _verify_out(out, n_traj, K, d, dev):
     import torch
-    n_traj, K, d = m_target.shape
-    dev = m_target.device
     if out is None:
         out = dict(log_ratio=torch.empty(n_traj, K, dtype=torch.float32, device=dev),
                    accept=torch.empty(n_traj, K, dtype=torch.uint8, device=dev),
                    n_accept=torch.empty(n_traj, dtype=torch.int32, device=dev),
                    x_out=torch.zeros(n_traj, d, dtype=torch.float32, device=dev))
+    return out
+
+
+def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None, out=None, workspace=None):
+    """Device tensors in, dict of device tensors out.  m_*, x_draft: [n_traj, K, d] fp32."""
+    import torch
+    f32 = torch.float32
+    n_traj, K, d = m_target.shape
+    dev = m_target.device
+    out = _verify_out(out, n_traj, K, d, dev)
     if workspace is None:
         workspace = torch.empty(max(256, spec_verify_workspace_bytes(n_traj, K, d)), dtype=torch.uint8, device=dev)
-    _check(load().spec_verify(_ptr(m_target), _ptr(m_draft), _ptr(x_draft), _ptr(sigma), _ptr(u), _ptr(lam),
-                              n_traj, K, d, _ptr(out["log_ratio"]), _ptr(out["accept"]), _ptr(out["n_accept"]),
-                              _ptr(out["x_out"]), _ptr(workspace), workspace.numel(), _stream()), "spec_verify")
+    _check(load().spec_verify(_dev(m_target, f32, "m_target"), _dev(m_draft, f32, "m_draft", (n_traj, K, d)),
+                              _dev(x_draft, f32, "x_draft", (n_traj, K, d)), _dev(sigma, f32, "sigma", (n_traj, K)),
+                              _dev(u, f32, "u", (n_traj, K)), _dev(lam, f32, "lambda", (n_traj, K), optional=True),
+                              n_traj, K, d, _dev(out["log_ratio"], f32, "log_ratio", (n_traj, K)),
+                              _dev(out["accept"], torch.uint8, "accept", (n_traj, K)),
+                              _dev(out["n_accept"], torch.int32, "n_accept", (n_traj,)),
+                              _dev(out["x_out"], f32, "x_out", (n_traj, d)),
+                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()), "spec_verify")
     return out
 
 
@@ -261,11 +276,38 @@ class FreeDit:
         self.ntok = (self.H // cfg["patch"]) * (self.W // cfg["patch"])
         self.d = self.C * self.H * self.W
 
-    def stream_choice(self) -> int:
-        """What the timed choice between one and two streams has settled on (0 while undecided)."""
-        st = int(load().free_dit_stream_choice(self.handle))
+    def set_streams(self, n: int) -> None:
+        """1 or 2: force that schedule of the block stack for every batch size; 0: what tune() measured per
+        batch size, one stream where nothing was measured (the initial state)."""
+        _check(load().free_dit_set_streams(self.handle, int(n)), "free_dit_set_streams")
+
+    def stream_choice(self, B: int) -> int:
+        """The schedule (1 or 2 streams) a forward on B packed states would use now."""
+        st = int(load().free_dit_stream_choice(self.handle, int(B)))
         _check(min(st, 0), "free_dit_stream_choice")
         return st
+
+    def tune(self, x, t, y) -> int:
+        """Blocking, not a hot-path call: times both schedules on these inputs and keeps the faster one for
+        this batch size.  Returns the choice."""
+        import torch
+        B = x.shape[0]
+        eps = torch.empty(B, self.c_out, self.H, self.W, dtype=torch.float32, device=self.device)
+        ws = self.workspace(B)
+        _check(load().free_dit_tune(self.handle, _dev(x, torch.float32, "x", (B, self.C, self.H, self.W)),
+                                    _dev(t, torch.int32, "t", (B,)), _dev(y, torch.int32, "y", (B,)), B, _ptr(eps),
+                                    _ptr(ws), ws.numel(), _stream()), "free_dit_tune")
+        return self.stream_choice(B)
+
+    def profile_begin(self) -> None:
+        _check(load().free_profile_begin(self.handle), "free_profile_begin")
+
+    def profile_end(self) -> dict:
+        """{category: (total_ms, launches)} for this handle's launches since profile_begin."""
+        ms = np.zeros(PROF_NCAT, np.float32)
+        cnt = np.zeros(PROF_NCAT, np.int32)
+        _check(load().free_profile_end(self.handle, ms.ctypes.data, cnt.ctypes.data), "free_profile_end")
+        return {load().free_profile_category_name(c).decode(): (float(ms[c]), int(cnt[c])) for c in range(PROF_NCAT)}
 
     def close(self):
         if getattr(self, "handle", None) is not None and self.handle.value:
@@ -293,8 +335,9 @@ class FreeDit:
         eps = torch.empty(B, self.c_out, self.H, self.W, dtype=torch.float32, device=self.device)
         feat = torch.empty(B, self.ntok, self.cfg["hidden"], dtype=torch.float32, device=self.device) if want_feat else None
         ws = self.workspace(B)
-        _check(load().dit_forward_packed(self.handle, _ptr(x), _ptr(t), _ptr(y), B, _ptr(eps), _ptr(feat),
-                                         _ptr(ws), ws.numel(), _stream()), "dit_forward_packed")
+        _check(load().dit_forward_packed(self.handle, _dev(x, torch.float32, "x", (B, self.C, self.H, self.W)),
+                                         _dev(t, torch.int32, "t", (B,)), _dev(y, torch.int32, "y", (B,)), B,
+                                         _ptr(eps), _ptr(feat), _ptr(ws), ws.numel(), _stream()), "dit_forward_packed")
         return (eps, feat) if want_feat else eps
 
     def spec_round(self, x_states, x_last, m_draft, t, y: int, cfg_scale: float, coef_x, coef_eps, sigma, u,
@@ -310,10 +353,20 @@ class FreeDit:
                        n_accept=torch.empty(1, dtype=torch.int32, device=dev),
                        x_out=torch.zeros(self.d, dtype=torch.float32, device=dev))
         ws = self.workspace(B)
-        _check(load().spec_round(self.handle, _ptr(x_states), _ptr(x_last), _ptr(m_draft), _ptr(t), int(y),
-                                 float(cfg_scale), _ptr(coef_x), _ptr(coef_eps), _ptr(sigma), _ptr(u), _ptr(lam),
-                                 K, _ptr(out["m_target"]), _ptr(out["log_ratio"]), _ptr(out["accept"]),
-                                 _ptr(out["n_accept"]), _ptr(out["x_out"]), _ptr(ws), ws.numel(), _stream()),
+        f32 = torch.float32
+        if x_last.numel() != self.d:
+            raise FreeError(FREE_ERR_SHAPE, "x_last: wrong number of elements")
+        _check(load().spec_round(self.handle, _dev(x_states, f32, "x_states", (K, self.C, self.H, self.W)),
+                                 _dev(x_last, f32, "x_last"), _dev(m_draft, f32, "m_draft", (K, self.d)),
+                                 _dev(t, torch.int32, "t", (K,)), int(y), float(cfg_scale),
+                                 _dev(coef_x, f32, "coef_x", (K,)), _dev(coef_eps, f32, "coef_eps", (K,)),
+                                 _dev(sigma, f32, "sigma", (K,)), _dev(u, f32, "u", (K,)),
+                                 _dev(lam, f32, "lambda", (K,), optional=True), K,
+                                 _dev(out["m_target"], f32, "m_target", (K, self.d), optional=True),
+                                 _dev(out["log_ratio"], f32, "log_ratio", (K,)),
+                                 _dev(out["accept"], torch.uint8, "accept", (K,)),
+                                 _dev(out["n_accept"], torch.int32, "n_accept", (1,)),
+                                 _dev(out["x_out"], f32, "x_out", (self.d,)), _ptr(ws), ws.numel(), _stream()),
                "spec_round")
         return out
 
@@ -367,8 +420,10 @@ class FreeDrafter:
         eps = torch.empty(B, tg.c_out, tg.H, tg.W, dtype=torch.float32, device=self.device)
         f = torch.empty(B, tg.ntok, tg.cfg["hidden"], dtype=torch.float32, device=self.device)
         ws = self.workspace(B)
-        _check(load().drafter_forward(self.handle, _ptr(x), _ptr(f_prev), _ptr(t), _ptr(y), B, _ptr(eps), _ptr(f),
-                                      _ptr(ws), ws.numel(), _stream()), "drafter_forward")
+        _check(load().drafter_forward(self.handle, _dev(x, torch.float32, "x", (B, tg.C, tg.H, tg.W)),
+                                      _dev(f_prev, torch.float32, "f_prev", (B, tg.ntok, tg.cfg["hidden"])),
+                                      _dev(t, torch.int32, "t", (B,)), _dev(y, torch.int32, "y", (B,)), B, _ptr(eps),
+                                      _ptr(f), _ptr(ws), ws.numel(), _stream()), "drafter_forward")
         return eps, f
 
     def draft_round(self, x_a, f_a, t, y: int, cfg_scale: float, coef_x, coef_eps, sigma, xi, want_feat=False,
@@ -386,9 +441,18 @@ class FreeDrafter:
                        f_last=torch.empty(dup, tg.ntok, tg.cfg["hidden"], dtype=torch.float32, device=dev)
                        if want_feat else None)
         ws = self.workspace(dup)
-        _check(load().draft_round(self.handle, _ptr(x_a), _ptr(f_a), _ptr(t), int(y), float(cfg_scale), _ptr(coef_x),
-                                  _ptr(coef_eps), _ptr(sigma), _ptr(xi), K, _ptr(out["x_states"]), _ptr(out["x_last"]),
-                                  _ptr(out["m_draft"]), _ptr(out["f_last"]), _ptr(ws), ws.numel(), _stream()),
+        f32 = torch.float32
+        if x_a.numel() != tg.d:
+            raise FreeError(FREE_ERR_SHAPE, "x_a: wrong number of elements")
+        _check(load().draft_round(self.handle, _dev(x_a, f32, "x_a"),
+                                  _dev(f_a, f32, "f_a", (dup, tg.ntok, tg.cfg["hidden"])),
+                                  _dev(t, torch.int32, "t", (K,)), int(y), float(cfg_scale),
+                                  _dev(coef_x, f32, "coef_x", (K,)), _dev(coef_eps, f32, "coef_eps", (K,)),
+                                  _dev(sigma, f32, "sigma", (K,)), _dev(xi, f32, "xi", (K, tg.d)), K,
+                                  _dev(out["x_states"], f32, "x_states", (K, tg.C, tg.H, tg.W)),
+                                  _dev(out["x_last"], f32, "x_last", (tg.d,)),
+                                  _dev(out["m_draft"], f32, "m_draft", (K, tg.d)),
+                                  _dev(out["f_last"], f32, "f_last", optional=True), _ptr(ws), ws.numel(), _stream()),
                "draft_round")
         return out
 
@@ -406,8 +470,14 @@ def free_sample(drafter: "FreeDrafter", x_init, y: int, cfg_scale: float, n_spec
     x_out = torch.empty_like(x_init)
     stats = (C.c_int32 * 4)()
     log = (C.c_int32 * S)()
-    _check(load().free_sample(drafter.handle, _ptr(x_init), int(y), float(cfg_scale), S, int(n_spec), int(L),
-                              _ptr(tmap), _ptr(coef_x), _ptr(coef_eps), _ptr(sigma), _ptr(xi), _ptr(u), _ptr(lam),
+    f32, d = torch.float32, drafter.target.d
+    if x_init.numel() != d:
+        raise FreeError(FREE_ERR_SHAPE, "x_init: wrong number of elements")
+    _check(load().free_sample(drafter.handle, _dev(x_init, f32, "x_init"), int(y), float(cfg_scale), S, int(n_spec), int(L),
+                              _dev(tmap, torch.int32, "tmap", (S,)), _dev(coef_x, f32, "coef_x", (S,)),
+                              _dev(coef_eps, f32, "coef_eps", (S,)), _dev(sigma, f32, "sigma", (S,)),
+                              _dev(xi, f32, "xi", (S, d)), _dev(u, f32, "u", (S,)),
+                              _dev(lam, f32, "lambda", (S,), optional=True),
                               _ptr(x_out), stats, log, _ptr(ws), ws.numel(), _stream()), "free_sample")
     st = dict(target_calls=stats[0], rounds=stats[1], accepted=stats[2], drafter_steps=stats[3])
     return x_out, st, [log[r] for r in range(stats[1])]
@@ -429,9 +499,15 @@ def free_self_speculative(target: FreeDit, x_init, y: int, cfg_scale: float, n_s
     log = (C.c_int32 * S)()
     delta = np.empty(S, np.float32)
     acc = np.empty(S, np.int8)
-    _check(load().free_self_speculative(target.handle, _ptr(x_init), int(y), float(cfg_scale), S, int(n_spec), int(L),
-                                        _ptr(tmap), _ptr(coef_x), _ptr(coef_eps), _ptr(sigma), _ptr(xi), _ptr(u),
-                                        _ptr(lam), _ptr(x_out), stats, log, delta.ctypes.data, acc.ctypes.data,
+    f32, d = torch.float32, target.d
+    if x_init.numel() != d:
+        raise FreeError(FREE_ERR_SHAPE, "x_init: wrong number of elements")
+    _check(load().free_self_speculative(target.handle, _dev(x_init, f32, "x_init"), int(y), float(cfg_scale), S,
+                                        int(n_spec), int(L), _dev(tmap, torch.int32, "tmap", (S,)),
+                                        _dev(coef_x, f32, "coef_x", (S,)), _dev(coef_eps, f32, "coef_eps", (S,)),
+                                        _dev(sigma, f32, "sigma", (S,)), _dev(xi, f32, "xi", (S, d)),
+                                        _dev(u, f32, "u", (S,)), _dev(lam, f32, "lambda", (S,), optional=True),
+                                        _ptr(x_out), stats, log, delta.ctypes.data, acc.ctypes.data,
                                         _ptr(ws), ws.numel(), _stream()), "free_self_speculative")
     st = dict(target_calls=stats[0], rounds=stats[1], accepted=stats[2], drafter_steps=stats[3])
     return x_out, st, [log[r] for r in range(stats[1])], delta, acc

@@ -18,39 +18,38 @@ static thread_local int32_t g_last_hip_error = 0;
 void note_hip_error(hipError_t e) { g_last_hip_error = static_cast<int32_t>(e); }
 
 // ---- per-kernel timing ------------------------------------------------------------
-namespace {
 struct Profiler {
     bool on = false;
     std::vector<hipEvent_t> ev;      // pairs: 2*slot = start, 2*slot+1 = stop
     std::vector<int> cat;            // category of each used slot
     size_t used = 0;
 };
-Profiler g_prof;
-int32_t g_batch_streams = 0;                  // 1: serial, 2: halves of a packed batch on two streams, 0: timed choice
-constexpr int kTuneTrials = 24;               // calls that try the two modes in turn ...
-constexpr int kTuneSkip = 8;                  // ... of which the first ones (clocks and caches settling) are not counted
-constexpr int kTuneAgain = 1000;              // forwards after which the counted trials are repeated (machines drift)
+
+namespace {
+constexpr int kTuneTrials = 16;               // forwards of free_dit_tune, the two schedules in turn ...
+constexpr int kTuneSkip = 4;                  // ... of which the first ones (clocks and caches settling) are not counted
+constexpr int kTuneSlots = 8;                 // batch sizes a handle remembers a tuned schedule for
 constexpr int64_t kMinSplitRows = 2048;       // token rows per half below which the split does not pay
 constexpr size_t kMaxProfSlots = 8192;
 }  // namespace
 
-ProfScope::ProfScope(int c, hipStream_t s) : slot(-1), stream(s) {
-    if (!g_prof.on || g_prof.used >= kMaxProfSlots) return;
-    const size_t k = g_prof.used;
-    while (g_prof.ev.size() < 2 * (k + 1)) {
+ProfScope::ProfScope(Profiler* p, int c, hipStream_t s) : prof(p), slot(-1), stream(s) {
+    if (!p || !p->on || p->used >= kMaxProfSlots) return;
+    const size_t k = p->used;
+    while (p->ev.size() < 2 * (k + 1)) {
         hipEvent_t e;
         if (!hip_ok(hipEventCreate(&e))) return;
-        g_prof.ev.push_back(e);
+        p->ev.push_back(e);
     }
-    if (!hip_ok(hipEventRecord(g_prof.ev[2 * k], s))) return;
-    if (g_prof.cat.size() <= k) g_prof.cat.resize(k + 1);
-    g_prof.cat[k] = c;
-    g_prof.used = k + 1;
+    if (!hip_ok(hipEventRecord(p->ev[2 * k], s))) return;
+    if (p->cat.size() <= k) p->cat.resize(k + 1);
+    p->cat[k] = c;
+    p->used = k + 1;
     slot = static_cast<int>(k);
 }
 
 ProfScope::~ProfScope() {
-    if (slot >= 0) (void)hip_ok(hipEventRecord(g_prof.ev[2 * slot + 1], stream));
+    if (slot >= 0) (void)hip_ok(hipEventRecord(prof->ev[2 * slot + 1], stream));
 }
 
 namespace {
@@ -89,7 +88,7 @@ bool make_dims(const free_dit_config* c, Dims* o) {
 
 // Workspace carve-up for a forward on B packed states (offsets in bytes).
 struct WsLayout {
-    size_t cond_h, sc, mod, tpack, ypack, xres, xn, qkv, att, hmid, eps, mtarget, vpart, total;
+    size_t cond_h, sc, mod, tpack, ypack, xres, xn, qkv, att, hmid, eps, mtarget, vpart, vpart_bytes, total;
 };
 
 WsLayout make_layout(const Dims& d, int32_t B) {
@@ -110,7 +109,9 @@ WsLayout make_layout(const Dims& d, int32_t B) {
     L.hmid = take(M * d.F * es);
     L.eps = take(static_cast<size_t>(B) * d.c_out * d.H * d.W * 4);
     L.mtarget = take(static_cast<size_t>(B) * d.d * 4);
-    L.vpart = take(verify_workspace_bytes(1, B, d.d));
+    // verification of the round's drafts: K = B without guidance, K = B / 2 with it
+    L.vpart_bytes = std::max(verify_workspace_bytes(1, B, d.d), verify_workspace_bytes(1, (B + 1) / 2, d.d));
+    L.vpart = take(L.vpart_bytes);
     L.total = off;
     return L;
 }
@@ -135,16 +136,20 @@ struct free_dit_s {
     hipStream_t side[2] = {nullptr, nullptr};
     hipEvent_t ev_fork = nullptr;
     hipEvent_t ev_join[2] = {nullptr, nullptr};
-    // Timed choice between one and two streams: the first kTuneTrials forwards at a batch size use the two
-    // modes in turn, bracketed by events on the caller's stream; the faster one is kept for that batch size.
-    struct StreamTune {
-        int32_t batch = 0;                    // batch size the trials refer to
-        int32_t trial = 0;                    // trials enqueued so far
-        int32_t choice = 0;                   // 0: trying, else 1 or 2
-        int32_t last = 0;                     // the previous choice while trying again (0: none yet)
-        int32_t since = 0;                    // forwards since the choice was made
-        hipEvent_t ev[kTuneTrials][2] = {};   // [trial][start, stop], created with the handle
-    } tune;
+    // Schedule of the block stack: forced (1 or 2) for every batch size, or 0 = per batch size what
+    // free_dit_tune measured, one stream where nothing was measured.
+    int32_t forced_streams = 0;
+    struct Tuned { int32_t batch = 0, choice = 0; } tuned[kTuneSlots];
+    int32_t tuned_next = 0;                   // slot the next new batch size overwrites
+    hipEvent_t tune_ev[kTuneTrials][2] = {};  // [trial][start, stop], created on first use by free_dit_tune
+    Profiler prof;
+
+    int32_t streams_for(int32_t B) const {
+        if (forced_streams) return forced_streams;
+        for (const Tuned& t : tuned)
+            if (t.batch == B && t.choice) return t.choice;
+        return 1;
+    }
 
     const void* blk(int l, int which) const { return w[7 + 10 * l + which]; }
     const void* fin(int which) const { return w[7 + 10 * dims.depth + which]; }
@@ -206,7 +211,7 @@ struct ActBufs {
 // (B_* order); block l's six modulation vectors of sample b are mod[b * mod_rows + l * 6D ..].
 // cu_share: number of such stacks running side by side on different streams (tile choice of the GEMMs).
 int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const float* mod, int32_t mod_rows,
-                        const ActBufs& a, int b0, int nb, hipStream_t s, int cu_share = 1) {
+                        const ActBufs& a, int b0, int nb, hipStream_t s, Profiler* pf, int cu_share = 1) {
     const size_t esz = d.mode == FREE_BF16 ? 2 : 4;
     const int32_t M = nb * d.ntok;
     const int64_t r0 = static_cast<int64_t>(b0) * d.ntok;
@@ -228,58 +233,39 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
     for (int l = 0; l < nblk; ++l) {
         // x += gate1 * Proj(Attn(LN(x)(1+scale1)+shift1))
         {
-            ProfScope prof(PROF_LN_MOD, s);
+            ProfScope prof(pf, PROF_LN_MOD, s);
             FREE_TRY(launch_ln_modulate(xres_h, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn_h, s));
         }
         {
-            ProfScope prof(PROF_GEMM_QKV, s);
+            ProfScope prof(pf, PROF_GEMM_QKV, s);
             FREE_TRY(linear_dispatch(d, xn_h, W(l, B_QKV_W), Bv(l, B_QKV_B), M, 3 * d.D, d.D, FREE_EPI_BIAS, qkv_h,
                                      nullptr, RowVec{nullptr, 0, 1}, s, cu_share));
         }
         {
-            ProfScope prof(PROF_ATTN, s);
+            ProfScope prof(pf, PROF_ATTN, s);
             FREE_TRY(attention_dispatch(d, qkv_h, nb, att_h, s));
         }
         {
-            ProfScope prof(PROF_GEMM_PROJ, s);
+            ProfScope prof(pf, PROF_GEMM_PROJ, s);
             FREE_TRY(linear_dispatch(d, att_h, W(l, B_PROJ_W), Bv(l, B_PROJ_B), M, d.D, d.D, FREE_EPI_GATE_RESID,
                                      nullptr, xres_h, vec(l, 2), s, cu_share));
         }
         // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
         {
-            ProfScope prof(PROF_LN_MOD, s);
+            ProfScope prof(pf, PROF_LN_MOD, s);
             FREE_TRY(launch_ln_modulate(xres_h, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn_h, s));
         }
         {
-            ProfScope prof(PROF_GEMM_FC1, s);
+            ProfScope prof(pf, PROF_GEMM_FC1, s);
             FREE_TRY(linear_dispatch(d, xn_h, W(l, B_FC1_W), Bv(l, B_FC1_B), M, d.F, d.D, FREE_EPI_BIAS_GELU, hmid_h,
                                      nullptr, RowVec{nullptr, 0, 1}, s, cu_share));
         }
         {
-            ProfScope prof(PROF_GEMM_FC2, s);
+            ProfScope prof(pf, PROF_GEMM_FC2, s);
             FREE_TRY(linear_dispatch(d, hmid_h, W(l, B_FC2_W), Bv(l, B_FC2_B), M, d.D, d.F, FREE_EPI_GATE_RESID,
                                      nullptr, xres_h, vec(l, 5), s, cu_share));
         }
     }
-    return FREE_OK;
-}
-
-// Ends the trial phase: the median of the counted trials of each mode decides (ties go to one stream).
-int32_t choose_streams(free_dit_s::StreamTune* tn) {
-    float ms[2][kTuneTrials];
-    int n[2] = {0, 0};
-    for (int i = kTuneSkip; i < kTuneTrials; ++i) {
-        float t = 0.f;
-        if (!hip_ok(hipEventSynchronize(tn->ev[i][1])) || !hip_ok(hipEventElapsedTime(&t, tn->ev[i][0], tn->ev[i][1])))
-            return FREE_ERR_HIP;
-        ms[i & 1][n[i & 1]++] = t;
-    }
-    float med[2];
-    for (int m = 0; m < 2; ++m) {
-        std::sort(ms[m], ms[m] + n[m]);
-        med[m] = 0.5f * (ms[m][(n[m] - 1) / 2] + ms[m][n[m] / 2]);
-    }
-    tn->choice = med[0] <= med[1] ? 1 : 2;
     return FREE_OK;
 }
 
@@ -298,14 +284,14 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     void* hmid = ws + L.hmid;
 
     {
-    ProfScope prof(PROF_COND, s);
+    ProfScope prof(&h->prof, PROF_COND, s);
     FREE_TRY(launch_conditioning(t, y, B, d.D, d.tfreq, static_cast<const float*>(h->w[W_T_W1]),
                                  static_cast<const float*>(h->w[W_T_B1]), static_cast<const float*>(h->w[W_T_W2]),
                                  static_cast<const float*>(h->w[W_T_B2]),
                                  static_cast<const float*>(h->w[W_Y_TABLE]), cond_h, sc, s));
     }
     {
-    ProfScope prof(PROF_ADALN, s);
+    ProfScope prof(&h->prof, PROF_ADALN, s);
     if (d.mode == FREE_BF16 && adaln_mfma_supported(d.D, d.mod_rows))
         FREE_TRY(launch_adaln_mfma(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1,
                                    d.mod_rows, mod, s));
@@ -314,55 +300,25 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
                               d.mode, mod, s));
     }
     {
-    ProfScope prof(PROF_PATCH, s);
+    ProfScope prof(&h->prof, PROF_PATCH, s);
     FREE_TRY(launch_patch_embed(x, x_mod, B, d.C, d.H, d.W, d.p, d.D, static_cast<const float*>(h->w[W_PATCH_W]),
                                 static_cast<const float*>(h->w[W_PATCH_B]), h->pos, xres, s));
     }
     const ActBufs act{xres, xn, qkv, att, hmid};
     const void* const* blkw = h->w.data() + 7;
     auto run_blocks = [&](int b0, int nb, hipStream_t st, int cu_share) -> int32_t {
-        return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st, cu_share);
+        return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st, &h->prof, cu_share);
     };
-    // The samples of a packed batch are independent through all blocks, so the batch is cut in two
+    // The samples of a packed batch are independent through all blocks, so the batch can be cut in two
     // halves that run on two streams forked from (and joined back into) the caller's stream: while
     // one half is in a bandwidth-bound phase (layer norm, the residual read-modify-write at the end
     // of a GEMM, the first and last wave of tiles) the other half's matrix kernels fill the idle
-    // compute units.  Which schedule is faster differs between machines of the same type (12 x 1024 tokens,
-    // two streams / one stream: 15.0 / 14.6 ms, 15.0 / 15.4, 14.7 / 14.5, 14.8 / 14.2), so by default the
-    // first 24 forwards at a batch size time both in turn and the faster one is kept.  Both give the same numbers.
-    // Per-kernel profiling needs serial execution, and small batches are launch bound, so both keep the
-    // single stream.
-    const bool eligible = !g_prof.on && B >= 2 && static_cast<int64_t>(B / 2) * d.ntok >= kMinSplitRows;
-    int mode = g_batch_streams, trial = -1;
-    if (mode == 0) {
-        mode = 2;
-        free_dit_s::StreamTune& tn = h->tune;
-        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-        if (eligible && !hip_ok(hipStreamIsCapturing(s, &capturing))) return FREE_ERR_HIP;
-        if (eligible && capturing != hipStreamCaptureStatusNone) {
-            // no timing inside a capture: what an earlier eager call at this batch size decided, else two streams
-            if (tn.batch == B && (tn.choice || tn.last)) mode = tn.choice ? tn.choice : tn.last;
-        } else if (eligible) {
-            if (tn.batch != B) {
-                tn.batch = B;
-                tn.trial = 0;
-                tn.choice = tn.last = tn.since = 0;
-            } else if (tn.choice && ++tn.since >= kTuneAgain) {
-                tn.last = tn.choice;
-                tn.choice = tn.since = 0;
-                tn.trial = kTuneSkip;             // warm already: counted trials only
-            }
-            if (!tn.choice && tn.trial == kTuneTrials) FREE_TRY(choose_streams(&tn));
-            if (tn.choice) {
-                mode = tn.choice;
-            } else {
-                trial = tn.trial++;
-                mode = 1 + (trial & 1);
-            }
-        }
-    }
-    const bool split = mode == 2 && eligible;
-    if (trial >= 0 && !hip_ok(hipEventRecord(h->tune.ev[trial][0], s))) return FREE_ERR_HIP;
+    // compute units.  Which schedule is faster differs between machines of the same type by a few
+    // per cent either way, so one stream is the default and free_dit_tune measures on request.
+    // Both give the same numbers.  Per-kernel profiling needs serial execution, and small batches are
+    // launch bound, so both keep the single stream.  Nothing here waits on the host.
+    const bool eligible = !h->prof.on && B >= 2 && static_cast<int64_t>(B / 2) * d.ntok >= kMinSplitRows;
+    const bool split = eligible && h->streams_for(B) == 2;
     if (split) {
         if (!hip_ok(hipEventRecord(h->ev_fork, s))) return FREE_ERR_HIP;
         for (int i = 0; i < 2; ++i) {
@@ -375,14 +331,13 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     } else {
         FREE_TRY(run_blocks(0, B, s, 1));
     }
-    if (trial >= 0 && !hip_ok(hipEventRecord(h->tune.ev[trial][1], s))) return FREE_ERR_HIP;
     if (top_feat) {
         if (!hip_ok(hipMemcpyAsync(top_feat, xres, static_cast<size_t>(M) * d.D * 4, hipMemcpyDeviceToDevice, s)))
             return FREE_ERR_HIP;
     }
     RowVec fsh{mod + static_cast<int64_t>(d.depth) * 6 * d.D, d.mod_rows, d.ntok};
     RowVec fsc{mod + static_cast<int64_t>(d.depth) * 6 * d.D + d.D, d.mod_rows, d.ntok};
-    ProfScope prof(PROF_FINAL, s);
+    ProfScope prof(&h->prof, PROF_FINAL, s);
     FREE_TRY(launch_final_layer(xres, fsh, fsc, B, d.gh, d.gw, d.p, d.c_out, d.D, h->fin(F_W),
                                 static_cast<const float*>(h->fin(F_B)), d.mode, eps_out, s));
     return FREE_OK;
@@ -414,37 +369,41 @@ const char* free_status_string(int32_t st) {
 
 int32_t free_last_hip_error(void) { return g_last_hip_error; }
 
-int32_t free_set_batch_streams(int32_t n) {
-    if (n < 0 || n > 2) return FREE_ERR_RANGE;
-    g_batch_streams = n;
-    return FREE_OK;
-}
-
-int32_t free_get_batch_streams(void) { return g_batch_streams; }
-
-int32_t free_dit_stream_choice(free_dit_t h) {
+int32_t free_dit_set_streams(free_dit_t h, int32_t n) {
     if (!h) return FREE_ERR_NULL;
-    return h->tune.choice ? h->tune.choice : h->tune.last;
-}
-
-int32_t free_profile_begin(void) {
-    g_prof.used = 0;
-    g_prof.on = true;
+    if (n < 0 || n > 2) return FREE_ERR_RANGE;
+    h->forced_streams = n;
     return FREE_OK;
 }
 
-int32_t free_profile_end(float* ms, int32_t* launches) {
-    g_prof.on = false;
+int32_t free_dit_stream_choice(free_dit_t h, int32_t B) {
+    if (!h) return FREE_ERR_NULL;
+    if (B < 1) return FREE_ERR_SHAPE;
+    const bool eligible = B >= 2 && static_cast<int64_t>(B / 2) * h->dims.ntok >= kMinSplitRows;
+    return eligible ? h->streams_for(B) : 1;
+}
+
+int32_t free_profile_begin(free_dit_t h) {
+    if (!h) return FREE_ERR_NULL;
+    h->prof.used = 0;
+    h->prof.on = true;
+    return FREE_OK;
+}
+
+int32_t free_profile_end(free_dit_t h, float* ms, int32_t* launches) {
+    if (!h) return FREE_ERR_NULL;
+    Profiler& pf = h->prof;
+    pf.on = false;
     if (!ms || !launches) return FREE_ERR_NULL;
     for (int c = 0; c < FREE_PROF_NCAT; ++c) { ms[c] = 0.f; launches[c] = 0; }
-    for (size_t k = 0; k < g_prof.used; ++k) {
-        if (!hip_ok(hipEventSynchronize(g_prof.ev[2 * k + 1]))) return FREE_ERR_HIP;
+    for (size_t k = 0; k < pf.used; ++k) {
+        if (!hip_ok(hipEventSynchronize(pf.ev[2 * k + 1]))) return FREE_ERR_HIP;
         float t = 0.f;
-        if (!hip_ok(hipEventElapsedTime(&t, g_prof.ev[2 * k], g_prof.ev[2 * k + 1]))) return FREE_ERR_HIP;
-        ms[g_prof.cat[k]] += t;
-        launches[g_prof.cat[k]] += 1;
+        if (!hip_ok(hipEventElapsedTime(&t, pf.ev[2 * k], pf.ev[2 * k + 1]))) return FREE_ERR_HIP;
+        ms[pf.cat[k]] += t;
+        launches[pf.cat[k]] += 1;
     }
-    g_prof.used = 0;
+    pf.used = 0;
     return FREE_OK;
 }
 
@@ -465,7 +424,7 @@ int32_t free_mfma_ceiling(int32_t iters, double* tflops, double* mhz, void* stre
 const char* free_profile_category_name(int32_t c) {
     static const char* names[FREE_PROF_NCAT] = {"conditioning", "adaln", "patch_embed", "ln_modulate", "gemm_qkv",
                                                 "attention", "gemm_proj", "gemm_fc1", "gemm_fc2", "final_layer",
-                                                "eps_to_mean", "verify_partial", "verify_finish"};
+                                                "eps_to_mean", "verify"};
     return (c >= 0 && c < FREE_PROF_NCAT) ? names[c] : "unknown";
 }
 
@@ -578,8 +537,6 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
     for (int i = 0; i < 2 && ok; ++i)
         ok = hip_ok(hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking)) &&
              hip_ok(hipEventCreateWithFlags(&h->ev_join[i], hipEventDisableTiming));
-    for (int i = 0; i < kTuneTrials && ok; ++i)
-        ok = hip_ok(hipEventCreate(&h->tune.ev[i][0])) && hip_ok(hipEventCreate(&h->tune.ev[i][1]));
     if (!ok) {
         (void)free_dit_destroy(h);
         return FREE_ERR_HIP;
@@ -599,7 +556,9 @@ int32_t free_dit_destroy(free_dit_t h) {
     if (h->ev_fork && !hip_ok(hipEventDestroy(h->ev_fork))) st = FREE_ERR_HIP;
     for (int i = 0; i < kTuneTrials; ++i)
         for (int j = 0; j < 2; ++j)
-            if (h->tune.ev[i][j] && !hip_ok(hipEventDestroy(h->tune.ev[i][j]))) st = FREE_ERR_HIP;
+            if (h->tune_ev[i][j] && !hip_ok(hipEventDestroy(h->tune_ev[i][j]))) st = FREE_ERR_HIP;
+    for (hipEvent_t e : h->prof.ev)
+        if (!hip_ok(hipEventDestroy(e))) st = FREE_ERR_HIP;
     if (h->dev_block && !hip_ok(hipFree(h->dev_block))) st = FREE_ERR_HIP;
     delete h;
     return st;
@@ -620,6 +579,58 @@ int32_t dit_forward_packed(free_dit_t h, const float* x, const int32_t* t, const
                         static_cast<hipStream_t>(stream));
 }
 
+int32_t free_dit_tune(free_dit_t h, const float* x, const int32_t* t, const int32_t* y, int32_t B, float* eps_out,
+                      void* workspace, size_t ws_bytes, void* stream) {
+    if (!h || !x || !t || !y || !eps_out) return FREE_ERR_NULL;
+    if (B < 1 || static_cast<int64_t>(B) * h->dims.ntok > INT32_MAX / 4) return FREE_ERR_SHAPE;
+    FREE_TRY(check_ws(workspace, ws_bytes, make_layout(h->dims, B).total));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool eligible = B >= 2 && static_cast<int64_t>(B / 2) * h->dims.ntok >= kMinSplitRows;
+    if (!eligible) return FREE_OK;                      // such a batch never splits: nothing to measure
+    for (int i = 0; i < kTuneTrials; ++i)
+        for (int j = 0; j < 2; ++j)
+            if (!h->tune_ev[i][j] && !hip_ok(hipEventCreate(&h->tune_ev[i][j]))) return FREE_ERR_HIP;
+    const int32_t forced_before = h->forced_streams;
+    const bool prof_before = h->prof.on;
+    h->prof.on = false;
+    int32_t st = FREE_OK;
+    for (int i = 0; i < kTuneTrials && st == FREE_OK; ++i) {
+        h->forced_streams = 1 + (i & 1);
+        if (!hip_ok(hipEventRecord(h->tune_ev[i][0], s))) st = FREE_ERR_HIP;
+        if (st == FREE_OK) st = forward_impl(h, x, B, t, y, B, eps_out, nullptr, static_cast<char*>(workspace), s);
+        if (st == FREE_OK && !hip_ok(hipEventRecord(h->tune_ev[i][1], s))) st = FREE_ERR_HIP;
+    }
+    h->forced_streams = forced_before;
+    h->prof.on = prof_before;
+    if (st != FREE_OK) return st;
+    // the median of the counted trials of each schedule decides (ties go to one stream)
+    float ms[2][kTuneTrials];
+    int n[2] = {0, 0};
+    for (int i = kTuneSkip; i < kTuneTrials; ++i) {
+        float el = 0.f;
+        if (!hip_ok(hipEventSynchronize(h->tune_ev[i][1])) ||
+            !hip_ok(hipEventElapsedTime(&el, h->tune_ev[i][0], h->tune_ev[i][1])))
+            return FREE_ERR_HIP;
+        ms[i & 1][n[i & 1]++] = el;
+    }
+    float med[2];
+    for (int m = 0; m < 2; ++m) {
+        std::sort(ms[m], ms[m] + n[m]);
+        med[m] = 0.5f * (ms[m][(n[m] - 1) / 2] + ms[m][n[m] / 2]);
+    }
+    const int32_t choice = med[0] <= med[1] ? 1 : 2;
+    int slot = -1;
+    for (int i = 0; i < kTuneSlots; ++i)
+        if (h->tuned[i].batch == B) slot = i;
+    if (slot < 0) {
+        slot = h->tuned_next;
+        h->tuned_next = (h->tuned_next + 1) % kTuneSlots;
+    }
+    h->tuned[slot].batch = B;
+    h->tuned[slot].choice = choice;
+    return FREE_OK;
+}
+
 size_t spec_verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d) {
     if (K > FREE_MAX_DRAFTS) return 0;
     return verify_workspace_bytes(n_traj, K, d);
@@ -634,8 +645,8 @@ int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_
     if (n_traj < 0 || K < 1 || K > FREE_MAX_DRAFTS || d < 1) return FREE_ERR_SHAPE;
     if (n_traj == 0) return FREE_OK;
     VerifyArgs a{m_target, m_draft, x_draft, nullptr, sigma, u, lambda, n_traj, K, d,
-                 log_ratio, accept, n_accept, x_out};
-    return launch_verify(a, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+                 log_ratio, accept, n_accept, x_out, nullptr};
+    return launch_verify(a, workspace, ws_bytes, false, static_cast<hipStream_t>(stream));
 }
 
 int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, const float* m_draft,
@@ -660,15 +671,17 @@ int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, con
     int32_t* yp = reinterpret_cast<int32_t*>(ws + L.ypack);
     float* eps = reinterpret_cast<float*>(ws + L.eps);
     float* mt = m_target_out ? m_target_out : reinterpret_cast<float*>(ws + L.mtarget);
-    FREE_TRY(launch_pack_cond(t, y, d.classes, K, dup, tp, yp, s));
+    // the same small kernel clears the arrival counter of the verification at the end of the round
+    FREE_TRY(launch_pack_cond(t, y, d.classes, K, dup, tp, yp, s, verify_counters(ws + L.vpart), 1));
     FREE_TRY(forward_impl(h, x_states, K, tp, yp, B, eps, nullptr, ws, s));
     {
-        ProfScope prof(PROF_EPS2MEAN, s);
+        ProfScope prof(&h->prof, PROF_EPS2MEAN, s);
         FREE_TRY(launch_eps_to_mean(eps, x_states, coef_x, coef_eps, cfg_scale, K, d.C, d.c_out,
                                     static_cast<int64_t>(d.H) * d.W, mt, s));
     }
-    VerifyArgs a{mt, m_draft, x_states, x_last, sigma, u, lambda, 1, K, d.d, log_ratio, accept, n_accept, x_out};
-    return launch_verify(a, ws + L.vpart, verify_workspace_bytes(1, K, d.d), s);
+    VerifyArgs a{mt, m_draft, x_states, x_last, sigma, u, lambda, 1, K, d.d, log_ratio, accept, n_accept, x_out,
+                 &h->prof};
+    return launch_verify(a, ws + L.vpart, L.vpart_bytes, true, s);
 }
 
 int32_t free_op_linear(const void* A, const void* W, const float* bias, int32_t M, int32_t N, int32_t Kdim,
@@ -797,7 +810,7 @@ int32_t drafter_forward_impl(free_drafter_t dr, const float* x, int32_t x_mod, c
     FREE_TRY(linear_dispatch(d, fin, dr->w[0], static_cast<const float*>(dr->w[1]), static_cast<int32_t>(M), d.D,
                              2 * d.D, FREE_EPI_GATE_RESID, nullptr, f_out, RowVec{dr->ones, 0, 1}, s));
     const ActBufs act{f_out, ws + L.xn, ws + L.qkv, ws + L.att, ws + L.hmid};
-    FREE_TRY(run_block_stack(d, dr->blkw(), dr->depth, mod, mod_stride, act, 0, B, s));
+    FREE_TRY(run_block_stack(d, dr->blkw(), dr->depth, mod, mod_stride, act, 0, B, s, &h->prof));
     RowVec fsh{mod + static_cast<int64_t>(dr->depth) * 6 * d.D, mod_stride, d.ntok};
     RowVec fsc{mod + static_cast<int64_t>(dr->depth) * 6 * d.D + d.D, mod_stride, d.ntok};
     return launch_final_layer(f_out, fsh, fsc, B, d.gh, d.gw, d.p, d.c_out, d.D, dr->fin(F_W),
@@ -1048,16 +1061,17 @@ int32_t sample_loop(free_dit_t h, free_drafter_t dr, const float* x_init, int32_
             FREE_TRY(draft_round(dr, x_cur, feat, tmap + i, y, cfg_scale, coef_x + i, coef_eps + i, sigma + i,
                                  xi + static_cast<int64_t>(i) * d.d, K, F(o.x_states), F(o.x_last), F(o.m_draft), feat,
                                  ws + o.ws_draft, make_draft_layout(d, dr->mod_rows, dup).total, s));
-        FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, K, dup, tp, yp, s));
+        const WsLayout TL = make_layout(d, B);
+        FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, K, dup, tp, yp, s,
+                                  verify_counters(ws + o.ws_target + TL.vpart), 1));
         FREE_TRY(forward_impl(h, F(o.x_states), K, tp, yp, B, F(o.eps), frozen ? nullptr : top, ws + o.ws_target, s));
         FREE_TRY(launch_eps_to_mean(F(o.eps), F(o.x_states), coef_x + i, coef_eps + i, cfg_scale, K, d.C, d.c_out, hw,
                                     F(o.m_target), s, frozen ? eps_g : nullptr));
         if (eps_delta) FREE_TRY(launch_sqdist(F(o.m_draft), F(o.m_target), K, d.d, dist, s));
         VerifyArgs a{F(o.m_target), F(o.m_draft), F(o.x_states), F(o.x_last), sigma + i, u + i,
                      lambda ? lambda + i : nullptr, 1, K, d.d, F(o.log_ratio),
-                     reinterpret_cast<uint8_t*>(ws + o.accept), n_acc_dev, F(o.x_refl)};
-        const WsLayout TL = make_layout(d, B);
-        FREE_TRY(launch_verify(a, ws + o.ws_target + TL.vpart, verify_workspace_bytes(1, K, d.d), s));
+                     reinterpret_cast<uint8_t*>(ws + o.accept), n_acc_dev, F(o.x_refl), &h->prof};
+        FREE_TRY(launch_verify(a, ws + o.ws_target + TL.vpart, TL.vpart_bytes, true, s));
         int32_t n = 0;
         if (!hip_ok(hipMemcpyAsync(&n, n_acc_dev, 4, hipMemcpyDeviceToHost, s)) || !hip_ok(hipStreamSynchronize(s)))
             return FREE_ERR_HIP;

@@ -247,6 +247,10 @@ SOURCE_MUTANTS = [
      lambda: _edited(fo.frozen_draft_steps, "xs.append(m + float(sigma[k]) * np.asarray(xi, F64)[k].reshape(x.shape))",
                      "xs.append(m)"),
      [profile_pins.test_frozen_drafts_closed_form]),
+    # the recorded deviation left in units of the mean: not divided by the coefficient of the noise estimate
+    ("deviation_not_divided_by_coef_eps", "self_speculative_run",
+     lambda: _edited(fo.self_speculative_run, " / abs(float(coef_eps[i]))", ""),
+     [profile_pins.test_recorded_deviation_is_the_distance_between_the_two_noise_estimates]),
 ]
 
 

@@ -99,3 +99,38 @@ def test_self_speculation_records_deviation_and_outcome_per_checked_step():
     assert checked.sum() >= st["accepted"] and checked.sum() <= st["accepted"] + st["rounds"]
     lam = fo.relaxation_profile_from_deltas(delta, 3)
     assert lam.shape == (12,) and lam[0] == 1.0 and np.all(np.diff(lam) <= 1e-15)
+
+
+def test_recorded_deviation_is_the_distance_between_the_two_noise_estimates():
+    """Magnitude of eps_delta (Sec. 3.4: the deviation between the reused noise estimate and the target's own
+    at the drafted state).  With one draft per round and u = 0 (every draft passes whatever the ratio) the chain
+    is a plain recurrence that can be written down without the loop: e_i = eps_guided(x_i, t_i),
+    x_1 = c_x x_0 + c_e e_0 + s xi_0, then x_{i+1} = c_x x_i + c_e e_{i-1} + s xi_i, and the deviation recorded
+    at step i is || e_{i-1} - e_i ||_2, computed here from dit_forward on the visited states."""
+    cfg = synth.dit_config("tiny")
+    w = synth.make_weights(cfg, seed=4, std=0.3)
+    for cfg_scale in (4.0, 1.0):
+        a = _run_case(w, cfg, cfg_scale=cfg_scale, S=6, L=1, seed=8)
+        a["u"] = np.zeros_like(a["u"])
+        x, st, delta, acc = fo.self_speculative_run(w, cfg, **a)
+        C, S = cfg["in_ch"], len(a["tmap"])
+
+        def guided(xs, t):
+            if cfg_scale > 1.0:
+                out, _ = fo.dit_forward(w, cfg, np.stack([xs, xs]), np.array([t, t]), np.array([a["y"], cfg["num_classes"]]))
+                return fo.cfg_combine(out[:1, :C], out[1:, :C], cfg_scale)[0]
+            out, _ = fo.dit_forward(w, cfg, xs[None], np.array([t]), np.array([a["y"]]))
+            return out[0, :C]
+
+        xs = [np.asarray(a["x0"], np.float64)]
+        es = []
+        for i in range(S):
+            es.append(guided(xs[i], a["tmap"][i]))
+            used = es[i] if (i == 0 or i >= a["n_spec"]) else es[i - 1]      # plain target step / frozen draft
+            xs.append(a["coef_x"][i] * xs[i] + a["coef_eps"][i] * used + a["sigma"][i] * a["xi"][i].reshape(xs[i].shape))
+        assert st["rounds"] == S - 2 and st["accepted"] == S - 2
+        for i in range(1, S - 1):
+            want = np.linalg.norm((es[i - 1] - es[i]).ravel())
+            assert want > 1e-6 and abs(delta[i] - want) <= 1e-9 * want, (i, delta[i], want)
+        assert np.isnan(delta[0]) and np.isnan(delta[S - 1])
+        assert np.allclose(x, xs[S], rtol=1e-10, atol=1e-12)
