@@ -46,7 +46,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "spec_round_xl2_512_hbm_traffic.md
 CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<384, 192, 4, 2, 1, true>`", "gemm_qkv": "gemm_bf16_kernel<256, 256, 4, 2, 0, true>`",
                    "gemm_fc2": "gemm_bf16_kernel<256, 256, 4, 2, 2, true>` FC2",
                    "gemm_proj": "gemm_bf16_kernel<256, 256, 4, 2, 2, true>` out-projection",
-                   "attention": "attn_mfma_kernel<72, 1>`", "verify": "verify_fused_kernel<true>`"}
+                   "attention": "attn_mfma_kernel<72, 1>`", "verify_partial": "verify_partial_kernel<true>`"}
 
 
 def measured_traffic(category):
@@ -217,17 +217,20 @@ def bench_draft(args, cfg, model, ri, sched, a, verify_step):
 
 def bench_verify(args, n_sets=6):
     """spec_verify alone at 64 x 6 x 16384 fp32, rotating over n_sets distinct input sets
-    (> 256 MB in total) so that the Infinity Cache cannot stand in for HBM.  A call is one small fill
-    kernel (the arrival counters) and ONE streaming kernel that also takes the decisions and writes the
-    reflected samples; every call is bracketed by HIP events on the launch stream (torch's current stream
-    is the stream the binding hands to the library)."""
+    (> 256 MB in total) so that the Infinity Cache cannot stand in for HBM.  A call is two launches: the
+    streaming kernel (verify_partial_kernel, the dominant one: 12 bytes per latent element and draft) and
+    the finishing kernel (decisions + reflected samples).  Per-launch durations come from the library's
+    benchmark variant of the call, which brackets both launches with HIP events on the launch stream;
+    whole calls are also timed back to back with events before and after every call."""
     import torch
     from paper_2511_20390_amd import binding, synth
     n_traj, K, d = 64, 6, 16384
     _, _, sg = binding.free_ddpm_schedule()
+    blocker = torch.ones(256 << 20, device="cuda:0", dtype=torch.float32)       # 1 GiB: a copy takes ~0.4 ms
+    blocker_out = torch.empty_like(blocker)
 
     def event_us(calls):
-        """Average time per call from events recorded before the first and after every call."""
+        """Time of every call from events recorded before the first and after every call."""
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
         torch.cuda.synchronize()
         # a few milliseconds of unrelated device work first: the host then enqueues all the calls while the
@@ -241,8 +244,18 @@ def bench_verify(args, n_sets=6):
         torch.cuda.synchronize()
         return sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(len(calls)))
 
-    blocker = torch.ones(256 << 20, device="cuda:0", dtype=torch.float32)       # 1 GiB: a copy takes ~0.4 ms
-    blocker_out = torch.empty_like(blocker)
+    def timed_us(call_args, out, ws, reps):
+        """(streaming launch, finishing launch) microseconds per call, by events inside the call; an untimed
+        call on another input set goes first, so the timed one meets the device as back-to-back calls do."""
+        a, b = [], []
+        for _ in range(reps):
+            for i, ca in enumerate(call_args):
+                binding.spec_verify(*call_args[(i + 1) % len(call_args)], out=out, workspace=ws)
+                r = binding.spec_verify(*ca, out=out, workspace=ws, timed=True)
+                a.append(r["stream_us"])
+                b.append(r["finish_us"])
+        return sum(a) / len(a), sum(b) / len(b), sorted(a)[len(a) // 2]
+
     sets = []
     for i in range(n_sets):
         vi = synth.make_verify_inputs(n_traj, K, d, 0.01, 100 + i, sg)
@@ -258,10 +271,11 @@ def bench_verify(args, n_sets=6):
     for c in rot:
         c()
     torch.cuda.synchronize()
-    call_us = (time.perf_counter() - t0) * 1e6 / len(rot)
+    host_call_us = (time.perf_counter() - t0) * 1e6 / len(rot)
     us = event_us(rot)
-    launch_us = sum(us) / len(us)
-    warm = event_us([lambda: binding.spec_verify(*sets[0], out=out, workspace=ws) for _ in range(reps * n_sets)])
+    call_us = sum(us) / len(us)
+    stream_us, finish_us, stream_med = timed_us(sets, out, ws, reps)
+    warm_us, _, _ = timed_us(sets[:1], out, ws, reps * n_sets)
     nrej = int((out["n_accept"] < K).sum().item())
     # the same kernel on a problem large enough to leave the launch ramp behind: 384 trajectories (453 MB)
     nl = 384
@@ -269,24 +283,24 @@ def bench_verify(args, n_sets=6):
     big = [torch.from_numpy(vl[k]).to("cuda:0") for k in ("m_target", "m_draft", "x_draft", "sigma", "u")]
     out_l = binding.spec_verify(*big)
     ws_l = torch.empty(binding.spec_verify_workspace_bytes(nl, K, d), dtype=torch.uint8, device="cuda:0")
-    lus = event_us([lambda: binding.spec_verify(*big, out=out_l, workspace=ws_l) for _ in range(8)])
-    nrej_l = int((out_l["n_accept"] < K).sum().item())
-    large_gbs = (nl * K * 3 * d * 4 + nrej_l * 4 * d * 4) / (sum(lus) / len(lus) * 1e-6) / 1e9
+    large_us, _, _ = timed_us([big], out_l, ws_l, 8)
     del big, out_l, ws_l
     bytes_stream = n_traj * K * 3 * d * 4            # 12 bytes per latent element and draft
     bytes_reflect = nrej * 4 * d * 4                 # + 16 bytes per element of a rejected draft
-    gbs = (bytes_stream + bytes_reflect) / (launch_us * 1e-6) / 1e9
-    return {"kernel": "verify_fused_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic("verify"), "avg_launch_us": launch_us,
-            "median_launch_us": us[len(us) // 2],
-            "measured": "HIP events on the launch stream before and after every call (fill kernel + streaming kernel, "
-                        "launch gaps included), 6 rotating input sets",
-            "streaming_only_GBs": bytes_stream / (launch_us * 1e-6) / 1e9,
-            "warm_cache_GBs": (bytes_stream + bytes_reflect) / (sum(warm) / len(warm) * 1e-6) / 1e9,
-            "GBs_at_384_trajectories_453MB": large_gbs,
-            "call_us_back_to_back": call_us, "rounds_per_s_64traj": 64e6 / call_us,
-            "algorithmic_bytes": bytes_stream + bytes_reflect, "algorithmic_bytes_streaming": bytes_stream,
-            "reflected_rows": nrej,
+    gbs = bytes_stream / (stream_us * 1e-6) / 1e9
+    return {"kernel": "verify_partial_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic("verify_partial"), "avg_launch_us": stream_us,
+            "median_launch_us": stream_med,
+            "measured": "HIP events on the launch stream around each of the call's two launches, 6 rotating input sets",
+            "finish_avg_us": finish_us, "warm_cache_GBs": bytes_stream / (warm_us * 1e-6) / 1e9,
+            "GBs_at_384_trajectories_453MB": nl * K * 3 * d * 4 / (large_us * 1e-6) / 1e9,
+            "whole_call": {"avg_us": call_us, "median_us": us[len(us) // 2],
+                           "algorithmic_bytes": bytes_stream + bytes_reflect,
+                           "GBs": (bytes_stream + bytes_reflect) / (call_us * 1e-6) / 1e9,
+                           "frac": (bytes_stream + bytes_reflect) / (call_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                           "measured": "events before and after every call, calls enqueued back to back"},
+            "host_call_us_back_to_back": host_call_us, "rounds_per_s_64traj": 64e6 / max(call_us, host_call_us),
+            "algorithmic_bytes": bytes_stream, "reflected_rows": nrej,
             "workload": "64 traj x 6 drafts x 16384 fp32, 6 rotating input sets (453 MB)"}
 
 
@@ -475,6 +489,8 @@ def main():
     ap.add_argument("--gemm-only", default=None, metavar="M,N,K,EPI",
                     help="time one linear layer out = epilogue(X W^T + b) of the given shape through the C ABI "
                          "(EPI 0: bias, 1: bias + GELU, 2: gated fp32 residual update), e.g. under rocprofv3")
+    ap.add_argument("--verify-only", action="store_true",
+                    help="time only spec_verify at 64 x 6 x 16384 (the HBM roofline), e.g. under rocprofv3")
     ap.add_argument("--loop", action="store_true", help="time the whole sampler (Alg. 1) instead of the verification round")
     ap.add_argument("--loop-steps", type=int, default=250)
     ap.add_argument("--loop-images", type=int, default=1)
@@ -500,6 +516,12 @@ def main():
         del src, dst
     if args.gemm_only:
         print(json.dumps(bench_gemm(args)))
+        return
+    if args.verify_only:
+        r = bench_verify(args)
+        print(json.dumps({"metric": "spec_verify call", "unit": "us", "value": r["avg_launch_us"], "higher_is_better": False,
+                          "n_gpus": 1, "dtype": "f32", "data": "synthetic", "config": {"workload": r["workload"]},
+                          "roofline": r}))
         return
     if args.loop:
         print(json.dumps({"metric": "whole sampler (Alg. 1), wall time per image", "unit": "s", "n_gpus": 1,

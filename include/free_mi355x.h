@@ -200,19 +200,30 @@ int32_t dit_forward_packed(free_dit_t h, const float* x, const int32_t* t, const
  * Sums over d are accumulated in fp64 in a fixed order: results are
  * deterministic run to run.
  * Workspace: spec_verify_workspace_bytes(n_traj, K, d) bytes of device memory,
- * 8-byte aligned, contents arbitrary (one arrival counter per trajectory, which
- * the call clears itself, and the partial sums); FREE_ERR_WORKSPACE if missing
- * or too small.  Limits: 1 <= K <= FREE_MAX_DRAFTS; n_traj * K * ceil(d / chunk)
- * workgroups must fit a one-dimensional grid (2^31 - 1; chunk >= 1024 elements);
- * states of more than 2^18 elements are reflected by a second launch, which
- * needs n_traj <= 65535; FREE_ERR_SHAPE otherwise.  Enqueues one small fill
- * kernel and ONE streaming kernel; no host synchronisation. */
+ * 8-byte aligned, contents arbitrary (the partial sums of the first launch);
+ * FREE_ERR_WORKSPACE if missing or too small.  Limits: 1 <= K <= FREE_MAX_DRAFTS;
+ * n_traj <= 65535 (second grid dimension of the finishing launch) and
+ * n_traj * K * ceil(d / chunk) workgroups must fit a one-dimensional grid
+ * (2^31 - 1; chunk >= 1024 elements); FREE_ERR_SHAPE otherwise.  Enqueues two
+ * kernels (streaming sums; decisions + reflection); no host synchronisation. */
 size_t spec_verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d);
 int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_draft,
                     const float* sigma, const float* u, const float* lambda,
                     int32_t n_traj, int32_t K, int64_t d,
                     float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out,
                     void* workspace, size_t ws_bytes, void* stream);
+
+/* Benchmark helper, NOT a hot-path call: spec_verify with a start and a stop HIP event
+ * attached to each of its two dispatches on `stream` (the events are created and
+ * destroyed inside the call); waits for the call to finish and returns [host] the
+ * milliseconds the streaming kernel and the finishing kernel ran.  Same arguments, results and status codes as spec_verify,
+ * n_traj >= 1. */
+int32_t spec_verify_timed(const float* m_target, const float* m_draft, const float* x_draft,
+                          const float* sigma, const float* u, const float* lambda,
+                          int32_t n_traj, int32_t K, int64_t d,
+                          float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out,
+                          void* workspace, size_t ws_bytes, void* stream,
+                          float* stream_ms, float* finish_ms);
 
 /* ---- one verification round of one trajectory (Alg. 1 body after drafting) -
  * Packed forward on the K states x_states = (x_a, x^_{a+1}, ..., x^_{a+K-1})

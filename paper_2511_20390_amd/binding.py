@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "free_version", "free_status_string", "free_last_hip_error", "free_dit_set_streams",
     "free_dit_tune", "free_dit_stream_choice", "free_ddpm_schedule", "free_sde_schedule",
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
-    "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_round",
+    "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_verify_timed", "spec_round",
     "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
     "drafter_forward", "draft_round", "free_sample_workspace_bytes", "free_sample",
     "free_self_speculative_workspace_bytes", "free_self_speculative", "free_lambda_profile",
@@ -88,6 +88,8 @@ def load():
     lib.spec_verify_workspace_bytes.argtypes = [i32, i32, i64]
     lib.spec_verify.restype = i32
     lib.spec_verify.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp, sz, vp]
+    lib.spec_verify_timed.restype = i32
+    lib.spec_verify_timed.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp, sz, vp, vp, vp]
     lib.spec_round.restype = i32
     lib.spec_round.argtypes = [vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.free_drafter_weight_count.restype = i32
@@ -145,12 +147,11 @@ def _dev(t, dtype, name, shape=None, optional=False):
     """Pointer of a device tensor handed to the library, after the checks the C side cannot make: the
     library reads raw memory, so a tensor of another element type (torch integers default to int64), a
     strided view or a host tensor would give wrong results or out-of-bounds device reads, not an error."""
-    import torch
     if t is None:
         if optional:
             return None
         raise FreeError(FREE_ERR_NULL, name)
-    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+    if not getattr(t, "is_cuda", False):
         raise FreeError(FREE_ERR_NULL, f"{name}: not a device tensor")
     if t.dtype != dtype:
         raise FreeError(FREE_ERR_DTYPE, f"{name}: element type {t.dtype}, expected {dtype}")
@@ -229,8 +230,10 @@ def _verify_out(out, n_traj, K, d, dev):
     return out
 
 
-def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None, out=None, workspace=None):
-    """Device tensors in, dict of device tensors out.  m_*, x_draft: [n_traj, K, d] fp32."""
+def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None, out=None, workspace=None, timed=False):
+    """Device tensors in, dict of device tensors out.  m_*, x_draft: [n_traj, K, d] fp32.
+    timed: blocking benchmark variant; the dict then also holds "stream_us" and "finish_us", the durations
+    of the call's two launches by HIP events on the launch stream."""
     import torch
     f32 = torch.float32
     n_traj, K, d = m_target.shape
@@ -238,14 +241,20 @@ def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None, out=None, worksp
     out = _verify_out(out, n_traj, K, d, dev)
     if workspace is None:
         workspace = torch.empty(max(256, spec_verify_workspace_bytes(n_traj, K, d)), dtype=torch.uint8, device=dev)
-    _check(load().spec_verify(_dev(m_target, f32, "m_target"), _dev(m_draft, f32, "m_draft", (n_traj, K, d)),
-                              _dev(x_draft, f32, "x_draft", (n_traj, K, d)), _dev(sigma, f32, "sigma", (n_traj, K)),
-                              _dev(u, f32, "u", (n_traj, K)), _dev(lam, f32, "lambda", (n_traj, K), optional=True),
-                              n_traj, K, d, _dev(out["log_ratio"], f32, "log_ratio", (n_traj, K)),
-                              _dev(out["accept"], torch.uint8, "accept", (n_traj, K)),
-                              _dev(out["n_accept"], torch.int32, "n_accept", (n_traj,)),
-                              _dev(out["x_out"], f32, "x_out", (n_traj, d)),
-                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()), "spec_verify")
+    args = [_dev(m_target, f32, "m_target"), _dev(m_draft, f32, "m_draft", (n_traj, K, d)),
+            _dev(x_draft, f32, "x_draft", (n_traj, K, d)), _dev(sigma, f32, "sigma", (n_traj, K)),
+            _dev(u, f32, "u", (n_traj, K)), _dev(lam, f32, "lambda", (n_traj, K), optional=True),
+            n_traj, K, d, _dev(out["log_ratio"], f32, "log_ratio", (n_traj, K)),
+            _dev(out["accept"], torch.uint8, "accept", (n_traj, K)),
+            _dev(out["n_accept"], torch.int32, "n_accept", (n_traj,)),
+            _dev(out["x_out"], f32, "x_out", (n_traj, d)),
+            _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()]
+    if timed:
+        a, b = C.c_float(0.0), C.c_float(0.0)
+        _check(load().spec_verify_timed(*args, C.addressof(a), C.addressof(b)), "spec_verify_timed")
+        out = dict(out, stream_us=a.value * 1e3, finish_us=b.value * 1e3)
+    else:
+        _check(load().spec_verify(*args), "spec_verify")
     return out
 
 

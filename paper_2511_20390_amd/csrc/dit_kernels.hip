@@ -789,10 +789,8 @@ __global__ void eps_to_mean_kernel(const float* __restrict__ eps_out, const floa
 }
 
 __global__ void pack_cond_kernel(const int32_t* __restrict__ t, int32_t y, int32_t null_label, int32_t K,
-                                 int32_t dup, int32_t* __restrict__ t_out, int32_t* __restrict__ y_out,
-                                 uint32_t* __restrict__ clear, int32_t n_clear) {
+                                 int32_t dup, int32_t* __restrict__ t_out, int32_t* __restrict__ y_out) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < n_clear) clear[b] = 0u;
     if (b >= K * dup) return;
     t_out[b] = t[b % K];
     y_out[b] = (b < K) ? y : null_label;
@@ -1141,11 +1139,10 @@ int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const fl
 }
 
 int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_t K, int32_t dup,
-                         int32_t* t_out, int32_t* y_out, hipStream_t s, uint32_t* clear, int32_t n_clear) {
-    if (!clear) n_clear = 0;
-    const int n = K * dup > n_clear ? K * dup : n_clear;
+                         int32_t* t_out, int32_t* y_out, hipStream_t s) {
+    const int n = K * dup;
     hipLaunchKernelGGL(pack_cond_kernel, dim3((n + 63) / 64), dim3(64), 0, s, t, y, null_label, K, dup, t_out,
-                       y_out, clear, n_clear);
+                       y_out);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 

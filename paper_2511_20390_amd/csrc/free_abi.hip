@@ -646,7 +646,33 @@ int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_
     if (n_traj == 0) return FREE_OK;
     VerifyArgs a{m_target, m_draft, x_draft, nullptr, sigma, u, lambda, n_traj, K, d,
                  log_ratio, accept, n_accept, x_out, nullptr};
-    return launch_verify(a, workspace, ws_bytes, false, static_cast<hipStream_t>(stream));
+    return launch_verify(a, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int32_t spec_verify_timed(const float* m_target, const float* m_draft, const float* x_draft, const float* sigma,
+                          const float* u, const float* lambda, int32_t n_traj, int32_t K, int64_t d, float* log_ratio,
+                          uint8_t* accept, int32_t* n_accept, float* x_out, void* workspace, size_t ws_bytes,
+                          void* stream, float* stream_ms, float* finish_ms) {
+    if (!m_target || !m_draft || !x_draft || !sigma || !u || !log_ratio || !accept || !n_accept || !x_out ||
+        !stream_ms || !finish_ms)
+        return FREE_ERR_NULL;
+    if (n_traj < 1 || K < 1 || K > FREE_MAX_DRAFTS || d < 1) return FREE_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    int32_t st = FREE_OK;
+    for (int i = 0; i < 4 && st == FREE_OK; ++i)
+        if (!hip_ok(hipEventCreate(&ev[i]))) st = FREE_ERR_HIP;
+    if (st == FREE_OK) {
+        VerifyArgs a{m_target, m_draft, x_draft, nullptr, sigma, u, lambda, n_traj, K, d,
+                     log_ratio, accept, n_accept, x_out, nullptr};
+        st = launch_verify(a, workspace, ws_bytes, s, ev);
+    }
+    if (st == FREE_OK && (!hip_ok(hipEventSynchronize(ev[3])) || !hip_ok(hipEventElapsedTime(stream_ms, ev[0], ev[1])) ||
+                          !hip_ok(hipEventElapsedTime(finish_ms, ev[2], ev[3]))))
+        st = FREE_ERR_HIP;
+    for (int i = 0; i < 4; ++i)
+        if (ev[i]) (void)hipEventDestroy(ev[i]);
+    return st;
 }
 
 int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, const float* m_draft,
@@ -671,8 +697,7 @@ int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, con
     int32_t* yp = reinterpret_cast<int32_t*>(ws + L.ypack);
     float* eps = reinterpret_cast<float*>(ws + L.eps);
     float* mt = m_target_out ? m_target_out : reinterpret_cast<float*>(ws + L.mtarget);
-    // the same small kernel clears the arrival counter of the verification at the end of the round
-    FREE_TRY(launch_pack_cond(t, y, d.classes, K, dup, tp, yp, s, verify_counters(ws + L.vpart), 1));
+    FREE_TRY(launch_pack_cond(t, y, d.classes, K, dup, tp, yp, s));
     FREE_TRY(forward_impl(h, x_states, K, tp, yp, B, eps, nullptr, ws, s));
     {
         ProfScope prof(&h->prof, PROF_EPS2MEAN, s);
@@ -681,7 +706,7 @@ int32_t spec_round(free_dit_t h, const float* x_states, const float* x_last, con
     }
     VerifyArgs a{mt, m_draft, x_states, x_last, sigma, u, lambda, 1, K, d.d, log_ratio, accept, n_accept, x_out,
                  &h->prof};
-    return launch_verify(a, ws + L.vpart, L.vpart_bytes, true, s);
+    return launch_verify(a, ws + L.vpart, L.vpart_bytes, s);
 }
 
 int32_t free_op_linear(const void* A, const void* W, const float* bias, int32_t M, int32_t N, int32_t Kdim,
@@ -1062,8 +1087,7 @@ int32_t sample_loop(free_dit_t h, free_drafter_t dr, const float* x_init, int32_
                                  xi + static_cast<int64_t>(i) * d.d, K, F(o.x_states), F(o.x_last), F(o.m_draft), feat,
                                  ws + o.ws_draft, make_draft_layout(d, dr->mod_rows, dup).total, s));
         const WsLayout TL = make_layout(d, B);
-        FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, K, dup, tp, yp, s,
-                                  verify_counters(ws + o.ws_target + TL.vpart), 1));
+        FREE_TRY(launch_pack_cond(tmap + i, y, d.classes, K, dup, tp, yp, s));
         FREE_TRY(forward_impl(h, F(o.x_states), K, tp, yp, B, F(o.eps), frozen ? nullptr : top, ws + o.ws_target, s));
         FREE_TRY(launch_eps_to_mean(F(o.eps), F(o.x_states), coef_x + i, coef_eps + i, cfg_scale, K, d.C, d.c_out, hw,
                                     F(o.m_target), s, frozen ? eps_g : nullptr));
@@ -1071,7 +1095,7 @@ int32_t sample_loop(free_dit_t h, free_drafter_t dr, const float* x_init, int32_
         VerifyArgs a{F(o.m_target), F(o.m_draft), F(o.x_states), F(o.x_last), sigma + i, u + i,
                      lambda ? lambda + i : nullptr, 1, K, d.d, F(o.log_ratio),
                      reinterpret_cast<uint8_t*>(ws + o.accept), n_acc_dev, F(o.x_refl), &h->prof};
-        FREE_TRY(launch_verify(a, ws + o.ws_target + TL.vpart, TL.vpart_bytes, true, s));
+        FREE_TRY(launch_verify(a, ws + o.ws_target + TL.vpart, TL.vpart_bytes, s));
         int32_t n = 0;
         if (!hip_ok(hipMemcpyAsync(&n, n_acc_dev, 4, hipMemcpyDeviceToHost, s)) || !hip_ok(hipStreamSynchronize(s)))
             return FREE_ERR_HIP;

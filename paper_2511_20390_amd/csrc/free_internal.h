@@ -107,12 +107,8 @@ struct VerifyArgs {
     Profiler* prof;          // nullptr, or the profiler of the handle the call belongs to
 };
 size_t verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d);
-// The first n_traj 32-bit words of a verification workspace are the arrival counters of the trajectories.
-// They must be zero when the verification kernel starts; it leaves them zero.  counters_are_zero: a kernel
-// earlier on the stream has cleared them (verify_counters gives their address); otherwise launch_verify
-// launches a small fill kernel first.
-uint32_t* verify_counters(void* ws);
-int32_t launch_verify(const VerifyArgs& a, void* ws, size_t ws_bytes, bool counters_are_zero, hipStream_t s);
+// ev4 (nullable): four events, attached as start / stop to the dispatches of the two launches (benchmark timing)
+int32_t launch_verify(const VerifyArgs& a, void* ws, size_t ws_bytes, hipStream_t s, hipEvent_t* ev4 = nullptr);
 
 // ---- simple DiT kernels, both dtypes (dit_kernels.hip) ---------------------------
 int32_t launch_conditioning(const int32_t* t, const int32_t* y, int32_t B, int32_t D, int32_t tfreq,
@@ -141,10 +137,8 @@ int32_t launch_eps_to_mean(const float* eps_out, const float* x_states, const fl
                            const float* coef_eps, float cfg_scale, int32_t K, int32_t C, int32_t c_out,
                            int64_t hw, float* m_out, hipStream_t s, float* eps_guided = nullptr,
                            const float* sigma_step = nullptr, const float* xi = nullptr, float* x_next = nullptr);
-// also clears n_clear 32-bit words at `clear` (nullable): the arrival counters of the verification that follows
 int32_t launch_pack_cond(const int32_t* t, int32_t y, int32_t null_label, int32_t K, int32_t dup,
-                         int32_t* t_out, int32_t* y_out, hipStream_t s, uint32_t* clear = nullptr,
-                         int32_t n_clear = 0);
+                         int32_t* t_out, int32_t* y_out, hipStream_t s);
 
 // drafter helper: fin = [emb | feat] in the compute type, zero_out (nullable) cleared
 int32_t launch_fuse_pack(const float* emb, const float* feat, int64_t M, int32_t D, int32_t dtype, void* fin,

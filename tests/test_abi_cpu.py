@@ -106,13 +106,12 @@ def test_argument_errors_are_status_codes(lib):
     cc.mode = 5
     assert lib.free_dit_create(C.byref(cc), arr, 31, C.byref(h)) == binding.FREE_ERR_DTYPE
     assert lib.free_dit_destroy(None) == binding.FREE_ERR_NULL
-    # schedule of the packed forward: 0 (timed choice, the default), 1 or 2 streams
-    assert lib.free_get_batch_streams() == 0
-    assert lib.free_set_batch_streams(3) == binding.FREE_ERR_RANGE
-    assert lib.free_set_batch_streams(-1) == binding.FREE_ERR_RANGE
-    assert lib.free_set_batch_streams(2) == binding.FREE_OK and lib.free_get_batch_streams() == 2
-    assert lib.free_set_batch_streams(0) == binding.FREE_OK
-    assert lib.free_dit_stream_choice(None) == binding.FREE_ERR_NULL
+    # schedule of the packed forward and per-kernel timing: settings of a handle
+    assert lib.free_dit_set_streams(None, 1) == binding.FREE_ERR_NULL
+    assert lib.free_dit_stream_choice(None, 12) == binding.FREE_ERR_NULL
+    assert lib.free_dit_tune(None, one, one, one, 12, one, one, 1 << 20, None) == binding.FREE_ERR_NULL
+    assert lib.free_profile_begin(None) == binding.FREE_ERR_NULL
+    assert lib.free_profile_end(None, one, one) == binding.FREE_ERR_NULL
     assert lib.dit_forward_packed(None, one, one, one, 6, one, None, one, 1 << 20, None) == binding.FREE_ERR_NULL
     assert lib.spec_round(None, one, one, one, one, 0, 4.0, one, one, one, one, None, 6, None, one, one, one, one,
                           one, 1 << 20, None) == binding.FREE_ERR_NULL
@@ -181,3 +180,85 @@ def test_sde_schedule_helper_matches_oracle(lib):
         np.testing.assert_allclose(sg, osg, rtol=1e-14, atol=0)
     assert lib.free_sde_schedule(10, 1e-4, 0.02, -1.0, None, None, None) == binding.FREE_ERR_RANGE
     assert lib.free_sde_schedule(1, 1e-4, 0.02, 1.0, None, None, None) == binding.FREE_ERR_SHAPE
+
+
+def _function_body(text, signature_start):
+    """Source text of the function whose definition starts with `signature_start` (brace matching)."""
+    at = text.index(signature_start)
+    i = text.index("{", at)
+    depth, j = 0, i
+    while True:
+        depth += {"{": 1, "}": -1}.get(text[j], 0)
+        j += 1
+        if depth == 0:
+            return text[at:j]
+
+
+def test_hot_path_calls_never_wait_for_the_device():
+    """The hot-path entry points only enqueue: no host-side wait (stream, event or device synchronisation,
+    blocking copies, allocation) appears in their bodies or in the launch chains they call."""
+    csrc = os.path.join(ROOT, "paper_2511_20390_amd", "csrc")
+    abi = open(os.path.join(csrc, "free_abi.hip")).read()
+    ver = open(os.path.join(csrc, "verify.hip")).read()
+    bodies = [_function_body(abi, "int32_t forward_impl("), _function_body(abi, "int32_t run_block_stack("),
+              _function_body(abi, "int32_t dit_forward_packed("), _function_body(abi, "int32_t spec_round("),
+              _function_body(abi, "int32_t spec_verify("), _function_body(abi, "int32_t drafter_forward_impl("),
+              _function_body(abi, "int32_t draft_round("), _function_body(ver, "int32_t launch_verify(")]
+    banned = ("Synchronize", "hipMalloc", "hipFree", "hipMemcpy(", "hipMemset", "hipEventElapsedTime",
+              "hipEventQuery", "hipStreamQuery")
+    for body in bodies:
+        for word in banned:
+            assert word not in body, f"{word} in {body[:60]!r}"
+    # the blocking calls exist, outside the hot path, and say so
+    assert "Synchronize" in _function_body(abi, "int32_t free_dit_tune(")
+
+
+def test_verify_workspace_sizes():
+    """Workspace of the verification: one pair of fp64 partial sums per workgroup of the streaming launch;
+    positive and 256-byte granular over a sweep of shapes, zero for shapes the call refuses."""
+    lib = binding.load()
+    for d in (1, 5, 1023, 1024, 4096, 16384, 65536, 1 << 20, (1 << 22) + 3):
+        for K in (1, 2, 6, 12, 64, 256):
+            for n in (1, 3, 64, 1000):
+                b = lib.spec_verify_workspace_bytes(n, K, d)
+                assert b % 256 == 0 and b >= 16 * n * K
+    assert lib.spec_verify_workspace_bytes(0, 6, 64) == 0
+    assert lib.spec_verify_workspace_bytes(4, 0, 64) == 0
+    assert lib.spec_verify_workspace_bytes(4, 6, 0) == 0
+
+
+def test_binding_refuses_tensors_the_library_would_misread():
+    """The C side sees raw pointers: the binding checks device, element type, contiguity and shape first
+    and raises without making a call (host tensors here, so nothing touches a GPU)."""
+    import torch
+    binding.load()
+    f = torch.zeros(2, 3, 8)
+    with pytest.raises(binding.FreeError) as e:
+        binding._dev(f, torch.float32, "m_target")
+    assert e.value.status == binding.FREE_ERR_NULL                      # not a device tensor
+    with pytest.raises(binding.FreeError):
+        binding._dev(None, torch.float32, "sigma")
+    assert binding._dev(None, torch.float32, "lambda", optional=True) is None
+
+    class Fake:                       # stands in for a device tensor: only the attributes _dev looks at
+        is_cuda = True
+
+        def __init__(self, t):
+            self.t = t
+            self.dtype, self.shape = t.dtype, t.shape
+
+        def is_contiguous(self):
+            return self.t.is_contiguous()
+
+        def data_ptr(self):
+            return self.t.data_ptr()
+
+    good = torch.zeros(4, 6)
+    assert binding._dev(Fake(good), torch.float32, "sigma", (4, 6)).value == good.data_ptr()
+    for bad, status in [(Fake(torch.zeros(4, 6, dtype=torch.float64)), binding.FREE_ERR_DTYPE),
+                        (Fake(torch.zeros(6, dtype=torch.int64)), binding.FREE_ERR_DTYPE),
+                        (Fake(torch.zeros(4, 12)[:, ::2]), binding.FREE_ERR_SHAPE),
+                        (Fake(torch.zeros(4, 5)), binding.FREE_ERR_SHAPE)]:
+        with pytest.raises(binding.FreeError) as e:
+            binding._dev(bad, torch.int32 if bad.dtype == torch.int64 else torch.float32, "x", (4, 6))
+        assert e.value.status == status

@@ -12,6 +12,7 @@ from tests import parity_util as pu
 pytestmark = pytest.mark.gpu
 
 OP_TOL = {"fp32": 2e-5, "bf16": 6e-3}
+ROW_TOL = {"fp32": 1e-4, "bf16": 2e-2}      # worst row of an operator's output against the rms row norm
 
 
 def _tdtype(mode):
@@ -24,10 +25,13 @@ def _vals(a, mode):
     return (synth.bf16_round(a) if mode == "bf16" else np.asarray(a, np.float32)).astype(np.float64)
 
 
+# the last five select the large tiles of the 12288-row GEMMs of the headline shape (and of its halves), one ragged
 @pytest.mark.parametrize("mode", ["fp32", "bf16"])
 @pytest.mark.parametrize("M,N,K", [(96, 192, 64), (576, 432, 144), (300, 1152, 1152), (1536, 3456, 1152),
                                    (257, 136, 328), (1024, 1152, 4608), (1000, 1152, 2304),
-                                   (2048, 1152, 4608), (200, 136, 2176)])
+                                   (2048, 1152, 4608), (200, 136, 2176),
+                                   (12288, 3456, 1152), (12288, 4608, 1152), (12288, 1152, 4608),
+                                   (6144, 1152, 4608), (12100, 3400, 1152)])
 def test_op_linear(mode, M, N, K):
     import torch
     from paper_2511_20390_amd import binding
@@ -38,10 +42,10 @@ def test_op_linear(mode, M, N, K):
     Av, Wv = _vals(A, mode), _vals(W, mode)
     ref = Av @ Wv.T + bias
     dA, dW, db = pu.to_dev(A, _tdtype(mode)), pu.to_dev(W, _tdtype(mode)), pu.to_dev(bias)
-    out = binding.op_linear(dA, dW, db, mode, binding.EPI_BIAS)
-    assert pu.rel_l2(out.float().cpu().numpy(), ref) < OP_TOL[mode]
-    out = binding.op_linear(dA, dW, db, mode, binding.EPI_BIAS_GELU)
-    assert pu.rel_l2(out.float().cpu().numpy(), fo.gelu_tanh(ref)) < OP_TOL[mode]
+    out = binding.op_linear(dA, dW, db, mode, binding.EPI_BIAS).float().cpu().numpy()
+    assert pu.rel_l2(out, ref) < OP_TOL[mode] and pu.row_rel_l2(out, ref, N) < ROW_TOL[mode]
+    out = binding.op_linear(dA, dW, db, mode, binding.EPI_BIAS_GELU).float().cpu().numpy()
+    assert pu.rel_l2(out, fo.gelu_tanh(ref)) < OP_TOL[mode] and pu.row_rel_l2(out, fo.gelu_tanh(ref), N) < ROW_TOL[mode]
     rows = 48 if M % 48 == 0 else M
     nb = M // rows
     gate = rng.standard_normal((nb, 3 * N)).astype(np.float32)
@@ -52,7 +56,8 @@ def test_op_linear(mode, M, N, K):
                       rows_per_sample=rows)
     torch.cuda.synchronize()
     ref2 = resid + np.repeat(gate[:, N:2 * N], rows, axis=0) * ref
-    assert pu.rel_l2(dres.cpu().numpy(), ref2) < OP_TOL[mode]
+    got2 = dres.cpu().numpy()
+    assert pu.rel_l2(got2, ref2) < OP_TOL[mode] and pu.row_rel_l2(got2, ref2, N) < ROW_TOL[mode]
 
 
 @pytest.mark.parametrize("mode", ["fp32", "bf16"])
@@ -68,8 +73,9 @@ def test_op_attention(mode, B, N, heads, dh):
     for b in range(B):
         for h in range(heads):
             ref[b, :, h] = fo.attention(v[b, :, 0, h], v[b, :, 1, h], v[b, :, 2, h])
-    out = binding.op_attention(pu.to_dev(qkv, _tdtype(mode)), B, N, heads, dh, mode)
-    assert pu.rel_l2(out.float().cpu().numpy(), ref.reshape(B * N, D)) < OP_TOL[mode]
+    out = binding.op_attention(pu.to_dev(qkv, _tdtype(mode)), B, N, heads, dh, mode).float().cpu().numpy()
+    assert pu.rel_l2(out, ref.reshape(B * N, D)) < OP_TOL[mode]
+    assert pu.row_rel_l2(out, ref, dh) < ROW_TOL[mode]                 # per (token, head)
 
 
 @pytest.mark.parametrize("mode", ["fp32", "bf16"])
@@ -81,8 +87,9 @@ def test_op_ln_modulate(mode, M, D, rows):
     mod = rng.standard_normal((M // rows, 2 * D)).astype(np.float32)
     ref = fo.layer_norm(x.astype(np.float64)) * (1 + np.repeat(mod[:, D:], rows, 0)) + np.repeat(mod[:, :D], rows, 0)
     dmod = pu.to_dev(mod)
-    out = binding.op_ln_modulate(pu.to_dev(x), dmod[:, :D], dmod[:, D:], rows, mode)
-    assert pu.rel_l2(out.float().cpu().numpy(), ref) < (2e-6 if mode == "fp32" else 4e-3)
+    out = binding.op_ln_modulate(pu.to_dev(x), dmod[:, :D], dmod[:, D:], rows, mode).float().cpu().numpy()
+    assert pu.rel_l2(out, ref) < (2e-6 if mode == "fp32" else 4e-3)
+    assert pu.row_rel_l2(out, ref, D) < (1e-5 if mode == "fp32" else 1e-2)
 
 
 def _forward_case(name, mode, B, seed, cfg_over=None, **wkw):
@@ -108,6 +115,9 @@ def test_forward_parity(name, B, mode):
     e1, e2 = pu.rel_l2(eps, ref), pu.rel_l2(feat, ref_feat)
     print(f"{name}/{mode} B={B}: eps rel-L2 {e1:.3e}, top-feature rel-L2 {e2:.3e}")
     assert e1 <= pu.DIT_REL_L2[mode] and e2 <= pu.DIT_REL_L2[mode]
+    p = cfg["patch"]
+    assert pu.row_rel_l2(pu.token_rows(eps, p), pu.token_rows(ref, p), eps.shape[1] * p * p) <= pu.ROW_REL_L2[mode]
+    assert pu.row_rel_l2(feat, ref_feat, cfg["hidden"]) <= pu.ROW_REL_L2[mode]
     model.close()
 
 
@@ -170,54 +180,82 @@ def test_round_k1_and_all_outcomes():
 
 
 # ---- full DiT-XL/2 shapes, in the launch configuration bench.py times -------------
-def _xl_round(name, K, cfg_scale, mode, oracle_states):
-    """spec_round at a DiT-XL/2 shape.  The oracle (fp64, minutes for a whole pack) is run
-    on `oracle_states` of the K packed states only (each with its null-label twin): the
-    states of a pack are independent, so their means are comparable one by one; the
-    verification outputs are checked by composition on the GPU-produced means."""
+_XL_CACHE = {}
+
+
+def _xl_gpu_round(name, K, cfg_scale, mode):
+    """spec_round at a DiT-XL/2 shape, run ONCE per (shape, mode) and kept for the per-state comparisons:
+    inputs, weights, the GPU outputs as NumPy arrays.  The verification outputs are checked here by
+    composition on the GPU-produced means (bit-exact decisions need identical inputs)."""
     import torch
     from paper_2511_20390_amd import binding
+    key = (name, K, cfg_scale, mode)
+    if key in _XL_CACHE:
+        return _XL_CACHE[key]
+    _XL_CACHE.clear()                         # one set of DiT-XL weights in host memory at a time
     cfg = synth.dit_config(name)
     w = pu.weights_for(cfg, mode, seed=0)
     sched = fo.ddpm_schedule()
     ri = synth.make_round_inputs(cfg, K, 0, sched["sigma_clipped"], 0.1)
     cx, ce = fo.mean_coefficients(ri["t"], sched)
     d = synth.latent_dim(cfg)
-    # oracle means of the sampled states
-    m_ref = {}
-    for k in oracle_states:
-        m_ref[k] = fo.round_means(w, cfg, ri["x_states"][k:k + 1], ri["t"][k:k + 1], ri["y"], cfg_scale,
-                                  cx[k:k + 1], ce[k:k + 1]).reshape(d)
     model = binding.FreeDit(cfg, w, mode)
     out = model.spec_round(pu.to_dev(ri["x_states"]), pu.to_dev(ri["x_last"]), pu.to_dev(ri["m_draft"]),
                            pu.to_dev(ri["t"]), ri["y"], cfg_scale, pu.to_dev(cx.astype(np.float32)),
                            pu.to_dev(ce.astype(np.float32)), pu.to_dev(ri["sigma"]), pu.to_dev(ri["u"]), None)
     torch.cuda.synchronize()
     m_gpu = out["m_target"].cpu().numpy().astype(np.float64)
-    xs = ri["x_states"].reshape(K, d).astype(np.float64)
-    for k in oracle_states:
-        eps_ref = (m_ref[k] - cx[k] * xs[k]) / ce[k]
-        eps_gpu = (m_gpu[k] - np.float32(cx[k]).astype(np.float64) * xs[k]) / np.float32(ce[k]).astype(np.float64)
-        err = pu.rel_l2(eps_gpu, eps_ref)
-        print(f"{name}/{mode} state {k}: eps rel-L2 {err:.3e}")
-        assert err <= pu.DIT_REL_L2[mode]
     xd = np.concatenate([ri["x_states"][1:], ri["x_last"][None]], 0).reshape(K, d)
     ref = fo.spec_verify(m_gpu[None], ri["m_draft"][None], xd[None], ri["sigma"][None], ri["u"][None])
     pu.compare_verify(dict(accept=out["accept"], n_accept=out["n_accept"], log_ratio=out["log_ratio"],
                            x_out=out["x_out"]), ref, None, ri["u"], f"xl round {name}/{mode}")
     model.close()
+    del model, out
+    torch.cuda.empty_cache()
+    _XL_CACHE[key] = dict(cfg=cfg, w=w, ri=ri, cx=cx, ce=ce, d=d, m_gpu=m_gpu)
+    return _XL_CACHE[key]
 
 
-def test_xl2_256_round_bf16():
-    _xl_round("xl2_256", 6, 1.0, "bf16", oracle_states=[0, 5])
+def _xl_state_parity(name, K, cfg_scale, mode, k):
+    """Packed state k (with its null-label twin under guidance) against the oracle (fp64, ~17 s per state at
+    1024 tokens): the states of a pack are independent, so their means are comparable one by one.  State 0
+    and state K-1 sit in the first and last row tiles of the large GEMM configurations of the pack."""
+    r = _xl_gpu_round(name, K, cfg_scale, mode)
+    cfg, ri, cx, ce, d = r["cfg"], r["ri"], r["cx"], r["ce"], r["d"]
+    m_ref = fo.round_means(r["w"], cfg, ri["x_states"][k:k + 1], ri["t"][k:k + 1], ri["y"], cfg_scale,
+                           cx[k:k + 1], ce[k:k + 1]).reshape(d)
+    xs = ri["x_states"][k].reshape(d).astype(np.float64)
+    eps_ref = (m_ref - cx[k] * xs) / ce[k]
+    eps_gpu = (r["m_gpu"][k] - np.float32(cx[k]).astype(np.float64) * xs) / np.float32(ce[k]).astype(np.float64)
+    err = pu.rel_l2(eps_gpu, eps_ref)
+    shape = (1,) + ri["x_states"].shape[1:]
+    p = cfg["patch"]
+    err_tok = pu.row_rel_l2(pu.token_rows(eps_gpu.reshape(shape), p), pu.token_rows(eps_ref.reshape(shape), p),
+                            cfg["in_ch"] * p * p)
+    print(f"{name}/{mode} state {k}: eps rel-L2 {err:.3e}, worst token {err_tok:.3e}")
+    assert err <= pu.DIT_REL_L2[mode]
+    assert err_tok <= pu.ROW_REL_L2[mode]
 
 
-def test_xl2_512_cfg_round_bf16():
-    _xl_round("xl2_512", 6, 4.0, "bf16", oracle_states=[3])
+@pytest.mark.parametrize("k", [0, 5])
+def test_xl2_256_round_bf16(k):
+    _xl_state_parity("xl2_256", 6, 1.0, "bf16", k)
+
+
+@pytest.mark.parametrize("k", [0, 1, 2, 3, 4, 5])
+def test_xl2_512_cfg_round_bf16(k):
+    """The headline shape (12 packed samples, 12288 token rows): every one of the six states."""
+    _xl_state_parity("xl2_512", 6, 4.0, "bf16", k)
 
 
 def test_xl2_256_round_fp32():
-    _xl_round("xl2_256", 6, 4.0, "fp32", oracle_states=[2])
+    _xl_state_parity("xl2_256", 6, 4.0, "fp32", 2)
+
+
+@pytest.mark.parametrize("k", [0, 4])
+def test_xl2_512_cfg_round_fp32(k):
+    """The headline shape in fp32 mode."""
+    _xl_state_parity("xl2_512", 6, 4.0, "fp32", k)
 
 
 def test_mfma_calibration_is_sane():
@@ -238,61 +276,55 @@ def test_mfma_calibration_is_sane():
 def test_batch_streams_same_result():
     """The two halves of a large batch can run on two streams; the serial schedule (one stream) must give
     the same numbers: every kernel reduces in the same order whatever the number of rows it is launched on.
-    By default the library times both schedules over the first 24 forwards at a batch size and keeps one."""
+    One stream is the default; free_dit_tune (blocking, outside the hot path) measures both and keeps one."""
     import torch
     from paper_2511_20390_amd import binding
-    assert binding.get_batch_streams() == 0
     # B = 5 at 1024 tokens: halves of 2 and 3 samples, both at or above the split threshold
     cfg, w, x, t, y, eps0, feat0, model = _forward_case("xl2_512", "bf16", 5, seed=0)
     dx, dt, dy = pu.to_dev(x), pu.to_dev(t), pu.to_dev(y)
-    assert model.stream_choice() == 0                    # one forward so far: still trying
+    assert model.stream_choice(5) == 1                   # nothing measured, nothing forced: one stream
     results = {}
-    try:
-        for n in (1, 2):
-            binding.set_batch_streams(n)
-            eps, feat = model.dit_forward_packed(dx, dt, dy, want_feat=True)
-            torch.cuda.synchronize()
-            results[n] = (eps.cpu().numpy(), feat.cpu().numpy())
-    finally:
-        binding.set_batch_streams(0)
-    assert model.stream_choice() == 0                    # forced schedules are not trials
-    for _ in range(23):                                  # the remaining trials
+    for n in (1, 2):
+        model.set_streams(n)
+        assert model.stream_choice(5) == n
+        assert model.stream_choice(1) == 1               # a batch of one sample never splits
         eps, feat = model.dit_forward_packed(dx, dt, dy, want_feat=True)
-    assert model.stream_choice() == 0
-    eps, feat = model.dit_forward_packed(dx, dt, dy, want_feat=True)    # the call that decides
+        torch.cuda.synchronize()
+        results[n] = (eps.cpu().numpy(), feat.cpu().numpy())
+    model.set_streams(0)
+    assert model.stream_choice(5) == 1
+    choice = model.tune(dx, dt, dy)                      # times both schedules on these inputs
+    assert choice in (1, 2) and model.stream_choice(5) == choice
+    assert model.stream_choice(4) == 1                   # measured for 5 packed states only
+    eps, feat = model.dit_forward_packed(dx, dt, dy, want_feat=True)
     torch.cuda.synchronize()
-    assert model.stream_choice() in (1, 2)
     results[0] = (eps.cpu().numpy(), feat.cpu().numpy())
     for n in (1, 2, 0):
-        e, f = pu.rel_l2(eps0, results[n][0]), pu.rel_l2(feat0, results[n][1])
-        print(f"streams setting {n} vs the first call: eps rel-L2 {e:.3e}, top-feature rel-L2 {f:.3e}")
-        assert e < 1e-6 and f < 1e-6
-    # a smaller batch of the same handle does not split and leaves the choice alone
-    choice = model.stream_choice()
-    model.dit_forward_packed(dx[:1], dt[:1], dy[:1])
-    torch.cuda.synchronize()
-    assert model.stream_choice() == choice
+        assert np.array_equal(eps0, results[n][0]) and np.array_equal(feat0, results[n][1]), n
     with pytest.raises(binding.FreeError):
-        binding.set_batch_streams(3)
+        model.set_streams(3)
     model.close()
 
 
-def test_stream_choice_is_made_again_after_many_forwards():
-    """The timed choice between one and two streams is repeated after every 1000 forwards at a batch size;
-    while the 16 counted trials run again the previous choice stays reported, and the output never changes.
-    A narrow model with 1024 tokens keeps the 1100 forwards short."""
-    over = dict(lat_h=64, lat_w=64, hidden=64, heads=2, mlp_hidden=128, depth=2)
-    cfg, w, x, t, y, eps0, feat0, model = _forward_case("tiny", "bf16", 4, seed=3, cfg_over=over)
+def test_per_kernel_profile_belongs_to_the_handle():
+    """Per-kernel timing is a setting of one handle: a second handle running meanwhile records nothing, and
+    the profiled forward gives the same numbers as the plain one."""
+    import torch
+    cfg, w, x, t, y, eps0, feat0, a = _forward_case("small", "bf16", 4, seed=3)
+    _, _, _, _, _, _, _, b = _forward_case("small", "bf16", 4, seed=3)
     dx, dt, dy = pu.to_dev(x), pu.to_dev(t), pu.to_dev(y)
-    for _ in range(24):
-        model.dit_forward_packed(dx, dt, dy)
-    assert model.stream_choice() in (1, 2)               # 24 trials, decided at the 25th forward
-    for i in range(1000 + 17):
-        eps = model.dit_forward_packed(dx, dt, dy)
-        assert model.stream_choice() in (1, 2), i
-        if i % 100 == 0 or i >= 995:
-            assert np.array_equal(eps.cpu().numpy(), eps0), i
-    model.close()
+    a.profile_begin()
+    eps = a.dit_forward_packed(dx, dt, dy)
+    b.dit_forward_packed(dx, dt, dy)
+    prof = a.profile_end()
+    depth = cfg["depth"]
+    assert prof["gemm_qkv"][1] == depth and prof["ln_modulate"][1] == 2 * depth and prof["final_layer"][1] == 1
+    assert prof["verify"][1] == 0 and all(ms >= 0.0 for ms, _ in prof.values())
+    assert np.array_equal(eps.cpu().numpy(), eps0)
+    b.profile_begin()
+    assert sum(n for _, n in b.profile_end().values()) == 0
+    a.close()
+    b.close()
 
 
 @pytest.mark.parametrize("name,mode,cfg_scale", [("small", "fp32", 4.0), ("xl2_512", "bf16", 4.0)])

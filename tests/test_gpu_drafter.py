@@ -57,8 +57,9 @@ def _run_draft(drafter, di, cfg_scale, cx, ce, sigma, want_feat=True):
 
 
 @pytest.mark.parametrize("mode", ["fp32", "bf16"])
+# ("tiny", 9, 4.0, 1): 18 conditioning rows, more than one modulation pass holds - the per-step conditioning path
 @pytest.mark.parametrize("name,K,cfg_scale,depth", [("tiny", 5, 4.0, 1), ("tiny", 1, 1.0, 1), ("small", 6, 4.0, 1),
-                                                    ("small", 3, 1.0, 2)])
+                                                    ("small", 3, 1.0, 2), ("tiny", 9, 4.0, 1)])
 def test_draft_round_parity(name, K, cfg_scale, depth, mode):
     """The whole autoregressive chain: errors compound over the K steps, so the last draft is the
     strictest check.  The oracle is fed the float32-rounded coefficients the library receives."""
@@ -126,11 +127,13 @@ def test_draft_then_verify_round_chain():
     target.close()
 
 
-def test_drafter_xl2_512_bf16():
-    """DiT-XL/2 width at 1024 tokens with guidance (the shape bench.py times): one block on two
-    samples is cheap enough for the oracle to check every output."""
-    cfg, w, wd, target, drafter = _models("xl2_512", "bf16", 1)
-    K, cfg_scale = 2, 4.0
+@pytest.mark.parametrize("depth,K", [(1, 2), (2, 1)])
+def test_drafter_xl2_512_bf16(depth, K):
+    """DiT-XL/2 width at 1024 tokens with guidance (the shape bench.py times; two blocks in the sampler
+    benchmark): one or two blocks on two samples are cheap enough for the oracle to check every output."""
+    cfg, w, wd, target, drafter = _models("xl2_512", "bf16", depth)
+    cfg = dict(cfg, drafter_depth=depth)
+    cfg_scale = 4.0
     sched, di, cx, ce, sigma = _draft_inputs(cfg, K, 1, cfg_scale)
     out = _run_draft(drafter, di, cfg_scale, cx, ce, sigma)
     ref = fo.draft_steps(wd, w, cfg, di["x_a"], di["f_a"], di["t"], di["y"], cfg_scale, cx.astype(np.float32),
