@@ -43,6 +43,7 @@ extern "C" {
 #define FREE_ERR_DTYPE      -4   /* unknown compute mode */
 #define FREE_ERR_WORKSPACE  -5   /* workspace missing, misaligned or too small */
 #define FREE_ERR_HIP        -6   /* HIP runtime error; see free_last_hip_error */
+#define FREE_ERR_LIMIT      -7   /* problem larger than a fixed built-in limit */
 
 #define FREE_FP32 0   /* fp32 weights and activations, fp32 accumulation */
 #define FREE_BF16 1   /* bf16 large matrices and activations, fp32 accumulation,
@@ -212,6 +213,28 @@ int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_
                     int32_t n_traj, int32_t K, int64_t d,
                     float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out,
                     void* workspace, size_t ws_bytes, void* stream);
+
+/* spec_verify for callers that cannot allocate device memory or bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (minus the workspace), same kernels, same results and
+ * status codes as spec_verify; the partial sums live in a static device array of
+ * FREE_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the
+ * process ends).  The call allocates and frees nothing.  Problems whose partial
+ * sums do not fit - spec_verify_workspace_bytes(n_traj, K, d) >
+ * FREE_STATIC_SCRATCH_BYTES, i.e. more than 65536 streaming workgroups - are
+ * refused with FREE_ERR_LIMIT before anything is launched; the headline
+ * verification workload (64 x 6 x 16384) needs 24 KiB.  The first call on a
+ * device looks the array's address up (hipGetSymbolAddress, once per device):
+ * make that call outside a stream capture.  Nothing in the array has to start at
+ * zero (every partial sum is written before it is read), but all calls on one
+ * GPU share it: calls that overlap in time on one GPU - different streams, or
+ * replays of two captured graphs - race and must be ordered by the caller. */
+#define FREE_STATIC_SCRATCH_BYTES (1u << 20)
+int32_t spec_verify_static(const float* m_target, const float* m_draft, const float* x_draft,
+                           const float* sigma, const float* u, const float* lambda,
+                           int32_t n_traj, int32_t K, int64_t d,
+                           float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out,
+                           void* stream);
 
 /* Benchmark helper, NOT a hot-path call: spec_verify with a start and a stop HIP event
  * attached to each of its two dispatches on `stream` (the events are created and

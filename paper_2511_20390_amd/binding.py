@@ -16,6 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libfree_mi355x.so")
 
 FREE_OK = 0
 FREE_ERR_NULL, FREE_ERR_SHAPE, FREE_ERR_RANGE, FREE_ERR_DTYPE, FREE_ERR_WORKSPACE, FREE_ERR_HIP = -1, -2, -3, -4, -5, -6
+FREE_ERR_LIMIT = -7
+STATIC_SCRATCH_BYTES = 1 << 20
 FREE_FP32, FREE_BF16 = 0, 1
 EPI_BIAS, EPI_BIAS_GELU, EPI_GATE_RESID = 0, 1, 2
 MODES = {"fp32": FREE_FP32, "bf16": FREE_BF16}
@@ -24,7 +26,7 @@ EXPORTED_SYMBOLS = [
     "free_version", "free_status_string", "free_last_hip_error", "free_dit_set_streams",
     "free_dit_tune", "free_dit_stream_choice", "free_ddpm_schedule", "free_sde_schedule",
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
-    "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_verify_timed", "spec_round",
+    "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_verify_static", "spec_verify_timed", "spec_round",
     "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
     "drafter_forward", "draft_round", "free_sample_workspace_bytes", "free_sample",
     "free_self_speculative_workspace_bytes", "free_self_speculative", "free_lambda_profile",
@@ -88,6 +90,8 @@ def load():
     lib.spec_verify_workspace_bytes.argtypes = [i32, i32, i64]
     lib.spec_verify.restype = i32
     lib.spec_verify.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp, sz, vp]
+    lib.spec_verify_static.restype = i32
+    lib.spec_verify_static.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp]
     lib.spec_verify_timed.restype = i32
     lib.spec_verify_timed.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp, sz, vp, vp, vp]
     lib.spec_round.restype = i32
@@ -255,6 +259,23 @@ def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None, out=None, worksp
         out = dict(out, stream_us=a.value * 1e3, finish_us=b.value * 1e3)
     else:
         _check(load().spec_verify(*args), "spec_verify")
+    return out
+
+
+def spec_verify_static(m_target, m_draft, x_draft, sigma, u, lam=None, out=None):
+    """spec_verify through the entry point that allocates nothing (static scratch inside the library); the
+    outputs are the caller's (allocated here when `out` is None)."""
+    import torch
+    f32 = torch.float32
+    n_traj, K, d = m_target.shape
+    out = _verify_out(out, n_traj, K, d, m_target.device)
+    _check(load().spec_verify_static(
+        _dev(m_target, f32, "m_target"), _dev(m_draft, f32, "m_draft", (n_traj, K, d)),
+        _dev(x_draft, f32, "x_draft", (n_traj, K, d)), _dev(sigma, f32, "sigma", (n_traj, K)),
+        _dev(u, f32, "u", (n_traj, K)), _dev(lam, f32, "lambda", (n_traj, K), optional=True), n_traj, K, d,
+        _dev(out["log_ratio"], f32, "log_ratio", (n_traj, K)), _dev(out["accept"], torch.uint8, "accept", (n_traj, K)),
+        _dev(out["n_accept"], torch.int32, "n_accept", (n_traj,)), _dev(out["x_out"], f32, "x_out", (n_traj, d)),
+        _stream()), "spec_verify_static")
     return out
 
 

@@ -363,6 +363,7 @@ const char* free_status_string(int32_t st) {
         case FREE_ERR_DTYPE: return "unknown compute mode";
         case FREE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case FREE_ERR_HIP: return "HIP runtime error";
+        case FREE_ERR_LIMIT: return "problem larger than a fixed built-in limit";
         default: return "unknown status";
     }
 }
@@ -647,6 +648,21 @@ int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_
     VerifyArgs a{m_target, m_draft, x_draft, nullptr, sigma, u, lambda, n_traj, K, d,
                  log_ratio, accept, n_accept, x_out, nullptr};
     return launch_verify(a, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int32_t spec_verify_static(const float* m_target, const float* m_draft, const float* x_draft, const float* sigma,
+                           const float* u, const float* lambda, int32_t n_traj, int32_t K, int64_t d,
+                           float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out, void* stream) {
+    if (!m_target || !m_draft || !x_draft || !sigma || !u || !log_ratio || !accept || !n_accept || !x_out)
+        return FREE_ERR_NULL;
+    if (n_traj < 0 || K < 1 || K > FREE_MAX_DRAFTS || d < 1) return FREE_ERR_SHAPE;
+    if (n_traj == 0) return FREE_OK;
+    if (verify_workspace_bytes(n_traj, K, d) > FREE_STATIC_SCRATCH_BYTES) return FREE_ERR_LIMIT;
+    void* ws = nullptr;
+    FREE_TRY(static_verify_scratch(&ws));
+    VerifyArgs a{m_target, m_draft, x_draft, nullptr, sigma, u, lambda, n_traj, K, d,
+                 log_ratio, accept, n_accept, x_out, nullptr};
+    return launch_verify(a, ws, FREE_STATIC_SCRATCH_BYTES, static_cast<hipStream_t>(stream));
 }
 
 int32_t spec_verify_timed(const float* m_target, const float* m_draft, const float* x_draft, const float* sigma,

@@ -107,6 +107,9 @@ struct VerifyArgs {
     Profiler* prof;          // nullptr, or the profiler of the handle the call belongs to
 };
 size_t verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d);
+// device address, on the current device, of the library's static scratch array (FREE_STATIC_SCRATCH_BYTES);
+// looked up once per device with hipGetSymbolAddress, no allocation
+int32_t static_verify_scratch(void** ptr);
 // ev4 (nullable): four events, attached as start / stop to the dispatches of the two launches (benchmark timing)
 int32_t launch_verify(const VerifyArgs& a, void* ws, size_t ws_bytes, hipStream_t s, hipEvent_t* ev4 = nullptr);
 

@@ -25,7 +25,14 @@
 // workgroup) made it 139 us.  Not kept.
 #include <hip/hip_ext.h>
 
+#include <mutex>
+
 #include "free_internal.h"
+
+// Scratch memory of spec_verify_static, the entry point for callers that cannot allocate: the partial sums of
+// the streaming launch.  One copy per GPU the library runs on, held until the process ends.  In host code
+// the name below is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[FREE_STATIC_SCRATCH_BYTES];
 
 namespace freemi {
 
@@ -279,6 +286,23 @@ size_t verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d) {
     Plan p = make_plan(n_traj, K, d, kPartialThreads, kPartialDepth);
     size_t bytes = static_cast<size_t>(n_traj) * K * p.splits * 2 * sizeof(double);
     return (bytes + 255) / 256 * 256;
+}
+
+int32_t static_verify_scratch(void** ptr) {
+    constexpr int kMaxDevices = 64;
+    static void* dev_ptr[kMaxDevices] = {};          // address of this library's array on each device
+    static std::mutex mu;
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev))) return FREE_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return FREE_ERR_LIMIT;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!dev_ptr[dev]) {
+        void* p = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) || !p) return FREE_ERR_HIP;
+        dev_ptr[dev] = p;
+    }
+    *ptr = dev_ptr[dev];
+    return FREE_OK;
 }
 
 int32_t launch_verify(const VerifyArgs& a, void* ws, size_t ws_bytes, hipStream_t s, hipEvent_t* ev4) {

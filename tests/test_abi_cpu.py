@@ -39,8 +39,8 @@ def test_header_symbols_are_exported_and_bound(lib):
 
 def test_version_and_status_strings(lib):
     assert b"gfx950" in lib.free_version()
-    seen = {lib.free_status_string(s) for s in range(0, -7, -1)}
-    assert len(seen) == 7 and lib.free_status_string(-99) == b"unknown status"
+    seen = {lib.free_status_string(s) for s in range(0, -8, -1)}
+    assert len(seen) == 8 and lib.free_status_string(-99) == b"unknown status"
 
 
 def test_schedule_helper_matches_oracle(lib):
@@ -91,6 +91,12 @@ def test_argument_errors_are_status_codes(lib):
     # missing / too small workspace
     assert lib.spec_verify(one, one, one, one, one, None, 1, 6, 64, one, one, one, one, None, 0, None) == binding.FREE_ERR_WORKSPACE
     assert lib.spec_verify(one, one, one, one, one, None, 4, 6, 4096, one, one, one, one, one, 8, None) == binding.FREE_ERR_WORKSPACE
+    # the entry point with built-in scratch: argument checks first, then the size limit, all before any device call
+    assert lib.spec_verify_static(None, one, one, one, one, None, 1, 6, 64, one, one, one, one, None) == binding.FREE_ERR_NULL
+    assert lib.spec_verify_static(one, one, one, one, one, None, 1, 0, 64, one, one, one, one, None) == binding.FREE_ERR_SHAPE
+    assert lib.spec_verify_static(one, one, one, one, one, None, 0, 6, 64, one, one, one, one, None) == binding.FREE_OK
+    assert lib.spec_verify_workspace_bytes(20000, 6, 16384) > binding.STATIC_SCRATCH_BYTES
+    assert lib.spec_verify_static(one, one, one, one, one, None, 20000, 6, 16384, one, one, one, one, None) == binding.FREE_ERR_LIMIT
     assert lib.spec_verify_workspace_bytes(64, 6, 16384) >= 64 * 6 * 16
     assert lib.spec_verify_workspace_bytes(64, 300, 16384) == 0
     # model handle
