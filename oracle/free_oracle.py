@@ -29,6 +29,13 @@ and agreement with an independent implementation built from library routines.
 The DiT forward has no published activations to compare against: beyond those
 invariants and the library-routine cross-check it is "parity unpinned".
 
+* Verification with one variance per element (App. C names fixed-variance
+  schedules richer than one scalar per step; Sec. 3.3 only requires that draft
+  and target share the covariance): Alg. 2 in whitened coordinates.  Pins: the
+  scalar case, library log-densities with a diagonal covariance, equivalence
+  with the scalar routine on whitened inputs, preservation of the target
+  marginal and the closed-form acceptance rate at the whitened distance.
+
 * The drafter and the drafting loop (Sec. 3.2, "Feature-Level Autoregressive
   Drafting"; Alg. 1, inner drafting loop): shared embedding -> FC layer fusing
   the embedding output with the propagated top-block feature -> DiT block(s)
@@ -211,6 +218,81 @@ def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None) -> dict:
         n_accept[n] = first_reject
     return dict(log_ratio=lr, accept=acc, n_accept=n_accept, x_out=x_out,
                 has_reflect=has_reflect, tie=tie)
+
+
+# ----------------------------------------------------------------------------
+# Verification with one variance per element (App. C: fixed-variance schedules richer than a scalar per
+# step; Sec. 3.3 only needs draft and target to share the covariance).  Both transitions are
+# N(mean, diag(s^2)) with the same vector s: in the whitened coordinates z = (x - c) / s they are isotropic
+# with unit variance, so Alg. 2 applies there unchanged and the result is mapped back.
+# ----------------------------------------------------------------------------
+def log_ratio_diag(m_hat, m, sigma_vec, x_hat) -> float:
+    """log of N(x^; m, diag(s^2)) / N(x^; m^, diag(s^2)) = sum_i (m_i - m^_i)(x^_i - mid_i) / s_i^2
+    (Eq. qp with the per-element variance inside the sum)."""
+    m_hat = np.asarray(m_hat, F64).ravel()
+    m = np.asarray(m, F64).ravel()
+    x_hat = np.asarray(x_hat, F64).ravel()
+    s = np.asarray(sigma_vec, F64).ravel()
+    mid = 0.5 * (m + m_hat)
+    return float(np.sum((m - m_hat) * (x_hat - mid) / (s * s)))
+
+
+def reflect_diag(m_hat, m, sigma_vec, x_hat) -> np.ndarray:
+    """Rejection branch of Alg. 2 in the whitened coordinates: e = ((m^ - m)/s) / ||(m^ - m)/s||,
+    x = m + s * (I - 2 e e^T) ((x^ - m^)/s)."""
+    m_hat = np.asarray(m_hat, F64)
+    m = np.asarray(m, F64)
+    x_hat = np.asarray(x_hat, F64)
+    s = np.asarray(sigma_vec, F64).ravel()
+    dw = (m_hat - m).ravel() / s
+    e = dw / math.sqrt(float(np.dot(dw, dw)))
+    z = (x_hat - m_hat).ravel() / s
+    out = m.ravel() + s * (z - 2.0 * e * float(np.dot(e, z)))
+    return out.reshape(m.shape)
+
+
+def verification_diag(m_hat, m, sigma_vec, x_hat, u: float, lam: float = 1.0):
+    """Alg. 2 (with the relaxed rule of Eq. acc_relax) for transitions that share a diagonal covariance.
+    Same conventions as `verification`: decision in the log domain, u = 0 and m^ == m accept."""
+    m_hat = np.asarray(m_hat, F64)
+    m = np.asarray(m, F64)
+    x_hat = np.asarray(x_hat, F64)
+    l = log_ratio_diag(m_hat, m, sigma_vec, x_hat)
+    if not np.any(m_hat != m) or u <= 0.0:
+        return x_hat.copy(), True, l, False
+    logu = math.log(u)
+    accepted = logu <= min(0.0, float(lam) * l)
+    tie = abs(float(lam) * l - logu) < TIE_WINDOW
+    if accepted:
+        return x_hat.copy(), True, l, tie
+    return reflect_diag(m_hat, m, sigma_vec, x_hat), False, l, tie
+
+
+def spec_verify_diag(m_target, m_draft, x_draft, sigma_elem, u, lam=None) -> dict:
+    """spec_verify with sigma_elem [n_traj, K, d]: one standard deviation per element of every draft."""
+    m_target = np.asarray(m_target, F64)
+    n_traj, K, d = m_target.shape
+    m_draft = np.asarray(m_draft, F64)
+    x_draft = np.asarray(x_draft, F64)
+    sigma_elem = np.asarray(sigma_elem, F64).reshape(n_traj, K, d)
+    u = np.asarray(u, F64).reshape(n_traj, K)
+    lam = np.ones((n_traj, K), F64) if lam is None else np.asarray(lam, F64).reshape(n_traj, K)
+    lr = np.zeros((n_traj, K), F64)
+    acc = np.zeros((n_traj, K), np.uint8)
+    tie = np.zeros((n_traj, K), bool)
+    n_accept = np.full(n_traj, K, np.int32)
+    x_out = np.zeros((n_traj, d), F64)
+    has_reflect = np.zeros(n_traj, bool)
+    for n in range(n_traj):
+        for k in range(K):
+            x, ok, l, tk = verification_diag(m_draft[n, k], m_target[n, k], sigma_elem[n, k], x_draft[n, k],
+                                             u[n, k], lam[n, k])
+            lr[n, k], acc[n, k], tie[n, k] = l, 1 if ok else 0, tk
+            if not ok and not has_reflect[n]:
+                n_accept[n] = k
+                x_out[n] = x
+                has_reflect[n] = True
+    return dict(log_ratio=lr, accept=acc, n_accept=n_accept, x_out=x_out, has_reflect=has_reflect, tie=tie)
 
 
 # ----------------------------------------------------------------------------

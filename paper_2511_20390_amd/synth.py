@@ -179,6 +179,24 @@ def make_round_inputs(cfg: dict, K: int, seed: int, sigma_table: np.ndarray,
                 lam=relaxation_profile(t, T))
 
 
+def make_verify_inputs_diag(n_traj: int, K: int, d: int, delta: float, seed: int, sigma_table: np.ndarray,
+                            spread: float = 0.4, T: int = 1000) -> dict:
+    """Verification workload with one standard deviation per element: the step's sigma times a log-normal
+    factor exp(spread * N(0, 1)) per element; draft means = target means + delta * sigma_elem * N(0, I);
+    drafts = draft means + sigma_elem * N(0, I)."""
+    rng = np.random.default_rng(seed)
+    t = rng.integers(0, T, size=(n_traj, K))
+    sigma = np.asarray(sigma_table, np.float64)[t].astype(np.float32)
+    sigma_elem = (sigma[..., None] * np.exp(np.float32(spread) * rng.standard_normal((n_traj, K, d), dtype=np.float32)))
+    sigma_elem = np.ascontiguousarray(sigma_elem.astype(np.float32))
+    m_target = rng.standard_normal((n_traj, K, d), dtype=np.float32)
+    m_draft = m_target + np.float32(delta) * sigma_elem * rng.standard_normal((n_traj, K, d), dtype=np.float32)
+    x_draft = m_draft + sigma_elem * rng.standard_normal((n_traj, K, d), dtype=np.float32)
+    u = rng.random((n_traj, K), dtype=np.float32)
+    return dict(m_target=m_target, m_draft=np.ascontiguousarray(m_draft), x_draft=np.ascontiguousarray(x_draft),
+                sigma_elem=sigma_elem, u=u, lam=relaxation_profile(t, T), t=t.astype(np.int32))
+
+
 def make_verify_inputs(n_traj: int, K: int, d: int, delta: float, seed: int,
                        sigma_table: np.ndarray, T: int = 1000) -> dict:
     """Stand-alone verification workload: target means ~ N(0, I); sigma from the

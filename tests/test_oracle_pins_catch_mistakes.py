@@ -10,6 +10,7 @@ import pytest
 
 from oracle import free_oracle as fo
 
+import test_oracle_diag_pins as diag_pins
 import test_oracle_dit_pins as dit_pins
 import test_oracle_drafter_pins as drafter_pins
 import test_oracle_loop_pins as loop_pins
@@ -81,7 +82,7 @@ def _verification_relaxes_additively(m_hat, m, sigma, x_hat, u, lam=1.0):
     return (np.asarray(x_hat, F64).copy() if ok else fo.reflect(m_hat, m, x_hat)), ok, l, False
 
 
-_ORIGINAL = {"verification": fo.verification}
+_ORIGINAL = {"verification": fo.verification, "reflect": fo.reflect, "log_ratio": fo.log_ratio}
 
 VERIFY_MUTANTS = [
     ("log_ratio", _lr_no_midpoint, [lambda: verify_pins.test_log_ratio_matches_library_gaussian_logpdf(4),
@@ -178,6 +179,33 @@ DIT_MUTANTS = [
     ("eps_to_mean", _eps_to_mean_plus, [dit_pins.test_eps_to_mean_is_posterior_mean_for_the_true_noise]),
     ("cfg_combine", _cfg_combine_swapped, [dit_pins.test_guidance_special_cases]),
 ]
+
+
+# ---- per-element variance: mistakes planted into the whitened rule
+def _reflect_diag_unwhitened_direction(m_hat, m, sigma_vec, x_hat):
+    """The reflection direction taken in the original coordinates (the variances ignored)."""
+    return _ORIGINAL["reflect"](m_hat, m, x_hat)
+
+
+def _log_ratio_diag_mean_variance(m_hat, m, sigma_vec, x_hat):
+    """One pooled variance instead of the per-element ones."""
+    s = np.asarray(sigma_vec, F64).ravel()
+    return _ORIGINAL["log_ratio"](m_hat, m, math.sqrt(float(np.mean(s * s))), x_hat)
+
+
+DIAG_MUTANTS = [
+    ("reflect_diag", _reflect_diag_unwhitened_direction,
+     [diag_pins.test_diag_is_the_scalar_rule_on_whitened_inputs, diag_pins.test_diag_reflection_preserves_the_whitened_distances]),
+    ("log_ratio_diag", _log_ratio_diag_mean_variance,
+     [diag_pins.test_diag_log_ratio_matches_library_gaussian_logpdf, diag_pins.test_diag_is_the_scalar_rule_on_whitened_inputs]),
+]
+
+
+@pytest.mark.parametrize("name,mutant,pins", DIAG_MUTANTS, ids=[m.__name__.lstrip("_") for _, m, _ in DIAG_MUTANTS])
+def test_planted_mistake_in_the_per_element_rule_is_caught(monkeypatch, name, mutant, pins):
+    assert not _some_pin_fails(pins), "the pins must pass on the oracle as it stands"
+    monkeypatch.setattr(fo, name, mutant)
+    assert _some_pin_fails(pins), f"no pin noticed the mistake planted into {name}"
 
 
 # ---- the loop of Alg. 1 and the relaxation profile (Sec. 3.4): mistakes planted into the source text ---------------
