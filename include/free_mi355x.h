@@ -214,6 +214,21 @@ int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_
                     float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out,
                     void* workspace, size_t ws_bytes, void* stream);
 
+/* Verification with one variance per ELEMENT (App. C: fixed-variance schedules richer
+ * than one scalar per step; Sec. 3.3 requires only that draft and target share the
+ * covariance).  Both transitions are N(mean, diag(s^2)) with the same vector s, so in
+ * the whitened coordinates (x - c) / s Alg. 2 applies unchanged:
+ *   l = sum_i (m_i - m^_i)(x^_i - (m_i + m^_i)/2) / s_i^2,
+ *   e = ((m^ - m)/s) / ||(m^ - m)/s||,  x = m + s * (I - 2 e e^T)((x^ - m^)/s).
+ * sigma_elem [n_traj, K, d] fp32 (> 0) takes the place of sigma [n_traj, K]; every
+ * other argument, the outputs, the workspace, the limits and the status codes are
+ * those of spec_verify.  Streams 16 bytes per latent element and draft. */
+int32_t spec_verify_diag(const float* m_target, const float* m_draft, const float* x_draft,
+                         const float* sigma_elem, const float* u, const float* lambda,
+                         int32_t n_traj, int32_t K, int64_t d,
+                         float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out,
+                         void* workspace, size_t ws_bytes, void* stream);
+
 /* spec_verify for callers that cannot allocate device memory or bring a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments (minus the workspace), same kernels, same results and

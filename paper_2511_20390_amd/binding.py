@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = [
     "free_version", "free_status_string", "free_last_hip_error", "free_dit_set_streams",
     "free_dit_tune", "free_dit_stream_choice", "free_ddpm_schedule", "free_sde_schedule",
     "free_weight_count", "free_dit_create", "free_dit_destroy", "free_workspace_bytes",
-    "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_verify_static", "spec_verify_timed", "spec_round",
+    "dit_forward_packed", "spec_verify_workspace_bytes", "spec_verify", "spec_verify_diag", "spec_verify_static", "spec_verify_timed", "spec_round",
     "free_drafter_weight_count", "free_drafter_create", "free_drafter_destroy", "free_drafter_workspace_bytes",
     "drafter_forward", "draft_round", "free_sample_workspace_bytes", "free_sample",
     "free_self_speculative_workspace_bytes", "free_self_speculative", "free_lambda_profile",
@@ -90,6 +90,8 @@ def load():
     lib.spec_verify_workspace_bytes.argtypes = [i32, i32, i64]
     lib.spec_verify.restype = i32
     lib.spec_verify.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp, sz, vp]
+    lib.spec_verify_diag.restype = i32
+    lib.spec_verify_diag.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp, sz, vp]
     lib.spec_verify_static.restype = i32
     lib.spec_verify_static.argtypes = [vp] * 6 + [i32, i32, i64] + [vp] * 4 + [vp]
     lib.spec_verify_timed.restype = i32
@@ -259,6 +261,25 @@ def spec_verify(m_target, m_draft, x_draft, sigma, u, lam=None, out=None, worksp
         out = dict(out, stream_us=a.value * 1e3, finish_us=b.value * 1e3)
     else:
         _check(load().spec_verify(*args), "spec_verify")
+    return out
+
+
+def spec_verify_diag(m_target, m_draft, x_draft, sigma_elem, u, lam=None, out=None, workspace=None):
+    """spec_verify with one standard deviation per element: sigma_elem [n_traj, K, d] fp32."""
+    import torch
+    f32 = torch.float32
+    n_traj, K, d = m_target.shape
+    dev = m_target.device
+    out = _verify_out(out, n_traj, K, d, dev)
+    if workspace is None:
+        workspace = torch.empty(max(256, spec_verify_workspace_bytes(n_traj, K, d)), dtype=torch.uint8, device=dev)
+    _check(load().spec_verify_diag(
+        _dev(m_target, f32, "m_target"), _dev(m_draft, f32, "m_draft", (n_traj, K, d)),
+        _dev(x_draft, f32, "x_draft", (n_traj, K, d)), _dev(sigma_elem, f32, "sigma_elem", (n_traj, K, d)),
+        _dev(u, f32, "u", (n_traj, K)), _dev(lam, f32, "lambda", (n_traj, K), optional=True), n_traj, K, d,
+        _dev(out["log_ratio"], f32, "log_ratio", (n_traj, K)), _dev(out["accept"], torch.uint8, "accept", (n_traj, K)),
+        _dev(out["n_accept"], torch.int32, "n_accept", (n_traj,)), _dev(out["x_out"], f32, "x_out", (n_traj, d)),
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()), "spec_verify_diag")
     return out
 
 

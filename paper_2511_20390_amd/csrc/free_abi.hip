@@ -650,6 +650,19 @@ int32_t spec_verify(const float* m_target, const float* m_draft, const float* x_
     return launch_verify(a, workspace, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+int32_t spec_verify_diag(const float* m_target, const float* m_draft, const float* x_draft, const float* sigma_elem,
+                         const float* u, const float* lambda, int32_t n_traj, int32_t K, int64_t d, float* log_ratio,
+                         uint8_t* accept, int32_t* n_accept, float* x_out, void* workspace, size_t ws_bytes,
+                         void* stream) {
+    if (!m_target || !m_draft || !x_draft || !sigma_elem || !u || !log_ratio || !accept || !n_accept || !x_out)
+        return FREE_ERR_NULL;
+    if (n_traj < 0 || K < 1 || K > FREE_MAX_DRAFTS || d < 1) return FREE_ERR_SHAPE;
+    if (n_traj == 0) return FREE_OK;
+    VerifyArgs a{m_target, m_draft, x_draft, nullptr, nullptr, u, lambda, n_traj, K, d,
+                 log_ratio, accept, n_accept, x_out, nullptr, sigma_elem};
+    return launch_verify(a, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
 int32_t spec_verify_static(const float* m_target, const float* m_draft, const float* x_draft, const float* sigma,
                            const float* u, const float* lambda, int32_t n_traj, int32_t K, int64_t d,
                            float* log_ratio, uint8_t* accept, int32_t* n_accept, float* x_out, void* stream) {

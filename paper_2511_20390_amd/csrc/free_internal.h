@@ -101,10 +101,11 @@ struct VerifyArgs {
     const float* x_draft;    // [n_traj, K, d]; or, when x_last != nullptr, the K packed
                              // states of ONE trajectory: draft k is x_draft + (k+1) d
     const float* x_last;     // nullptr, or the K-th draft of the single trajectory
-    const float* sigma; const float* u; const float* lambda;
+    const float* sigma; const float* u; const float* lambda;   // sigma [n_traj, K]; nullptr with sigma_elem
     int32_t n_traj, K; int64_t d;
     float* log_ratio; uint8_t* accept; int32_t* n_accept; float* x_out;
     Profiler* prof;          // nullptr, or the profiler of the handle the call belongs to
+    const float* sigma_elem = nullptr;   // nullptr, or one standard deviation per element [n_traj, K, d]
 };
 size_t verify_workspace_bytes(int32_t n_traj, int32_t K, int64_t d);
 // device address, on the current device, of the library's static scratch array (FREE_STATIC_SCRATCH_BYTES);

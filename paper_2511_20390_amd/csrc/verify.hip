@@ -89,6 +89,15 @@ __device__ inline void accum(double& s2, double& s3, float m, float mh, float xh
     s3 = fma(dm, r, s3);
 }
 
+// per-element variance: both factors divided by the element's standard deviation (whitened coordinates)
+__device__ inline void accum_w(double& s2, double& s3, float m, float mh, float xh, float sg) {
+    const double inv = 1.0 / static_cast<double>(sg);
+    const double dm = (static_cast<double>(mh) - static_cast<double>(m)) * inv;
+    const double r = (static_cast<double>(xh) - static_cast<double>(mh)) * inv;
+    s2 = fma(dm, dm, s2);
+    s3 = fma(dm, r, s3);
+}
+
 template <bool NT>
 __device__ inline f32x4 stream_load(const f32x4* p) {
     if (NT) return __builtin_nontemporal_load(p);
@@ -96,53 +105,59 @@ __device__ inline f32x4 stream_load(const f32x4* p) {
 }
 
 // kThreads lanes; DEPTH float4 per lane and array in flight; VEC: d % 4 == 0 and 16-byte aligned bases;
-// NT: loads marked non-temporal (the inputs are read once by this launch)
-template <int kThreads, int DEPTH, bool VEC, bool NT>
+// NT: loads marked non-temporal (the inputs are read once by this launch); DIAG: sigma_elem [pairs, d] holds
+// one standard deviation per element and the sums are taken in whitened coordinates
+template <int kThreads, int DEPTH, bool VEC, bool NT, bool DIAG>
 __global__ __launch_bounds__(kThreads) void verify_partial_kernel(
     const float* __restrict__ m_target, const float* __restrict__ m_draft,
-    const float* __restrict__ x_draft, const float* __restrict__ x_last, int32_t K, int64_t d,
-    int64_t chunk, int32_t splits, double* __restrict__ partial) {
+    const float* __restrict__ x_draft, const float* __restrict__ x_last, const float* __restrict__ sigma_elem,
+    int32_t K, int64_t d, int64_t chunk, int32_t splits, double* __restrict__ partial) {
     const int64_t pair = blockIdx.x / splits;
     const int32_t split = blockIdx.x % splits;
     const float* m = m_target + pair * d;
     const float* mh = m_draft + pair * d;
     const float* xh = draft_ptr(x_draft, x_last, pair, K, d);
+    const float* sg = DIAG ? sigma_elem + pair * d : nullptr;
     const int64_t lo = static_cast<int64_t>(split) * chunk;
     int64_t hi = lo + chunk;
     if (hi > d) hi = d;
 
     double s2 = 0.0, s3 = 0.0;
+    auto add4 = [&](const f32x4& a, const f32x4& b, const f32x4& c, const f32x4& w) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (DIAG) accum_w(s2, s3, a[e], b[e], c[e], w[e]);
+            else accum(s2, s3, a[e], b[e], c[e]);
+        }
+    };
     if (VEC) {
         const f32x4* m4 = reinterpret_cast<const f32x4*>(m);
         const f32x4* mh4 = reinterpret_cast<const f32x4*>(mh);
         const f32x4* xh4 = reinterpret_cast<const f32x4*>(xh);
+        const f32x4* sg4 = reinterpret_cast<const f32x4*>(sg);
         const int64_t lo4 = lo >> 2, hi4 = hi >> 2;
         int64_t i = lo4 + threadIdx.x;
         for (; i + (DEPTH - 1) * kThreads < hi4; i += DEPTH * kThreads) {
-            f32x4 a[DEPTH], b[DEPTH], c[DEPTH];
+            f32x4 a[DEPTH], b[DEPTH], c[DEPTH], w[DEPTH];
 #pragma unroll
             for (int j = 0; j < DEPTH; ++j) {
                 a[j] = stream_load<NT>(m4 + i + j * kThreads);
                 b[j] = stream_load<NT>(mh4 + i + j * kThreads);
                 c[j] = stream_load<NT>(xh4 + i + j * kThreads);
+                if (DIAG) w[j] = stream_load<NT>(sg4 + i + j * kThreads);
             }
 #pragma unroll
-            for (int j = 0; j < DEPTH; ++j) {
-                accum(s2, s3, a[j].x, b[j].x, c[j].x);
-                accum(s2, s3, a[j].y, b[j].y, c[j].y);
-                accum(s2, s3, a[j].z, b[j].z, c[j].z);
-                accum(s2, s3, a[j].w, b[j].w, c[j].w);
-            }
+            for (int j = 0; j < DEPTH; ++j) add4(a[j], b[j], c[j], w[j]);
         }
         for (; i < hi4; i += kThreads) {
-            f32x4 a = m4[i], b = mh4[i], c = xh4[i];
-            accum(s2, s3, a.x, b.x, c.x);
-            accum(s2, s3, a.y, b.y, c.y);
-            accum(s2, s3, a.z, b.z, c.z);
-            accum(s2, s3, a.w, b.w, c.w);
+            const f32x4 w = DIAG ? sg4[i] : f32x4{1.f, 1.f, 1.f, 1.f};
+            add4(m4[i], mh4[i], xh4[i], w);
         }
     } else {
-        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) accum(s2, s3, m[i], mh[i], xh[i]);
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+            if (DIAG) accum_w(s2, s3, m[i], mh[i], xh[i], sg[i]);
+            else accum(s2, s3, m[i], mh[i], xh[i]);
+        }
     }
 
     s2 = wave_sum(s2);
@@ -183,7 +198,7 @@ __global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(
             const int64_t pr = traj * K + k;
             const double* p = partial + pr * splits * 2;
             for (int s = 0; s < splits; ++s) { s2 += p[2 * s]; s3 += p[2 * s + 1]; }
-            const double sg = static_cast<double>(sigma[pr]);
+            const double sg = sigma ? static_cast<double>(sigma[pr]) : 1.0;   // null: the sums are whitened already
             const double l = -(s3 + 0.5 * s2) / (sg * sg);          // Eq. (qp)
             const double lam = lambda ? static_cast<double>(lambda[pr]) : 1.0;
             const double thr = fmin(0.0, lam * l);                  // Eq. (acc_relax) in the log domain
@@ -209,7 +224,7 @@ __global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(
             const double* p = partial + pr * splits * 2;
             double s2 = 0.0, s3 = 0.0;
             for (int s = 0; s < splits; ++s) { s2 += p[2 * s]; s3 += p[2 * s + 1]; }
-            const double sg = static_cast<double>(sigma[pr]);
+            const double sg = sigma ? static_cast<double>(sigma[pr]) : 1.0;
             const double l = -(s3 + 0.5 * s2) / (sg * sg);
             const double lam = lambda ? static_cast<double>(lambda[pr]) : 1.0;
             const float uu = u[pr];
@@ -313,15 +328,21 @@ int32_t launch_verify(const VerifyArgs& a, void* ws, size_t ws_bytes, hipStream_
     if (blocks > 0x7fffffffll || a.n_traj > 65535) return FREE_ERR_SHAPE;   // grid.x of launch 1, grid.y of launch 2
     double* partial = static_cast<double*>(ws);
     const bool vec = (a.d % 4 == 0) && aligned16(a.m_target) && aligned16(a.m_draft) &&
-                     aligned16(a.x_draft) && (a.x_last == nullptr || aligned16(a.x_last));
+                     aligned16(a.x_draft) && (a.x_last == nullptr || aligned16(a.x_last)) &&
+                     (a.sigma_elem == nullptr || aligned16(a.sigma_elem));
     ProfScope prof(a.prof, PROF_VERIFY, s);
     const dim3 g1(static_cast<unsigned>(blocks)), b1(kPartialThreads);
-    if (vec)
-        launch_timed(verify_partial_kernel<kPartialThreads, kPartialDepth, true, true>, g1, b1, s, ev4, a.m_target,
-                     a.m_draft, a.x_draft, a.x_last, a.K, a.d, p.chunk, p.splits, partial);
-    else
-        launch_timed(verify_partial_kernel<kPartialThreads, kPartialDepth, false, true>, g1, b1, s, ev4, a.m_target,
-                     a.m_draft, a.x_draft, a.x_last, a.K, a.d, p.chunk, p.splits, partial);
+#define FREE_VERIFY_PARTIAL(VEC, DIAG)                                                                              \
+    launch_timed(verify_partial_kernel<kPartialThreads, kPartialDepth, VEC, true, DIAG>, g1, b1, s, ev4, a.m_target, \
+                 a.m_draft, a.x_draft, a.x_last, a.sigma_elem, a.K, a.d, p.chunk, p.splits, partial)
+    if (a.sigma_elem) {
+        if (vec) FREE_VERIFY_PARTIAL(true, true);
+        else FREE_VERIFY_PARTIAL(false, true);
+    } else {
+        if (vec) FREE_VERIFY_PARTIAL(true, false);
+        else FREE_VERIFY_PARTIAL(false, false);
+    }
+#undef FREE_VERIFY_PARTIAL
     if (!launch_ok()) return FREE_ERR_HIP;
     const unsigned rchunks = static_cast<unsigned>((a.d + kReflectChunk - 1) / kReflectChunk);
     launch_timed(verify_finish_kernel, dim3(rchunks, a.n_traj), dim3(kFinishThreads), s, ev4 ? ev4 + 2 : nullptr,

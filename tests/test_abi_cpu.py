@@ -91,6 +91,9 @@ def test_argument_errors_are_status_codes(lib):
     # missing / too small workspace
     assert lib.spec_verify(one, one, one, one, one, None, 1, 6, 64, one, one, one, one, None, 0, None) == binding.FREE_ERR_WORKSPACE
     assert lib.spec_verify(one, one, one, one, one, None, 4, 6, 4096, one, one, one, one, one, 8, None) == binding.FREE_ERR_WORKSPACE
+    assert lib.spec_verify_diag(one, one, one, None, one, None, 1, 6, 64, one, one, one, one, one, 4096, None) == binding.FREE_ERR_NULL
+    assert lib.spec_verify_diag(one, one, one, one, one, None, 1, 6, 0, one, one, one, one, one, 4096, None) == binding.FREE_ERR_SHAPE
+    assert lib.spec_verify_diag(one, one, one, one, one, None, 1, 6, 64, one, one, one, one, None, 0, None) == binding.FREE_ERR_WORKSPACE
     # the entry point with built-in scratch: argument checks first, then the size limit, all before any device call
     assert lib.spec_verify_static(None, one, one, one, one, None, 1, 6, 64, one, one, one, one, None) == binding.FREE_ERR_NULL
     assert lib.spec_verify_static(one, one, one, one, one, None, 1, 0, 64, one, one, one, one, None) == binding.FREE_ERR_SHAPE

@@ -116,3 +116,29 @@ def test_validate_inputs_flags_each_kind_of_violation():
     lam[6, 0] = 7.0
     assert binding.validate_inputs(t, 1000, sigma, u, lam) == 4 | 8
     assert binding.validate_inputs(t, 500, None, None, None) == 1     # the same timesteps against a shorter schedule
+
+
+@pytest.mark.parametrize("n_traj,K,d,relaxed", [(16, 6, 3220, False), (64, 6, 16384, False), (3, 2, 5, True),
+                                                 (5, 3, 4096, True), (2, 7, 4099, False)])
+def test_verify_per_element_variance(n_traj, K, d, relaxed):
+    """One standard deviation per element (the rule in whitened coordinates): every output against the oracle,
+    mixed outcomes, aligned and unaligned sizes, up to the full verification workload."""
+    import torch
+    from oracle import free_oracle as fo
+    from paper_2511_20390_amd import binding, synth
+    vi = synth.make_verify_inputs_diag(n_traj, K, d, 1.349 / math.sqrt(d), 300 + d, fo.ddpm_schedule()["sigma_clipped"])
+    lam = vi["lam"] if relaxed else None
+    ref = fo.spec_verify_diag(vi["m_target"], vi["m_draft"], vi["x_draft"], vi["sigma_elem"], vi["u"], lam)
+    out = dict(log_ratio=torch.empty(n_traj, K, dtype=torch.float32, device="cuda:0"),
+               accept=torch.empty(n_traj, K, dtype=torch.uint8, device="cuda:0"),
+               n_accept=torch.empty(n_traj, dtype=torch.int32, device="cuda:0"),
+               x_out=torch.full((n_traj, d), 7.25, dtype=torch.float32, device="cuda:0"))
+    gpu = binding.spec_verify_diag(pu.to_dev(vi["m_target"]), pu.to_dev(vi["m_draft"]), pu.to_dev(vi["x_draft"]),
+                                   pu.to_dev(vi["sigma_elem"]), pu.to_dev(vi["u"]), None if lam is None else pu.to_dev(lam),
+                                   out=out)
+    torch.cuda.synchronize()
+    st = pu.compare_verify(gpu, ref, lam, vi["u"], f"per-element variance n={n_traj} K={K} d={d}")
+    nacc = gpu["n_accept"].cpu().numpy()
+    assert np.all(gpu["x_out"].cpu().numpy()[nacc == K] == 7.25)
+    if n_traj >= 16:
+        assert 0 < st["accepted"] < n_traj * K and st["reflected"] > 0
