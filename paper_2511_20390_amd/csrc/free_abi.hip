@@ -181,6 +181,9 @@ int32_t linear_dispatch(const Dims& d, const void* A, const void* W, const float
     if (d.mode == FREE_BF16 && mfma_linear_supported(M, N, K))
         return launch_linear_mfma(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, M, N, K, epi,
                                   static_cast<bf16_t*>(out), resid, gate, s, cu_share);
+    if (d.mode == FREE_FP32 && mfma_linear_f32_supported(M, N, K))
+        return launch_linear_mfma_f32(static_cast<const float*>(A), static_cast<const float*>(W), bias, M, N, K, epi,
+                                      static_cast<float*>(out), resid, gate, s, cu_share);
     return launch_linear_simple(A, W, bias, M, N, K, d.mode, epi, out, resid, gate, s);
 }
 

@@ -174,6 +174,11 @@ int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* con
 bool mfma_linear_supported(int32_t M, int32_t N, int32_t K);
 int32_t launch_linear_mfma(const bf16_t* A, const bf16_t* W, const float* bias, int32_t M, int32_t N,
                            int32_t K, int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s, int cu_share = 1);
+// the same kernel on fp32 operands (v_mfma_f32_32x32x2_f32), fp32 output
+bool mfma_linear_f32_supported(int32_t M, int32_t N, int32_t K);
+int32_t launch_linear_mfma_f32(const float* A, const float* W, const float* bias, int32_t M, int32_t N,
+                               int32_t K, int32_t epi, float* out, float* resid, RowVec gate, hipStream_t s,
+                               int cu_share = 1);
 bool mfma_attention_supported(int32_t N, int32_t dh);
 int32_t launch_attention_mfma(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh,
                               bf16_t* out, hipStream_t s);

@@ -39,6 +39,11 @@
 //    works on a compact, L2-friendly group of tiles.
 //  * the tile configuration is chosen per problem from a measured time model (whole
 //    rounds of workgroups x (K slices x time per slice + per-tile fixed cost)).
+//  * FREE_FP32 mode runs the same kernel on fp32 operands: a K slice is still 128 bytes per row
+//    (32 values), a fragment still one 16-byte chunk per lane, and each chunk pair feeds four
+//    v_mfma_f32_32x32x2_f32 (one per element of the chunk: lane group 0 supplies k = 4 c + e,
+//    group 1 supplies k = 4 (c + 1) + e, the same pairing for both operands); full fp32
+//    products and accumulation, fp32 output through the LDS-staged row-major stores.
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
@@ -117,16 +122,40 @@ __device__ inline void tile_coords(int kGroupM, int pid, int tiles_m, int tiles_
 // m = gm_lane + 32 i (gm_lane already includes l % 32), column n = gn_wave + 32 j + 8 (e/4) + 4 lhi + e%4.
 // QB: for the residual update, chunks per lane whose loads are in flight together in the LDS-staged form; 0
 // selects the direct form.
-template <int TM, int TN, int EPI, int QB>
+template <typename OT, int TM, int TN, int EPI, int QB>
 __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm_lane, int gn_wave, int lane, int32_t M,
                                            int32_t N, int32_t vec_ok, const float* __restrict__ bias,
-                                           bf16_t* __restrict__ out, float* __restrict__ resid, const RowVec& gate,
+                                           OT* __restrict__ out, float* __restrict__ resid, const RowVec& gate,
                                            char* wave_lds) {
+    constexpr bool kF32Out = std::is_same<OT, float>::value;   // fp32 mode: the output of the bias / GELU epilogues is fp32
     const int lhi = lane >> 5;
     if (vec_ok) {
         // N % 8 == 0 and 16-byte aligned rows: runs of 4 / 8 columns are all inside or all outside.
         // Rows past M and runs past N (ragged edge tiles) are masked per lane.
-        if constexpr (EPI == FREE_EPI_GATE_RESID && QB == 0) {
+        if constexpr (kF32Out && EPI != FREE_EPI_GATE_RESID && QB == 0) {
+            // fp32 output straight from the accumulator layout (four-wavefront configurations)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int gn0 = gn_wave + j * 32 + 4 * lhi;
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    if (gn0 + 8 * e4 >= N) continue;
+                    const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(bias + gn0 + 8 * e4);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        const int gm = gm_lane + i * 32;
+                        if (gm >= M) continue;
+                        f32x4_t o;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            o[c] = acc[i][j][4 * e4 + c] + bv[c];
+                            if (EPI == FREE_EPI_BIAS_GELU) o[c] = gelu_fast(o[c]);
+                        }
+                        *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(out) + static_cast<int64_t>(gm) * N + gn0 + 8 * e4) = o;
+                    }
+                }
+            }
+        } else if constexpr (EPI == FREE_EPI_GATE_RESID && QB == 0) {
             // read-modify-write of the fp32 residual stream straight from the accumulator layout (32 rows x
             // 32 bytes per instruction).  All loads of a column tile j are issued before its first store (a
             // store would otherwise fence the following loads).  Faster than the staged form below for the
@@ -167,8 +196,9 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                             *reinterpret_cast<f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4) = r[i][e4];
                         }
             }
-        } else if constexpr (EPI == FREE_EPI_GATE_RESID) {
-            // read-modify-write of the fp32 residual stream.  As for the bf16 output below, the accumulator
+        } else if constexpr (EPI == FREE_EPI_GATE_RESID || kF32Out) {
+            // read-modify-write of the fp32 residual stream (or, in fp32 mode, the plain fp32 output of the
+            // bias / GELU epilogues: same staging, no read).  As for the bf16 output below, the accumulator
             // layout would touch 32 rows x 32 bytes per instruction; each 32-row block is staged in the
             // wave-private LDS region CG column tiles at a time (rows padded by 16 bytes) and read back
             // row-major, so that the loads and stores of the residual cover whole 128-byte lines.
@@ -197,7 +227,7 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                         }
                     // batches of 4 chunks per lane: all loads of a batch before its first store, and few
                     // enough registers beside the accumulators
-                    constexpr int QN = QB < NQ ? QB : NQ;
+                    constexpr int QN = (QB > 0 && QB < NQ) ? QB : NQ;
                     static_assert(NQ % QN == 0, "whole batches");
 #pragma unroll
                     for (int q0 = 0; q0 < NQ; q0 += QN) {
@@ -212,9 +242,11 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                             ok[q] = gm < M && gn < N;
                             off[q] = static_cast<int64_t>(gm) * N + gn;
                             if (ok[q]) {
-                                const int smp = one_sample ? s_first : gm / gate.rows_per_sample;
-                                r[q] = *reinterpret_cast<const f32x4_t*>(resid + off[q]);
-                                g[q] = *reinterpret_cast<const f32x4_t*>(gbase + static_cast<int64_t>(smp) * gate.stride + gn);
+                                if constexpr (EPI == FREE_EPI_GATE_RESID) {
+                                    const int smp = one_sample ? s_first : gm / gate.rows_per_sample;
+                                    r[q] = *reinterpret_cast<const f32x4_t*>(resid + off[q]);
+                                    g[q] = *reinterpret_cast<const f32x4_t*>(gbase + static_cast<int64_t>(smp) * gate.stride + gn);
+                                }
                                 bv[q] = *reinterpret_cast<const f32x4_t*>(bias + gn);
                             }
                         }
@@ -223,9 +255,18 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                             if (ok[q]) {
                                 const int f = (q0 + q) * 64 + lane;
                                 const f32x4_t v = *reinterpret_cast<const f32x4_t*>(wave_lds + (f / CH) * kStageRow + ((f % CH) << 4));
+                                if constexpr (EPI == FREE_EPI_GATE_RESID) {
 #pragma unroll
-                                for (int c = 0; c < 4; ++c) r[q][c] = fmaf(g[q][c], v[c] + bv[q][c], r[q][c]);
-                                *reinterpret_cast<f32x4_t*>(resid + off[q]) = r[q];
+                                    for (int c = 0; c < 4; ++c) r[q][c] = fmaf(g[q][c], v[c] + bv[q][c], r[q][c]);
+                                    *reinterpret_cast<f32x4_t*>(resid + off[q]) = r[q];
+                                } else {
+#pragma unroll
+                                    for (int c = 0; c < 4; ++c) {
+                                        r[q][c] = v[c] + bv[q][c];
+                                        if (EPI == FREE_EPI_BIAS_GELU) r[q][c] = gelu_fast(r[q][c]);
+                                    }
+                                    *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(out) + off[q]) = r[q];
+                                }
                             }
                     }
                 }
@@ -286,7 +327,8 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                     if ((32 * CH) % 64 != 0 && f >= 32 * CH) continue;
                     const u32x4_t o = *reinterpret_cast<const u32x4_t*>(wave_lds + row * kStageRow + (ch << 4));
                     const int gm = gm_lane - l32 + i * 32 + row, gn = gn_wave + ch * 8;
-                    if (gm < M && gn < N) *reinterpret_cast<u32x4_t*>(out + static_cast<int64_t>(gm) * N + gn) = o;
+                    if (gm < M && gn < N)
+                        *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(out) + static_cast<int64_t>(gm) * N + gn) = o;
                 }
             }
         }
@@ -306,9 +348,9 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                 const float v = acc[i][j][e] + bias[gn];
                 const int64_t o = static_cast<int64_t>(gm) * N + gn;
                 if (EPI == FREE_EPI_BIAS) {
-                    out[o] = float_to_bf16(v);
+                    store_f(out + o, v);
                 } else if (EPI == FREE_EPI_BIAS_GELU) {
-                    out[o] = float_to_bf16(gelu_fast(v));
+                    store_f(out + o, gelu_fast(v));
                 } else {
                     const float g = gate.base[static_cast<int64_t>(gm / gate.rows_per_sample) * gate.stride + gn];
                     resid[o] = fmaf(g, v, resid[o]);
@@ -317,14 +359,19 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
         }
 }
 
-// EVEN_K: K % 64 == 0 (no predicates in the K loop).  Ragged M / N tiles are handled
-// by clamping the loaded row index (extra rows are computed, never stored).
-template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
+// T: bf16_t or float (operands and the output of the bias / GELU epilogues).  EVEN_K: K a multiple of the
+// slice (64 bf16 or 32 fp32: no predicates in the K loop).  Rows past the end of a ragged M / N tile read
+// as zero (extra rows are computed, never stored).
+template <typename T, int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
-    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, const float* __restrict__ bias, int32_t M,
+    const T* __restrict__ X, const T* __restrict__ W, const float* __restrict__ bias, int32_t M,
     int32_t N, int32_t K, int32_t tiles_m, int32_t tiles_n, int32_t group_m, int32_t vec_ok,
-    bf16_t* __restrict__ out, float* __restrict__ resid, RowVec gate) {
+    T* __restrict__ out, float* __restrict__ resid, RowVec gate) {
     static_assert(WGM * WGN == 4 || WGM * WGN == 8, "four or eight wavefronts per workgroup");
+    constexpr bool kF32 = std::is_same<T, float>::value;
+    constexpr int ES = static_cast<int>(sizeof(T));    // bytes per element
+    constexpr int BKE = kRowBytes / ES;                // elements per K slice
+    constexpr int CE = 16 / ES;                        // elements per 16-byte chunk
     constexpr int NT = WGM * WGN * 64;                 // threads per workgroup
     constexpr int RP = NT / 8;                         // tile rows covered by one pass of 16-byte loads
     constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
@@ -344,24 +391,24 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     // Buffer descriptors over the rows of this tile: a load past the end of the matrix (rows
     // of a ragged edge tile) returns zeros, so no row clamping and no address registers -
     // one per-lane byte offset plus wave-uniform (scalar) offsets per load and per slice.
-    const int64_t x_left = static_cast<int64_t>(M - m0) * K * 2, w_left = static_cast<int64_t>(N - n0) * K * 2;
+    const int64_t x_left = static_cast<int64_t>(M - m0) * K * ES, w_left = static_cast<int64_t>(N - n0) * K * ES;
     const __amdgpu_buffer_rsrc_t xsrd = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t*>(X + static_cast<int64_t>(m0) * K), 0,
+        const_cast<T*>(X + static_cast<int64_t>(m0) * K), 0,
         static_cast<int>(x_left < 0x7fffffff ? x_left : 0x7fffffff), 0x00020000);
     const __amdgpu_buffer_rsrc_t wsrd = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t*>(W + static_cast<int64_t>(n0) * K), 0,
+        const_cast<T*>(W + static_cast<int64_t>(n0) * K), 0,
         static_cast<int>(w_left < 0x7fffffff ? w_left : 0x7fffffff), 0x00020000);
-    const int ld_voff = ld_row * K * 2 + ld_chunk * 16;       // per-lane byte offset inside the tile
-    const int pass_bytes = RP * K * 2;                        // RP rows further down per load index
+    const int ld_voff = ld_row * K * ES + ld_chunk * 16;      // per-lane byte offset inside the tile
+    const int pass_bytes = RP * K * ES;                       // RP rows further down per load index
     const int st_off = ld_row * kRowBytes + ((ld_chunk ^ ((ld_row >> 1) & 7)) << 4);   // + i*RP rows per load
     u32x4_t sreg[LA + LB];                              // staging registers: one K slice in flight
-    const int nk = (K + BK - 1) / BK;
+    const int nk = (K + BKE - 1) / BKE;
 
     // staging register idx in [0, LA + LB): the first LA hold X rows, the rest W rows
     constexpr int NS = LA + LB;
     auto fetch_range = [&](int kt, int lo, int hi) {
         const int kbyte = kt * kRowBytes;
-        const bool in_k = EVEN_K || (kt * BK + ld_chunk * 8) < K;   // K % 8 == 0: a chunk is all in or all out
+        const bool in_k = EVEN_K || (kt * BKE + ld_chunk * CE) < K;   // K a multiple of the chunk: all in or all out
 #pragma unroll
         for (int idx = 0; idx < NS; ++idx) {
             if (idx < lo || idx >= hi) continue;
@@ -386,15 +433,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     const int sw = (l32 >> 1) & 7;                         // (row / 2) % 8 (tile row offsets are multiples of 32)
     const int x_row0 = (wm * TM * 32 + l32) * kRowBytes;           // + i*32 rows
     const int w_row0 = (BM + wn * TN * 32 + l32) * kRowBytes;      // + j*32 rows
-    bf16x8_t fx[2][TM], fw[2][TN];
+    u32x4_t fx[2][TM], fw[2][TN];                      // one 16-byte chunk each: 8 bf16 or 4 fp32
     auto load_frags = [&](const char* base, int ks, int buf) {
         const int choff = (((ks << 1) | lhi) ^ sw) << 4;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            fx[buf][i] = *reinterpret_cast<const bf16x8_t*>(base + x_row0 + i * 32 * kRowBytes + choff);
+            fx[buf][i] = *reinterpret_cast<const u32x4_t*>(base + x_row0 + i * 32 * kRowBytes + choff);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            fw[buf][j] = *reinterpret_cast<const bf16x8_t*>(base + w_row0 + j * 32 * kRowBytes + choff);
+            fw[buf][j] = *reinterpret_cast<const u32x4_t*>(base + w_row0 + j * 32 * kRowBytes + choff);
     };
 
     f32x16_t acc[TM][TN];                                  // acc[i][j]: rows n (tile j), columns m (tile i)
@@ -406,11 +453,29 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     auto mma = [&](int buf) {
+        if constexpr (kF32) {
+            // element e of the chunk: the lanes of group 0 / 1 hold the two k of one 32x32x2 product
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][j], fx[buf][i], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        // (copied out first: a bit cast applied directly to a vector element read element 0)
+                        const uint32_t wbits = fw[buf][j][e], xbits = fx[buf][i][e];
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, wbits),
+                                                                        __builtin_bit_cast(float, xbits),
+                                                                        acc[i][j], 0, 0, 0);
+                    }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fw[buf][j]),
+                                                                        __builtin_bit_cast(bf16x8_t, fx[buf][i]),
+                                                                        acc[i][j], 0, 0, 0);
+        }
     };
     // One K slice.  Precondition: fragments of k-step 0 are in buffer 0.  The staging
     // registers hold slice kt+1; they are written to the other LDS stage in three
@@ -420,7 +485,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     //   k-step 0..2: multiply | read fragments of the next step | write + refill a third
     //   barrier: the other stage is complete, this stage will not be read again
     //   k-step 3: multiply | read fragments of step 0 of slice kt+1 from the other stage
-    constexpr int MF = TM * TN, NR = TM + TN;
+    constexpr int MF = TM * TN * (kF32 ? 4 : 1), NR = TM + TN;
     constexpr int C1 = (NS + 2) / 3, C2 = (2 * NS + 2) / 3;      // portion boundaries
     auto slice = [&](int kt, auto stash_next, auto fetch_ahead) {
         constexpr bool kStash = decltype(stash_next)::value, kFetch = decltype(fetch_ahead)::value;
@@ -468,11 +533,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     // ---- epilogue
     // after the barrier of the last slice no wavefront reads the LDS tiles any more: each wavefront
     // may use a private region of them to transpose its output
-    constexpr int kWaveStage = EPI == FREE_EPI_GATE_RESID ? 32 * (((TN % 2 == 0 ? 2 : 1) * 8 + 1) * 16)   // fp32 groups
-                                                          : 32 * (TN * 64 + 16);                            // bf16 rows
+    constexpr int kWaveStage = (EPI == FREE_EPI_GATE_RESID || kF32) ? 32 * (((TN % 2 == 0 ? 2 : 1) * 8 + 1) * 16)   // fp32 groups
+                                                                    : 32 * (TN * 64 + 16);                            // bf16 rows
     static_assert(WGM * WGN * kWaveStage <= 2 * kStageBytes, "output staging must fit in the K-loop tiles");
     constexpr int kResidBatch = (WGM * WGN == 8) ? 4 : 0;
-    write_tile<TM, TN, EPI, kResidBatch>(acc, m0 + wm * TM * 32 + l32, n0 + wn * TN * 32, lane, M, N, vec_ok, bias, out, resid, gate,
+    write_tile<T, TM, TN, EPI, kResidBatch>(acc, m0 + wm * TM * 32 + l32, n0 + wn * TN * 32, lane, M, N, vec_ok, bias, out, resid, gate,
                             lds + wave * kWaveStage);
 }
 
@@ -487,12 +552,12 @@ int device_cus() {
     return cus;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
-int32_t launch_one(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K, bf16_t* out,
+template <typename T, int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
+int32_t launch_one(const T* X, const T* W, const float* bias, int32_t M, int32_t N, int32_t K, T* out,
                    float* resid, RowVec gate, hipStream_t s) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const size_t lds = 2 * static_cast<size_t>(BM + BN) * kRowBytes;
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, EVEN_K>;
+    auto kern = gemm_bf16_kernel<T, BM, BN, WGM, WGN, EPI, EVEN_K>;
     static bool attr_set = false;
     if (!attr_set) {
         if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -522,14 +587,14 @@ int32_t launch_one(const bf16_t* X, const bf16_t* W, const float* bias, int32_t 
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 
-template <int BM, int BN, int WGM, int WGN>
-int32_t launch_cfg(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
-                   int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s) {
-    const bool even = (K % BK) == 0;
+template <typename T, int BM, int BN, int WGM, int WGN>
+int32_t launch_cfg(const T* X, const T* W, const float* bias, int32_t M, int32_t N, int32_t K,
+                   int32_t epi, T* out, float* resid, RowVec gate, hipStream_t s) {
+    const bool even = (K % (kRowBytes / static_cast<int>(sizeof(T)))) == 0;
 #define FREE_GEMM_CASE(E)                                                                                    \
     case E:                                                                                                  \
-        return even ? launch_one<BM, BN, WGM, WGN, E, true>(X, W, bias, M, N, K, out, resid, gate, s)        \
-                    : launch_one<BM, BN, WGM, WGN, E, false>(X, W, bias, M, N, K, out, resid, gate, s)
+        return even ? launch_one<T, BM, BN, WGM, WGN, E, true>(X, W, bias, M, N, K, out, resid, gate, s)     \
+                    : launch_one<T, BM, BN, WGM, WGN, E, false>(X, W, bias, M, N, K, out, resid, gate, s)
     switch (epi) {
         FREE_GEMM_CASE(FREE_EPI_BIAS);
         FREE_GEMM_CASE(FREE_EPI_BIAS_GELU);
@@ -540,26 +605,67 @@ int32_t launch_cfg(const bf16_t* X, const bf16_t* W, const float* bias, int32_t 
 }
 
 // Estimated time (us) of a tile configuration on `cus` compute units: workgroup rounds times
-// (K slices x measured time per slice + per-tile prologue/epilogue), measured on MI355X.
-double cfg_time(int M, int N, int K, int bm, int bn, double us_per_slice, double us_fixed, int cus) {
+// (K slices x measured time per slice + per-tile prologue/epilogue), measured on MI355X in bf16 (one machine's
+// microseconds: machines of the type differ by a few per cent, and half-share launches reuse them).  nk: 128-byte
+// K slices; slice_scale: time of a slice relative to bf16 (fp32: 4.4 - four 16-pass MFMAs per chunk pair instead of
+// one 8-pass MFMA, at the slightly higher clock the fp32 products leave).
+double cfg_time(int M, int N, int nk, int bm, int bn, double us_per_slice, double us_fixed, int cus) {
     const double tiles = static_cast<double>((M + bm - 1) / bm) * ((N + bn - 1) / bn);
     const double rounds = std::ceil(tiles / cus);
-    return rounds * (((K + BK - 1) / BK) * us_per_slice + us_fixed);
+    return rounds * (nk * us_per_slice + us_fixed);
 }
 
 // The 128x128 configuration is small enough for two workgroups per CU: measured 0.6 us per slice for a
 // workgroup that has its CU to itself and 1.05 us each for two that share one.  Used for problems of
 // few rows (the drafter, single-state steps), where it decides between half-empty rounds of large
 // tiles and fuller rounds of small ones.
-double small_tile_time(int M, int N, int K, int cus) {
+double small_tile_time(int M, int N, int nk, double sc, int cus) {
     const double tiles = static_cast<double>((M + 127) / 128) * ((N + 127) / 128);
-    const int nk = (K + BK - 1) / BK;
-    const double shared = nk * 1.05 + 4.0, alone = nk * 0.6 + 4.0;
+    const double shared = nk * 1.05 * sc + 4.0, alone = nk * 0.6 * sc + 4.0;
     const double full = std::floor(tiles / (2.0 * cus));
     const double rest = tiles - full * 2.0 * cus;
     return full * shared + (rest == 0.0 ? 0.0 : (rest <= cus ? alone : shared));
 }
 
+// cu_share: how many launches of this size are expected to run side by side (the halves of a packed batch on two
+// streams); the tile configuration is chosen for that share of the compute units.  Tiles change how the output
+// is cut, never the order in which a dot product is summed, so the result does not depend on it.
+template <typename T>
+int32_t choose_and_launch(const T* X, const T* W, const float* bias, int32_t M, int32_t N, int32_t K, int32_t epi,
+                          T* out, float* resid, RowVec gate, hipStream_t s, int cu_share) {
+    if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W)) & 15u) return FREE_ERR_SHAPE;
+    constexpr int kSliceElems = kRowBytes / static_cast<int>(sizeof(T));
+    const double sc = sizeof(T) == 4 ? 4.4 : 1.0;
+    const int nk = (K + kSliceElems - 1) / kSliceElems;
+    const int cus = std::max(1, device_cus() / std::max(1, cu_share));
+    const double t256 = cfg_time(M, N, nk, 256, 256, 1.83 * sc, 9.0, cus);
+    const double t384 = cfg_time(M, N, nk, 384, 192, 2.06 * sc, 10.0, cus);
+    const double t2x1 = cfg_time(M, N, nk, 256, 128, 1.31 * sc, 6.0, cus);
+    const double t128 = M <= 4096 ? small_tile_time(M, N, nk, sc, cus) : cfg_time(M, N, nk, 128, 128, 0.80 * sc, 4.0, cus);
+    // 96 x 128 (one row of four wavefronts, each 96 x 32): for problems of few rows and few columns, where
+    // 128 x 128 tiles leave compute units empty (2048 x 1152: 144 tiles on 256 CUs; 198 of three quarters the work)
+    double t96 = 1e30;
+    {
+        const double tiles = static_cast<double>((M + 95) / 96) * ((N + 127) / 128);
+        if (tiles <= cus && M <= 4096) t96 = nk * 0.47 * sc + 4.0;      // measured 0.47 us per slice
+    }
+    // 160 x 128 (same shape of workgroup, 160 x 32 per wavefront): for few rows and many columns, where 128 x 128
+    // tiles spill into a second round (2048 x 4608: 576 tiles on 512 slots; 468 of 160 x 128).  Measured about
+    // 1.25 x the slice time of 128 x 128, alone and shared.
+    double t160 = 1e30;
+    if (M <= 4096) {
+        const double tiles = static_cast<double>((M + 159) / 160) * ((N + 127) / 128);
+        if (tiles <= cus) t160 = nk * 0.80 * sc + 4.0;
+        else if (tiles <= 2.0 * cus) t160 = nk * 1.40 * sc + 4.0;
+    }
+    const double best = std::fmin(std::fmin(std::fmin(t256, t384), std::fmin(t2x1, t128)), std::fmin(t96, t160));
+    if (best == t160) return launch_cfg<T, 160, 128, 1, 4>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    if (best == t96) return launch_cfg<T, 96, 128, 1, 4>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    if (best == t384) return launch_cfg<T, 384, 192, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    if (best == t256) return launch_cfg<T, 256, 256, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    if (best == t2x1) return launch_cfg<T, 256, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    return launch_cfg<T, 128, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+}
 
 }  // namespace
 
@@ -568,42 +674,21 @@ bool mfma_linear_supported(int32_t M, int32_t N, int32_t K) {
     return M >= 1 && N >= 1 && K >= 8 && (K % 8) == 0 && static_cast<int64_t>(K) * 2 * 384 < (1ll << 31);
 }
 
-// cu_share: how many launches of this size are expected to run side by side (the halves of a packed batch on two
-// streams); the tile configuration is chosen for that share of the compute units.  Tiles change how the output
-// is cut, never the order in which a dot product is summed, so the result does not depend on it.
+bool mfma_linear_f32_supported(int32_t M, int32_t N, int32_t K) {
+    // whole 16-byte chunks of fp32; 32-bit byte offsets inside a tile: up to 384 rows of K fp32
+    return M >= 1 && N >= 1 && K >= 4 && (K % 4) == 0 && static_cast<int64_t>(K) * 4 * 384 < (1ll << 31);
+}
+
 int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
                            int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s, int cu_share) {
     if (!mfma_linear_supported(M, N, K)) return FREE_ERR_SHAPE;
-    if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W)) & 15u) return FREE_ERR_SHAPE;
-    const int cus = std::max(1, device_cus() / std::max(1, cu_share));
-    const double t256 = cfg_time(M, N, K, 256, 256, 1.83, 9.0, cus);
-    const double t384 = cfg_time(M, N, K, 384, 192, 2.06, 10.0, cus);
-    const double t2x1 = cfg_time(M, N, K, 256, 128, 1.31, 6.0, cus);
-    const double t128 = M <= 4096 ? small_tile_time(M, N, K, cus) : cfg_time(M, N, K, 128, 128, 0.80, 4.0, cus);
-    // 96 x 128 (one row of four wavefronts, each 96 x 32): for problems of few rows and few columns, where
-    // 128 x 128 tiles leave compute units empty (2048 x 1152: 144 tiles on 256 CUs; 198 of three quarters the work)
-    double t96 = 1e30;
-    {
-        const double tiles = static_cast<double>((M + 95) / 96) * ((N + 127) / 128);
-        if (tiles <= cus && M <= 4096) t96 = ((K + BK - 1) / BK) * 0.47 + 4.0;      // measured 0.47 us per slice
-    }
-    // 160 x 128 (same shape of workgroup, 160 x 32 per wavefront): for few rows and many columns, where 128 x 128
-    // tiles spill into a second round (2048 x 4608: 576 tiles on 512 slots; 468 of 160 x 128).  Measured about
-    // 1.25 x the slice time of 128 x 128, alone and shared.
-    double t160 = 1e30;
-    if (M <= 4096) {
-        const double tiles = static_cast<double>((M + 159) / 160) * ((N + 127) / 128);
-        const int nk = (K + BK - 1) / BK;
-        if (tiles <= cus) t160 = nk * 0.80 + 4.0;
-        else if (tiles <= 2.0 * cus) t160 = nk * 1.40 + 4.0;
-    }
-    const double best = std::fmin(std::fmin(std::fmin(t256, t384), std::fmin(t2x1, t128)), std::fmin(t96, t160));
-    if (best == t160) return launch_cfg<160, 128, 1, 4>(X, W, bias, M, N, K, epi, out, resid, gate, s);
-    if (best == t96) return launch_cfg<96, 128, 1, 4>(X, W, bias, M, N, K, epi, out, resid, gate, s);
-    if (best == t384) return launch_cfg<384, 192, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
-    if (best == t256) return launch_cfg<256, 256, 4, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
-    if (best == t2x1) return launch_cfg<256, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
-    return launch_cfg<128, 128, 2, 2>(X, W, bias, M, N, K, epi, out, resid, gate, s);
+    return choose_and_launch<bf16_t>(X, W, bias, M, N, K, epi, out, resid, gate, s, cu_share);
+}
+
+int32_t launch_linear_mfma_f32(const float* X, const float* W, const float* bias, int32_t M, int32_t N, int32_t K,
+                               int32_t epi, float* out, float* resid, RowVec gate, hipStream_t s, int cu_share) {
+    if (!mfma_linear_f32_supported(M, N, K)) return FREE_ERR_SHAPE;
+    return choose_and_launch<float>(X, W, bias, M, N, K, epi, out, resid, gate, s, cu_share);
 }
 
 }  // namespace freemi
