@@ -43,10 +43,12 @@ def forward_flops(cfg, B):
 # kernel symbol (as rocprofv3 prints it) behind each profiled category, to look its measured
 # HBM traffic up in the committed rocprofv3 --pmc summary
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "spec_round_xl2_512_hbm_traffic.md")
-CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<384, 192, 4, 2, 1, true>`", "gemm_qkv": "gemm_bf16_kernel<256, 256, 4, 2, 0, true>`",
-                   "gemm_fc2": "gemm_bf16_kernel<256, 256, 4, 2, 2, true>` FC2",
-                   "gemm_proj": "gemm_bf16_kernel<256, 256, 4, 2, 2, true>` out-projection",
-                   "attention": "attn_mfma_kernel<72, 1>`", "verify_partial": "verify_partial_kernel<true>`"}
+CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<bf16_t, 384, 192, 4, 2, 1, true>`",
+                   "gemm_qkv": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 0, true>`",
+                   "gemm_fc2": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 2, true>` FC2",
+                   "gemm_proj": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 2, true>` out-projection",
+                   "attention": "attn_mfma_kernel<72, 1>`",
+                   "verify_partial": "verify_partial_kernel<256, 4, true, true, false>`"}
 
 
 def measured_traffic(category):
