@@ -191,6 +191,9 @@ int32_t attention_dispatch(const Dims& d, const void* qkv, int32_t B, void* out,
     if (d.mode == FREE_BF16 && mfma_attention_supported(d.ntok, d.dh))
         return launch_attention_mfma(static_cast<const bf16_t*>(qkv), B, d.ntok, d.heads, d.dh,
                                      static_cast<bf16_t*>(out), s);
+    if (d.mode == FREE_FP32 && mfma_attention_f32_supported(d.ntok, d.dh))
+        return launch_attention_mfma_f32(static_cast<const float*>(qkv), B, d.ntok, d.heads, d.dh,
+                                         static_cast<float*>(out), s);
     return launch_attention_simple(qkv, B, d.ntok, d.heads, d.dh, d.mode, out, s);
 }
 

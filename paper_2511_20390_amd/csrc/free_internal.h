@@ -182,5 +182,9 @@ int32_t launch_linear_mfma_f32(const float* A, const float* W, const float* bias
 bool mfma_attention_supported(int32_t N, int32_t dh);
 int32_t launch_attention_mfma(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh,
                               bf16_t* out, hipStream_t s);
+// fp32 operands and softmax on the matrix cores (attn_f32_mfma.hip); qkv and out 16-byte aligned
+bool mfma_attention_f32_supported(int32_t N, int32_t dh);
+int32_t launch_attention_mfma_f32(const float* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh,
+                                  float* out, hipStream_t s);
 
 }  // namespace freemi
