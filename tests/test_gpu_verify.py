@@ -64,6 +64,24 @@ def test_verify_is_deterministic_run_to_run():
         assert torch.equal(a[k], b[k])
 
 
+def test_verify_timed_variant_returns_the_same_results_and_launch_durations():
+    """spec_verify_timed is the benchmark's variant of the call: same two launches with events attached; its
+    outputs equal the plain call's bit for bit and both durations are positive and far below a millisecond."""
+    import torch
+    from paper_2511_20390_amd import binding, synth
+    from oracle import free_oracle as fo
+    vi = synth.make_verify_inputs(16, 6, 8192 + 36, 0.02, 5, fo.ddpm_schedule()["sigma_clipped"])
+    args = [pu.to_dev(vi[k]) for k in ("m_target", "m_draft", "x_draft", "sigma", "u")]
+    a = binding.spec_verify(*args)
+    b = binding.spec_verify(*args, timed=True)
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    assert 0.0 < b["stream_us"] < 1000.0 and 0.0 < b["finish_us"] < 1000.0
+    ref = fo.spec_verify(vi["m_target"], vi["m_draft"], vi["x_draft"], vi["sigma"], vi["u"])
+    pu.compare_verify({k: v for k, v in b.items() if not k.endswith("_us")}, ref, None, vi["u"], "timed")
+
+
 @pytest.mark.parametrize("delta", [0.01, 0.1, 0.5, 1.0])
 def test_verify_full_size_config(delta):
     """64 trajectories x 6 drafts x 4x64x64 latent: full comparison with the oracle
