@@ -163,6 +163,37 @@ int32_t free_dit_tune(free_dit_t h, const float* x, const int32_t* t, const int3
                       float* eps_out, void* workspace, size_t ws_bytes, void* stream);
 int32_t free_dit_stream_choice(free_dit_t h, int32_t B);
 
+/* ---- LayerNorm folded into the neighbouring GEMMs (bf16 mode) --------------
+ * The adaLN-Zero block of the packed forward (Alg. 1; the DiT the paper samples
+ * from, Sec. 4) normalises the residual stream twice per block:
+ * LN(x) (1 + scale) + shift, followed by a linear layer with weights W, bias b.
+ * With z = x (1 + scale), row mean mu and r = 1 / sqrt(var + eps) this equals
+ *     r (z W^T) - r mu c1 + c0,  c1 = (1 + scale) W^T,  c0 = shift W^T + b
+ * (c1, c0 per packed sample).  In the folded form the GEMM that updates the
+ * residual stream (attention out-projection, MLP second layer) also writes z in
+ * bf16 and per-row partial sums of x and x^2, one launch computes c1 and c0 of
+ * every block from the modulation vectors, and the GEMM that follows the
+ * LayerNorm (QKV, MLP first layer) applies r, mu, c1, c0 in its epilogue: the
+ * separate LayerNorm pass over the residual stream disappears (all but the
+ * first one of block 0, whose input no GEMM produced).  Same result up to
+ * rounding: z is rounded to bf16 where the separate pass rounds the normalised
+ * row, and the variance is E[x^2] - mu^2 in fp32.
+ * Covered: FREE_BF16, hidden % 128 == 0, tokens per sample % 32 == 0.
+ *   FREE_LN_FOLD_AUTO (initial state): folded when covered and the batch has at
+ *     least 4096 token rows (its GEMMs use the two large tile shapes only),
+ *     the separate LayerNorm kernel otherwise.
+ *   FREE_LN_FOLD_OFF: always the separate kernel.
+ *   FREE_LN_FOLD_REQUIRE: always folded; free_dit_set_ln_fold returns
+ *     FREE_ERR_SHAPE when the model is not covered - never a silent switch.
+ * free_dit_ln_fold_active(h, B): 1 if a forward on B packed states would take
+ * the folded path now, else 0.  The drafter's blocks always use the separate
+ * kernel. */
+#define FREE_LN_FOLD_OFF     0
+#define FREE_LN_FOLD_AUTO    1
+#define FREE_LN_FOLD_REQUIRE 2
+int32_t free_dit_set_ln_fold(free_dit_t h, int32_t mode);
+int32_t free_dit_ln_fold_active(free_dit_t h, int32_t B);
+
 /* ---- the packed target forward (Alg. 1, "in parallel"; Sec. 3.3) ----------
  * One forward of the class-conditional DiT on B packed states, each with its
  * own timestep t[b] and label y[b] (int32, device).
@@ -430,6 +461,30 @@ int32_t free_op_attention(const void* qkv, int32_t B, int32_t N, int32_t heads, 
 int32_t free_op_ln_modulate(const float* x, const float* shift, const float* scale,
                             int32_t mod_stride, int32_t M, int32_t D, int32_t rows_per_sample,
                             int32_t dtype, void* out, void* stream);
+
+/* The three pieces of the folded LayerNorm (see free_dit_set_ln_fold), bf16 only, for parity tests.
+ * free_op_ln_fold_vectors: c1 | c0 for `depth` blocks from mod [B, mod_stride] (block l: shift1, scale1, gate1,
+ *   shift2, scale2, gate2, `hidden` floats each, at l * 6 hidden); w_qkv / b_qkv / w_fc1 / b_fc1: host arrays of
+ *   `depth` device pointers (bf16 [3 hidden, hidden] / fp32 [3 hidden] / bf16 [ffn, hidden] / fp32 [ffn]);
+ *   fold [B, fold_stride] fp32 out, fold_stride >= 2 depth (3 hidden + ffn): c1 of block l's QKV rows at
+ *   l (3 hidden + ffn), its MLP-1 rows behind them, and c0 depth (3 hidden + ffn) floats further.  Blocks: it
+ *   copies the pointer tables to the device and waits (a test entry point, not a hot-path call).
+ * free_op_linear_resid_prep: resid += gate * (A W^T + bias) as FREE_EPI_GATE_RESID, and z [M, N] bf16 =
+ *   resid_new * (1 + scale_next[m / rows_per_sample, :]), stats [M, N / 128, 2] fp32 = per row and 128-column
+ *   slot the sums of resid_new and resid_new^2.  N % 128 == 0; gate and scale_next share mod_stride.
+ * free_op_linear_ln: out [M, N] bf16 = act(r (z W^T) - r mu c1 + c0), r and mu of row m from stats
+ *   [M, Kdim / 128, 2], c1 / c0 of sample s at c1[s * fold_stride + n]; gelu != 0 applies gelu_tanh. */
+int32_t free_op_ln_fold_vectors(const float* mod, int32_t B, int32_t hidden, int32_t ffn, int32_t mod_stride,
+                                int32_t depth, const void* const* w_qkv, const float* const* b_qkv,
+                                const void* const* w_fc1, const float* const* b_fc1, float* fold,
+                                int64_t fold_stride, void* stream);
+int32_t free_op_linear_resid_prep(const void* A, const void* W, const float* bias, int32_t M, int32_t N,
+                                  int32_t Kdim, float* resid, const float* gate, const float* scale_next,
+                                  int32_t mod_stride, int32_t rows_per_sample, void* z, float* stats,
+                                  void* stream);
+int32_t free_op_linear_ln(const void* z, const void* W, int32_t M, int32_t N, int32_t Kdim, const float* stats,
+                          const float* c1, const float* c0, int64_t fold_stride, int32_t rows_per_sample,
+                          int32_t gelu, void* out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -20,6 +20,8 @@ FREE_ERR_LIMIT = -7
 STATIC_SCRATCH_BYTES = 1 << 20
 FREE_FP32, FREE_BF16 = 0, 1
 EPI_BIAS, EPI_BIAS_GELU, EPI_GATE_RESID = 0, 1, 2
+LN_FOLD_OFF, LN_FOLD_AUTO, LN_FOLD_REQUIRE = 0, 1, 2
+LN_SLOT_COLS = 128
 MODES = {"fp32": FREE_FP32, "bf16": FREE_BF16}
 
 EXPORTED_SYMBOLS = [
@@ -31,6 +33,8 @@ EXPORTED_SYMBOLS = [
     "drafter_forward", "draft_round", "free_sample_workspace_bytes", "free_sample",
     "free_self_speculative_workspace_bytes", "free_self_speculative", "free_lambda_profile",
     "free_op_linear", "free_op_attention", "free_op_ln_modulate",
+    "free_dit_set_ln_fold", "free_dit_ln_fold_active", "free_op_ln_fold_vectors", "free_op_linear_resid_prep",
+    "free_op_linear_ln",
     "free_profile_begin", "free_profile_end", "free_profile_category_name", "free_mfma_ceiling", "free_validate_inputs",
 ]
 PROF_NCAT = 12
@@ -126,6 +130,16 @@ def load():
     lib.free_op_attention.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
     lib.free_op_ln_modulate.restype = i32
     lib.free_op_ln_modulate.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.free_dit_set_ln_fold.restype = i32
+    lib.free_dit_set_ln_fold.argtypes = [vp, i32]
+    lib.free_dit_ln_fold_active.restype = i32
+    lib.free_dit_ln_fold_active.argtypes = [vp, i32]
+    lib.free_op_ln_fold_vectors.restype = i32
+    lib.free_op_ln_fold_vectors.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i64, vp]
+    lib.free_op_linear_resid_prep.restype = i32
+    lib.free_op_linear_resid_prep.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp]
+    lib.free_op_linear_ln.restype = i32
+    lib.free_op_linear_ln.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i64, i32, i32, vp, vp]
     lib.free_profile_begin.restype = i32
     lib.free_profile_begin.argtypes = [vp]
     lib.free_profile_end.restype = i32
@@ -331,6 +345,16 @@ class FreeDit:
         """1 or 2: force that schedule of the block stack for every batch size; 0: what tune() measured per
         batch size, one stream where nothing was measured (the initial state)."""
         _check(load().free_dit_set_streams(self.handle, int(n)), "free_dit_set_streams")
+
+    def set_ln_fold(self, mode: int) -> None:
+        """LN_FOLD_OFF / LN_FOLD_AUTO / LN_FOLD_REQUIRE: whether the LayerNorms of the blocks are folded into the
+        GEMMs around them (bf16 only).  REQUIRE on a model the folded path does not cover raises."""
+        _check(load().free_dit_set_ln_fold(self.handle, int(mode)), "free_dit_set_ln_fold")
+
+    def ln_fold_active(self, B: int) -> bool:
+        st = int(load().free_dit_ln_fold_active(self.handle, int(B)))
+        _check(min(st, 0), "free_dit_ln_fold_active")
+        return bool(st)
 
     def stream_choice(self, B: int) -> int:
         """The schedule (1 or 2 streams) a forward on B packed states would use now."""
@@ -590,6 +614,47 @@ def op_attention(qkv, B: int, N: int, heads: int, dh: int, mode: str):
     out = torch.empty(B * N, heads * dh, dtype=qkv.dtype, device=qkv.device)
     _check(load().free_op_attention(_ptr(qkv), B, N, heads, dh, MODES[mode], _ptr(out), _stream()),
            "free_op_attention")
+    return out
+
+
+def op_ln_fold_vectors(mod, hidden: int, ffn: int, w_qkv, b_qkv, w_fc1, b_fc1):
+    """mod [B, >= 6 depth hidden] fp32; w_qkv ...: lists of `depth` device tensors.  Returns fold [B, 2 depth (3 hidden + ffn)]:
+    c1 of all layers, then c0 (free_op_ln_fold_vectors)."""
+    import torch
+    depth = len(w_qkv)
+    B = mod.shape[0]
+    rows = depth * (3 * hidden + ffn)
+    fold = torch.empty(B, 2 * rows, dtype=torch.float32, device=mod.device)
+    arr = lambda ts: (C.c_void_p * depth)(*[t.data_ptr() for t in ts])
+    _check(load().free_op_ln_fold_vectors(_ptr(mod), B, hidden, ffn, mod.stride(0), depth, arr(w_qkv), arr(b_qkv),
+                                          arr(w_fc1), arr(b_fc1), _ptr(fold), fold.stride(0), _stream()),
+           "free_op_ln_fold_vectors")
+    return fold
+
+
+def op_linear_resid_prep(A, W, bias, resid, gate, scale_next, rows_per_sample: int):
+    """resid += gate * (A W^T + bias) in place; returns (z bf16 [M, N], stats fp32 [M, N / 128, 2])."""
+    import torch
+    M, K = A.shape
+    N = W.shape[0]
+    z = torch.empty(M, N, dtype=torch.bfloat16, device=A.device)
+    stats = torch.empty(M, N // LN_SLOT_COLS, 2, dtype=torch.float32, device=A.device)
+    assert gate.stride(0) == scale_next.stride(0)
+    _check(load().free_op_linear_resid_prep(_ptr(A), _ptr(W), _ptr(bias), M, N, K, _ptr(resid), _ptr(gate),
+                                            _ptr(scale_next), gate.stride(0), rows_per_sample, _ptr(z), _ptr(stats),
+                                            _stream()), "free_op_linear_resid_prep")
+    return z, stats
+
+
+def op_linear_ln(z, W, stats, c1, c0, rows_per_sample: int, gelu: bool):
+    """out bf16 [M, N] = act(r (z W^T) - r mu c1 + c0); c1 / c0 [samples, N] views with a common row stride."""
+    import torch
+    M, K = z.shape
+    N = W.shape[0]
+    out = torch.empty(M, N, dtype=torch.bfloat16, device=z.device)
+    assert c1.stride(0) == c0.stride(0)
+    _check(load().free_op_linear_ln(_ptr(z), _ptr(W), M, N, K, _ptr(stats), _ptr(c1), _ptr(c0), c1.stride(0),
+                                    rows_per_sample, int(bool(gelu)), _ptr(out), _stream()), "free_op_linear_ln")
     return out
 
 

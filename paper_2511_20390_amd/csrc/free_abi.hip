@@ -30,6 +30,8 @@ constexpr int kTuneTrials = 16;               // forwards of free_dit_tune, the 
 constexpr int kTuneSkip = 4;                  // ... of which the first ones (clocks and caches settling) are not counted
 constexpr int kTuneSlots = 8;                 // batch sizes a handle remembers a tuned schedule for
 constexpr int64_t kMinSplitRows = 2048;       // token rows per half below which the split does not pay
+// token rows from which the folded-LayerNorm path is taken by default: its GEMMs use the two large tiles only
+constexpr int64_t kMinFoldRows = 4096;
 constexpr size_t kMaxProfSlots = 8192;
 }  // namespace
 
@@ -88,8 +90,11 @@ bool make_dims(const free_dit_config* c, Dims* o) {
 
 // Workspace carve-up for a forward on B packed states (offsets in bytes).
 struct WsLayout {
-    size_t cond_h, sc, mod, tpack, ypack, xres, xn, qkv, att, hmid, eps, mtarget, vpart, vpart_bytes, total;
+    size_t cond_h, sc, mod, tpack, ypack, xres, xn, qkv, att, hmid, eps, mtarget, vpart, vpart_bytes, fold, stats, total;
 };
+
+// floats per sample of the fold vectors: c1 of every block's QKV and MLP-1 rows, then c0 of the same
+int64_t fold_stride(const Dims& d) { return 2 * static_cast<int64_t>(d.depth) * (3 * d.D + d.F); }
 
 WsLayout make_layout(const Dims& d, int32_t B) {
     WsLayout L;
@@ -112,6 +117,9 @@ WsLayout make_layout(const Dims& d, int32_t B) {
     // verification of the round's drafts: K = B without guidance, K = B / 2 with it
     L.vpart_bytes = std::max(verify_workspace_bytes(1, B, d.d), verify_workspace_bytes(1, (B + 1) / 2, d.d));
     L.vpart = take(L.vpart_bytes);
+    // folded LayerNorm (bf16): c1 | c0 of both folded layers of every block per sample, partial row sums per token row
+    L.fold = take(d.mode == FREE_BF16 ? static_cast<size_t>(B) * fold_stride(d) * 4 : 0);
+    L.stats = take(d.mode == FREE_BF16 ? M * ((d.D + kLnSlotCols - 1) / kLnSlotCols) * 2 * 4 : 0);
     L.total = off;
     return L;
 }
@@ -131,6 +139,10 @@ struct free_dit_s {
     const float* const* ada_b_tab = nullptr;
     const int32_t* ada_row_start = nullptr;
     const float* pos = nullptr;
+    // folded LayerNorm: device tables of the 2 * depth weight / bias pointers (block l: QKV, MLP-1)
+    const void* const* fold_w_tab = nullptr;
+    const float* const* fold_b_tab = nullptr;
+    int32_t ln_fold = FREE_LN_FOLD_AUTO;
     int device = 0;
     // two side streams (default priority) on which the halves of a packed batch run concurrently
     hipStream_t side[2] = {nullptr, nullptr};
@@ -153,6 +165,16 @@ struct free_dit_s {
 
     const void* blk(int l, int which) const { return w[7 + 10 * l + which]; }
     const void* fin(int which) const { return w[7 + 10 * dims.depth + which]; }
+    // shapes the folded-LayerNorm path covers, and whether a forward on B samples takes it
+    bool ln_fold_covers() const {
+        const Dims& d = dims;
+        return d.mode == FREE_BF16 && mfma_ln_fold_supported(d.ntok, d.D, d.ntok) && ln_fold_supported(d.D, 3 * d.D, d.F) &&
+               d.D % 64 == 0 && d.F % 64 == 0 && d.depth >= 1;
+    }
+    bool ln_fold_for(int32_t B) const {
+        if (ln_fold == FREE_LN_FOLD_OFF || !ln_fold_covers()) return false;
+        return ln_fold == FREE_LN_FOLD_REQUIRE || static_cast<int64_t>(B) * dims.ntok >= kMinFoldRows;
+    }
 };
 
 struct free_drafter_s {
@@ -177,10 +199,12 @@ enum { B_ADA_W = 0, B_ADA_B, B_QKV_W, B_QKV_B, B_PROJ_W, B_PROJ_B, B_FC1_W, B_FC
 enum { F_ADA_W = 0, F_ADA_B, F_W, F_B };
 
 int32_t linear_dispatch(const Dims& d, const void* A, const void* W, const float* bias, int32_t M, int32_t N,
-                        int32_t K, int32_t epi, void* out, float* resid, RowVec gate, hipStream_t s, int cu_share = 1) {
+                        int32_t K, int32_t epi, void* out, float* resid, RowVec gate, hipStream_t s, int cu_share = 1,
+                        const LnFold* ln = nullptr) {
     if (d.mode == FREE_BF16 && mfma_linear_supported(M, N, K))
         return launch_linear_mfma(static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, M, N, K, epi,
-                                  static_cast<bf16_t*>(out), resid, gate, s, cu_share);
+                                  static_cast<bf16_t*>(out), resid, gate, s, cu_share, ln);
+    if (ln != nullptr) return FREE_ERR_SHAPE;                 // the folded-LayerNorm epilogues exist on that path only
     if (d.mode == FREE_FP32 && mfma_linear_f32_supported(M, N, K))
         return launch_linear_mfma_f32(static_cast<const float*>(A), static_cast<const float*>(W), bias, M, N, K, epi,
                                       static_cast<float*>(out), resid, gate, s, cu_share);
@@ -216,8 +240,18 @@ struct ActBufs {
 // `nblk` adaLN-Zero blocks on samples [b0, b0 + nb) of a batch.  blkw holds 10 pointers per block
 // (B_* order); block l's six modulation vectors of sample b are mod[b * mod_rows + l * 6D ..].
 // cu_share: number of such stacks running side by side on different streams (tile choice of the GEMMs).
+// fold (nullable): the LayerNorms are folded into the GEMMs around them (all but the first one of block 0, whose
+// input no GEMM of this stack produced): fold->vec holds the fold vectors of all samples of the batch, fold->stats the
+// partial row sums of all token rows.
+struct FoldBufs {
+    const float* vec;     // [B, stride]
+    int64_t stride;
+    float* stats;         // [B*ntok, slots, 2]
+    int32_t slots;
+};
 int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const float* mod, int32_t mod_rows,
-                        const ActBufs& a, int b0, int nb, hipStream_t s, Profiler* pf, int cu_share = 1) {
+                        const ActBufs& a, int b0, int nb, hipStream_t s, Profiler* pf, int cu_share = 1,
+                        const FoldBufs* fold = nullptr) {
     const size_t esz = d.mode == FREE_BF16 ? 2 : 4;
     const int32_t M = nb * d.ntok;
     const int64_t r0 = static_cast<int64_t>(b0) * d.ntok;
@@ -236,13 +270,39 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
     };
     auto W = [&](int l, int which) { return blkw[10 * l + which]; };
     auto Bv = [&](int l, int which) { return static_cast<const float*>(blkw[10 * l + which]); };
+    // folded LayerNorm: consumer side (which = 0: QKV, 1: MLP-1) and producer side (scale of the next LayerNorm)
+    const int64_t fold_rows = static_cast<int64_t>(nblk) * (3 * d.D + d.F);
+    auto consumer = [&](int l, int which) {
+        LnFold f;
+        f.stats = fold->stats + r0 * fold->slots * 2;
+        f.slots = fold->slots;
+        f.c1 = fold->vec + static_cast<int64_t>(b0) * fold->stride + static_cast<int64_t>(l) * (3 * d.D + d.F) + (which ? 3 * d.D : 0);
+        f.c0 = f.c1 + fold_rows;
+        f.fold_stride = fold->stride;
+        f.rows_per_sample = d.ntok;
+        f.inv_width = 1.0f / static_cast<float>(d.D);
+        return f;
+    };
+    auto producer = [&](const RowVec& scale_next) {
+        LnFold f;
+        f.scale_next = scale_next.base;
+        f.z = xn_h;
+        f.stats = fold->stats + r0 * fold->slots * 2;
+        f.slots = fold->slots;
+        return f;
+    };
     for (int l = 0; l < nblk; ++l) {
         // x += gate1 * Proj(Attn(LN(x)(1+scale1)+shift1))
-        {
-            ProfScope prof(pf, PROF_LN_MOD, s);
-            FREE_TRY(launch_ln_modulate(xres_h, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn_h, s));
-        }
-        {
+        if (fold && l > 0) {
+            ProfScope prof(pf, PROF_GEMM_QKV, s);
+            const LnFold f = consumer(l, 0);
+            FREE_TRY(linear_dispatch(d, xn_h, W(l, B_QKV_W), Bv(l, B_QKV_B), M, 3 * d.D, d.D, FREE_EPI_LN_BIAS, qkv_h,
+                                     nullptr, RowVec{nullptr, 0, 1}, s, cu_share, &f));
+        } else {
+            {
+                ProfScope prof(pf, PROF_LN_MOD, s);
+                FREE_TRY(launch_ln_modulate(xres_h, vec(l, 0), vec(l, 1), M, d.D, d.mode, xn_h, s));
+            }
             ProfScope prof(pf, PROF_GEMM_QKV, s);
             FREE_TRY(linear_dispatch(d, xn_h, W(l, B_QKV_W), Bv(l, B_QKV_B), M, 3 * d.D, d.D, FREE_EPI_BIAS, qkv_h,
                                      nullptr, RowVec{nullptr, 0, 1}, s, cu_share));
@@ -251,22 +311,39 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
             ProfScope prof(pf, PROF_ATTN, s);
             FREE_TRY(attention_dispatch(d, qkv_h, nb, att_h, s));
         }
-        {
+        if (fold) {
+            // the out-projection also prepares the second LayerNorm: z = x (1 + scale2), partial row sums
+            ProfScope prof(pf, PROF_GEMM_PROJ, s);
+            const LnFold f = producer(vec(l, 4));
+            FREE_TRY(linear_dispatch(d, att_h, W(l, B_PROJ_W), Bv(l, B_PROJ_B), M, d.D, d.D, FREE_EPI_GATE_RESID_PREP,
+                                     nullptr, xres_h, vec(l, 2), s, cu_share, &f));
+        } else {
             ProfScope prof(pf, PROF_GEMM_PROJ, s);
             FREE_TRY(linear_dispatch(d, att_h, W(l, B_PROJ_W), Bv(l, B_PROJ_B), M, d.D, d.D, FREE_EPI_GATE_RESID,
                                      nullptr, xres_h, vec(l, 2), s, cu_share));
         }
         // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
-        {
-            ProfScope prof(pf, PROF_LN_MOD, s);
-            FREE_TRY(launch_ln_modulate(xres_h, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn_h, s));
-        }
-        {
+        if (fold) {
+            ProfScope prof(pf, PROF_GEMM_FC1, s);
+            const LnFold f = consumer(l, 1);
+            FREE_TRY(linear_dispatch(d, xn_h, W(l, B_FC1_W), Bv(l, B_FC1_B), M, d.F, d.D, FREE_EPI_LN_BIAS_GELU, hmid_h,
+                                     nullptr, RowVec{nullptr, 0, 1}, s, cu_share, &f));
+        } else {
+            {
+                ProfScope prof(pf, PROF_LN_MOD, s);
+                FREE_TRY(launch_ln_modulate(xres_h, vec(l, 3), vec(l, 4), M, d.D, d.mode, xn_h, s));
+            }
             ProfScope prof(pf, PROF_GEMM_FC1, s);
             FREE_TRY(linear_dispatch(d, xn_h, W(l, B_FC1_W), Bv(l, B_FC1_B), M, d.F, d.D, FREE_EPI_BIAS_GELU, hmid_h,
                                      nullptr, RowVec{nullptr, 0, 1}, s, cu_share));
         }
-        {
+        if (fold && l + 1 < nblk) {
+            // the MLP's second layer prepares the first LayerNorm of the next block
+            ProfScope prof(pf, PROF_GEMM_FC2, s);
+            const LnFold f = producer(vec(l + 1, 1));
+            FREE_TRY(linear_dispatch(d, hmid_h, W(l, B_FC2_W), Bv(l, B_FC2_B), M, d.D, d.F, FREE_EPI_GATE_RESID_PREP,
+                                     nullptr, xres_h, vec(l, 5), s, cu_share, &f));
+        } else {
             ProfScope prof(pf, PROF_GEMM_FC2, s);
             FREE_TRY(linear_dispatch(d, hmid_h, W(l, B_FC2_W), Bv(l, B_FC2_B), M, d.D, d.F, FREE_EPI_GATE_RESID,
                                      nullptr, xres_h, vec(l, 5), s, cu_share));
@@ -305,6 +382,15 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
         FREE_TRY(launch_adaln(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1, d.mod_rows,
                               d.mode, mod, s));
     }
+    const bool folded = h->ln_fold_for(B);
+    if (h->ln_fold == FREE_LN_FOLD_REQUIRE && !folded) return FREE_ERR_SHAPE;
+    FoldBufs fb{reinterpret_cast<const float*>(ws + L.fold), fold_stride(d), reinterpret_cast<float*>(ws + L.stats),
+                d.D / kLnSlotCols};
+    if (folded) {
+        ProfScope prof(&h->prof, PROF_ADALN, s);
+        FREE_TRY(launch_ln_fold(mod, B, d.D, d.mod_rows, d.depth, 3 * d.D, d.F, h->fold_w_tab, h->fold_b_tab,
+                                reinterpret_cast<float*>(ws + L.fold), fb.stride, s));
+    }
     {
     ProfScope prof(&h->prof, PROF_PATCH, s);
     FREE_TRY(launch_patch_embed(x, x_mod, B, d.C, d.H, d.W, d.p, d.D, static_cast<const float*>(h->w[W_PATCH_W]),
@@ -313,7 +399,8 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     const ActBufs act{xres, xn, qkv, att, hmid};
     const void* const* blkw = h->w.data() + 7;
     auto run_blocks = [&](int b0, int nb, hipStream_t st, int cu_share) -> int32_t {
-        return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st, &h->prof, cu_share);
+        return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st, &h->prof, cu_share,
+                               folded ? &fb : nullptr);
     };
     // The samples of a packed batch are independent through all blocks, so the batch can be cut in two
     // halves that run on two streams forked from (and joined back into) the caller's stream: while
@@ -381,6 +468,20 @@ int32_t free_dit_set_streams(free_dit_t h, int32_t n) {
     if (n < 0 || n > 2) return FREE_ERR_RANGE;
     h->forced_streams = n;
     return FREE_OK;
+}
+
+int32_t free_dit_set_ln_fold(free_dit_t h, int32_t mode) {
+    if (!h) return FREE_ERR_NULL;
+    if (mode != FREE_LN_FOLD_OFF && mode != FREE_LN_FOLD_AUTO && mode != FREE_LN_FOLD_REQUIRE) return FREE_ERR_RANGE;
+    if (mode == FREE_LN_FOLD_REQUIRE && !h->ln_fold_covers()) return FREE_ERR_SHAPE;
+    h->ln_fold = mode;
+    return FREE_OK;
+}
+
+int32_t free_dit_ln_fold_active(free_dit_t h, int32_t B) {
+    if (!h) return FREE_ERR_NULL;
+    if (B < 1) return FREE_ERR_SHAPE;
+    return h->ln_fold_for(B) ? 1 : 0;
 }
 
 int32_t free_dit_stream_choice(free_dit_t h, int32_t B) {
@@ -495,13 +596,16 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
     h->w.assign(weight_ptrs, weight_ptrs + n_ptrs);
     if (!hip_ok(hipGetDevice(&h->device))) { delete h; return FREE_ERR_HIP; }
 
-    // device block: [w_tab (depth+1 ptrs) | b_tab (depth+1 ptrs) | row_start (depth+2 ints) | pos (ntok*D floats)]
+    // device block: [w_tab (depth+1 ptrs) | b_tab (depth+1 ptrs) | row_start (depth+2 ints) | pos (ntok*D floats) |
+    //                fold_w_tab (2 depth ptrs) | fold_b_tab (2 depth ptrs)]
     const int n_mats = d.depth + 1;
     const size_t off_w = 0;
     const size_t off_b = align_up(off_w + n_mats * sizeof(void*));
     const size_t off_r = align_up(off_b + n_mats * sizeof(void*));
     const size_t off_p = align_up(off_r + (n_mats + 1) * sizeof(int32_t));
-    const size_t total = off_p + static_cast<size_t>(d.ntok) * d.D * sizeof(float);
+    const size_t off_fw = align_up(off_p + static_cast<size_t>(d.ntok) * d.D * sizeof(float));
+    const size_t off_fb = align_up(off_fw + 2 * d.depth * sizeof(void*));
+    const size_t total = off_fb + 2 * d.depth * sizeof(void*);
     std::vector<char> host(total, 0);
     const void** wt = reinterpret_cast<const void**>(host.data() + off_w);
     const void** bt = reinterpret_cast<const void**>(host.data() + off_b);
@@ -510,6 +614,14 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
         wt[l] = h->blk(l, B_ADA_W);
         bt[l] = h->blk(l, B_ADA_B);
         rs[l] = l * 6 * d.D;
+    }
+    const void** fwt = reinterpret_cast<const void**>(host.data() + off_fw);
+    const void** fbt = reinterpret_cast<const void**>(host.data() + off_fb);
+    for (int l = 0; l < d.depth; ++l) {
+        fwt[2 * l] = h->blk(l, B_QKV_W);
+        fbt[2 * l] = h->blk(l, B_QKV_B);
+        fwt[2 * l + 1] = h->blk(l, B_FC1_W);
+        fbt[2 * l + 1] = h->blk(l, B_FC1_B);
     }
     wt[d.depth] = h->fin(F_ADA_W);
     bt[d.depth] = h->fin(F_ADA_B);
@@ -540,6 +652,8 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
     h->ada_b_tab = reinterpret_cast<const float* const*>(db + off_b);
     h->ada_row_start = reinterpret_cast<const int32_t*>(db + off_r);
     h->pos = reinterpret_cast<const float*>(db + off_p);
+    h->fold_w_tab = reinterpret_cast<const void* const*>(db + off_fw);
+    h->fold_b_tab = reinterpret_cast<const float* const*>(db + off_fb);
     bool ok = hip_ok(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
     for (int i = 0; i < 2 && ok; ++i)
         ok = hip_ok(hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking)) &&
@@ -762,6 +876,73 @@ int32_t free_op_linear(const void* A, const void* W, const float* bias, int32_t 
     d.mode = dtype;
     RowVec g{gate, gate_stride, rows_per_sample > 0 ? rows_per_sample : 1};
     return linear_dispatch(d, A, W, bias, M, N, Kdim, epilogue, out, resid, g, static_cast<hipStream_t>(stream));
+}
+
+int32_t free_op_ln_fold_vectors(const float* mod, int32_t B, int32_t hidden, int32_t ffn, int32_t mod_stride,
+                                int32_t depth, const void* const* w_qkv, const float* const* b_qkv,
+                                const void* const* w_fc1, const float* const* b_fc1, float* fold,
+                                int64_t fold_stride, void* stream) {
+    if (!mod || !w_qkv || !b_qkv || !w_fc1 || !b_fc1 || !fold) return FREE_ERR_NULL;
+    if (B < 1 || hidden < 1 || ffn < 1 || depth < 1 || depth > 4096 || mod_stride < 6 * depth * hidden) return FREE_ERR_SHAPE;
+    if (!ln_fold_supported(hidden, 3 * hidden, ffn)) return FREE_ERR_SHAPE;
+    std::vector<const void*> tab(4 * static_cast<size_t>(depth));
+    for (int l = 0; l < depth; ++l) {
+        if (!w_qkv[l] || !b_qkv[l] || !w_fc1[l] || !b_fc1[l]) return FREE_ERR_NULL;
+        tab[2 * l] = w_qkv[l];
+        tab[2 * l + 1] = w_fc1[l];
+        tab[2 * depth + 2 * l] = b_qkv[l];
+        tab[2 * depth + 2 * l + 1] = b_fc1[l];
+    }
+    void* dev = nullptr;
+    if (!hip_ok(hipMalloc(&dev, tab.size() * sizeof(void*)))) return FREE_ERR_HIP;
+    int32_t st = FREE_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!hip_ok(hipMemcpy(dev, tab.data(), tab.size() * sizeof(void*), hipMemcpyHostToDevice))) st = FREE_ERR_HIP;
+    if (st == FREE_OK)
+        st = launch_ln_fold(mod, B, hidden, mod_stride, depth, 3 * hidden, ffn, static_cast<const void* const*>(dev),
+                            reinterpret_cast<const float* const*>(static_cast<const void* const*>(dev) + 2 * depth), fold,
+                            fold_stride, s);
+    if (!hip_ok(hipStreamSynchronize(s)) && st == FREE_OK) st = FREE_ERR_HIP;
+    if (!hip_ok(hipFree(dev)) && st == FREE_OK) st = FREE_ERR_HIP;
+    return st;
+}
+
+int32_t free_op_linear_resid_prep(const void* A, const void* W, const float* bias, int32_t M, int32_t N,
+                                  int32_t Kdim, float* resid, const float* gate, const float* scale_next,
+                                  int32_t mod_stride, int32_t rows_per_sample, void* z, float* stats,
+                                  void* stream) {
+    if (!A || !W || !bias || !resid || !gate || !scale_next || !z || !stats) return FREE_ERR_NULL;
+    if (M < 1 || N < 1 || Kdim < 1 || rows_per_sample < 1 || N % kLnSlotCols != 0) return FREE_ERR_SHAPE;
+    Dims d{};
+    d.mode = FREE_BF16;
+    LnFold f;
+    f.scale_next = scale_next;
+    f.z = z;
+    f.stats = stats;
+    f.slots = N / kLnSlotCols;
+    return linear_dispatch(d, A, W, bias, M, N, Kdim, FREE_EPI_GATE_RESID_PREP, nullptr, resid,
+                           RowVec{gate, mod_stride, rows_per_sample}, static_cast<hipStream_t>(stream), 1, &f);
+}
+
+int32_t free_op_linear_ln(const void* z, const void* W, int32_t M, int32_t N, int32_t Kdim, const float* stats,
+                          const float* c1, const float* c0, int64_t fold_stride, int32_t rows_per_sample,
+                          int32_t gelu, void* out, void* stream) {
+    if (!z || !W || !stats || !c1 || !c0 || !out) return FREE_ERR_NULL;
+    if (M < 1 || N < 1 || Kdim < 1 || Kdim % kLnSlotCols != 0) return FREE_ERR_SHAPE;
+    if (!mfma_ln_fold_supported(M, Kdim, rows_per_sample)) return FREE_ERR_SHAPE;
+    Dims d{};
+    d.mode = FREE_BF16;
+    LnFold f;
+    f.stats = const_cast<float*>(stats);
+    f.slots = Kdim / kLnSlotCols;
+    f.c1 = c1;
+    f.c0 = c0;
+    f.fold_stride = fold_stride;
+    f.rows_per_sample = rows_per_sample;
+    f.inv_width = 1.0f / static_cast<float>(Kdim);
+    // (the bias is inside c0; the kernel still wants a valid, aligned pointer for the argument)
+    return linear_dispatch(d, z, W, c0, M, N, Kdim, gelu ? FREE_EPI_LN_BIAS_GELU : FREE_EPI_LN_BIAS, out, nullptr,
+                           RowVec{nullptr, 0, 1}, static_cast<hipStream_t>(stream), 1, &f);
 }
 
 int32_t free_op_attention(const void* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh, int32_t dtype,

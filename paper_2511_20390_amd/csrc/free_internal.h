@@ -68,6 +68,32 @@ struct RowVec {
     int32_t rows_per_sample;
 };
 
+// LayerNorm + modulate folded into the GEMMs on both sides of it (bf16 matrix-core path only).
+// With z = x (1 + scale) rounded to bf16, row mean mu and r = 1 / sqrt(var + eps):
+//   (LN(x) (1 + scale) + shift) W^T + b = r (z W^T) - r mu c1 + c0,
+//   c1[n] = sum_k (1 + scale[k]) W[n, k],  c0[n] = sum_k shift[k] W[n, k] + b[n]   (per sample).
+// The GEMM that updates the residual stream (producer, FREE_EPI_GATE_RESID_PREP) also writes z for the
+// next LayerNorm and, per row and per 128-column slot, the sums of x and x^2; the GEMM that consumes the
+// normalised rows (FREE_EPI_LN_BIAS / FREE_EPI_LN_BIAS_GELU) multiplies z and applies r, mu, c1, c0 in
+// its epilogue.  No separate pass over the residual stream, no atomics: every partial sum has one writer
+// and the consumer adds the slots of a row in a fixed order.
+constexpr int FREE_EPI_LN_BIAS = 3, FREE_EPI_LN_BIAS_GELU = 4, FREE_EPI_GATE_RESID_PREP = 5;
+constexpr int kLnSlotCols = 128;           // columns of the residual stream per partial-sum slot
+struct LnFold {
+    // producer: scale vector of the NEXT LayerNorm (indexed like the gate: same stride and rows per sample),
+    // z [M, N] bf16 and stats [M, slots, 2] fp32 are outputs.  consumer: stats is an input.
+    const float* scale_next = nullptr;
+    void* z = nullptr;
+    float* stats = nullptr;
+    int32_t slots = 0;                     // width of the normalised rows / kLnSlotCols
+    // consumer: c1 / c0 of sample s start at c1[s * fold_stride] (N entries each, 16-byte aligned)
+    const float* c1 = nullptr;
+    const float* c0 = nullptr;
+    int64_t fold_stride = 0;
+    int32_t rows_per_sample = 1;
+    float inv_width = 0.f;                 // 1 / width of the normalised rows
+};
+
 // Thread-local HIP error memo (free_last_hip_error).
 void note_hip_error(hipError_t e);
 inline bool hip_ok(hipError_t e) {
@@ -173,12 +199,20 @@ int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* con
 // ---- MFMA kernels, bf16 only (gemm_mfma.hip, attn_mfma.hip) ------------------------
 bool mfma_linear_supported(int32_t M, int32_t N, int32_t K);
 int32_t launch_linear_mfma(const bf16_t* A, const bf16_t* W, const float* bias, int32_t M, int32_t N,
-                           int32_t K, int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s, int cu_share = 1);
+                           int32_t K, int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s, int cu_share = 1,
+                           const LnFold* ln = nullptr);
+// shapes the folded-LayerNorm epilogues cover: M rows of width D normalised, rows_per_sample tokens per sample
+bool mfma_ln_fold_supported(int32_t M, int32_t D, int32_t rows_per_sample);
 // the same kernel on fp32 operands (v_mfma_f32_32x32x2_f32), fp32 output
 bool mfma_linear_f32_supported(int32_t M, int32_t N, int32_t K);
 int32_t launch_linear_mfma_f32(const float* A, const float* W, const float* bias, int32_t M, int32_t N,
                                int32_t K, int32_t epi, float* out, float* resid, RowVec gate, hipStream_t s,
                                int cu_share = 1);
+// fold vectors of all blocks in one launch (lnfold_mfma.hip); see LnFold
+bool ln_fold_supported(int32_t D, int32_t rows_qkv, int32_t rows_fc1);
+int32_t launch_ln_fold(const float* mod, int32_t B, int32_t D, int32_t mod_stride, int32_t depth, int32_t rows_qkv,
+                       int32_t rows_fc1, const void* const* w_tab, const float* const* b_tab, float* fold,
+                       int64_t fold_stride, hipStream_t s);
 bool mfma_attention_supported(int32_t N, int32_t dh);
 int32_t launch_attention_mfma(const bf16_t* qkv, int32_t B, int32_t N, int32_t heads, int32_t dh,
                               bf16_t* out, hipStream_t s);

@@ -122,17 +122,29 @@ __device__ inline void tile_coords(int kGroupM, int pid, int tiles_m, int tiles_
 // m = gm_lane + 32 i (gm_lane already includes l % 32), column n = gn_wave + 32 j + 8 (e/4) + 4 lhi + e%4.
 // QB: for the residual update, chunks per lane whose loads are in flight together in the LDS-staged form; 0
 // selects the direct form.
+// Folded LayerNorm (see LnFold): kPrep - the residual update also writes z and the partial row sums;
+// kLn - the output is r acc - r mu c1 + c0 with the per-row factors ln_a = r, ln_b = -r mu of this lane's
+// rows and c1 / c0 staged in LDS at fold_lds (per 32-row block i: vectors of sample index ln_si[i], c1 then
+// c0, BN floats each, first column of the tile = fold_col0 columns before this wavefront's first).
 template <typename OT, int TM, int TN, int EPI, int QB>
 __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm_lane, int gn_wave, int lane, int32_t M,
                                            int32_t N, int32_t vec_ok, const float* __restrict__ bias,
                                            OT* __restrict__ out, float* __restrict__ resid, const RowVec& gate,
-                                           char* wave_lds) {
+                                           char* wave_lds, const LnFold& ln, const float (&ln_a)[TM],
+                                           const float (&ln_b)[TM], const int (&ln_si)[TM], const char* fold_lds,
+                                           int fold_col0, int fold_bn) {
     constexpr bool kF32Out = std::is_same<OT, float>::value;   // fp32 mode: the output of the bias / GELU epilogues is fp32
+    constexpr bool kPrep = EPI == FREE_EPI_GATE_RESID_PREP;
+    constexpr bool kResid = EPI == FREE_EPI_GATE_RESID || kPrep;
+    constexpr bool kLn = EPI == FREE_EPI_LN_BIAS || EPI == FREE_EPI_LN_BIAS_GELU;
+    constexpr bool kGelu = EPI == FREE_EPI_BIAS_GELU || EPI == FREE_EPI_LN_BIAS_GELU;
+    static_assert(!kPrep || (QB > 0 && TN == 4), "z and the row sums come out of the staged residual update of a 128-column wavefront");
+    static_assert(!kLn || !kF32Out, "folded LayerNorm: bf16 path only");
     const int lhi = lane >> 5;
     if (vec_ok) {
         // N % 8 == 0 and 16-byte aligned rows: runs of 4 / 8 columns are all inside or all outside.
         // Rows past M and runs past N (ragged edge tiles) are masked per lane.
-        if constexpr (kF32Out && EPI != FREE_EPI_GATE_RESID && QB == 0) {
+        if constexpr (kF32Out && !kResid && QB == 0) {
             // fp32 output straight from the accumulator layout (four-wavefront configurations)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
@@ -149,7 +161,7 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
                             o[c] = acc[i][j][4 * e4 + c] + bv[c];
-                            if (EPI == FREE_EPI_BIAS_GELU) o[c] = gelu_fast(o[c]);
+                            if (kGelu) o[c] = gelu_fast(o[c]);
                         }
                         *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(out) + static_cast<int64_t>(gm) * N + gn0 + 8 * e4) = o;
                     }
@@ -196,7 +208,7 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                             *reinterpret_cast<f32x4_t*>(resid + r_off[i] + gn0 + 8 * e4) = r[i][e4];
                         }
             }
-        } else if constexpr (EPI == FREE_EPI_GATE_RESID || kF32Out) {
+        } else if constexpr (kResid || kF32Out) {
             // read-modify-write of the fp32 residual stream (or, in fp32 mode, the plain fp32 output of the
             // bias / GELU epilogues: same staging, no read).  As for the bf16 output below, the accumulator
             // layout would touch 32 rows x 32 bytes per instruction; each 32-row block is staged in the
@@ -214,6 +226,13 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                 // one sample for the whole block (the usual case: rows per sample a multiple of 32)?
                 const int s_first = gm_blk / gate.rows_per_sample;
                 const bool one_sample = (gm_blk + 31) / gate.rows_per_sample == s_first;
+                // kPrep: sums of x and x^2 over this wavefront's 128 columns, for the rows 4 q + lane / 16 of the block
+                // (ps[2 q], ps[2 q + 1]); this lane adds the four columns of its chunk in each staged group
+                [[maybe_unused]] float ps[2 * NQ];
+                if constexpr (kPrep) {
+#pragma unroll
+                    for (int k = 0; k < 2 * NQ; ++k) ps[k] = 0.f;
+                }
 #pragma unroll
                 for (int jg = 0; jg < TN; jg += CG) {
 #pragma unroll
@@ -232,6 +251,7 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
 #pragma unroll
                     for (int q0 = 0; q0 < NQ; q0 += QN) {
                         f32x4_t r[QN], g[QN], bv[QN];
+                        [[maybe_unused]] f32x4_t sn[QN];
                         int64_t off[QN];
                         bool ok[QN];
 #pragma unroll
@@ -242,10 +262,12 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                             ok[q] = gm < M && gn < N;
                             off[q] = static_cast<int64_t>(gm) * N + gn;
                             if (ok[q]) {
-                                if constexpr (EPI == FREE_EPI_GATE_RESID) {
+                                if constexpr (kResid) {
                                     const int smp = one_sample ? s_first : gm / gate.rows_per_sample;
                                     r[q] = *reinterpret_cast<const f32x4_t*>(resid + off[q]);
                                     g[q] = *reinterpret_cast<const f32x4_t*>(gbase + static_cast<int64_t>(smp) * gate.stride + gn);
+                                    if constexpr (kPrep)
+                                        sn[q] = *reinterpret_cast<const f32x4_t*>(ln.scale_next + static_cast<int64_t>(smp) * gate.stride + gn);
                                 }
                                 bv[q] = *reinterpret_cast<const f32x4_t*>(bias + gn);
                             }
@@ -255,20 +277,57 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                             if (ok[q]) {
                                 const int f = (q0 + q) * 64 + lane;
                                 const f32x4_t v = *reinterpret_cast<const f32x4_t*>(wave_lds + (f / CH) * kStageRow + ((f % CH) << 4));
-                                if constexpr (EPI == FREE_EPI_GATE_RESID) {
+                                if constexpr (kResid) {
 #pragma unroll
                                     for (int c = 0; c < 4; ++c) r[q][c] = fmaf(g[q][c], v[c] + bv[q][c], r[q][c]);
                                     *reinterpret_cast<f32x4_t*>(resid + off[q]) = r[q];
+                                    if constexpr (kPrep) {
+                                        const u32x2_t zz = {pack2(r[q][0] * (1.0f + sn[q][0]), r[q][1] * (1.0f + sn[q][1])),
+                                                            pack2(r[q][2] * (1.0f + sn[q][2]), r[q][3] * (1.0f + sn[q][3]))};
+                                        *reinterpret_cast<u32x2_t*>(static_cast<bf16_t*>(ln.z) + off[q]) = zz;
+                                        ps[2 * (q0 + q)] += (r[q][0] + r[q][1]) + (r[q][2] + r[q][3]);
+                                        ps[2 * (q0 + q) + 1] += (r[q][0] * r[q][0] + r[q][1] * r[q][1]) +
+                                                                (r[q][2] * r[q][2] + r[q][3] * r[q][3]);
+                                    }
                                 } else {
 #pragma unroll
                                     for (int c = 0; c < 4; ++c) {
                                         r[q][c] = v[c] + bv[q][c];
-                                        if (EPI == FREE_EPI_BIAS_GELU) r[q][c] = gelu_fast(r[q][c]);
+                                        if (kGelu) r[q][c] = gelu_fast(r[q][c]);
                                     }
                                     *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(out) + off[q]) = r[q];
                                 }
                             }
                     }
+                }
+                if constexpr (kPrep) {
+                    // The 16 lanes that share lane / 16 hold partial sums ps[k] of the same rows 4 q + lane / 16
+                    // (k = 2 q + 0 / 1): a halving exchange (each step a lane keeps the half of its
+                    // values whose index bit matches its lane bit and adds the partner's) leaves sum k in the
+                    // lane with lane % 16 == k.  Fixed order: the result does not depend on timing.
+                    float w8[8], w4[4], w2[2];
+                    const bool b3 = lane & 8, b2 = lane & 4, b1 = lane & 2, b0 = lane & 1;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const float keep = b3 ? ps[8 + k] : ps[k], give = b3 ? ps[k] : ps[8 + k];
+                        w8[k] = keep + __shfl_xor(give, 8, 64);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float keep = b2 ? w8[4 + k] : w8[k], give = b2 ? w8[k] : w8[4 + k];
+                        w4[k] = keep + __shfl_xor(give, 4, 64);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        const float keep = b1 ? w4[2 + k] : w4[k], give = b1 ? w4[k] : w4[2 + k];
+                        w2[k] = keep + __shfl_xor(give, 2, 64);
+                    }
+                    const float keep = b0 ? w2[1] : w2[0], give = b0 ? w2[0] : w2[1];
+                    const float total = keep + __shfl_xor(give, 1, 64);
+                    const int k = lane & 15;                       // = 2 q + (0: sum, 1: sum of squares)
+                    const int gm = gm_blk + 4 * (k >> 1) + (lane >> 4);
+                    if (gm < M && gn_wave < N)
+                        ln.stats[(static_cast<int64_t>(gm) * ln.slots + gn_wave / kLnSlotCols) * 2 + (k & 1)] = total;
                 }
             }
         } else {
@@ -280,32 +339,50 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
             constexpr int CH = TN * 4;                         // 16-byte chunks per staged row
             constexpr int kStageRow = (CH + 1) * 16;           // bytes per staged row
             const int l32 = lane & 31;
-            f32x4_t blo[TN][2], bhi[TN][2];
+            [[maybe_unused]] f32x4_t blo[kLn ? 1 : TN][2], bhi[kLn ? 1 : TN][2];
+            if constexpr (!kLn) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int e8 = 0; e8 < 2; ++e8) {
-                    // this lane's two runs: n = nb + 4 lhi + {0..3} (lo) and nb + 8 + 4 lhi + {0..3} (hi);
-                    // nb is a multiple of 16 and N of 8, so nb < N covers the lo run and nb + 8 < N the hi run
-                    const int nb = gn_wave + j * 32 + 16 * e8;
-                    blo[j][e8] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                    bhi[j][e8] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                    if (nb < N) blo[j][e8] = *reinterpret_cast<const f32x4_t*>(bias + nb + 4 * lhi);
-                    if (nb + 8 < N) bhi[j][e8] = *reinterpret_cast<const f32x4_t*>(bias + nb + 8 + 4 * lhi);
-                }
+                    for (int e8 = 0; e8 < 2; ++e8) {
+                        // this lane's two runs: n = nb + 4 lhi + {0..3} (lo) and nb + 8 + 4 lhi + {0..3} (hi);
+                        // nb is a multiple of 16 and N of 8, so nb < N covers the lo run and nb + 8 < N the hi run
+                        const int nb = gn_wave + j * 32 + 16 * e8;
+                        blo[j][e8] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        bhi[j][e8] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        if (nb < N) blo[j][e8] = *reinterpret_cast<const f32x4_t*>(bias + nb + 4 * lhi);
+                        if (nb + 8 < N) bhi[j][e8] = *reinterpret_cast<const f32x4_t*>(bias + nb + 8 + 4 * lhi);
+                    }
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
+                // folded LayerNorm: c1 / c0 of this block's sample, staged in LDS (columns beyond N hold zeros)
+                [[maybe_unused]] const char* c1p = fold_lds + (static_cast<size_t>(ln_si[i]) * 2 * fold_bn + fold_col0 + 4 * lhi) * 4;
+                [[maybe_unused]] const char* c0p = c1p + static_cast<size_t>(fold_bn) * 4;
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int e8 = 0; e8 < 2; ++e8) {
                         float v[8];
+                        if constexpr (kLn) {
+                            const int cb = (j * 32 + 16 * e8) * 4;
+                            const f32x4_t c1l = *reinterpret_cast<const f32x4_t*>(c1p + cb);
+                            const f32x4_t c1h = *reinterpret_cast<const f32x4_t*>(c1p + cb + 32);
+                            const f32x4_t c0l = *reinterpret_cast<const f32x4_t*>(c0p + cb);
+                            const f32x4_t c0h = *reinterpret_cast<const f32x4_t*>(c0p + cb + 32);
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            v[c] = acc[i][j][8 * e8 + c] + blo[j][e8][c];
-                            v[4 + c] = acc[i][j][8 * e8 + 4 + c] + bhi[j][e8][c];
+                            for (int c = 0; c < 4; ++c) {
+                                v[c] = fmaf(ln_a[i], acc[i][j][8 * e8 + c], fmaf(ln_b[i], c1l[c], c0l[c]));
+                                v[4 + c] = fmaf(ln_a[i], acc[i][j][8 * e8 + 4 + c], fmaf(ln_b[i], c1h[c], c0h[c]));
+                            }
+                        } else {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                v[c] = acc[i][j][8 * e8 + c] + blo[j][e8][c];
+                                v[4 + c] = acc[i][j][8 * e8 + 4 + c] + bhi[j][e8][c];
+                            }
                         }
-                        if (EPI == FREE_EPI_BIAS_GELU) {
+                        if (kGelu) {
 #pragma unroll
                             for (int c = 0; c < 8; ++c) v[c] = gelu_fast(v[c]);
                         }
@@ -334,7 +411,9 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
         }
         return;
     }
-    // unaligned output: element-wise with bounds checks
+    // unaligned output: element-wise with bounds checks (the folded-LayerNorm epilogues are launched on
+    // aligned shapes only)
+    if constexpr (kLn || kPrep) return;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -366,7 +445,7 @@ template <typename T, int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     const T* __restrict__ X, const T* __restrict__ W, const float* __restrict__ bias, int32_t M,
     int32_t N, int32_t K, int32_t tiles_m, int32_t tiles_n, int32_t group_m, int32_t vec_ok,
-    T* __restrict__ out, float* __restrict__ resid, RowVec gate) {
+    T* __restrict__ out, float* __restrict__ resid, RowVec gate, LnFold ln) {
     static_assert(WGM * WGN == 4 || WGM * WGN == 8, "four or eight wavefronts per workgroup");
     constexpr bool kF32 = std::is_same<T, float>::value;
     constexpr int ES = static_cast<int>(sizeof(T));    // bytes per element
@@ -533,12 +612,57 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     // ---- epilogue
     // after the barrier of the last slice no wavefront reads the LDS tiles any more: each wavefront
     // may use a private region of them to transpose its output
-    constexpr int kWaveStage = (EPI == FREE_EPI_GATE_RESID || kF32) ? 32 * (((TN % 2 == 0 ? 2 : 1) * 8 + 1) * 16)   // fp32 groups
-                                                                    : 32 * (TN * 64 + 16);                            // bf16 rows
-    static_assert(WGM * WGN * kWaveStage <= 2 * kStageBytes, "output staging must fit in the K-loop tiles");
+    constexpr bool kResidEpi = EPI == FREE_EPI_GATE_RESID || EPI == FREE_EPI_GATE_RESID_PREP;
+    constexpr bool kLnEpi = EPI == FREE_EPI_LN_BIAS || EPI == FREE_EPI_LN_BIAS_GELU;
+    constexpr int kWaveStage = (kResidEpi || kF32) ? 32 * (((TN % 2 == 0 ? 2 : 1) * 8 + 1) * 16)   // fp32 groups
+                                                   : 32 * (TN * 64 + 16);                            // bf16 rows
+    constexpr int kFoldBytes = kLnEpi ? (BM / 32) * 2 * BN * 4 : 0;     // c1 and c0 of up to BM / 32 samples
+    static_assert(WGM * WGN * kWaveStage + kFoldBytes <= 2 * kStageBytes, "output staging must fit in the K-loop tiles");
     constexpr int kResidBatch = (WGM * WGN == 8) ? 4 : 0;
+    float ln_a[TM], ln_b[TM];
+    int ln_si[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) { ln_a[i] = 0.f; ln_b[i] = 0.f; ln_si[i] = 0; }
+    const char* fold_lds = lds + WGM * WGN * kWaveStage;
+    if constexpr (kLnEpi) {
+        // Folded LayerNorm.  (1) The fold vectors c1, c0 of the samples this tile's rows belong to go to LDS
+        // (every 32-row block lies in one sample: rows per sample a multiple of 32); (2) each lane turns the
+        // partial sums of its rows into r = 1 / sqrt(var + eps) and -r mu, adding the slots in index order.
+        const int rps = ln.rows_per_sample;
+        const int s_lo = m0 / rps;
+        const int m_last = (m0 + BM < M ? m0 + BM : M) - 1;
+        const int ns = m_last / rps - s_lo + 1;
+        constexpr int kVec4 = BN / 4;                                  // f32x4 per vector
+        for (int u = tid; u < ns * 2 * kVec4; u += NT) {
+            const int si = u / (2 * kVec4), rem = u % (2 * kVec4);
+            const int n = n0 + (rem % kVec4) * 4;
+            f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+            if (n < N) v = *reinterpret_cast<const f32x4_t*>((rem < kVec4 ? ln.c1 : ln.c0) + static_cast<int64_t>(s_lo + si) * ln.fold_stride + n);
+            *reinterpret_cast<f32x4_t*>(lds + WGM * WGN * kWaveStage + (static_cast<size_t>(si) * 2 * BN + (rem < kVec4 ? 0 : BN) + (rem % kVec4) * 4) * 4) = v;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int gm_blk = m0 + wm * TM * 32 + i * 32;
+            const int gm = gm_blk + l32;
+            ln_si[i] = (gm_blk < M ? gm_blk : M - 1) / rps - s_lo;
+            if (gm < M) {
+                float s1 = 0.f, s2 = 0.f;
+                const float2* st = reinterpret_cast<const float2*>(ln.stats) + static_cast<int64_t>(gm) * ln.slots;
+                for (int k = 0; k < ln.slots; ++k) {
+                    const float2 p = st[k];
+                    s1 += p.x;
+                    s2 += p.y;
+                }
+                const float mean = s1 * ln.inv_width;
+                const float var = fmaxf(s2 * ln.inv_width - mean * mean, 0.f);
+                ln_a[i] = rsqrtf(var + kLnEps);
+                ln_b[i] = -ln_a[i] * mean;
+            }
+        }
+        __syncthreads();
+    }
     write_tile<T, TM, TN, EPI, kResidBatch>(acc, m0 + wm * TM * 32 + l32, n0 + wn * TN * 32, lane, M, N, vec_ok, bias, out, resid, gate,
-                            lds + wave * kWaveStage);
+                            lds + wave * kWaveStage, ln, ln_a, ln_b, ln_si, fold_lds, wn * TN * 32, BN);
 }
 
 int device_cus() {
@@ -554,7 +678,7 @@ int device_cus() {
 
 template <typename T, int BM, int BN, int WGM, int WGN, int EPI, bool EVEN_K>
 int32_t launch_one(const T* X, const T* W, const float* bias, int32_t M, int32_t N, int32_t K, T* out,
-                   float* resid, RowVec gate, hipStream_t s) {
+                   float* resid, RowVec gate, hipStream_t s, const LnFold& ln = LnFold{}) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const size_t lds = 2 * static_cast<size_t>(BM + BN) * kRowBytes;
     auto kern = gemm_bf16_kernel<T, BM, BN, WGM, WGN, EPI, EVEN_K>;
@@ -582,8 +706,10 @@ int32_t launch_one(const T* X, const T* W, const float* bias, int32_t M, int32_t
         const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
         group_m = std::max(1, (per_xcd + tiles_n / 2) / tiles_n);
     }
+    if ((EPI == FREE_EPI_LN_BIAS || EPI == FREE_EPI_LN_BIAS_GELU || EPI == FREE_EPI_GATE_RESID_PREP) && !vec)
+        return FREE_ERR_SHAPE;                                   // the folded-LayerNorm epilogues have no element-wise form
     hipLaunchKernelGGL(kern, dim3(total), dim3(WGM * WGN * 64), lds, s, X, W, bias, M, N, K, tiles_m, tiles_n, group_m,
-                       vec_ok, out, resid, gate);
+                       vec_ok, out, resid, gate, ln);
     return launch_ok() ? FREE_OK : FREE_ERR_HIP;
 }
 
@@ -632,7 +758,7 @@ double small_tile_time(int M, int N, int nk, double sc, int cus) {
 // is cut, never the order in which a dot product is summed, so the result does not depend on it.
 template <typename T>
 int32_t choose_and_launch(const T* X, const T* W, const float* bias, int32_t M, int32_t N, int32_t K, int32_t epi,
-                          T* out, float* resid, RowVec gate, hipStream_t s, int cu_share) {
+                          T* out, float* resid, RowVec gate, hipStream_t s, int cu_share, const LnFold* ln) {
     if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W)) & 15u) return FREE_ERR_SHAPE;
     constexpr int kSliceElems = kRowBytes / static_cast<int>(sizeof(T));
     const double sc = sizeof(T) == 4 ? 4.4 : 1.0;
@@ -640,6 +766,21 @@ int32_t choose_and_launch(const T* X, const T* W, const float* bias, int32_t M, 
     const int cus = std::max(1, device_cus() / std::max(1, cu_share));
     const double t256 = cfg_time(M, N, nk, 256, 256, 1.83 * sc, 9.0, cus);
     const double t384 = cfg_time(M, N, nk, 384, 192, 2.06 * sc, 10.0, cus);
+    if (epi == FREE_EPI_LN_BIAS || epi == FREE_EPI_LN_BIAS_GELU || epi == FREE_EPI_GATE_RESID_PREP) {
+        // folded LayerNorm: the two large eight-wavefront tiles only, K a whole number of slices
+        if constexpr (std::is_same<T, bf16_t>::value) {
+            if (ln == nullptr || K % kSliceElems != 0) return FREE_ERR_SHAPE;
+            if (epi == FREE_EPI_GATE_RESID_PREP)
+                return launch_one<T, 256, 256, 4, 2, FREE_EPI_GATE_RESID_PREP, true>(X, W, bias, M, N, K, out, resid, gate, s, *ln);
+            if (epi == FREE_EPI_LN_BIAS)
+                return t384 < t256 ? launch_one<T, 384, 192, 4, 2, FREE_EPI_LN_BIAS, true>(X, W, bias, M, N, K, out, resid, gate, s, *ln)
+                                   : launch_one<T, 256, 256, 4, 2, FREE_EPI_LN_BIAS, true>(X, W, bias, M, N, K, out, resid, gate, s, *ln);
+            return t384 < t256 ? launch_one<T, 384, 192, 4, 2, FREE_EPI_LN_BIAS_GELU, true>(X, W, bias, M, N, K, out, resid, gate, s, *ln)
+                               : launch_one<T, 256, 256, 4, 2, FREE_EPI_LN_BIAS_GELU, true>(X, W, bias, M, N, K, out, resid, gate, s, *ln);
+        } else {
+            return FREE_ERR_SHAPE;
+        }
+    }
     const double t2x1 = cfg_time(M, N, nk, 256, 128, 1.31 * sc, 6.0, cus);
     const double t128 = M <= 4096 ? small_tile_time(M, N, nk, sc, cus) : cfg_time(M, N, nk, 128, 128, 0.80 * sc, 4.0, cus);
     // 96 x 128 (one row of four wavefronts, each 96 x 32): for problems of few rows and few columns, where
@@ -680,15 +821,35 @@ bool mfma_linear_f32_supported(int32_t M, int32_t N, int32_t K) {
 }
 
 int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, int32_t M, int32_t N, int32_t K,
-                           int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s, int cu_share) {
+                           int32_t epi, bf16_t* out, float* resid, RowVec gate, hipStream_t s, int cu_share,
+                           const LnFold* ln) {
     if (!mfma_linear_supported(M, N, K)) return FREE_ERR_SHAPE;
-    return choose_and_launch<bf16_t>(X, W, bias, M, N, K, epi, out, resid, gate, s, cu_share);
+    if (ln != nullptr) {
+        // producer: the rows being normalised are this GEMM's output rows (width N); consumer: its input rows (width K)
+        const int32_t width = epi == FREE_EPI_GATE_RESID_PREP ? N : K;
+        const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+        if (width % kLnSlotCols != 0 || ln->slots != width / kLnSlotCols || ln->stats == nullptr ||
+            (reinterpret_cast<uintptr_t>(ln->stats) & 7u))
+            return FREE_ERR_SHAPE;
+        if (epi == FREE_EPI_GATE_RESID_PREP) {
+            if (ln->z == nullptr || ln->scale_next == nullptr || !al16(ln->z) || !al16(ln->scale_next)) return FREE_ERR_SHAPE;
+        } else {
+            if (ln->c1 == nullptr || ln->c0 == nullptr || !al16(ln->c1) || !al16(ln->c0) || (ln->fold_stride & 3) ||
+                ln->rows_per_sample < 32 || ln->rows_per_sample % 32 != 0)
+                return FREE_ERR_SHAPE;
+        }
+    }
+    return choose_and_launch<bf16_t>(X, W, bias, M, N, K, epi, out, resid, gate, s, cu_share, ln);
+}
+
+bool mfma_ln_fold_supported(int32_t M, int32_t D, int32_t rows_per_sample) {
+    return M >= 1 && D % kLnSlotCols == 0 && D % 64 == 0 && rows_per_sample >= 32 && rows_per_sample % 32 == 0;
 }
 
 int32_t launch_linear_mfma_f32(const float* X, const float* W, const float* bias, int32_t M, int32_t N, int32_t K,
                                int32_t epi, float* out, float* resid, RowVec gate, hipStream_t s, int cu_share) {
     if (!mfma_linear_f32_supported(M, N, K)) return FREE_ERR_SHAPE;
-    return choose_and_launch<float>(X, W, bias, M, N, K, epi, out, resid, gate, s, cu_share);
+    return choose_and_launch<float>(X, W, bias, M, N, K, epi, out, resid, gate, s, cu_share, nullptr);
 }
 
 }  // namespace freemi

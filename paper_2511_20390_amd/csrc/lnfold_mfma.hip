@@ -1,0 +1,171 @@
+// Fold vectors of the LayerNorms that are folded into the GEMMs around them (bf16 weights), for every
+// block of the packed target forward (Alg. 1) in one launch.  With the modulation of a block's LayerNorm,
+// LN(x) (1 + scale) + shift, followed by the linear layer y = (.) W^T + b:
+//   y = r (z W^T) - r mu c1 + c0,   z = x (1 + scale),
+//   c1[s, n] = sum_k (1 + scale[s, k]) W[n, k],   c0[s, n] = sum_k shift[s, k] W[n, k] + b[n]
+// per packed sample s.  Two such layers per block: QKV (first LayerNorm) and the MLP's first layer (second).
+// HBM-bound like the adaLN modulation: every weight row is read once.  Weight rows are the A operand of
+// v_mfma_f32_16x16x32_bf16, straight from global memory in the operand layout; the packed batch (<= 16 samples
+// per pass) is the N dimension; the two activation vectors of each sample are staged in LDS as a bf16 high part
+// plus a bf16 remainder (two products per vector and k-step), so the fp32 modulation loses no precision.
+#include "free_internal.h"
+
+namespace freemi {
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = 8;                  // per workgroup: they share one staged copy of the activations
+constexpr int kThreads = 64 * kWaves;
+constexpr int kChunk = 6;                  // k-steps (1 KB of weights per wavefront each) per register set
+constexpr int kBatch = 16;
+constexpr int kBlocksPerWave = 3;          // 16-row blocks per wavefront
+constexpr int kSegRows = 16 * kWaves * kBlocksPerWave;      // weight rows per workgroup: 384
+
+// Workgroup -> (block l, layer which, row segment).  mod: [B, mod_stride] adaLN output, block l's vectors at
+// l * 6 D + {0: shift1, 1: scale1, 2: gate1, 3: shift2, 4: scale2, 5: gate2} * D.  w_tab / b_tab: 2 * depth
+// pointers (block l: QKV at 2 l, MLP-1 at 2 l + 1).  fold: [B, fold_stride]: c1 of all layers (block l: QKV rows,
+// then MLP-1 rows), then, total_rows further, c0 in the same order.
+__global__ __launch_bounds__(kThreads) void ln_fold_kernel(
+    const float* __restrict__ mod, int32_t B, int32_t D, int32_t mod_stride, int32_t rows_qkv, int32_t rows_fc1,
+    const void* const* __restrict__ w_tab, const float* const* __restrict__ b_tab, float* __restrict__ fold,
+    int64_t fold_stride, int32_t total_rows) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int row_bytes = D * 2 + 16;                       // odd number of 16-byte chunks per row
+    const int set_bytes = kBatch * row_bytes;
+    char* s1_hi = lds;                                      // 1 + scale
+    char* s1_lo = lds + set_bytes;
+    char* s0_hi = lds + 2 * set_bytes;                      // shift
+    char* s0_lo = lds + 3 * set_bytes;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    const int segs_qkv = (rows_qkv + kSegRows - 1) / kSegRows, segs_fc1 = (rows_fc1 + kSegRows - 1) / kSegRows;
+    const int per_block = segs_qkv + segs_fc1;
+    const int l = blockIdx.x / per_block, sidx = blockIdx.x % per_block;
+    const int which = sidx < segs_qkv ? 0 : 1;
+    const int seg = which ? sidx - segs_qkv : sidx;
+    const int rows = which ? rows_fc1 : rows_qkv;
+    const int out_row0 = l * (rows_qkv + rows_fc1) + (which ? rows_qkv : 0);     // first output row of this layer
+    const float* shift = mod + static_cast<int64_t>(l) * 6 * D + (which ? 3 : 0) * D;
+    const float* scale = shift + D;
+
+    // stage (1 + scale) and shift of every sample as hi + lo bf16 parts; rows past B are zero
+    for (int i = tid; i < kBatch * (D / 2); i += kThreads) {
+        const int b = i / (D / 2), p = i % (D / 2);
+        float a0 = 0.f, a1 = 0.f, t0 = 0.f, t1 = 0.f;
+        if (b < B) {
+            const float2 sc = reinterpret_cast<const float2*>(scale + static_cast<int64_t>(b) * mod_stride)[p];
+            const float2 sh = reinterpret_cast<const float2*>(shift + static_cast<int64_t>(b) * mod_stride)[p];
+            a0 = 1.0f + sc.x;
+            a1 = 1.0f + sc.y;
+            t0 = sh.x;
+            t1 = sh.y;
+        }
+        const uint32_t ah = pack_bf16_pair(a0, a1), th = pack_bf16_pair(t0, t1);
+        *reinterpret_cast<uint32_t*>(s1_hi + b * row_bytes + p * 4) = ah;
+        *reinterpret_cast<uint32_t*>(s1_lo + b * row_bytes + p * 4) =
+            pack_bf16_pair(a0 - __uint_as_float(ah << 16), a1 - __uint_as_float(ah & 0xffff0000u));
+        *reinterpret_cast<uint32_t*>(s0_hi + b * row_bytes + p * 4) = th;
+        *reinterpret_cast<uint32_t*>(s0_lo + b * row_bytes + p * 4) =
+            pack_bf16_pair(t0 - __uint_as_float(th << 16), t1 - __uint_as_float(th & 0xffff0000u));
+    }
+    __syncthreads();
+
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int act_off = l16 * row_bytes + lq * 16;
+    const int steps = D / 32;
+    const int nblocks = rows / 16;
+    const int first = seg * (kSegRows / 16) + wave * kBlocksPerWave;
+    const int last = first + kBlocksPerWave < nblocks ? first + kBlocksPerWave : nblocks;
+    // (global address space stated explicitly: the pointer comes from a table in memory, and as a generic
+    // pointer every load would be a flat load ordered against the LDS reads)
+    using gvec = const __attribute__((address_space(1))) u32x4_t*;
+    const char* wmat = static_cast<const char*>(w_tab[2 * l + which]);
+    const float* bias = b_tab[2 * l + which];
+    u32x4_t wa[kChunk], wb[kChunk];
+    auto load = [&](u32x4_t (&dst)[kChunk], const char* wrow, int st0) {
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u)
+            if (st0 + u < steps) dst[u] = *(gvec)(wrow + (st0 + u) * 64);
+    };
+    auto row_ptr = [&](int blk) { return wmat + (static_cast<int64_t>(blk * 16 + l16) * D) * 2 + lq * 16; };
+    const char* wrow = nullptr;
+    if (first < last) {
+        wrow = row_ptr(first);
+        load(wa, wrow, 0);
+    }
+    for (int blk = first; blk < last; ++blk) {
+        const int r0 = blk * 16;
+        const char* wnext = (blk + 1 < last) ? row_ptr(blk + 1) : nullptr;
+        f32x4_t acc1 = {0.f, 0.f, 0.f, 0.f}, acc0 = {0.f, 0.f, 0.f, 0.f};
+        auto multiply = [&](const u32x4_t (&src)[kChunk], int st0) {
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u)
+                if (st0 + u < steps) {
+                    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, src[u]);
+                    const int o = act_off + (st0 + u) * 64;
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s1_hi + o), acc1, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s1_lo + o), acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s0_hi + o), acc0, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s0_lo + o), acc0, 0, 0, 0);
+                }
+        };
+        for (int st0 = 0; st0 < steps; st0 += 2 * kChunk) {
+            load(wb, wrow, st0 + kChunk);
+            multiply(wa, st0);
+            if (st0 + 2 * kChunk < steps) load(wa, wrow, st0 + 2 * kChunk);
+            else if (wnext) load(wa, wnext, 0);
+            multiply(wb, st0 + kChunk);
+        }
+        wrow = wnext;
+        // accumulator register i of lane l: weight row 4 (l / 16) + i, sample l % 16
+        if (l16 < B) {
+            const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(bias + r0 + 4 * lq);
+            f32x4_t o0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o0[i] = acc0[i] + bv[i];
+            float* dst = fold + static_cast<int64_t>(l16) * fold_stride + out_row0 + r0 + 4 * lq;
+            *reinterpret_cast<f32x4_t*>(dst) = acc1;
+            *reinterpret_cast<f32x4_t*>(dst + total_rows) = o0;
+        }
+    }
+}
+
+}  // namespace
+
+// Supported: bf16 weights, D % 32 == 0, D <= 1152 (four staged vectors sets of 16 rows in 160 KB of LDS), both row
+// counts multiples of 16; 16-byte aligned weight rows, biases, mod and fold rows.
+bool ln_fold_supported(int32_t D, int32_t rows_qkv, int32_t rows_fc1) {
+    return D % 32 == 0 && rows_qkv % 16 == 0 && rows_fc1 % 16 == 0 &&
+           4 * static_cast<size_t>(kBatch) * (static_cast<size_t>(D) * 2 + 16) <= 160 * 1024;
+}
+
+int32_t launch_ln_fold(const float* mod, int32_t B, int32_t D, int32_t mod_stride, int32_t depth, int32_t rows_qkv,
+                       int32_t rows_fc1, const void* const* w_tab, const float* const* b_tab, float* fold,
+                       int64_t fold_stride, hipStream_t s) {
+    if (!ln_fold_supported(D, rows_qkv, rows_fc1)) return FREE_ERR_SHAPE;
+    const int32_t total_rows = depth * (rows_qkv + rows_fc1);
+    if (fold_stride < 2 * static_cast<int64_t>(total_rows) || (fold_stride & 3) || (mod_stride & 3)) return FREE_ERR_SHAPE;
+    const size_t lds = 4 * static_cast<size_t>(kBatch) * (static_cast<size_t>(D) * 2 + 16);
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(ln_fold_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)))
+            return FREE_ERR_HIP;
+        attr_set = true;
+    }
+    const int per_block = (rows_qkv + kSegRows - 1) / kSegRows + (rows_fc1 + kSegRows - 1) / kSegRows;
+    for (int b0 = 0; b0 < B; b0 += kBatch) {
+        const int nb = (B - b0 < kBatch) ? B - b0 : kBatch;
+        hipLaunchKernelGGL(ln_fold_kernel, dim3(depth * per_block), dim3(kThreads), lds, s,
+                           mod + static_cast<int64_t>(b0) * mod_stride, nb, D, mod_stride, rows_qkv, rows_fc1, w_tab, b_tab,
+                           fold + static_cast<int64_t>(b0) * fold_stride, fold_stride, total_rows);
+        if (!launch_ok()) return FREE_ERR_HIP;
+    }
+    return FREE_OK;
+}
+
+}  // namespace freemi
