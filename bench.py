@@ -101,6 +101,8 @@ def bench_round(args):
     tp = torch.cat([a["t"], a["t"]]) if B == 2 * K else a["t"]
     yp = torch.tensor([ri["y"]] * K + [cfg["num_classes"]] * (B - K), dtype=torch.int32, device="cuda:0")
     xp = torch.cat([a["x_states"], a["x_states"]]) if B == 2 * K else a["x_states"]
+    if args.ln_fold != "auto":
+        model.set_ln_fold({"off": binding.LN_FOLD_OFF, "require": binding.LN_FOLD_REQUIRE}[args.ln_fold])
     model.set_streams(args.streams)
     if args.streams == 0:
         model.tune(xp, tp, yp)
@@ -485,6 +487,8 @@ def main():
     ap.add_argument("--K", type=int, default=6)
     ap.add_argument("--cfg-scale", type=float, default=4.0)
     ap.add_argument("--relaxed", action="store_true")
+    ap.add_argument("--ln-fold", default="auto", choices=["auto", "off", "require"],
+                    help="LayerNorm folded into the GEMMs around it (bf16): the library's rule, never, or always")
     ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
                     help="0 (library default): the library times one and two streams over its first forwards and "
                          "keeps the faster; 2: the halves of the packed batch run concurrently on two streams; "

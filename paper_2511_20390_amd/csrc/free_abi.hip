@@ -148,6 +148,11 @@ struct free_dit_s {
     hipStream_t side[2] = {nullptr, nullptr};
     hipEvent_t ev_fork = nullptr;
     hipEvent_t ev_join[2] = {nullptr, nullptr};
+    // third side stream (default priority): the fold vectors of the folded LayerNorms are computed on it while
+    // the first block runs up to its out-projection; ev_fold_go orders it after the modulation, the block
+    // stack waits for ev_fold_done before the first GEMM that reads the vectors
+    hipStream_t fold_stream = nullptr;
+    hipEvent_t ev_fold_go = nullptr, ev_fold_done = nullptr;
     // Schedule of the block stack: forced (1 or 2) for every batch size, or 0 = per batch size what
     // free_dit_tune measured, one stream where nothing was measured.
     int32_t forced_streams = 0;
@@ -240,6 +245,7 @@ struct ActBufs {
 // `nblk` adaLN-Zero blocks on samples [b0, b0 + nb) of a batch.  blkw holds 10 pointers per block
 // (B_* order); block l's six modulation vectors of sample b are mod[b * mod_rows + l * 6D ..].
 // cu_share: number of such stacks running side by side on different streams (tile choice of the GEMMs).
+// fold_ready (nullable): event after which fold->vec is complete; waited for on `s` before the first use.
 // fold (nullable): the LayerNorms are folded into the GEMMs around them (all but the first one of block 0, whose
 // input no GEMM of this stack produced): fold->vec holds the fold vectors of all samples of the batch, fold->stats the
 // partial row sums of all token rows.
@@ -251,7 +257,7 @@ struct FoldBufs {
 };
 int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const float* mod, int32_t mod_rows,
                         const ActBufs& a, int b0, int nb, hipStream_t s, Profiler* pf, int cu_share = 1,
-                        const FoldBufs* fold = nullptr) {
+                        const FoldBufs* fold = nullptr, hipEvent_t fold_ready = nullptr) {
     const size_t esz = d.mode == FREE_BF16 ? 2 : 4;
     const int32_t M = nb * d.ntok;
     const int64_t r0 = static_cast<int64_t>(b0) * d.ntok;
@@ -324,6 +330,8 @@ int32_t run_block_stack(const Dims& d, const void* const* blkw, int nblk, const 
         }
         // x += gate2 * FC2(gelu(FC1(LN(x)(1+scale2)+shift2)))
         if (fold) {
+            // (the first GEMM that reads the fold vectors: they may still be on their way on another stream)
+            if (l == 0 && fold_ready && !hip_ok(hipStreamWaitEvent(s, fold_ready, 0))) return FREE_ERR_HIP;
             ProfScope prof(pf, PROF_GEMM_FC1, s);
             const LnFold f = consumer(l, 1);
             FREE_TRY(linear_dispatch(d, xn_h, W(l, B_FC1_W), Bv(l, B_FC1_B), M, d.F, d.D, FREE_EPI_LN_BIAS_GELU, hmid_h,
@@ -386,10 +394,20 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     if (h->ln_fold == FREE_LN_FOLD_REQUIRE && !folded) return FREE_ERR_SHAPE;
     FoldBufs fb{reinterpret_cast<const float*>(ws + L.fold), fold_stride(d), reinterpret_cast<float*>(ws + L.stats),
                 d.D / kLnSlotCols};
-    if (folded) {
+    hipEvent_t fold_ready = nullptr;
+    if (folded && h->prof.on) {
         ProfScope prof(&h->prof, PROF_ADALN, s);
         FREE_TRY(launch_ln_fold(mod, B, d.D, d.mod_rows, d.depth, 3 * d.D, d.F, h->fold_w_tab, h->fold_b_tab,
                                 reinterpret_cast<float*>(ws + L.fold), fb.stride, s));
+    } else if (folded) {
+        // bandwidth-bound and needed only from the first block's MLP on: beside the main stream, so that it
+        // fills the compute units the first block's kernels leave idle
+        if (!hip_ok(hipEventRecord(h->ev_fold_go, s))) return FREE_ERR_HIP;
+        if (!hip_ok(hipStreamWaitEvent(h->fold_stream, h->ev_fold_go, 0))) return FREE_ERR_HIP;
+        FREE_TRY(launch_ln_fold(mod, B, d.D, d.mod_rows, d.depth, 3 * d.D, d.F, h->fold_w_tab, h->fold_b_tab,
+                                reinterpret_cast<float*>(ws + L.fold), fb.stride, h->fold_stream));
+        if (!hip_ok(hipEventRecord(h->ev_fold_done, h->fold_stream))) return FREE_ERR_HIP;
+        fold_ready = h->ev_fold_done;
     }
     {
     ProfScope prof(&h->prof, PROF_PATCH, s);
@@ -400,7 +418,7 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     const void* const* blkw = h->w.data() + 7;
     auto run_blocks = [&](int b0, int nb, hipStream_t st, int cu_share) -> int32_t {
         return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st, &h->prof, cu_share,
-                               folded ? &fb : nullptr);
+                               folded ? &fb : nullptr, fold_ready);
     };
     // The samples of a packed batch are independent through all blocks, so the batch can be cut in two
     // halves that run on two streams forked from (and joined back into) the caller's stream: while
@@ -658,6 +676,9 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
     for (int i = 0; i < 2 && ok; ++i)
         ok = hip_ok(hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking)) &&
              hip_ok(hipEventCreateWithFlags(&h->ev_join[i], hipEventDisableTiming));
+    ok = ok && hip_ok(hipStreamCreateWithFlags(&h->fold_stream, hipStreamNonBlocking)) &&
+         hip_ok(hipEventCreateWithFlags(&h->ev_fold_go, hipEventDisableTiming)) &&
+         hip_ok(hipEventCreateWithFlags(&h->ev_fold_done, hipEventDisableTiming));
     if (!ok) {
         (void)free_dit_destroy(h);
         return FREE_ERR_HIP;
@@ -675,6 +696,10 @@ int32_t free_dit_destroy(free_dit_t h) {
         if (h->ev_join[i] && !hip_ok(hipEventDestroy(h->ev_join[i]))) st = FREE_ERR_HIP;
     }
     if (h->ev_fork && !hip_ok(hipEventDestroy(h->ev_fork))) st = FREE_ERR_HIP;
+    if (h->fold_stream && !hip_ok(hipStreamSynchronize(h->fold_stream))) st = FREE_ERR_HIP;
+    if (h->fold_stream && !hip_ok(hipStreamDestroy(h->fold_stream))) st = FREE_ERR_HIP;
+    if (h->ev_fold_go && !hip_ok(hipEventDestroy(h->ev_fold_go))) st = FREE_ERR_HIP;
+    if (h->ev_fold_done && !hip_ok(hipEventDestroy(h->ev_fold_done))) st = FREE_ERR_HIP;
     for (int i = 0; i < kTuneTrials; ++i)
         for (int j = 0; j < 2; ++j)
             if (h->tune_ev[i][j] && !hip_ok(hipEventDestroy(h->tune_ev[i][j]))) st = FREE_ERR_HIP;

@@ -123,16 +123,14 @@ __device__ inline void tile_coords(int kGroupM, int pid, int tiles_m, int tiles_
 // QB: for the residual update, chunks per lane whose loads are in flight together in the LDS-staged form; 0
 // selects the direct form.
 // Folded LayerNorm (see LnFold): kPrep - the residual update also writes z and the partial row sums;
-// kLn - the output is r acc - r mu c1 + c0 with the per-row factors ln_a = r, ln_b = -r mu of this lane's
-// rows and c1 / c0 staged in LDS at fold_lds (per 32-row block i: vectors of sample index ln_si[i], c1 then
-// c0, BN floats each, first column of the tile = fold_col0 columns before this wavefront's first).
+// kLn - the accumulators hold z W^T - mu c1 + c0 / r (the kernel adds the rank-2 term as an extra k-step before
+// its K loop), so the output is r acc with the per-row factor ln_a = r of this lane's rows: no bias, one
+// multiplication per element.
 template <typename OT, int TM, int TN, int EPI, int QB>
 __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm_lane, int gn_wave, int lane, int32_t M,
                                            int32_t N, int32_t vec_ok, const float* __restrict__ bias,
                                            OT* __restrict__ out, float* __restrict__ resid, const RowVec& gate,
-                                           char* wave_lds, const LnFold& ln, const float (&ln_a)[TM],
-                                           const float (&ln_b)[TM], const int (&ln_si)[TM], const char* fold_lds,
-                                           int fold_col0, int fold_bn) {
+                                           char* wave_lds, const LnFold& ln, const float (&ln_a)[TM]) {
     constexpr bool kF32Out = std::is_same<OT, float>::value;   // fp32 mode: the output of the bias / GELU epilogues is fp32
     constexpr bool kPrep = EPI == FREE_EPI_GATE_RESID_PREP;
     constexpr bool kResid = EPI == FREE_EPI_GATE_RESID || kPrep;
@@ -245,31 +243,48 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                             *reinterpret_cast<f32x4_t*>(wave_lds + l32 * kStageRow + ((8 * jj + 2 * e4 + lhi) << 4)) = v;
                         }
                     // batches of 4 chunks per lane: all loads of a batch before its first store, and few
-                    // enough registers beside the accumulators
+                    // enough registers beside the accumulators.  A lane's chunks of a group are the same four
+                    // columns of different rows (64 % CH == 0), so the bias and - when the block lies in one sample -
+                    // the gate and the next scale are loaded once per group, not once per chunk: per chunk they
+                    // would quadruple what the epilogue pulls through the L1.
                     constexpr int QN = (QB > 0 && QB < NQ) ? QB : NQ;
-                    static_assert(NQ % QN == 0, "whole batches");
+                    static_assert(NQ % QN == 0 && 64 % CH == 0, "whole batches; one chunk column per lane");
+                    const int gn = gn_wave + jg * 32 + (lane % CH) * 4;
+                    f32x4_t bvc = {0.f, 0.f, 0.f, 0.f}, gc = {0.f, 0.f, 0.f, 0.f};
+                    [[maybe_unused]] f32x4_t snc = {0.f, 0.f, 0.f, 0.f};
+                    if (gn < N) {
+                        bvc = *reinterpret_cast<const f32x4_t*>(bias + gn);
+                        if constexpr (kResid) {
+                            if (one_sample) {
+                                gc = *reinterpret_cast<const f32x4_t*>(gbase + static_cast<int64_t>(s_first) * gate.stride + gn);
+                                if constexpr (kPrep)
+                                    snc = *reinterpret_cast<const f32x4_t*>(ln.scale_next + static_cast<int64_t>(s_first) * gate.stride + gn);
+                            }
+                        }
+                    }
 #pragma unroll
                     for (int q0 = 0; q0 < NQ; q0 += QN) {
-                        f32x4_t r[QN], g[QN], bv[QN];
+                        f32x4_t r[QN], g[QN];
                         [[maybe_unused]] f32x4_t sn[QN];
                         int64_t off[QN];
                         bool ok[QN];
 #pragma unroll
                         for (int q = 0; q < QN; ++q) {
                             const int f = (q0 + q) * 64 + lane;
-                            const int row = f / CH, ch = f % CH;
-                            const int gm = gm_blk + row, gn = gn_wave + jg * 32 + ch * 4;
+                            const int gm = gm_blk + f / CH;
                             ok[q] = gm < M && gn < N;
                             off[q] = static_cast<int64_t>(gm) * N + gn;
+                            g[q] = gc;
+                            if constexpr (kPrep) sn[q] = snc;
                             if (ok[q]) {
                                 if constexpr (kResid) {
-                                    const int smp = one_sample ? s_first : gm / gate.rows_per_sample;
                                     r[q] = *reinterpret_cast<const f32x4_t*>(resid + off[q]);
-                                    g[q] = *reinterpret_cast<const f32x4_t*>(gbase + static_cast<int64_t>(smp) * gate.stride + gn);
-                                    if constexpr (kPrep)
-                                        sn[q] = *reinterpret_cast<const f32x4_t*>(ln.scale_next + static_cast<int64_t>(smp) * gate.stride + gn);
+                                    if (!one_sample) {
+                                        const int64_t so = static_cast<int64_t>(gm / gate.rows_per_sample) * gate.stride + gn;
+                                        g[q] = *reinterpret_cast<const f32x4_t*>(gbase + so);
+                                        if constexpr (kPrep) sn[q] = *reinterpret_cast<const f32x4_t*>(ln.scale_next + so);
+                                    }
                                 }
-                                bv[q] = *reinterpret_cast<const f32x4_t*>(bias + gn);
                             }
                         }
 #pragma unroll
@@ -279,7 +294,7 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                                 const f32x4_t v = *reinterpret_cast<const f32x4_t*>(wave_lds + (f / CH) * kStageRow + ((f % CH) << 4));
                                 if constexpr (kResid) {
 #pragma unroll
-                                    for (int c = 0; c < 4; ++c) r[q][c] = fmaf(g[q][c], v[c] + bv[q][c], r[q][c]);
+                                    for (int c = 0; c < 4; ++c) r[q][c] = fmaf(g[q][c], v[c] + bvc[c], r[q][c]);
                                     *reinterpret_cast<f32x4_t*>(resid + off[q]) = r[q];
                                     if constexpr (kPrep) {
                                         const u32x2_t zz = {pack2(r[q][0] * (1.0f + sn[q][0]), r[q][1] * (1.0f + sn[q][1])),
@@ -292,7 +307,7 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
                                 } else {
 #pragma unroll
                                     for (int c = 0; c < 4; ++c) {
-                                        r[q][c] = v[c] + bv[q][c];
+                                        r[q][c] = v[c] + bvc[c];
                                         if (kGelu) r[q][c] = gelu_fast(r[q][c]);
                                     }
                                     *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(out) + off[q]) = r[q];
@@ -356,25 +371,14 @@ __device__ __forceinline__ void write_tile(const f32x16_t (&acc)[TM][TN], int gm
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                // folded LayerNorm: c1 / c0 of this block's sample, staged in LDS (columns beyond N hold zeros)
-                [[maybe_unused]] const char* c1p = fold_lds + (static_cast<size_t>(ln_si[i]) * 2 * fold_bn + fold_col0 + 4 * lhi) * 4;
-                [[maybe_unused]] const char* c0p = c1p + static_cast<size_t>(fold_bn) * 4;
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int e8 = 0; e8 < 2; ++e8) {
                         float v[8];
                         if constexpr (kLn) {
-                            const int cb = (j * 32 + 16 * e8) * 4;
-                            const f32x4_t c1l = *reinterpret_cast<const f32x4_t*>(c1p + cb);
-                            const f32x4_t c1h = *reinterpret_cast<const f32x4_t*>(c1p + cb + 32);
-                            const f32x4_t c0l = *reinterpret_cast<const f32x4_t*>(c0p + cb);
-                            const f32x4_t c0h = *reinterpret_cast<const f32x4_t*>(c0p + cb + 32);
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                v[c] = fmaf(ln_a[i], acc[i][j][8 * e8 + c], fmaf(ln_b[i], c1l[c], c0l[c]));
-                                v[4 + c] = fmaf(ln_a[i], acc[i][j][8 * e8 + 4 + c], fmaf(ln_b[i], c1h[c], c0h[c]));
-                            }
+                            for (int c = 0; c < 8; ++c) v[c] = ln_a[i] * acc[i][j][8 * e8 + c];
                         } else {
 #pragma unroll
                             for (int c = 0; c < 4; ++c) {
@@ -530,6 +534,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    constexpr bool kLnEpi = EPI == FREE_EPI_LN_BIAS || EPI == FREE_EPI_LN_BIAS_GELU;
+    [[maybe_unused]] float ln_a[TM];                       // folded LayerNorm: r of this lane's rows
 
     auto mma = [&](int buf) {
         if constexpr (kF32) {
@@ -595,8 +601,86 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
 
     // ---- prologue: slice 0 through the registers into LDS stage 0, slice 1 into the registers
     fetch_range(0, 0, NS);
+    // Folded LayerNorm: with mu and rho = sqrt(var + eps) of a row, the output is (z W^T - mu c1 + rho c0) / rho.
+    // The rank-2 term -mu c1 + rho c0 is one extra k-step of the matrix product, issued in this prologue: row m
+    // contributes the k-vector (-mu_h, -mu_l, -mu_h, rho_h, rho_l, rho_h, 0 ...), column n the k-vector
+    // (c1_h, c1_h, c1_l, c0_h, c0_h, c0_l, 0 ...), with _h the bf16 value and _l the bf16 value of the remainder
+    // (the product of two remainders, 2^-18 relative, is dropped).  Its loads - the partial sums of this lane's
+    // rows, c1 / c0 of its columns - are requested right behind slice 0 and consumed while slice 1 is in flight;
+    // nothing of it stays in registers through the K loop except 1 / rho per row, which the epilogue multiplies by.
+    // Every 32-row block lies in one sample (rows per sample a multiple of 32).  The lower half-wave adds the first
+    // half of a row's slots in index order, the upper one the rest, then the two sums are added - a fixed order.
+    constexpr int kHalfSlots = 8;                          // up to 16 slots: rows of up to 2048 values
+    [[maybe_unused]] float2 ln_p[kLnEpi ? TM : 1][kHalfSlots];
+    [[maybe_unused]] float ln_c1[kLnEpi ? TM : 1][TN], ln_c0[kLnEpi ? TM : 1][TN];
+    [[maybe_unused]] int ln_kn = 0;
+    if constexpr (kLnEpi) {
+        const int rps = ln.rows_per_sample;
+        const int half = (ln.slots + 1) / 2;
+        const int k0 = lhi ? half : 0;
+        ln_kn = lhi ? ln.slots - half : half;              // this half-wave's slots
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int gm_blk = m0 + wm * TM * 32 + i * 32;
+            const int gm = gm_blk + l32;
+            // (rows past M and slots past the end re-read a valid entry with weight zero: no branches)
+            const float2* st = reinterpret_cast<const float2*>(ln.stats) + static_cast<int64_t>(gm < M ? gm : M - 1) * ln.slots;
+#pragma unroll
+            for (int k = 0; k < kHalfSlots; ++k) ln_p[i][k] = st[k0 + (k < ln_kn ? k : 0)];
+            // c1 / c0 of this block's sample: loaded again only where the sample changes (wave-uniform)
+            const int smp = (gm_blk < M ? gm_blk : M - 1) / rps;
+            const int smp_prev = i == 0 ? -1 : ((gm_blk - 32 < M ? gm_blk - 32 : M - 1) / rps);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (smp != smp_prev) {
+                    const int n = n0 + wn * TN * 32 + j * 32 + l32;
+                    const int64_t o = static_cast<int64_t>(smp) * ln.fold_stride + (n < N ? n : 0);
+                    ln_c1[i][j] = ln.c1[o];
+                    ln_c0[i][j] = ln.c0[o];
+                } else {
+                    ln_c1[i][j] = ln_c1[i > 0 ? i - 1 : 0][j];
+                    ln_c0[i][j] = ln_c0[i > 0 ? i - 1 : 0][j];
+                }
+            }
+        }
+    }
     stash_range(0, 0, NS);
     if (nk > 1) fetch_range(1, 0, NS);
+    if constexpr (kLnEpi) {
+        const auto split = [](float v, float* hi, float* lo) {
+            *hi = __uint_as_float(pack2(v, 0.f) << 16);
+            *lo = v - *hi;
+        };
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+            for (int k = 0; k < kHalfSlots; ++k) {
+                s1 += k < ln_kn ? ln_p[i][k].x : 0.f;
+                s2 += k < ln_kn ? ln_p[i][k].y : 0.f;
+            }
+            const float o1 = __shfl_xor(s1, 32, 64), o2 = __shfl_xor(s2, 32, 64);
+            s1 = lhi ? o1 + s1 : s1 + o1;                  // first half + second half in both lanes
+            s2 = lhi ? o2 + s2 : s2 + o2;
+            const float mean = s1 * ln.inv_width;
+            const float var = fmaxf(s2 * ln.inv_width - mean * mean, 0.f);
+            ln_a[i] = rsqrtf(var + kLnEps);
+            float mh, ml, rh, rl;
+            split(-mean, &mh, &ml);
+            split(1.0f / ln_a[i], &rh, &rl);
+            const u32x4_t xk = lhi ? u32x4_t{0, 0, 0, 0} : u32x4_t{pack2(mh, ml), pack2(mh, rh), pack2(rl, rh), 0};
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * TN * 32 + j * 32 + l32;
+                float c1h, c1l, c0h, c0l;
+                split(n < N ? ln_c1[i][j] : 0.f, &c1h, &c1l);
+                split(n < N ? ln_c0[i][j] : 0.f, &c0h, &c0l);
+                const u32x4_t wk = lhi ? u32x4_t{0, 0, 0, 0} : u32x4_t{pack2(c1h, c1h), pack2(c1l, c0h), pack2(c0h, c0l), 0};
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wk),
+                                                                    __builtin_bit_cast(bf16x8_t, xk), acc[i][j], 0, 0, 0);
+            }
+        }
+    }
     __syncthreads();
     load_frags(lds, 0, 0);
     // ---- steady state: slice kt multiplies while slice kt+1 moves registers -> LDS and
@@ -613,56 +697,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     // after the barrier of the last slice no wavefront reads the LDS tiles any more: each wavefront
     // may use a private region of them to transpose its output
     constexpr bool kResidEpi = EPI == FREE_EPI_GATE_RESID || EPI == FREE_EPI_GATE_RESID_PREP;
-    constexpr bool kLnEpi = EPI == FREE_EPI_LN_BIAS || EPI == FREE_EPI_LN_BIAS_GELU;
     constexpr int kWaveStage = (kResidEpi || kF32) ? 32 * (((TN % 2 == 0 ? 2 : 1) * 8 + 1) * 16)   // fp32 groups
                                                    : 32 * (TN * 64 + 16);                            // bf16 rows
-    constexpr int kFoldBytes = kLnEpi ? (BM / 32) * 2 * BN * 4 : 0;     // c1 and c0 of up to BM / 32 samples
-    static_assert(WGM * WGN * kWaveStage + kFoldBytes <= 2 * kStageBytes, "output staging must fit in the K-loop tiles");
+    static_assert(WGM * WGN * kWaveStage <= 2 * kStageBytes, "output staging must fit in the K-loop tiles");
     constexpr int kResidBatch = (WGM * WGN == 8) ? 4 : 0;
-    float ln_a[TM], ln_b[TM];
-    int ln_si[TM];
+    float ln_scale[TM];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) { ln_a[i] = 0.f; ln_b[i] = 0.f; ln_si[i] = 0; }
-    const char* fold_lds = lds + WGM * WGN * kWaveStage;
+    for (int i = 0; i < TM; ++i) ln_scale[i] = 1.0f;
     if constexpr (kLnEpi) {
-        // Folded LayerNorm.  (1) The fold vectors c1, c0 of the samples this tile's rows belong to go to LDS
-        // (every 32-row block lies in one sample: rows per sample a multiple of 32); (2) each lane turns the
-        // partial sums of its rows into r = 1 / sqrt(var + eps) and -r mu, adding the slots in index order.
-        const int rps = ln.rows_per_sample;
-        const int s_lo = m0 / rps;
-        const int m_last = (m0 + BM < M ? m0 + BM : M) - 1;
-        const int ns = m_last / rps - s_lo + 1;
-        constexpr int kVec4 = BN / 4;                                  // f32x4 per vector
-        for (int u = tid; u < ns * 2 * kVec4; u += NT) {
-            const int si = u / (2 * kVec4), rem = u % (2 * kVec4);
-            const int n = n0 + (rem % kVec4) * 4;
-            f32x4_t v = {0.f, 0.f, 0.f, 0.f};
-            if (n < N) v = *reinterpret_cast<const f32x4_t*>((rem < kVec4 ? ln.c1 : ln.c0) + static_cast<int64_t>(s_lo + si) * ln.fold_stride + n);
-            *reinterpret_cast<f32x4_t*>(lds + WGM * WGN * kWaveStage + (static_cast<size_t>(si) * 2 * BN + (rem < kVec4 ? 0 : BN) + (rem % kVec4) * 4) * 4) = v;
-        }
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int gm_blk = m0 + wm * TM * 32 + i * 32;
-            const int gm = gm_blk + l32;
-            ln_si[i] = (gm_blk < M ? gm_blk : M - 1) / rps - s_lo;
-            if (gm < M) {
-                float s1 = 0.f, s2 = 0.f;
-                const float2* st = reinterpret_cast<const float2*>(ln.stats) + static_cast<int64_t>(gm) * ln.slots;
-                for (int k = 0; k < ln.slots; ++k) {
-                    const float2 p = st[k];
-                    s1 += p.x;
-                    s2 += p.y;
-                }
-                const float mean = s1 * ln.inv_width;
-                const float var = fmaxf(s2 * ln.inv_width - mean * mean, 0.f);
-                ln_a[i] = rsqrtf(var + kLnEps);
-                ln_b[i] = -ln_a[i] * mean;
-            }
-        }
-        __syncthreads();
+        for (int i = 0; i < TM; ++i) ln_scale[i] = ln_a[i];
     }
     write_tile<T, TM, TN, EPI, kResidBatch>(acc, m0 + wm * TM * 32 + l32, n0 + wn * TN * 32, lane, M, N, vec_ok, bias, out, resid, gate,
-                            lds + wave * kWaveStage, ln, ln_a, ln_b, ln_si, fold_lds, wn * TN * 32, BN);
+                            lds + wave * kWaveStage, ln, ln_scale);
 }
 
 int device_cus() {
@@ -843,7 +890,8 @@ int32_t launch_linear_mfma(const bf16_t* X, const bf16_t* W, const float* bias, 
 }
 
 bool mfma_ln_fold_supported(int32_t M, int32_t D, int32_t rows_per_sample) {
-    return M >= 1 && D % kLnSlotCols == 0 && D % 64 == 0 && rows_per_sample >= 32 && rows_per_sample % 32 == 0;
+    // (a 32-row block of a tile then lies in one sample; up to 16 slots of partial sums per row)
+    return M >= 1 && D % kLnSlotCols == 0 && D <= 16 * kLnSlotCols && rows_per_sample >= 32 && rows_per_sample % 32 == 0;
 }
 
 int32_t launch_linear_mfma_f32(const float* X, const float* W, const float* bias, int32_t M, int32_t N, int32_t K,

@@ -6,8 +6,9 @@
 // per packed sample s.  Two such layers per block: QKV (first LayerNorm) and the MLP's first layer (second).
 // HBM-bound like the adaLN modulation: every weight row is read once.  Weight rows are the A operand of
 // v_mfma_f32_16x16x32_bf16, straight from global memory in the operand layout; the packed batch (<= 16 samples
-// per pass) is the N dimension; the two activation vectors of each sample are staged in LDS as a bf16 high part
-// plus a bf16 remainder (two products per vector and k-step), so the fp32 modulation loses no precision.
+// per pass) is the N dimension; the two activation vectors of each sample are staged in LDS rounded to bf16 (the
+// error this leaves in c1 / c0, 2^-9 relative per term, is that of the bf16 operands of the GEMM they are
+// folded into; a second product with the remainders measured 40 % slower - twice the LDS, one workgroup per CU).
 #include "free_internal.h"
 
 namespace freemi {
@@ -37,9 +38,7 @@ __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
     const int row_bytes = D * 2 + 16;                       // odd number of 16-byte chunks per row
     const int set_bytes = kBatch * row_bytes;
     char* s1_hi = lds;                                      // 1 + scale
-    char* s1_lo = lds + set_bytes;
-    char* s0_hi = lds + 2 * set_bytes;                      // shift
-    char* s0_lo = lds + 3 * set_bytes;
+    char* s0_hi = lds + set_bytes;                          // shift
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     const int segs_qkv = (rows_qkv + kSegRows - 1) / kSegRows, segs_fc1 = (rows_fc1 + kSegRows - 1) / kSegRows;
@@ -64,13 +63,8 @@ __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
             t0 = sh.x;
             t1 = sh.y;
         }
-        const uint32_t ah = pack_bf16_pair(a0, a1), th = pack_bf16_pair(t0, t1);
-        *reinterpret_cast<uint32_t*>(s1_hi + b * row_bytes + p * 4) = ah;
-        *reinterpret_cast<uint32_t*>(s1_lo + b * row_bytes + p * 4) =
-            pack_bf16_pair(a0 - __uint_as_float(ah << 16), a1 - __uint_as_float(ah & 0xffff0000u));
-        *reinterpret_cast<uint32_t*>(s0_hi + b * row_bytes + p * 4) = th;
-        *reinterpret_cast<uint32_t*>(s0_lo + b * row_bytes + p * 4) =
-            pack_bf16_pair(t0 - __uint_as_float(th << 16), t1 - __uint_as_float(th & 0xffff0000u));
+        *reinterpret_cast<uint32_t*>(s1_hi + b * row_bytes + p * 4) = pack_bf16_pair(a0, a1);
+        *reinterpret_cast<uint32_t*>(s0_hi + b * row_bytes + p * 4) = pack_bf16_pair(t0, t1);
     }
     __syncthreads();
 
@@ -108,9 +102,7 @@ __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
                     const bf16x8_t a = __builtin_bit_cast(bf16x8_t, src[u]);
                     const int o = act_off + (st0 + u) * 64;
                     acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s1_hi + o), acc1, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s1_lo + o), acc1, 0, 0, 0);
                     acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s0_hi + o), acc0, 0, 0, 0);
-                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s0_lo + o), acc0, 0, 0, 0);
                 }
         };
         for (int st0 = 0; st0 < steps; st0 += 2 * kChunk) {
@@ -136,11 +128,10 @@ __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
 
 }  // namespace
 
-// Supported: bf16 weights, D % 32 == 0, D <= 1152 (four staged vectors sets of 16 rows in 160 KB of LDS), both row
-// counts multiples of 16; 16-byte aligned weight rows, biases, mod and fold rows.
+// Supported: bf16 weights, D % 32 == 0, D <= 2048 (two staged vector sets of 16 rows in LDS), both row counts
+// multiples of 16; 16-byte aligned weight rows, biases, mod and fold rows.
 bool ln_fold_supported(int32_t D, int32_t rows_qkv, int32_t rows_fc1) {
-    return D % 32 == 0 && rows_qkv % 16 == 0 && rows_fc1 % 16 == 0 &&
-           4 * static_cast<size_t>(kBatch) * (static_cast<size_t>(D) * 2 + 16) <= 160 * 1024;
+    return D % 32 == 0 && D <= 2048 && rows_qkv % 16 == 0 && rows_fc1 % 16 == 0;
 }
 
 int32_t launch_ln_fold(const float* mod, int32_t B, int32_t D, int32_t mod_stride, int32_t depth, int32_t rows_qkv,
@@ -149,7 +140,7 @@ int32_t launch_ln_fold(const float* mod, int32_t B, int32_t D, int32_t mod_strid
     if (!ln_fold_supported(D, rows_qkv, rows_fc1)) return FREE_ERR_SHAPE;
     const int32_t total_rows = depth * (rows_qkv + rows_fc1);
     if (fold_stride < 2 * static_cast<int64_t>(total_rows) || (fold_stride & 3) || (mod_stride & 3)) return FREE_ERR_SHAPE;
-    const size_t lds = 4 * static_cast<size_t>(kBatch) * (static_cast<size_t>(D) * 2 + 16);
+    const size_t lds = 2 * static_cast<size_t>(kBatch) * (static_cast<size_t>(D) * 2 + 16);
     static bool attr_set = false;
     if (!attr_set) {
         if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(ln_fold_kernel),
