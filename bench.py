@@ -43,17 +43,25 @@ def forward_flops(cfg, B):
 # kernel symbol (as rocprofv3 prints it) behind each profiled category, to look its measured
 # HBM traffic up in the committed rocprofv3 --pmc summary
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "spec_round_xl2_512_hbm_traffic.md")
-CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<bf16_t, 384, 192, 4, 2, 1, true>`",
-                   "gemm_qkv": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 0, true>`",
-                   "gemm_fc2": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 2, true>` FC2",
-                   "gemm_proj": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 2, true>` out-projection",
+# (epilogue codes in the kernel names: 0 bias, 1 bias + GELU, 2 gated residual update; with the LayerNorms folded
+# into the GEMMs 3 / 4 = the same two after a folded LayerNorm, 5 = residual update that prepares the next one)
+CATEGORY_SYMBOL = {"gemm_fc1": "gemm_bf16_kernel<bf16_t, 384, 192, 4, 2, 4, true>`",
+                   "gemm_qkv": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 3, true>`",
+                   "gemm_fc2": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 5, true>` FC2",
+                   "gemm_proj": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 5, true>` out-projection",
                    "attention": "attn_mfma_kernel<72, 1>`",
                    "verify_partial": "verify_partial_kernel<256, 4, true, true, false>`"}
 
 
-def measured_traffic(category):
+CATEGORY_SYMBOL_PLAIN = {"gemm_fc1": "gemm_bf16_kernel<bf16_t, 384, 192, 4, 2, 1, true>`",
+                         "gemm_qkv": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 0, true>`",
+                         "gemm_fc2": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 2, true>` FC2",
+                         "gemm_proj": "gemm_bf16_kernel<bf16_t, 256, 256, 4, 2, 2, true>` out-projection"}
+
+
+def measured_traffic(category, folded=True):
     """{'fetch_MB', 'write_MB'} per launch from the committed FETCH_SIZE / WRITE_SIZE summary, or None."""
-    sym = CATEGORY_SYMBOL.get(category)
+    sym = (CATEGORY_SYMBOL if folded else {**CATEGORY_SYMBOL, **CATEGORY_SYMBOL_PLAIN}).get(category)
     if sym is None or not os.path.exists(TRAFFIC_FILE):
         return None
     for line in open(TRAFFIC_FILE):
@@ -152,7 +160,8 @@ def bench_round(args):
     # 256 CUs x 4 SIMDs x 64 lanes x 2 flop x 2.4 GHz)
     roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": peak,
                 "unit": "TFLOP/s", "frac": kernels[dom]["tflops"] / peak,
-                "traffic": measured_traffic(dom) if args.config == "xl2_512" and mode == "bf16" else None,
+                "traffic": (measured_traffic(dom, bool(model.ln_fold_active(B)))
+                            if args.config == "xl2_512" and mode == "bf16" else None),
                 "avg_launch_us": kernels[dom]["avg_us"],
                 "measured": "HIP events around every launch of this kernel, same steps repeated right after the "
                             "timed region with all kernels in sequence on one stream"}
@@ -163,10 +172,31 @@ def bench_round(args):
         roofline["mfma_calibration"] = {"register_only_loop_tflops": cal["tflops"],
                                         "shader_clock_mhz": cal["shader_clock_mhz"],
                                         "frac_of_calibrated": kernels[dom]["tflops"] / cal["tflops"]}
+    ln_folded = bool(model.ln_fold_active(B))
+    roofline["note"] = ("the LayerNorms of the blocks are folded into the GEMMs: this kernel's time includes writing the "
+                        "next LayerNorm's input and row sums" if ln_folded and dom in ("gemm_fc2", "gemm_proj") else
+                        "the LayerNorms of the blocks are folded into the GEMMs: this kernel's time includes applying one"
+                        if ln_folded else "separate LayerNorm kernel")
+    ln_separate = None
+    if ln_folded:
+        # the same steps with the separate LayerNorm kernel, for the per-kernel comparison (not part of `value`)
+        model.set_ln_fold(binding.LN_FOLD_OFF)
+        model.set_streams(1)
+        step()
+        model.profile_begin()
+        for _ in range(args.steps):
+            step()
+        prof_off = model.profile_end()
+        model.set_ln_fold(binding.LN_FOLD_AUTO if args.ln_fold == "auto" else binding.LN_FOLD_REQUIRE)
+        model.set_streams(args.streams)
+        ln_separate = {name: {"avg_us": ms * 1e3 / n, "launches_per_step": n // args.steps,
+                              **({"tflops": per[name] / (ms / n * 1e-3) / 1e12} if name in per else {})}
+                       for name, (ms, n) in prof_off.items() if n}
     fwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if not k.startswith("verify") and k != "eps_to_mean")
     res = {
         "ms_per_step": ms_per_step, "ms_per_step_one_stream": ms_one_stream, "ms_per_step_two_streams": ms_two_streams,
         "batch_streams": args.streams, "stream_choice": stream_choice, "kernels": kernels, "roofline": roofline,
+        "ln_folded": ln_folded, "kernels_with_separate_layer_norm": ln_separate,
         "forward": {"algorithmic_tflop": total_flops / 1e12, "ms_sum_of_kernels": fwd_ms,
                     "tflops_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12,
                     "frac_of_peak_whole_step": total_flops / (ms_per_step * 1e-3) / 1e12 / peak},
@@ -562,6 +592,7 @@ def main():
         "batch_streams": res["batch_streams"], "stream_choice": res["stream_choice"], "ms_per_step_one_stream": res["ms_per_step_one_stream"],
         "ms_per_step_two_streams": res["ms_per_step_two_streams"],
         "roofline": res["roofline"], "forward": res["forward"], "kernels": res["kernels"],
+        "ln_folded": res["ln_folded"], "kernels_with_separate_layer_norm": res["kernels_with_separate_layer_norm"],
     }
     if "drafting" in res:
         line["drafting"] = res["drafting"]
