@@ -130,6 +130,17 @@ def test_argument_errors_are_status_codes(lib):
     assert lib.free_op_linear(one, one, one, 4, 4, 8, 0, 2, one, None, None, 0, 1, None) == binding.FREE_ERR_NULL
     assert lib.free_op_attention(one, 1, 16, 2, 200, 0, one, None) == binding.FREE_ERR_SHAPE
     assert lib.free_op_ln_modulate(one, one, None, 8, 4, 8, 1, 0, one, None) == binding.FREE_ERR_NULL
+    # LayerNorm folded into the GEMMs: setting of a handle, and the three pieces as operators
+    assert lib.free_dit_set_ln_fold(None, binding.LN_FOLD_OFF) == binding.FREE_ERR_NULL
+    assert lib.free_dit_ln_fold_active(None, 12) == binding.FREE_ERR_NULL
+    assert lib.free_op_ln_fold_vectors(None, 2, 128, 256, 1024, 1, one, one, one, one, one, 1 << 20, None) == binding.FREE_ERR_NULL
+    assert lib.free_op_ln_fold_vectors(one, 2, 128, 256, 100, 1, one, one, one, one, one, 1 << 20, None) == binding.FREE_ERR_SHAPE
+    assert lib.free_op_ln_fold_vectors(one, 2, 100, 256, 1024, 1, one, one, one, one, one, 1 << 20, None) == binding.FREE_ERR_SHAPE
+    assert lib.free_op_linear_resid_prep(one, one, one, 64, 128, 64, one, one, None, 384, 32, one, one, None) == binding.FREE_ERR_NULL
+    assert lib.free_op_linear_resid_prep(one, one, one, 64, 100, 64, one, one, one, 384, 32, one, one, None) == binding.FREE_ERR_SHAPE
+    assert lib.free_op_linear_ln(one, one, 64, 128, 128, None, one, one, 256, 32, 0, one, None) == binding.FREE_ERR_NULL
+    assert lib.free_op_linear_ln(one, one, 64, 128, 100, one, one, one, 256, 32, 0, one, None) == binding.FREE_ERR_SHAPE
+    assert lib.free_op_linear_ln(one, one, 64, 128, 128, one, one, one, 256, 33, 0, one, None) == binding.FREE_ERR_SHAPE
 
 
 def test_synth_is_deterministic_and_bf16_rounding_is_exact():
