@@ -148,11 +148,13 @@ size_t free_workspace_bytes(const free_dit_config* cfg, int32_t B);
  *   free_dit_set_streams(h, n): n = 1 or 2 forces that schedule for every batch
  *     size of the handle; n = 0 (initial state) uses, per batch size, what
  *     free_dit_tune measured, and one stream where nothing was measured.
- *   free_dit_tune: NOT a hot-path call - it blocks.  Runs 16 forwards on the given
- *     inputs (arguments as for dit_forward_packed, no top_feat), the two schedules
- *     in turn, each bracketed by events on `stream`, waits for them, compares the
- *     medians of the last 6 of each and remembers the faster schedule for this
- *     batch size (the handle keeps the 8 most recently tuned batch sizes).  A
+ *   free_dit_tune: NOT a hot-path call - it blocks.  Runs 24 forwards on the given
+ *     inputs (arguments as for dit_forward_packed, no top_feat): six runs of four,
+ *     the two schedules in turn; the last three forwards of a run are bracketed
+ *     together by events on `stream`.  It waits for them, adds up the last two
+ *     runs of each schedule and remembers two streams for this batch size if they
+ *     were more than 0.5 % faster, one stream otherwise (the handle keeps the 8
+ *     most recently tuned batch sizes).  A
  *     batch that can never split returns FREE_OK at once.  eps_out holds a valid
  *     forward result afterwards.
  *   free_dit_stream_choice(h, B): the schedule (1 or 2) a forward on B packed

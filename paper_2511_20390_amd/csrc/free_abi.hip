@@ -26,8 +26,11 @@ struct Profiler {
 };
 
 namespace {
-constexpr int kTuneTrials = 16;               // forwards of free_dit_tune, the two schedules in turn ...
-constexpr int kTuneSkip = 4;                  // ... of which the first ones (clocks and caches settling) are not counted
+// free_dit_tune: kTuneGroups runs of kTuneRun forwards, the two schedules in turn (1, 2, 1, 2, ...); the first
+// forward of a run is not timed (the schedules leave clocks and caches in different states), the others are
+// timed together, and the first pair of runs is not counted
+constexpr int kTuneGroups = 6, kTuneRun = 4;
+constexpr int kTuneTrials = kTuneGroups;      // event pairs the handle keeps for it
 constexpr int kTuneSlots = 8;                 // batch sizes a handle remembers a tuned schedule for
 constexpr int64_t kMinSplitRows = 2048;       // token rows per half below which the split does not pay
 // token rows from which the folded-LayerNorm path is taken by default: its GEMMs use the two large tiles only
@@ -740,31 +743,27 @@ int32_t free_dit_tune(free_dit_t h, const float* x, const int32_t* t, const int3
     const bool prof_before = h->prof.on;
     h->prof.on = false;
     int32_t st = FREE_OK;
-    for (int i = 0; i < kTuneTrials && st == FREE_OK; ++i) {
+    for (int i = 0; i < kTuneGroups && st == FREE_OK; ++i) {
         h->forced_streams = 1 + (i & 1);
-        if (!hip_ok(hipEventRecord(h->tune_ev[i][0], s))) st = FREE_ERR_HIP;
-        if (st == FREE_OK) st = forward_impl(h, x, B, t, y, B, eps_out, nullptr, static_cast<char*>(workspace), s);
+        for (int r = 0; r < kTuneRun && st == FREE_OK; ++r) {
+            if (r == 1 && !hip_ok(hipEventRecord(h->tune_ev[i][0], s))) st = FREE_ERR_HIP;
+            if (st == FREE_OK) st = forward_impl(h, x, B, t, y, B, eps_out, nullptr, static_cast<char*>(workspace), s);
+        }
         if (st == FREE_OK && !hip_ok(hipEventRecord(h->tune_ev[i][1], s))) st = FREE_ERR_HIP;
     }
     h->forced_streams = forced_before;
     h->prof.on = prof_before;
     if (st != FREE_OK) return st;
-    // the median of the counted trials of each schedule decides (ties go to one stream)
-    float ms[2][kTuneTrials];
-    int n[2] = {0, 0};
-    for (int i = kTuneSkip; i < kTuneTrials; ++i) {
+    // total time of the counted runs of each schedule; two streams must win by more than half a per cent
+    float tot[2] = {0.f, 0.f};
+    for (int i = 2; i < kTuneGroups; ++i) {
         float el = 0.f;
         if (!hip_ok(hipEventSynchronize(h->tune_ev[i][1])) ||
             !hip_ok(hipEventElapsedTime(&el, h->tune_ev[i][0], h->tune_ev[i][1])))
             return FREE_ERR_HIP;
-        ms[i & 1][n[i & 1]++] = el;
+        tot[i & 1] += el;
     }
-    float med[2];
-    for (int m = 0; m < 2; ++m) {
-        std::sort(ms[m], ms[m] + n[m]);
-        med[m] = 0.5f * (ms[m][(n[m] - 1) / 2] + ms[m][n[m] / 2]);
-    }
-    const int32_t choice = med[0] <= med[1] ? 1 : 2;
+    const int32_t choice = tot[1] < 0.995f * tot[0] ? 2 : 1;
     int slot = -1;
     for (int i = 0; i < kTuneSlots; ++i)
         if (h->tuned[i].batch == B) slot = i;

@@ -517,7 +517,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     const int x_row0 = (wm * TM * 32 + l32) * kRowBytes;           // + i*32 rows
     const int w_row0 = (BM + wn * TN * 32 + l32) * kRowBytes;      // + j*32 rows
     u32x4_t fx[2][TM], fw[2][TN];                      // one 16-byte chunk each: 8 bf16 or 4 fp32
+    // A wavefront whose part of the tile lies wholly past N or M (N = 1152 is 4.5 tiles of 256 columns: the right
+    // half of every fifth tile) takes part in the staging and the barriers only: its products would be thrown
+    // away, and on a chip that runs at its power limit they are not free for the others.
+    const bool wave_on = (n0 + wn * TN * 32 < N) && (m0 + wm * TM * 32 < M);
     auto load_frags = [&](const char* base, int ks, int buf) {
+        if (!wave_on) return;
         const int choff = (((ks << 1) | lhi) ^ sw) << 4;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -538,6 +543,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     [[maybe_unused]] float ln_a[TM];                       // folded LayerNorm: r of this lane's rows
 
     auto mma = [&](int buf) {
+        if (!wave_on) return;
         if constexpr (kF32) {
             // element e of the chunk: the lanes of group 0 / 1 hold the two k of one 32x32x2 product
 #pragma unroll
