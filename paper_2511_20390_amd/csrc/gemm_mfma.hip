@@ -520,7 +520,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     // A wavefront whose part of the tile lies wholly past N or M (N = 1152 is 4.5 tiles of 256 columns: the right
     // half of every fifth tile) takes part in the staging and the barriers only: its products would be thrown
     // away, and on a chip that runs at its power limit they are not free for the others.
-    const bool wave_on = (n0 + wn * TN * 32 < N) && (m0 + wm * TM * 32 < M);
+    // (bf16 only: in the fp32 instantiation, whose K loop is matrix-bound, the branch costs 4 % on every launch)
+    const bool wave_on = kF32 || ((n0 + wn * TN * 32 < N) && (m0 + wm * TM * 32 < M));
     auto load_frags = [&](const char* base, int ks, int buf) {
         if (!wave_on) return;
         const int choff = (((ks << 1) | lhi) ^ sw) << 4;
