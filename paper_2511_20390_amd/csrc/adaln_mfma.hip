@@ -23,6 +23,10 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kChunk = 6;                  // k-steps (1 KB of weights per wavefront each) per register set
 constexpr int kBatch = 16;
 
+// kExact: D / 32 is a multiple of 2 * kChunk (DiT-XL: 36 steps), so every load and product below is issued
+// unconditionally.  With the guards of the general form the compiler cannot count the loads in flight and waits
+// for all of them (vmcnt(0)) before the first product of a register set - the other set's loads included.
+template <bool kExact>
 __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
     const float* __restrict__ sc, int32_t B, int32_t D, const void* const* __restrict__ w_tab,
     const float* const* __restrict__ b_tab, const int32_t* __restrict__ row_start, int32_t n_mats,
@@ -31,21 +35,40 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
     const int row_bytes = D * 2 + 16;                       // odd number of 16-byte chunks per row
     char* s_hi = lds;
     char* s_lo = lds + kBatch * row_bytes;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // (the wavefront index is made a scalar: row blocks, matrix index and table lookups then stay in scalar
+    // registers - as per-lane values every table lookup is a vector load whose wait drains the weight loads)
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // stage SiLU(c) as hi + lo bf16 parts; rows past B are zero
-    for (int i = tid; i < kBatch * (D / 2); i += kThreads) {
-        const int b = i / (D / 2), p = i % (D / 2);
-        float v0 = 0.f, v1 = 0.f;
-        if (b < B) {
-            const float2 v = reinterpret_cast<const float2*>(sc + static_cast<int64_t>(b) * D)[p];
-            v0 = v.x;
-            v1 = v.y;
+    // stage SiLU(c) as hi + lo bf16 parts; rows past B are zero.  Every thread requests its (up to kStage) 16-byte
+    // pieces before it converts the first one: one memory round trip per batch instead of one per piece, and this
+    // prologue is exposed - all workgroups of the launch are resident at once and start with it.
+    {
+        constexpr int kStage = 9;
+        const int per_row = D / 4, nvec = kBatch * per_row;
+        for (int base = tid; base < nvec; base += kThreads * kStage) {
+            float4 v[kStage];
+#pragma unroll
+            for (int u = 0; u < kStage; ++u) {
+                const int i = base + u * kThreads;
+                const int b = i / per_row, p = i - b * per_row;
+                const bool live = i < nvec && b < B;
+                v[u] = reinterpret_cast<const float4*>(sc + static_cast<int64_t>(live ? b : 0) * D)[live ? p : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < kStage; ++u) {
+                const int i = base + u * kThreads;
+                if (i < nvec) {
+                    const int b = i / per_row, p = i - b * per_row;
+                    const bool live = b < B;
+                    const float x0 = live ? v[u].x : 0.f, x1 = live ? v[u].y : 0.f, x2 = live ? v[u].z : 0.f, x3 = live ? v[u].w : 0.f;
+                    const uint32_t h0 = pack_bf16_pair(x0, x1), h1 = pack_bf16_pair(x2, x3);
+                    const uint32_t l0 = pack_bf16_pair(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h0 & 0xffff0000u));
+                    const uint32_t l1 = pack_bf16_pair(x2 - __uint_as_float(h1 << 16), x3 - __uint_as_float(h1 & 0xffff0000u));
+                    *reinterpret_cast<uint2*>(s_hi + b * row_bytes + p * 8) = uint2{h0, h1};
+                    *reinterpret_cast<uint2*>(s_lo + b * row_bytes + p * 8) = uint2{l0, l1};
+                }
+            }
         }
-        const uint32_t hi = pack_bf16_pair(v0, v1);
-        const float r0 = v0 - __uint_as_float(hi << 16), r1 = v1 - __uint_as_float(hi & 0xffff0000u);
-        *reinterpret_cast<uint32_t*>(s_hi + b * row_bytes + p * 4) = hi;
-        *reinterpret_cast<uint32_t*>(s_lo + b * row_bytes + p * 4) = pack_bf16_pair(r0, r1);
     }
     __syncthreads();
 
@@ -66,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
     auto load = [&](u32x4_t (&dst)[kChunk], const char* wrow, int st0) {
 #pragma unroll
         for (int u = 0; u < kChunk; ++u)
-            if (st0 + u < steps) dst[u] = *(gvec)(wrow + (st0 + u) * 64);
+            if (kExact || st0 + u < steps) dst[u] = *(gvec)(wrow + (st0 + u) * 64);
     };
     int mat = 0;
     auto row_ptr = [&](int blk) {          // advances `mat` to the matrix that holds row block blk
@@ -84,12 +107,16 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
         const int r0 = blk * 16;
         const int cur_mat = mat;
         const int lr0 = r0 - row_start[cur_mat];
-        const char* wnext = (blk + 1 < last) ? row_ptr(blk + 1) : nullptr;
+        // (after the last block of an exact launch the prefetch re-reads this block's first chunk: in bounds, unused)
+        const char* wnext = (blk + 1 < last) ? row_ptr(blk + 1) : (kExact ? wrow : nullptr);
+        // (requested before the weights of this block: loads complete in order, so a bias load placed after the
+        // k loop would wait for the next block's prefetch)
+        const f32x4_t bias = *(const __attribute__((address_space(1))) f32x4_t*)(b_tab[cur_mat] + lr0 + 4 * lq);
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
         auto multiply = [&](const u32x4_t (&src)[kChunk], int st0) {
 #pragma unroll
             for (int u = 0; u < kChunk; ++u)
-                if (st0 + u < steps) {
+                if (kExact || st0 + u < steps) {
                     const bf16x8_t a = __builtin_bit_cast(bf16x8_t, src[u]);
                     const bf16x8_t h = *reinterpret_cast<const bf16x8_t*>(bh + (st0 + u) * 64);
                     const bf16x8_t l = *reinterpret_cast<const bf16x8_t*>(bl + (st0 + u) * 64);
@@ -97,20 +124,35 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acc, 0, 0, 0);
                 }
         };
-        for (int st0 = 0; st0 < steps; st0 += 2 * kChunk) {
-            load(wb, wrow, st0 + kChunk);
-            multiply(wa, st0);
-            if (st0 + 2 * kChunk < steps) load(wa, wrow, st0 + 2 * kChunk);
-            else if (wnext) load(wa, wnext, 0);
-            multiply(wb, st0 + kChunk);
+        if constexpr (kExact) {
+            // at least one pass (the launch checks steps >= 2 kChunk): a loop that may be skipped would make the
+            // bias load the youngest one on that path and the wait before the store a wait for everything
+            int st0 = 0;
+            do {
+                load(wb, wrow, st0 + kChunk);
+                __builtin_amdgcn_sched_barrier(0);      // the loads stay ahead of the products they overlap
+                multiply(wa, st0);
+                __builtin_amdgcn_sched_barrier(0);
+                load(wa, (st0 + 2 * kChunk < steps) ? wrow + (st0 + 2 * kChunk) * 64 : wnext, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(wb, st0 + kChunk);
+                st0 += 2 * kChunk;
+            } while (st0 < steps);
+        } else {
+            for (int st0 = 0; st0 < steps; st0 += 2 * kChunk) {
+                load(wb, wrow, st0 + kChunk);
+                multiply(wa, st0);
+                if (st0 + 2 * kChunk < steps) load(wa, wrow, st0 + 2 * kChunk);
+                else if (wnext) load(wa, wnext, 0);
+                multiply(wb, st0 + kChunk);
+            }
         }
         wrow = wnext;
         // accumulator register i of lane l: weight row 4*(l/16) + i, batch column l%16
-        if (l16 < B) {
-            const f32x4_t bias = *reinterpret_cast<const f32x4_t*>(b_tab[cur_mat] + lr0 + 4 * lq);
-            f32x4_t o;
+        f32x4_t o;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = acc[i] + bias[i];
+        for (int i = 0; i < 4; ++i) o[i] = acc[i] + bias[i];
+        if (l16 < B) {
             *reinterpret_cast<f32x4_t*>(mod + static_cast<int64_t>(l16) * total_rows + r0 + 4 * lq) = o;
         }
     }
@@ -125,22 +167,25 @@ bool adaln_mfma_supported(int32_t D, int32_t total_rows) { return D % 32 == 0 &&
 int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* const* w_tab,
                           const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
                           int32_t total_rows, float* mod, hipStream_t s) {
+    if ((reinterpret_cast<uintptr_t>(sc) | reinterpret_cast<uintptr_t>(mod)) & 15u) return FREE_ERR_SHAPE;
     const int nblocks = total_rows / 16;
     // about 16 wavefronts per CU at the DiT-XL size (12096 row blocks): measured best among 2, 3, 6, 12
     const int blocks_per_wave = nblocks >= 8192 ? 3 : 1;
     const int waves = (nblocks + blocks_per_wave - 1) / blocks_per_wave;
     const int grid = (waves + kWaves - 1) / kWaves;
     const size_t lds = 2 * static_cast<size_t>(kBatch) * (D * 2 + 16);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(adaln_mfma_kernel),
+    const bool exact = D >= 64 * kChunk && (D / 32) % (2 * kChunk) == 0;
+    auto kernel = exact ? adaln_mfma_kernel<true> : adaln_mfma_kernel<false>;
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[exact]) {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024)))
             return FREE_ERR_HIP;
-        attr_set = true;
+        attr_set[exact] = true;
     }
     for (int b0 = 0; b0 < B; b0 += kBatch) {
         const int nb = (B - b0 < kBatch) ? B - b0 : kBatch;
-        hipLaunchKernelGGL(adaln_mfma_kernel, dim3(grid), dim3(kThreads), lds, s, sc + static_cast<int64_t>(b0) * D,
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), lds, s, sc + static_cast<int64_t>(b0) * D,
                            nb, D, w_tab, b_tab, row_start, n_mats, total_rows, blocks_per_wave,
                            mod + static_cast<int64_t>(b0) * total_rows);
         if (!launch_ok()) return FREE_ERR_HIP;

@@ -30,6 +30,10 @@ constexpr int kSegRows = 16 * kWaves * kBlocksPerWave;      // weight rows per w
 // l * 6 D + {0: shift1, 1: scale1, 2: gate1, 3: shift2, 4: scale2, 5: gate2} * D.  w_tab / b_tab: 2 * depth
 // pointers (block l: QKV at 2 l, MLP-1 at 2 l + 1).  fold: [B, fold_stride]: c1 of all layers (block l: QKV rows,
 // then MLP-1 rows), then, total_rows further, c0 in the same order.
+// kExact: D / 32 is a multiple of 2 * kChunk and at least that (DiT-XL: 36 steps): every load and product is issued
+// unconditionally and the k loop runs at least once, so the compiler can count the loads in flight; with the guards
+// of the general form it waits for all of them before the first product of a register set.
+template <bool kExact>
 __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
     const float* __restrict__ mod, int32_t B, int32_t D, int32_t mod_stride, int32_t rows_qkv, int32_t rows_fc1,
     const void* const* __restrict__ w_tab, const float* const* __restrict__ b_tab, float* __restrict__ fold,
@@ -39,7 +43,8 @@ __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
     const int set_bytes = kBatch * row_bytes;
     char* s1_hi = lds;                                      // 1 + scale
     char* s0_hi = lds + set_bytes;                          // shift
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // (the wavefront index as a scalar: row-block bookkeeping stays in scalar registers)
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     const int segs_qkv = (rows_qkv + kSegRows - 1) / kSegRows, segs_fc1 = (rows_fc1 + kSegRows - 1) / kSegRows;
     const int per_block = segs_qkv + segs_fc1;
@@ -51,20 +56,36 @@ __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
     const float* shift = mod + static_cast<int64_t>(l) * 6 * D + (which ? 3 : 0) * D;
     const float* scale = shift + D;
 
-    // stage (1 + scale) and shift of every sample as hi + lo bf16 parts; rows past B are zero
-    for (int i = tid; i < kBatch * (D / 2); i += kThreads) {
-        const int b = i / (D / 2), p = i % (D / 2);
-        float a0 = 0.f, a1 = 0.f, t0 = 0.f, t1 = 0.f;
-        if (b < B) {
-            const float2 sc = reinterpret_cast<const float2*>(scale + static_cast<int64_t>(b) * mod_stride)[p];
-            const float2 sh = reinterpret_cast<const float2*>(shift + static_cast<int64_t>(b) * mod_stride)[p];
-            a0 = 1.0f + sc.x;
-            a1 = 1.0f + sc.y;
-            t0 = sh.x;
-            t1 = sh.y;
+    // stage (1 + scale) and shift of every sample rounded to bf16; rows past B are zero.  Every thread requests its
+    // (up to kStage) pairs of 16-byte pieces before it converts the first one: one memory round trip per batch.
+    {
+        constexpr int kStage = 9;
+        const int per_row = D / 4, nvec = kBatch * per_row;
+        for (int base = tid; base < nvec; base += kThreads * kStage) {
+            float4 vs[kStage], vt[kStage];
+#pragma unroll
+            for (int u = 0; u < kStage; ++u) {
+                const int i = base + u * kThreads;
+                const int b = i / per_row, p = i - b * per_row;
+                const bool live = i < nvec && b < B;
+                const int64_t off = static_cast<int64_t>(live ? b : 0) * mod_stride;
+                vs[u] = reinterpret_cast<const float4*>(scale + off)[live ? p : 0];
+                vt[u] = reinterpret_cast<const float4*>(shift + off)[live ? p : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < kStage; ++u) {
+                const int i = base + u * kThreads;
+                if (i < nvec) {
+                    const int b = i / per_row, p = i - b * per_row;
+                    const bool live = b < B;
+                    const float a0 = live ? 1.0f + vs[u].x : 0.f, a1 = live ? 1.0f + vs[u].y : 0.f;
+                    const float a2 = live ? 1.0f + vs[u].z : 0.f, a3 = live ? 1.0f + vs[u].w : 0.f;
+                    const float t0 = live ? vt[u].x : 0.f, t1 = live ? vt[u].y : 0.f, t2 = live ? vt[u].z : 0.f, t3 = live ? vt[u].w : 0.f;
+                    *reinterpret_cast<uint2*>(s1_hi + b * row_bytes + p * 8) = uint2{pack_bf16_pair(a0, a1), pack_bf16_pair(a2, a3)};
+                    *reinterpret_cast<uint2*>(s0_hi + b * row_bytes + p * 8) = uint2{pack_bf16_pair(t0, t1), pack_bf16_pair(t2, t3)};
+                }
+            }
         }
-        *reinterpret_cast<uint32_t*>(s1_hi + b * row_bytes + p * 4) = pack_bf16_pair(a0, a1);
-        *reinterpret_cast<uint32_t*>(s0_hi + b * row_bytes + p * 4) = pack_bf16_pair(t0, t1);
     }
     __syncthreads();
 
@@ -83,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
     auto load = [&](u32x4_t (&dst)[kChunk], const char* wrow, int st0) {
 #pragma unroll
         for (int u = 0; u < kChunk; ++u)
-            if (st0 + u < steps) dst[u] = *(gvec)(wrow + (st0 + u) * 64);
+            if (kExact || st0 + u < steps) dst[u] = *(gvec)(wrow + (st0 + u) * 64);
     };
     auto row_ptr = [&](int blk) { return wmat + (static_cast<int64_t>(blk * 16 + l16) * D) * 2 + lq * 16; };
     const char* wrow = nullptr;
@@ -93,32 +114,48 @@ __global__ __launch_bounds__(kThreads) void ln_fold_kernel(
     }
     for (int blk = first; blk < last; ++blk) {
         const int r0 = blk * 16;
-        const char* wnext = (blk + 1 < last) ? row_ptr(blk + 1) : nullptr;
+        // (after the last block of an exact launch the prefetch re-reads this block's first chunk: in bounds, unused)
+        const char* wnext = (blk + 1 < last) ? row_ptr(blk + 1) : (kExact ? wrow : nullptr);
+        // (requested before this block's weights: loads complete in order, and as a global - not generic - load)
+        const f32x4_t bv = *(const __attribute__((address_space(1))) f32x4_t*)(bias + r0 + 4 * lq);
         f32x4_t acc1 = {0.f, 0.f, 0.f, 0.f}, acc0 = {0.f, 0.f, 0.f, 0.f};
         auto multiply = [&](const u32x4_t (&src)[kChunk], int st0) {
 #pragma unroll
             for (int u = 0; u < kChunk; ++u)
-                if (st0 + u < steps) {
+                if (kExact || st0 + u < steps) {
                     const bf16x8_t a = __builtin_bit_cast(bf16x8_t, src[u]);
                     const int o = act_off + (st0 + u) * 64;
                     acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s1_hi + o), acc1, 0, 0, 0);
                     acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<const bf16x8_t*>(s0_hi + o), acc0, 0, 0, 0);
                 }
         };
-        for (int st0 = 0; st0 < steps; st0 += 2 * kChunk) {
-            load(wb, wrow, st0 + kChunk);
-            multiply(wa, st0);
-            if (st0 + 2 * kChunk < steps) load(wa, wrow, st0 + 2 * kChunk);
-            else if (wnext) load(wa, wnext, 0);
-            multiply(wb, st0 + kChunk);
+        if constexpr (kExact) {
+            int st0 = 0;
+            do {
+                load(wb, wrow, st0 + kChunk);
+                __builtin_amdgcn_sched_barrier(0);      // the loads stay ahead of the products they overlap
+                multiply(wa, st0);
+                __builtin_amdgcn_sched_barrier(0);
+                load(wa, (st0 + 2 * kChunk < steps) ? wrow + (st0 + 2 * kChunk) * 64 : wnext, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(wb, st0 + kChunk);
+                st0 += 2 * kChunk;
+            } while (st0 < steps);
+        } else {
+            for (int st0 = 0; st0 < steps; st0 += 2 * kChunk) {
+                load(wb, wrow, st0 + kChunk);
+                multiply(wa, st0);
+                if (st0 + 2 * kChunk < steps) load(wa, wrow, st0 + 2 * kChunk);
+                else if (wnext) load(wa, wnext, 0);
+                multiply(wb, st0 + kChunk);
+            }
         }
         wrow = wnext;
         // accumulator register i of lane l: weight row 4 (l / 16) + i, sample l % 16
-        if (l16 < B) {
-            const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(bias + r0 + 4 * lq);
-            f32x4_t o0;
+        f32x4_t o0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o0[i] = acc0[i] + bv[i];
+        for (int i = 0; i < 4; ++i) o0[i] = acc0[i] + bv[i];
+        if (l16 < B) {
             float* dst = fold + static_cast<int64_t>(l16) * fold_stride + out_row0 + r0 + 4 * lq;
             *reinterpret_cast<f32x4_t*>(dst) = acc1;
             *reinterpret_cast<f32x4_t*>(dst + total_rows) = o0;
@@ -139,19 +176,22 @@ int32_t launch_ln_fold(const float* mod, int32_t B, int32_t D, int32_t mod_strid
                        int64_t fold_stride, hipStream_t s) {
     if (!ln_fold_supported(D, rows_qkv, rows_fc1)) return FREE_ERR_SHAPE;
     const int32_t total_rows = depth * (rows_qkv + rows_fc1);
+    if ((reinterpret_cast<uintptr_t>(mod) | reinterpret_cast<uintptr_t>(fold)) & 15u) return FREE_ERR_SHAPE;
     if (fold_stride < 2 * static_cast<int64_t>(total_rows) || (fold_stride & 3) || (mod_stride & 3)) return FREE_ERR_SHAPE;
     const size_t lds = 2 * static_cast<size_t>(kBatch) * (static_cast<size_t>(D) * 2 + 16);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(ln_fold_kernel),
+    const bool exact = D >= 64 * kChunk && (D / 32) % (2 * kChunk) == 0;
+    auto kernel = exact ? ln_fold_kernel<true> : ln_fold_kernel<false>;
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[exact]) {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)))
             return FREE_ERR_HIP;
-        attr_set = true;
+        attr_set[exact] = true;
     }
     const int per_block = (rows_qkv + kSegRows - 1) / kSegRows + (rows_fc1 + kSegRows - 1) / kSegRows;
     for (int b0 = 0; b0 < B; b0 += kBatch) {
         const int nb = (B - b0 < kBatch) ? B - b0 : kBatch;
-        hipLaunchKernelGGL(ln_fold_kernel, dim3(depth * per_block), dim3(kThreads), lds, s,
+        hipLaunchKernelGGL(kernel, dim3(depth * per_block), dim3(kThreads), lds, s,
                            mod + static_cast<int64_t>(b0) * mod_stride, nb, D, mod_stride, rows_qkv, rows_fc1, w_tab, b_tab,
                            fold + static_cast<int64_t>(b0) * fold_stride, fold_stride, total_rows);
         if (!launch_ok()) return FREE_ERR_HIP;
