@@ -8,6 +8,9 @@
 // (lane l: row l%16, 16 bytes at k = 8*(l/16)), so they never touch LDS.  The activation
 // operand lives in LDS, split into a bf16 high part and a bf16 remainder (two MFMAs per
 // k-step) so that the fp32 conditioning vector loses no precision.
+// fp32 weights (FREE_FP32 mode) take the same route with v_mfma_f32_16x16x4_f32: a lane's 16 bytes are four
+// consecutive k of its row and feed four products, the activation operand is 16 bytes of the fp32 vector in LDS
+// at the same offset (lane group q of product j contracts k = 16 s + 4 q + j on both sides).
 #include "free_internal.h"
 
 namespace freemi {
@@ -26,14 +29,15 @@ constexpr int kBatch = 16;
 // kExact: D / 32 is a multiple of 2 * kChunk (DiT-XL: 36 steps), so every load and product below is issued
 // unconditionally.  With the guards of the general form the compiler cannot count the loads in flight and waits
 // for all of them (vmcnt(0)) before the first product of a register set - the other set's loads included.
-template <bool kExact>
+template <bool kExact, bool kF32>
 __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
     const float* __restrict__ sc, int32_t B, int32_t D, const void* const* __restrict__ w_tab,
     const float* const* __restrict__ b_tab, const int32_t* __restrict__ row_start, int32_t n_mats,
     int32_t total_rows, int32_t blocks_per_wave, float* __restrict__ mod) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int row_bytes = D * 2 + 16;                       // odd number of 16-byte chunks per row
-    char* s_hi = lds;
+    constexpr int kEl = kF32 ? 4 : 2;                       // bytes per weight
+    const int row_bytes = D * kEl + 16;                     // odd number of 16-byte chunks per row
+    char* s_hi = lds;                                       // (fp32 weights: the fp32 vector itself, one set)
     char* s_lo = lds + kBatch * row_bytes;
     // (the wavefront index is made a scalar: row blocks, matrix index and table lookups then stay in scalar
     // registers - as per-lane values every table lookup is a vector load whose wait drains the weight loads)
@@ -61,6 +65,10 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
                     const int b = i / per_row, p = i - b * per_row;
                     const bool live = b < B;
                     const float x0 = live ? v[u].x : 0.f, x1 = live ? v[u].y : 0.f, x2 = live ? v[u].z : 0.f, x3 = live ? v[u].w : 0.f;
+                    if constexpr (kF32) {
+                        *reinterpret_cast<float4*>(s_hi + b * row_bytes + p * 16) = float4{x0, x1, x2, x3};
+                        continue;
+                    }
                     const uint32_t h0 = pack_bf16_pair(x0, x1), h1 = pack_bf16_pair(x2, x3);
                     const uint32_t l0 = pack_bf16_pair(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h0 & 0xffff0000u));
                     const uint32_t l1 = pack_bf16_pair(x2 - __uint_as_float(h1 << 16), x3 - __uint_as_float(h1 & 0xffff0000u));
@@ -77,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
     const int first = (blockIdx.x * kWaves + wave) * blocks_per_wave;
     const char* bh = s_hi + l16 * row_bytes + lq * 16;
     const char* bl = s_lo + l16 * row_bytes + lq * 16;
-    const int steps = D / 32;
+    const int steps = D * kEl / 64;
     // Weight rows stream through two register sets of kChunk k-steps each: the loads of one set are in
     // flight while the other is multiplied, across row blocks too (the first chunk of the next block is
     // requested before the last chunk of this one is multiplied).  The pointers come from a table in
@@ -95,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
     auto row_ptr = [&](int blk) {          // advances `mat` to the matrix that holds row block blk
         const int r0 = blk * 16;
         while (mat + 1 < n_mats && r0 >= row_start[mat + 1]) ++mat;
-        return static_cast<const char*>(w_tab[mat]) + (static_cast<int64_t>(r0 - row_start[mat] + l16) * D) * 2 + lq * 16;
+        return static_cast<const char*>(w_tab[mat]) + (static_cast<int64_t>(r0 - row_start[mat] + l16) * D) * kEl + lq * 16;
     };
     const int last = (first + blocks_per_wave < nblocks) ? first + blocks_per_wave : nblocks;
     const char* wrow = nullptr;
@@ -117,6 +125,13 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
 #pragma unroll
             for (int u = 0; u < kChunk; ++u)
                 if (kExact || st0 + u < steps) {
+                    if constexpr (kF32) {
+                        const f32x4_t a = __builtin_bit_cast(f32x4_t, src[u]);
+                        const f32x4_t x = *reinterpret_cast<const f32x4_t*>(bh + (st0 + u) * 64);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j], x[j], acc, 0, 0, 0);
+                        continue;
+                    }
                     const bf16x8_t a = __builtin_bit_cast(bf16x8_t, src[u]);
                     const bf16x8_t h = *reinterpret_cast<const bf16x8_t*>(bh + (st0 + u) * 64);
                     const bf16x8_t l = *reinterpret_cast<const bf16x8_t*>(bl + (st0 + u) * 64);
@@ -160,28 +175,37 @@ __global__ __launch_bounds__(kThreads) void adaln_mfma_kernel(
 
 }  // namespace
 
-// Supported: bf16 weights, D % 32 == 0; every matrix has a multiple of 16 rows (true for
+// Supported: bf16 or fp32 weights, D % 32 == 0; every matrix has a multiple of 16 rows (true for
 // the 6D / 2D row stacks when D % 8 == 0).  16-byte aligned weight rows, biases and mod.
 bool adaln_mfma_supported(int32_t D, int32_t total_rows) { return D % 32 == 0 && total_rows % 16 == 0 && D <= 2048; }
 
 int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* const* w_tab,
                           const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
-                          int32_t total_rows, float* mod, hipStream_t s) {
+                          int32_t total_rows, int32_t mode, float* mod, hipStream_t s) {
     if ((reinterpret_cast<uintptr_t>(sc) | reinterpret_cast<uintptr_t>(mod)) & 15u) return FREE_ERR_SHAPE;
+    if (!adaln_mfma_supported(D, total_rows)) return FREE_ERR_SHAPE;
+    const bool f32 = mode == FREE_FP32;
     const int nblocks = total_rows / 16;
     // about 16 wavefronts per CU at the DiT-XL size (12096 row blocks): measured best among 2, 3, 6, 12
     const int blocks_per_wave = nblocks >= 8192 ? 3 : 1;
     const int waves = (nblocks + blocks_per_wave - 1) / blocks_per_wave;
     const int grid = (waves + kWaves - 1) / kWaves;
-    const size_t lds = 2 * static_cast<size_t>(kBatch) * (D * 2 + 16);
-    const bool exact = D >= 64 * kChunk && (D / 32) % (2 * kChunk) == 0;
-    auto kernel = exact ? adaln_mfma_kernel<true> : adaln_mfma_kernel<false>;
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[exact]) {
+    const int el = f32 ? 4 : 2;
+    const size_t lds = (f32 ? 1 : 2) * static_cast<size_t>(kBatch) * (D * el + 16);
+    const int steps = D * el / 64;
+    const bool exact = steps >= 2 * kChunk && steps % (2 * kChunk) == 0;
+    using kernel_t = void (*)(const float*, int32_t, int32_t, const void* const*, const float* const*, const int32_t*,
+                              int32_t, int32_t, int32_t, float*);
+    static const kernel_t kernels[4] = {adaln_mfma_kernel<false, false>, adaln_mfma_kernel<true, false>,
+                                        adaln_mfma_kernel<false, true>, adaln_mfma_kernel<true, true>};
+    const int which = 2 * f32 + exact;
+    const kernel_t kernel = kernels[which];
+    static bool attr_set[4] = {false, false, false, false};
+    if (!attr_set[which]) {
         if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024)))
             return FREE_ERR_HIP;
-        attr_set[exact] = true;
+        attr_set[which] = true;
     }
     for (int b0 = 0; b0 < B; b0 += kBatch) {
         const int nb = (B - b0 < kBatch) ? B - b0 : kBatch;

@@ -386,9 +386,9 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     }
     {
     ProfScope prof(&h->prof, PROF_ADALN, s);
-    if (d.mode == FREE_BF16 && adaln_mfma_supported(d.D, d.mod_rows))
+    if (adaln_mfma_supported(d.D, d.mod_rows))
         FREE_TRY(launch_adaln_mfma(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1,
-                                   d.mod_rows, mod, s));
+                                   d.mod_rows, d.mode, mod, s));
     else
         FREE_TRY(launch_adaln(sc, B, d.D, h->ada_w_tab, h->ada_b_tab, h->ada_row_start, d.depth + 1, d.mod_rows,
                               d.mode, mod, s));
@@ -1041,9 +1041,9 @@ int32_t drafter_modulation(free_drafter_t dr, const int32_t* t, const int32_t* y
                                  static_cast<const float*>(h->w[W_T_B1]), static_cast<const float*>(h->w[W_T_W2]),
                                  static_cast<const float*>(h->w[W_T_B2]),
                                  static_cast<const float*>(h->w[W_Y_TABLE]), cond_h, sc, s));
-    if (d.mode == FREE_BF16 && adaln_mfma_supported(d.D, dr->mod_rows))
+    if (adaln_mfma_supported(d.D, dr->mod_rows))
         return launch_adaln_mfma(sc, B, d.D, dr->ada_w_tab, dr->ada_b_tab, dr->ada_row_start, dr->depth + 1,
-                                 dr->mod_rows, mod, s);
+                                 dr->mod_rows, d.mode, mod, s);
     return launch_adaln(sc, B, d.D, dr->ada_w_tab, dr->ada_b_tab, dr->ada_row_start, dr->depth + 1, dr->mod_rows,
                         d.mode, mod, s);
 }

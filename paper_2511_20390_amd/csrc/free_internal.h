@@ -185,7 +185,7 @@ int32_t launch_frozen_draft(const float* x_a, const float* e, const float* coef_
                             float* m_draft, hipStream_t s);
 int32_t launch_sqdist(const float* a, const float* b, int32_t K, int64_t d, double* out, hipStream_t s);
 
-// ---- MFMA adaLN modulation GEMV, bf16 weights (adaln_mfma.hip)
+// ---- MFMA adaLN modulation GEMV, bf16 or fp32 weights as `mode` says (adaln_mfma.hip)
 bool adaln_mfma_supported(int32_t D, int32_t total_rows);
 // final_mfma.hip: final layer on the matrix cores (bf16 weights, DiT-S/B/L/XL widths)
 bool final_mfma_supported(int32_t D, int32_t P);
@@ -194,7 +194,7 @@ int32_t launch_final_layer_mfma(const float* x, RowVec shift, RowVec scale, int3
                                 hipStream_t s);
 int32_t launch_adaln_mfma(const float* sc, int32_t B, int32_t D, const void* const* w_tab,
                           const float* const* b_tab, const int32_t* row_start, int32_t n_mats,
-                          int32_t total_rows, float* mod, hipStream_t s);
+                          int32_t total_rows, int32_t mode, float* mod, hipStream_t s);
 
 // ---- MFMA kernels, bf16 only (gemm_mfma.hip, attn_mfma.hip) ------------------------
 bool mfma_linear_supported(int32_t M, int32_t N, int32_t K);
