@@ -465,7 +465,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     int tile_m, tile_n;
     tile_coords(group_m, blockIdx.x, tiles_m, tiles_n, &tile_m, &tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // (the wavefront index as a scalar: the position of the wavefront's part of the tile, the test for an all-padding
+    // wavefront and the LDS offsets that follow from it stay in scalar registers)
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
     // ---- global -> register staging: chunk idx = i*NT + tid, row = idx/8, chunk = idx%8
