@@ -249,6 +249,72 @@ __global__ __launch_bounds__(kThreads) void patch_embed16_kernel(
     }
 }
 
+// The same for widths up to 4 * kPeThreads (every DiT size) with four consecutive output columns per thread: the
+// position table is read and the tokens are written 16 bytes per lane, the four weight rows of a thread stay in
+// registers over kPeTok tokens, and the position loads of all of them are requested before the first is used.
+// Short workgroups (8 tokens) so that a two-sample launch still covers every CU.
+constexpr int kPeThreads = 320;            // 288 of them carry columns at D = 1152
+constexpr int kPeTok = 8;
+__global__ __launch_bounds__(kPeThreads) void patch_embed16v_kernel(
+    const float* __restrict__ x, int32_t x_mod, int32_t C, int32_t H, int32_t W, int32_t p, int32_t D,
+    const float* __restrict__ pw, const float* __restrict__ pb, const float* __restrict__ pos,
+    float* __restrict__ out, int32_t ntok) {
+    __shared__ __attribute__((aligned(16))) float patch[kPeTok][16];
+    const int gw = W / p;
+    const int n0 = blockIdx.x * kPeTok, b = blockIdx.y;
+    const float* xb = x + static_cast<int64_t>(b % x_mod) * C * H * W;
+    for (int e = threadIdx.x; e < kPeTok * 16; e += kPeThreads) {
+        const int tk = e >> 4, q = e & 15;
+        const int n = n0 + tk;
+        float v = 0.f;
+        if (n < ntok) {
+            const int gi = n / gw, gj = n % gw;
+            const int c = q / (p * p), ph = (q / p) % p, pq = q % p;
+            v = xb[(static_cast<int64_t>(c) * H + gi * p + ph) * W + gj * p + pq];
+        }
+        patch[tk][q] = v;
+    }
+    const int j0 = 4 * static_cast<int>(threadIdx.x);
+    const bool col_on = j0 < D;
+    const int jc = col_on ? j0 : 0;                     // idle lanes re-read column 0 and store nothing
+    float4 w[4][4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) w[c][q4] = reinterpret_cast<const float4*>(pw + static_cast<int64_t>(jc + c) * 16)[q4];
+    const float4 bias = *reinterpret_cast<const float4*>(pb + jc);
+    float4 pe[kPeTok];
+#pragma unroll
+    for (int u = 0; u < kPeTok; ++u) {
+        const int n = n0 + u < ntok ? n0 + u : ntok - 1;
+        pe[u] = *reinterpret_cast<const float4*>(pos + static_cast<int64_t>(n) * D + jc);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kPeTok; ++u) {
+        const int n = n0 + u;
+        float4 pv[4];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) pv[q4] = reinterpret_cast<const float4*>(patch[u])[q4];
+        float o[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float acc = c == 0 ? bias.x : (c == 1 ? bias.y : (c == 2 ? bias.z : bias.w));
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {               // same summation order as the generic kernel
+                acc = fmaf(pv[q4].x, w[c][q4].x, acc);
+                acc = fmaf(pv[q4].y, w[c][q4].y, acc);
+                acc = fmaf(pv[q4].z, w[c][q4].z, acc);
+                acc = fmaf(pv[q4].w, w[c][q4].w, acc);
+            }
+            o[c] = acc;
+        }
+        if (col_on && n < ntok)
+            *reinterpret_cast<float4*>(out + (static_cast<int64_t>(b) * ntok + n) * D + j0) =
+                make_float4(o[0] + pe[u].x, o[1] + pe[u].y, o[2] + pe[u].z, o[3] + pe[u].w);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // LayerNorm (no affine, biased variance, eps 1e-6) + per-sample modulate.
 // One wavefront per row; statistics in fp32, two-pass (mean, then centred
@@ -847,6 +913,12 @@ int32_t launch_patch_embed(const float* x, int32_t x_mod, int32_t B, int32_t C, 
                            int32_t p, int32_t D, const float* pw, const float* pb, const float* pos,
                            float* out, hipStream_t s) {
     const int ntok = (H / p) * (W / p);
+    auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    if (C * p * p == 16 && D % 4 == 0 && D <= 4 * kPeThreads && al16(pw) && al16(pb) && al16(pos) && al16(out)) {
+        hipLaunchKernelGGL(patch_embed16v_kernel, dim3((ntok + kPeTok - 1) / kPeTok, B), dim3(kPeThreads), 0, s, x, x_mod,
+                           C, H, W, p, D, pw, pb, pos, out, ntok);
+        return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+    }
     if (C * p * p == 16 && D <= 8 * kThreads && (reinterpret_cast<uintptr_t>(pw) & 15u) == 0) {
         const dim3 grid((ntok + kPatchTok - 1) / kPatchTok, B);
         const int nr = (D + kThreads - 1) / kThreads;
