@@ -104,7 +104,7 @@ def bench_round(args):
         model.close()
         return res, cfg, w, ri, (cx, ce, sg)
 
-    # set-up, untimed: --streams 0 asks the library to time both schedules of the block stack on these inputs
+    # set-up, untimed: --streams 0 asks the library to time the schedules (one, two, three streams) of the block stack on these inputs
     # (free_dit_tune, a blocking call outside the hot path) and to keep the faster one for this batch size
     tp = torch.cat([a["t"], a["t"]]) if B == 2 * K else a["t"]
     yp = torch.tensor([ri["y"]] * K + [cfg["num_classes"]] * (B - K), dtype=torch.int32, device="cuda:0")
@@ -126,7 +126,7 @@ def bench_round(args):
 
     # the same steps with each schedule forced (the per-kernel figures below refer to one stream)
     forced = {}
-    for n in (1, 2):
+    for n in (1, 2, 3):
         model.set_streams(n)
         step()
         torch.cuda.synchronize()
@@ -136,7 +136,7 @@ def bench_round(args):
         torch.cuda.synchronize()
         forced[n] = (time.perf_counter() - t0) * 1e3 / args.steps
     model.set_streams(args.streams)
-    ms_one_stream, ms_two_streams = forced[1], forced[2]
+    ms_one_stream, ms_two_streams, ms_three_streams = forced[1], forced[2], forced[3]
 
     # per-kernel durations: the same steps again, every launch bracketed by HIP events on its stream
     # (the library runs them in sequence on one stream while it profiles)
@@ -195,6 +195,7 @@ def bench_round(args):
     fwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if not k.startswith("verify") and k != "eps_to_mean")
     res = {
         "ms_per_step": ms_per_step, "ms_per_step_one_stream": ms_one_stream, "ms_per_step_two_streams": ms_two_streams,
+        "ms_per_step_three_streams": ms_three_streams,
         "batch_streams": args.streams, "stream_choice": stream_choice, "kernels": kernels, "roofline": roofline,
         "ln_folded": ln_folded, "kernels_with_separate_layer_norm": ln_separate,
         "forward": {"algorithmic_tflop": total_flops / 1e12, "ms_sum_of_kernels": fwd_ms,
@@ -519,9 +520,9 @@ def main():
     ap.add_argument("--relaxed", action="store_true")
     ap.add_argument("--ln-fold", default="auto", choices=["auto", "off", "require"],
                     help="LayerNorm folded into the GEMMs around it (bf16): the library's rule, never, or always")
-    ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
-                    help="0 (library default): the library times one and two streams over its first forwards and "
-                         "keeps the faster; 2: the halves of the packed batch run concurrently on two streams; "
+    ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="0: free_dit_tune times the schedules in the set-up and the faster one is kept; "
+                         "2 / 3: the halves / thirds of the packed batch run concurrently on as many streams; "
                          "1: every kernel in sequence on one stream (use this under rocprofv3 --kernel-trace so "
                          "that kernel durations are not inflated by overlap)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -591,6 +592,7 @@ def main():
                    "packed_batch": res["B"], "tokens": res["tokens_per_round"]},
         "batch_streams": res["batch_streams"], "stream_choice": res["stream_choice"], "ms_per_step_one_stream": res["ms_per_step_one_stream"],
         "ms_per_step_two_streams": res["ms_per_step_two_streams"],
+        "ms_per_step_three_streams": res["ms_per_step_three_streams"],
         "roofline": res["roofline"], "forward": res["forward"], "kernels": res["kernels"],
         "ln_folded": res["ln_folded"], "kernels_with_separate_layer_norm": res["kernels_with_separate_layer_norm"],
     }

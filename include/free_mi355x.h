@@ -138,27 +138,25 @@ size_t free_workspace_bytes(const free_dit_config* cfg, int32_t B);
 /* ---- schedule of the packed forward (Alg. 1: the K states of a round are
  *      independent samples of one batch) -------------------------------------
  * One stream (the default): the kernels of a forward run in sequence on the
- * caller's stream.  Two streams: when a batch has at least 2 samples and each
- * half at least 2048 token rows, the two halves of the batch run their
- * transformer blocks concurrently on two side streams owned by the handle; the
+ * caller's stream.  Several streams: when every part keeps at least 2048 token rows,
+ * the handle can cut the batch in two halves or three thirds and run their
+ * transformer blocks concurrently on side streams owned by the handle; the
  * work is forked from and joined back into the caller's stream by events, so
- * stream-ordered semantics towards the caller are unchanged, and the results are
- * bit-identical to those of one stream.  Which of the two is faster differs by
- * a few per cent either way between machines of the same type.
- *   free_dit_set_streams(h, n): n = 1 or 2 forces that schedule for every batch
- *     size of the handle; n = 0 (initial state) uses, per batch size, what
- *     free_dit_tune measured, and one stream where nothing was measured.
- *   free_dit_tune: NOT a hot-path call - it blocks.  Runs 24 forwards on the given
- *     inputs (arguments as for dit_forward_packed, no top_feat): six runs of four,
- *     the two schedules in turn; the last three forwards of a run are bracketed
- *     together by events on `stream`.  It waits for them, adds up the last two
- *     runs of each schedule and remembers two streams for this batch size if they
- *     were more than 0.5 % faster, one stream otherwise (the handle keeps the 8
- *     most recently tuned batch sizes).  A
- *     batch that can never split returns FREE_OK at once.  eps_out holds a valid
- *     forward result afterwards.
- *   free_dit_stream_choice(h, B): the schedule (1 or 2) a forward on B packed
- *     states would use now.
+ * stream-ordered semantics towards the caller are unchanged.  All schedules give bit-identical results; which one is
+ * faster differs by a few per cent between machines of one type.
+ *   free_dit_set_streams(h, n): n = 1, 2 or 3 forces that schedule for every batch
+ *     size (a batch too small for n parts takes the next smaller schedule); n = 0
+ *     (the initial state) uses, per batch size, what free_dit_tune measured, and
+ *     one stream where nothing was measured.
+ *   free_dit_tune(h, x, t, y, B, eps_out, workspace, ws_bytes, stream): NOT a
+ *     hot-path call - it enqueues up to 36 forwards of B samples (runs of four, the
+ *     schedules the batch allows in turn), WAITS for them on the host, adds up the
+ *     last two runs of each schedule and remembers the fastest split schedule for
+ *     this batch size if it was more than 0.5 % faster than one stream (up to 8
+ *     batch sizes per handle; the oldest entry is replaced).  eps_out holds a valid forward
+ *     afterwards.  Batches too small to split return at once.
+ *   free_dit_stream_choice(h, B): the schedule (1, 2 or 3) a forward on B packed
+ *     samples would take now.
  * Settings belong to the handle; calls on one handle must not race. */
 int32_t free_dit_set_streams(free_dit_t h, int32_t n);
 int32_t free_dit_tune(free_dit_t h, const float* x, const int32_t* t, const int32_t* y, int32_t B,

@@ -342,8 +342,9 @@ class FreeDit:
         self.d = self.C * self.H * self.W
 
     def set_streams(self, n: int) -> None:
-        """1 or 2: force that schedule of the block stack for every batch size; 0: what tune() measured per
-        batch size, one stream where nothing was measured (the initial state)."""
+        """1, 2 or 3: force that schedule of the block stack (the batch in one piece, two halves or three thirds on
+        as many streams) for every batch size; 0: what tune() measured per batch size, one stream where nothing
+        was measured (the initial state)."""
         _check(load().free_dit_set_streams(self.handle, int(n)), "free_dit_set_streams")
 
     def set_ln_fold(self, mode: int) -> None:
@@ -363,8 +364,8 @@ class FreeDit:
         return st
 
     def tune(self, x, t, y) -> int:
-        """Blocking, not a hot-path call: times both schedules on these inputs and keeps the faster one for
-        this batch size.  Returns the choice."""
+        """Blocking, not a hot-path call: times the schedules this batch allows (one, two, three streams) on these
+        inputs and keeps the fastest for this batch size.  Returns the choice."""
         import torch
         B = x.shape[0]
         eps = torch.empty(B, self.c_out, self.H, self.W, dtype=torch.float32, device=self.device)

@@ -26,13 +26,14 @@ struct Profiler {
 };
 
 namespace {
-// free_dit_tune: kTuneGroups runs of kTuneRun forwards, the two schedules in turn (1, 2, 1, 2, ...); the first
-// forward of a run is not timed (the schedules leave clocks and caches in different states), the others are
-// timed together, and the first pair of runs is not counted
-constexpr int kTuneGroups = 6, kTuneRun = 4;
-constexpr int kTuneTrials = kTuneGroups;      // event pairs the handle keeps for it
+// free_dit_tune: kTuneRounds runs of kTuneRun forwards per schedule, the eligible schedules in turn (1, 2, 3, 1, 2,
+// 3, ...); the first forward of a run is not timed (the schedules leave clocks and caches in different states), the
+// others are timed together, and the first run of each schedule is not counted
+constexpr int kMaxParts = 3;                  // streams the block stack of one forward may be cut over
+constexpr int kTuneRounds = 3, kTuneRun = 4;
+constexpr int kTuneTrials = kTuneRounds * kMaxParts;      // event pairs the handle keeps for it
 constexpr int kTuneSlots = 8;                 // batch sizes a handle remembers a tuned schedule for
-constexpr int64_t kMinSplitRows = 2048;       // token rows per half below which the split does not pay
+constexpr int64_t kMinSplitRows = 2048;       // token rows per part below which the split does not pay
 // token rows from which the folded-LayerNorm path is taken by default: its GEMMs use the two large tiles only
 constexpr int64_t kMinFoldRows = 4096;
 constexpr size_t kMaxProfSlots = 8192;
@@ -147,16 +148,16 @@ struct free_dit_s {
     const float* const* fold_b_tab = nullptr;
     int32_t ln_fold = FREE_LN_FOLD_AUTO;
     int device = 0;
-    // two side streams (default priority) on which the halves of a packed batch run concurrently
-    hipStream_t side[2] = {nullptr, nullptr};
+    // side streams (default priority) on which the two halves or three thirds of a packed batch run concurrently
+    hipStream_t side[kMaxParts] = {};
     hipEvent_t ev_fork = nullptr;
-    hipEvent_t ev_join[2] = {nullptr, nullptr};
-    // third side stream (default priority): the fold vectors of the folded LayerNorms are computed on it while
+    hipEvent_t ev_join[kMaxParts] = {};
+    // one more side stream (default priority): the fold vectors of the folded LayerNorms are computed on it while
     // the first block runs up to its out-projection; ev_fold_go orders it after the modulation, the block
     // stack waits for ev_fold_done before the first GEMM that reads the vectors
     hipStream_t fold_stream = nullptr;
     hipEvent_t ev_fold_go = nullptr, ev_fold_done = nullptr;
-    // Schedule of the block stack: forced (1 or 2) for every batch size, or 0 = per batch size what
+    // Schedule of the block stack: forced (1, 2 or 3 streams) for every batch size, or 0 = per batch size what
     // free_dit_tune measured, one stream where nothing was measured.
     int32_t forced_streams = 0;
     struct Tuned { int32_t batch = 0, choice = 0; } tuned[kTuneSlots];
@@ -169,6 +170,16 @@ struct free_dit_s {
         for (const Tuned& t : tuned)
             if (t.batch == B && t.choice) return t.choice;
         return 1;
+    }
+    // a batch may be cut into `parts` when every part keeps enough token rows to fill the chip
+    bool parts_eligible(int32_t B, int32_t parts) const {
+        return parts == 1 || (B >= parts && static_cast<int64_t>(B / parts) * dims.ntok >= kMinSplitRows);
+    }
+    // what a forward on B samples does: the wanted schedule, or the next smaller one that B allows
+    int32_t parts_for(int32_t B) const {
+        int32_t n = streams_for(B);
+        while (n > 1 && !parts_eligible(B, n)) --n;
+        return n;
     }
 
     const void* blk(int l, int which) const { return w[7 + 10 * l + which]; }
@@ -423,22 +434,22 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
         return run_block_stack(d, blkw, d.depth, mod, d.mod_rows, act, b0, nb, st, &h->prof, cu_share,
                                folded ? &fb : nullptr, fold_ready);
     };
-    // The samples of a packed batch are independent through all blocks, so the batch can be cut in two
-    // halves that run on two streams forked from (and joined back into) the caller's stream: while
-    // one half is in a bandwidth-bound phase (layer norm, the residual read-modify-write at the end
-    // of a GEMM, the first and last wave of tiles) the other half's matrix kernels fill the idle
+    // The samples of a packed batch are independent through all blocks, so the batch can be cut in two halves
+    // or three thirds that run on as many streams forked from (and joined back into) the caller's stream: while
+    // one part is in a bandwidth-bound phase (layer norm, the residual read-modify-write at the end
+    // of a GEMM, the first and last wave of tiles) the other parts' matrix kernels fill the idle
     // compute units.  Which schedule is faster differs between machines of the same type by a few
     // per cent either way, so one stream is the default and free_dit_tune measures on request.
-    // Both give the same numbers.  Per-kernel profiling needs serial execution, and small batches are
+    // All give the same numbers.  Per-kernel profiling needs serial execution, and small batches are
     // launch bound, so both keep the single stream.  Nothing here waits on the host.
-    const bool eligible = !h->prof.on && B >= 2 && static_cast<int64_t>(B / 2) * d.ntok >= kMinSplitRows;
-    const bool split = eligible && h->streams_for(B) == 2;
-    if (split) {
+    const int parts = h->prof.on ? 1 : h->parts_for(B);
+    if (parts > 1) {
         if (!hip_ok(hipEventRecord(h->ev_fork, s))) return FREE_ERR_HIP;
-        for (int i = 0; i < 2; ++i) {
-            const int b0 = i == 0 ? 0 : B / 2, b1 = i == 0 ? B / 2 : B;
+        for (int i = 0; i < parts; ++i) {
+            const int b0 = static_cast<int>(static_cast<int64_t>(i) * B / parts);
+            const int b1 = static_cast<int>(static_cast<int64_t>(i + 1) * B / parts);
             if (!hip_ok(hipStreamWaitEvent(h->side[i], h->ev_fork, 0))) return FREE_ERR_HIP;
-            FREE_TRY(run_blocks(b0, b1 - b0, h->side[i], 2));
+            FREE_TRY(run_blocks(b0, b1 - b0, h->side[i], parts));
             if (!hip_ok(hipEventRecord(h->ev_join[i], h->side[i]))) return FREE_ERR_HIP;
             if (!hip_ok(hipStreamWaitEvent(s, h->ev_join[i], 0))) return FREE_ERR_HIP;
         }
@@ -486,7 +497,7 @@ int32_t free_last_hip_error(void) { return g_last_hip_error; }
 
 int32_t free_dit_set_streams(free_dit_t h, int32_t n) {
     if (!h) return FREE_ERR_NULL;
-    if (n < 0 || n > 2) return FREE_ERR_RANGE;
+    if (n < 0 || n > kMaxParts) return FREE_ERR_RANGE;
     h->forced_streams = n;
     return FREE_OK;
 }
@@ -508,8 +519,7 @@ int32_t free_dit_ln_fold_active(free_dit_t h, int32_t B) {
 int32_t free_dit_stream_choice(free_dit_t h, int32_t B) {
     if (!h) return FREE_ERR_NULL;
     if (B < 1) return FREE_ERR_SHAPE;
-    const bool eligible = B >= 2 && static_cast<int64_t>(B / 2) * h->dims.ntok >= kMinSplitRows;
-    return eligible ? h->streams_for(B) : 1;
+    return h->parts_for(B);
 }
 
 int32_t free_profile_begin(free_dit_t h) {
@@ -676,7 +686,7 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
     h->fold_w_tab = reinterpret_cast<const void* const*>(db + off_fw);
     h->fold_b_tab = reinterpret_cast<const float* const*>(db + off_fb);
     bool ok = hip_ok(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
-    for (int i = 0; i < 2 && ok; ++i)
+    for (int i = 0; i < kMaxParts && ok; ++i)
         ok = hip_ok(hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking)) &&
              hip_ok(hipEventCreateWithFlags(&h->ev_join[i], hipEventDisableTiming));
     ok = ok && hip_ok(hipStreamCreateWithFlags(&h->fold_stream, hipStreamNonBlocking)) &&
@@ -693,7 +703,7 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
 int32_t free_dit_destroy(free_dit_t h) {
     if (!h) return FREE_ERR_NULL;
     int32_t st = FREE_OK;
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < kMaxParts; ++i) {
         if (h->side[i] && !hip_ok(hipStreamSynchronize(h->side[i]))) st = FREE_ERR_HIP;
         if (h->side[i] && !hip_ok(hipStreamDestroy(h->side[i]))) st = FREE_ERR_HIP;
         if (h->ev_join[i] && !hip_ok(hipEventDestroy(h->ev_join[i]))) st = FREE_ERR_HIP;
@@ -734,17 +744,21 @@ int32_t free_dit_tune(free_dit_t h, const float* x, const int32_t* t, const int3
     if (B < 1 || static_cast<int64_t>(B) * h->dims.ntok > INT32_MAX / 4) return FREE_ERR_SHAPE;
     FREE_TRY(check_ws(workspace, ws_bytes, make_layout(h->dims, B).total));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool eligible = B >= 2 && static_cast<int64_t>(B / 2) * h->dims.ntok >= kMinSplitRows;
-    if (!eligible) return FREE_OK;                      // such a batch never splits: nothing to measure
-    for (int i = 0; i < kTuneTrials; ++i)
+    int32_t sched[kMaxParts];
+    int ns = 0;
+    for (int32_t n = 1; n <= kMaxParts; ++n)
+        if (h->parts_eligible(B, n)) sched[ns++] = n;
+    if (ns < 2) return FREE_OK;                         // such a batch never splits: nothing to measure
+    const int groups = kTuneRounds * ns;
+    for (int i = 0; i < groups; ++i)
         for (int j = 0; j < 2; ++j)
             if (!h->tune_ev[i][j] && !hip_ok(hipEventCreate(&h->tune_ev[i][j]))) return FREE_ERR_HIP;
     const int32_t forced_before = h->forced_streams;
     const bool prof_before = h->prof.on;
     h->prof.on = false;
     int32_t st = FREE_OK;
-    for (int i = 0; i < kTuneGroups && st == FREE_OK; ++i) {
-        h->forced_streams = 1 + (i & 1);
+    for (int i = 0; i < groups && st == FREE_OK; ++i) {
+        h->forced_streams = sched[i % ns];
         for (int r = 0; r < kTuneRun && st == FREE_OK; ++r) {
             if (r == 1 && !hip_ok(hipEventRecord(h->tune_ev[i][0], s))) st = FREE_ERR_HIP;
             if (st == FREE_OK) st = forward_impl(h, x, B, t, y, B, eps_out, nullptr, static_cast<char*>(workspace), s);
@@ -754,16 +768,19 @@ int32_t free_dit_tune(free_dit_t h, const float* x, const int32_t* t, const int3
     h->forced_streams = forced_before;
     h->prof.on = prof_before;
     if (st != FREE_OK) return st;
-    // total time of the counted runs of each schedule; two streams must win by more than half a per cent
-    float tot[2] = {0.f, 0.f};
-    for (int i = 2; i < kTuneGroups; ++i) {
+    // total time of the counted runs of each schedule; several streams must win by more than half a per cent
+    float tot[kMaxParts] = {};
+    for (int i = ns; i < groups; ++i) {
         float el = 0.f;
         if (!hip_ok(hipEventSynchronize(h->tune_ev[i][1])) ||
             !hip_ok(hipEventElapsedTime(&el, h->tune_ev[i][0], h->tune_ev[i][1])))
             return FREE_ERR_HIP;
-        tot[i & 1] += el;
+        tot[i % ns] += el;
     }
-    const int32_t choice = tot[1] < 0.995f * tot[0] ? 2 : 1;
+    int best = 1;
+    for (int k = 2; k < ns; ++k)
+        if (tot[k] < tot[best]) best = k;
+    const int32_t choice = tot[best] < 0.995f * tot[0] ? sched[best] : 1;
     int slot = -1;
     for (int i = 0; i < kTuneSlots; ++i)
         if (h->tuned[i].batch == B) slot = i;

@@ -274,35 +274,36 @@ def test_mfma_calibration_is_sane():
 
 
 def test_batch_streams_same_result():
-    """The two halves of a large batch can run on two streams; the serial schedule (one stream) must give
-    the same numbers: every kernel reduces in the same order whatever the number of rows it is launched on.
-    One stream is the default; free_dit_tune (blocking, outside the hot path) measures both and keeps one."""
+    """The halves or thirds of a large batch can run on two or three streams; the serial schedule (one stream) must
+    give the same numbers: every kernel reduces in the same order whatever the number of rows it is launched on.
+    One stream is the default; free_dit_tune (blocking, outside the hot path) measures them and keeps one."""
     import torch
     from paper_2511_20390_amd import binding
-    # B = 5 at 1024 tokens: halves of 2 and 3 samples, both at or above the split threshold
-    cfg, w, x, t, y, eps0, feat0, model = _forward_case("xl2_512", "bf16", 5, seed=0)
+    # B = 7 at 1024 tokens: halves of 3 and 4 samples, thirds of 2, 2 and 3, all at or above the split threshold
+    cfg, w, x, t, y, eps0, feat0, model = _forward_case("xl2_512", "bf16", 7, seed=0)
     dx, dt, dy = pu.to_dev(x), pu.to_dev(t), pu.to_dev(y)
-    assert model.stream_choice(5) == 1                   # nothing measured, nothing forced: one stream
+    assert model.stream_choice(7) == 1                   # nothing measured, nothing forced: one stream
     results = {}
-    for n in (1, 2):
+    for n in (1, 2, 3):
         model.set_streams(n)
-        assert model.stream_choice(5) == n
+        assert model.stream_choice(7) == n
+        assert model.stream_choice(5) == min(n, 2)       # thirds of 5 samples would be too small: halves
         assert model.stream_choice(1) == 1               # a batch of one sample never splits
         eps, feat = model.dit_forward_packed(dx, dt, dy, want_feat=True)
         torch.cuda.synchronize()
         results[n] = (eps.cpu().numpy(), feat.cpu().numpy())
     model.set_streams(0)
-    assert model.stream_choice(5) == 1
-    choice = model.tune(dx, dt, dy)                      # times both schedules on these inputs
-    assert choice in (1, 2) and model.stream_choice(5) == choice
-    assert model.stream_choice(4) == 1                   # measured for 5 packed states only
+    assert model.stream_choice(7) == 1
+    choice = model.tune(dx, dt, dy)                      # times the schedules on these inputs
+    assert choice in (1, 2, 3) and model.stream_choice(7) == choice
+    assert model.stream_choice(6) == 1                   # measured for 7 packed states only
     eps, feat = model.dit_forward_packed(dx, dt, dy, want_feat=True)
     torch.cuda.synchronize()
     results[0] = (eps.cpu().numpy(), feat.cpu().numpy())
-    for n in (1, 2, 0):
+    for n in (1, 2, 3, 0):
         assert np.array_equal(eps0, results[n][0]) and np.array_equal(feat0, results[n][1]), n
     with pytest.raises(binding.FreeError):
-        model.set_streams(3)
+        model.set_streams(4)
     model.close()
 
 

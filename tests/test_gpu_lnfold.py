@@ -193,11 +193,11 @@ def test_folded_forward_is_the_default_at_the_headline_shape_and_both_schedules_
     t = pu.to_dev(rng.integers(0, 1000, B).astype(np.int32))
     y = pu.to_dev(rng.integers(0, cfg["num_classes"] + 1, B).astype(np.int32))
     outs = []
-    for n in (1, 2, 1):
+    for n in (1, 2, 3, 1):
         model.set_streams(n)
         outs.append(model.dit_forward_packed(x, t, y).clone())
     torch.cuda.synchronize()
-    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert all(torch.equal(outs[0], o) for o in outs[1:])
     model.set_ln_fold(binding.LN_FOLD_OFF)
     model.set_streams(1)
     off = model.dit_forward_packed(x, t, y)
