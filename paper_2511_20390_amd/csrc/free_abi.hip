@@ -148,10 +148,11 @@ struct free_dit_s {
     const float* const* fold_b_tab = nullptr;
     int32_t ln_fold = FREE_LN_FOLD_AUTO;
     int device = 0;
-    // side streams (default priority) on which the two halves or three thirds of a packed batch run concurrently
-    hipStream_t side[kMaxParts] = {};
+    // side streams (default priority): the parts of a packed batch after the first run on them, concurrently with
+    // the first part on the caller's stream
+    hipStream_t side[kMaxParts - 1] = {};
     hipEvent_t ev_fork = nullptr;
-    hipEvent_t ev_join[kMaxParts] = {};
+    hipEvent_t ev_join[kMaxParts - 1] = {};
     // one more side stream (default priority): the fold vectors of the folded LayerNorms are computed on it while
     // the first block runs up to its out-projection; ev_fold_go orders it after the modulation, the block
     // stack waits for ev_fold_done before the first GEMM that reads the vectors
@@ -444,15 +445,24 @@ int32_t forward_impl(free_dit_t h, const float* x, int32_t x_mod, const int32_t*
     // launch bound, so both keep the single stream.  Nothing here waits on the host.
     const int parts = h->prof.on ? 1 : h->parts_for(B);
     if (parts > 1) {
+        // the first part stays on the caller's stream, the others go to side streams (with the stream of the fold
+        // vectors that makes at most four streams, the number of hardware queues a process has by default)
         if (!hip_ok(hipEventRecord(h->ev_fork, s))) return FREE_ERR_HIP;
-        for (int i = 0; i < parts; ++i) {
-            const int b0 = static_cast<int>(static_cast<int64_t>(i) * B / parts);
-            const int b1 = static_cast<int>(static_cast<int64_t>(i + 1) * B / parts);
-            if (!hip_ok(hipStreamWaitEvent(h->side[i], h->ev_fork, 0))) return FREE_ERR_HIP;
-            FREE_TRY(run_blocks(b0, b1 - b0, h->side[i], parts));
-            if (!hip_ok(hipEventRecord(h->ev_join[i], h->side[i]))) return FREE_ERR_HIP;
-            if (!hip_ok(hipStreamWaitEvent(s, h->ev_join[i], 0))) return FREE_ERR_HIP;
+        auto bounds = [&](int i, int* b0, int* b1) {
+            *b0 = static_cast<int>(static_cast<int64_t>(i) * B / parts);
+            *b1 = static_cast<int>(static_cast<int64_t>(i + 1) * B / parts);
+        };
+        int b0, b1;
+        for (int i = 1; i < parts; ++i) {
+            bounds(i, &b0, &b1);
+            if (!hip_ok(hipStreamWaitEvent(h->side[i - 1], h->ev_fork, 0))) return FREE_ERR_HIP;
+            FREE_TRY(run_blocks(b0, b1 - b0, h->side[i - 1], parts));
+            if (!hip_ok(hipEventRecord(h->ev_join[i - 1], h->side[i - 1]))) return FREE_ERR_HIP;
         }
+        bounds(0, &b0, &b1);
+        FREE_TRY(run_blocks(b0, b1 - b0, s, parts));
+        for (int i = 1; i < parts; ++i)
+            if (!hip_ok(hipStreamWaitEvent(s, h->ev_join[i - 1], 0))) return FREE_ERR_HIP;
     } else {
         FREE_TRY(run_blocks(0, B, s, 1));
     }
@@ -686,7 +696,7 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
     h->fold_w_tab = reinterpret_cast<const void* const*>(db + off_fw);
     h->fold_b_tab = reinterpret_cast<const float* const*>(db + off_fb);
     bool ok = hip_ok(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
-    for (int i = 0; i < kMaxParts && ok; ++i)
+    for (int i = 0; i < kMaxParts - 1 && ok; ++i)
         ok = hip_ok(hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking)) &&
              hip_ok(hipEventCreateWithFlags(&h->ev_join[i], hipEventDisableTiming));
     ok = ok && hip_ok(hipStreamCreateWithFlags(&h->fold_stream, hipStreamNonBlocking)) &&
@@ -703,7 +713,7 @@ int32_t free_dit_create(const free_dit_config* cfg, const void* const* weight_pt
 int32_t free_dit_destroy(free_dit_t h) {
     if (!h) return FREE_ERR_NULL;
     int32_t st = FREE_OK;
-    for (int i = 0; i < kMaxParts; ++i) {
+    for (int i = 0; i < kMaxParts - 1; ++i) {
         if (h->side[i] && !hip_ok(hipStreamSynchronize(h->side[i]))) st = FREE_ERR_HIP;
         if (h->side[i] && !hip_ok(hipStreamDestroy(h->side[i]))) st = FREE_ERR_HIP;
         if (h->ev_join[i] && !hip_ok(hipEventDestroy(h->ev_join[i]))) st = FREE_ERR_HIP;
