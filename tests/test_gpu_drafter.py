@@ -78,10 +78,12 @@ def test_draft_round_parity(name, K, cfg_scale, depth, mode):
         eps_r = (ref["m_draft"][k] - cxk * ref["x_states"][k].reshape(-1)) / cek
         err = pu.rel_l2(eps_g, eps_r)
         print(f"{name}/{mode} K={K} step {k}: eps rel-L2 {err:.3e}")
-        assert err <= pu.DIT_REL_L2[mode] * (1 if mode == "fp32" else 2)
+        assert err <= pu.DIT_REL_L2[mode]               # the forward's tolerance, at every step of the chain
     tol = 1e-4 if mode == "fp32" else 2e-2
     assert pu.rel_l2(out["x_last"].cpu().numpy(), ref["x_last"].reshape(-1)) <= tol
-    assert pu.rel_l2(out["f_last"].cpu().numpy(), ref["f_last"]) <= tol * 2
+    e_f = pu.rel_l2(out["f_last"].cpu().numpy(), ref["f_last"])
+    print(f"{name}/{mode} K={K}: last feature rel-L2 {e_f:.3e}")
+    assert e_f <= tol
     assert np.array_equal(out["x_states"][0].cpu().numpy(), di["x_a"])
     drafter.close()
     target.close()
