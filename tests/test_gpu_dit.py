@@ -328,10 +328,11 @@ def test_per_kernel_profile_belongs_to_the_handle():
     b.close()
 
 
-@pytest.mark.parametrize("name,mode,cfg_scale", [("small", "fp32", 4.0), ("xl2_512", "bf16", 4.0)])
-def test_spec_round_in_a_captured_graph(name, mode, cfg_scale):
+@pytest.mark.parametrize("name,mode,cfg_scale,streams", [("small", "fp32", 4.0, 0), ("xl2_512", "bf16", 4.0, 3)])
+def test_spec_round_in_a_captured_graph(name, mode, cfg_scale, streams):
     """spec_round enqueues kernels only (no allocation, no memset, no host synchronisation), so a caller can
-    capture it in a HIP graph - including the fork onto the handle's two side streams at the large shape.
+    capture it in a HIP graph - including, at the large shape, the fork onto the handle's side streams (the thirds
+    of the packed batch, the fold vectors of the folded LayerNorms) and the joins back into the capturing stream.
     Several replays with fresh inputs, eager work in between, each compared with the eager call."""
     import torch
     from paper_2511_20390_amd import binding
@@ -339,6 +340,7 @@ def test_spec_round_in_a_captured_graph(name, mode, cfg_scale):
     cfg = synth.dit_config(name)
     w = pu.weights_for(cfg, mode, seed=0)
     model = binding.FreeDit(cfg, w, mode)
+    model.set_streams(streams)
     cx, ce, sg = binding.free_ddpm_schedule()
 
     def inputs(seed):
