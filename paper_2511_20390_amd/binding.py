@@ -358,7 +358,7 @@ class FreeDit:
         return bool(st)
 
     def stream_choice(self, B: int) -> int:
-        """The schedule (1 or 2 streams) a forward on B packed states would use now."""
+        """The schedule (1, 2 or 3 streams) a forward on B packed states would use now."""
         st = int(load().free_dit_stream_choice(self.handle, int(B)))
         _check(min(st, 0), "free_dit_stream_choice")
         return st
