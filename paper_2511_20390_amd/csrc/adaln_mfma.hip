@@ -1,4 +1,4 @@
-// adaLN modulation of every block and of the final layer in one launch, bf16 weights:
+// adaLN modulation of every block and of the final layer in one launch (bf16 weights; fp32 weights below):
 //   mod[b, r] = sum_i SiLU(c)[b, i] W_r[i] + bias_r       (packed batch b, row r of the
 //   stacked modulation matrices; the conditioning vector c is constant across blocks,
 //   so the whole stack is one skinny GEMM that reads a third of all DiT parameters).
@@ -26,7 +26,8 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kChunk = 6;                  // k-steps (1 KB of weights per wavefront each) per register set
 constexpr int kBatch = 16;
 
-// kExact: D / 32 is a multiple of 2 * kChunk (DiT-XL: 36 steps), so every load and product below is issued
+// kExact: the k-steps of a row (64 bytes each: D / 32 in bf16, D / 16 in fp32; DiT-XL: 36 / 72) are a multiple of
+// 2 * kChunk, so every load and product below is issued
 // unconditionally.  With the guards of the general form the compiler cannot count the loads in flight and waits
 // for all of them (vmcnt(0)) before the first product of a register set - the other set's loads included.
 template <bool kExact, bool kF32>
