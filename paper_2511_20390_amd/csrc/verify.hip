@@ -196,13 +196,28 @@ __global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(
         bool ok = true;
         if (k < K) {
             const int64_t pr = traj * K + k;
-            const double* p = partial + pr * splits * 2;
-            for (int s = 0; s < splits; ++s) { s2 += p[2 * s]; s3 += p[2 * s + 1]; }
-            const double sg = sigma ? static_cast<double>(sigma[pr]) : 1.0;   // null: the sums are whitened already
-            const double l = -(s3 + 0.5 * s2) / (sg * sg);          // Eq. (qp)
-            const double lam = lambda ? static_cast<double>(lambda[pr]) : 1.0;
-            const double thr = fmin(0.0, lam * l);                  // Eq. (acc_relax) in the log domain
+            // Everything this lane needs is requested before anything is used: the three scalars (a null pointer
+            // reads u in its place and is replaced by one below) and the partial sums eight at a time - one memory
+            // round trip per batch instead of one per value, on the critical path of every workgroup of the launch.
+            // The sums are added in index order whatever the batching (entries past the end add an exact zero).
             const float uu = u[pr];
+            const float sg_raw = (sigma ? sigma : u)[pr];
+            const float lam_raw = (lambda ? lambda : u)[pr];
+            const double2* p = reinterpret_cast<const double2*>(partial + pr * splits * 2);
+            for (int s0 = 0; s0 < splits; s0 += 8) {
+                double2 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = p[s0 + j < splits ? s0 + j : splits - 1];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    s2 += s0 + j < splits ? v[j].x : 0.0;
+                    s3 += s0 + j < splits ? v[j].y : 0.0;
+                }
+            }
+            const double sg = sigma ? static_cast<double>(sg_raw) : 1.0;      // null: the sums are whitened already
+            const double l = -(s3 + 0.5 * s2) / (sg * sg);          // Eq. (qp)
+            const double lam = lambda ? static_cast<double>(lam_raw) : 1.0;
+            const double thr = fmin(0.0, lam * l);                  // Eq. (acc_relax) in the log domain
             ok = (s2 == 0.0) || (uu <= 0.0f) || (log(static_cast<double>(uu)) <= thr);
             if (writer) {
                 log_ratio[pr] = static_cast<float>(l);
