@@ -60,6 +60,49 @@ __global__ __launch_bounds__(kThreads) void small_linear_kernel(
     }
 }
 
+// The same with one wavefront per output column j for ALL samples: the weight row is read once per eight samples
+// instead of once per sample, in 16-byte pieces, and a launch has N / 4 workgroups instead of B N / 4
+// (K % 4 == 0, 16-byte aligned rows).  Sample b0 + q is reduced in lane order and written by lane q.
+template <bool SILU>
+__global__ __launch_bounds__(kThreads) void small_linear_rows_kernel(
+    const float* __restrict__ in, int32_t B, int32_t K, int32_t N, const float* __restrict__ W,
+    const float* __restrict__ bias, const float* __restrict__ table, const int32_t* __restrict__ row,
+    float* __restrict__ out) {
+    constexpr int kSamples = 8;
+    const int j = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (j >= N) return;
+    const float4* w4 = reinterpret_cast<const float4*>(W + static_cast<int64_t>(j) * K);
+    const int k4 = K / 4;
+    for (int b0 = 0; b0 < B; b0 += kSamples) {
+        float acc[kSamples];
+#pragma unroll
+        for (int q = 0; q < kSamples; ++q) acc[q] = 0.f;
+#pragma unroll 2
+        for (int i = lane; i < k4; i += 64) {
+            const float4 wv = w4[i];
+#pragma unroll
+            for (int q = 0; q < kSamples; ++q) {
+                const int b = b0 + q < B ? b0 + q : B - 1;         // past the end: the last sample again, not stored
+                const float4 xv = reinterpret_cast<const float4*>(in + static_cast<int64_t>(b) * K)[i];
+                acc[q] = fmaf(xv.w, wv.w, fmaf(xv.z, wv.z, fmaf(xv.y, wv.y, fmaf(xv.x, wv.x, acc[q]))));
+            }
+        }
+        float mine = 0.f;
+#pragma unroll
+        for (int q = 0; q < kSamples; ++q) {
+            const float t = wave_sum_f(acc[q]);
+            if (lane == q) mine = t;
+        }
+        const int b = b0 + lane;
+        if (lane < kSamples && b < B) {
+            float v = mine + bias[j];
+            if (table) v += table[static_cast<int64_t>(row[b]) * N + j];
+            out[static_cast<int64_t>(b) * N + j] = SILU ? silu_f(v) : v;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // adaLN modulation for all blocks and the final layer in one launch:
 //   mod[b, r] = sum_i sc[b, i] W_r[i] + bias_r
@@ -875,6 +918,15 @@ int32_t launch_conditioning(const int32_t* t, const int32_t* y, int32_t B, int32
     const int n = B * (tfreq / 2);
     hipLaunchKernelGGL(timestep_embed_kernel, dim3((n + 255) / 256), dim3(256), 0, s, t, B, tfreq, temb);
     if (!launch_ok()) return FREE_ERR_HIP;
+    auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    if (tfreq % 4 == 0 && D % 4 == 0 && al16(h1) && al16(w1) && al16(w2)) {
+        const dim3 g((D + kWaves - 1) / kWaves);
+        hipLaunchKernelGGL(small_linear_rows_kernel<true>, g, dim3(kThreads), 0, s, temb, B, tfreq, D, w1, b1,
+                           static_cast<const float*>(nullptr), static_cast<const int32_t*>(nullptr), hid);
+        if (!launch_ok()) return FREE_ERR_HIP;
+        hipLaunchKernelGGL(small_linear_rows_kernel<true>, g, dim3(kThreads), 0, s, hid, B, D, D, w2, b2, ytab, y, sc);
+        return launch_ok() ? FREE_OK : FREE_ERR_HIP;
+    }
     dim3 g((D + kWaves - 1) / kWaves, B);
     hipLaunchKernelGGL(small_linear_kernel<true>, g, dim3(kThreads), 0, s, temb, B, tfreq, D, w1, b1,
                        static_cast<const float*>(nullptr), static_cast<const int32_t*>(nullptr), hid);
