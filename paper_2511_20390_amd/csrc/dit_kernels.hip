@@ -293,29 +293,32 @@ __global__ __launch_bounds__(kThreads) void patch_embed16_kernel(
 }
 
 // The same for widths up to 4 * kPeThreads (every DiT size) with four consecutive output columns per thread: the
-// position table is read and the tokens are written 16 bytes per lane, the four weight rows of a thread stay in
-// registers over kPeTok tokens, and the position loads of all of them are requested before the first is used.
-// Short workgroups (8 tokens) so that a two-sample launch still covers every CU.
+// position table is read and the tokens are written 16 bytes per lane, and the four weight rows of a thread stay in
+// registers.  A workgroup takes kPeTok consecutive tokens of up to kPeSamples samples: the position vectors are
+// loaded once and reused for every sample, all latent values it needs are gathered into LDS up front, and a
+// two-sample launch (the drafter's) still covers every CU.
 constexpr int kPeThreads = 320;            // 288 of them carry columns at D = 1152
-constexpr int kPeTok = 8;
+constexpr int kPeTok = 4;
+constexpr int kPeSamples = 16;
 __global__ __launch_bounds__(kPeThreads) void patch_embed16v_kernel(
-    const float* __restrict__ x, int32_t x_mod, int32_t C, int32_t H, int32_t W, int32_t p, int32_t D,
+    const float* __restrict__ x, int32_t x_mod, int32_t B, int32_t C, int32_t H, int32_t W, int32_t p, int32_t D,
     const float* __restrict__ pw, const float* __restrict__ pb, const float* __restrict__ pos,
     float* __restrict__ out, int32_t ntok) {
-    __shared__ __attribute__((aligned(16))) float patch[kPeTok][16];
+    __shared__ __attribute__((aligned(16))) float patch[kPeSamples][kPeTok][16];
     const int gw = W / p;
-    const int n0 = blockIdx.x * kPeTok, b = blockIdx.y;
-    const float* xb = x + static_cast<int64_t>(b % x_mod) * C * H * W;
-    for (int e = threadIdx.x; e < kPeTok * 16; e += kPeThreads) {
-        const int tk = e >> 4, q = e & 15;
+    const int n0 = blockIdx.x * kPeTok, b0 = blockIdx.y * kPeSamples;
+    const int nb = B - b0 < kPeSamples ? B - b0 : kPeSamples;
+    for (int e = threadIdx.x; e < nb * kPeTok * 16; e += kPeThreads) {
+        const int sb = e / (kPeTok * 16), tk = (e >> 4) % kPeTok, q = e & 15;
         const int n = n0 + tk;
         float v = 0.f;
         if (n < ntok) {
+            const float* xb = x + static_cast<int64_t>((b0 + sb) % x_mod) * C * H * W;
             const int gi = n / gw, gj = n % gw;
             const int c = q / (p * p), ph = (q / p) % p, pq = q % p;
             v = xb[(static_cast<int64_t>(c) * H + gi * p + ph) * W + gj * p + pq];
         }
-        patch[tk][q] = v;
+        patch[sb][tk][q] = v;
     }
     const int j0 = 4 * static_cast<int>(threadIdx.x);
     const bool col_on = j0 < D;
@@ -333,28 +336,30 @@ __global__ __launch_bounds__(kPeThreads) void patch_embed16v_kernel(
         pe[u] = *reinterpret_cast<const float4*>(pos + static_cast<int64_t>(n) * D + jc);
     }
     __syncthreads();
+    for (int sb = 0; sb < nb; ++sb) {
 #pragma unroll
-    for (int u = 0; u < kPeTok; ++u) {
-        const int n = n0 + u;
-        float4 pv[4];
+        for (int u = 0; u < kPeTok; ++u) {
+            const int n = n0 + u;
+            float4 pv[4];
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) pv[q4] = reinterpret_cast<const float4*>(patch[u])[q4];
-        float o[4];
+            for (int q4 = 0; q4 < 4; ++q4) pv[q4] = reinterpret_cast<const float4*>(patch[sb][u])[q4];
+            float o[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            float acc = c == 0 ? bias.x : (c == 1 ? bias.y : (c == 2 ? bias.z : bias.w));
+            for (int c = 0; c < 4; ++c) {
+                float acc = c == 0 ? bias.x : (c == 1 ? bias.y : (c == 2 ? bias.z : bias.w));
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {               // same summation order as the generic kernel
-                acc = fmaf(pv[q4].x, w[c][q4].x, acc);
-                acc = fmaf(pv[q4].y, w[c][q4].y, acc);
-                acc = fmaf(pv[q4].z, w[c][q4].z, acc);
-                acc = fmaf(pv[q4].w, w[c][q4].w, acc);
+                for (int q4 = 0; q4 < 4; ++q4) {               // same summation order as the generic kernel
+                    acc = fmaf(pv[q4].x, w[c][q4].x, acc);
+                    acc = fmaf(pv[q4].y, w[c][q4].y, acc);
+                    acc = fmaf(pv[q4].z, w[c][q4].z, acc);
+                    acc = fmaf(pv[q4].w, w[c][q4].w, acc);
+                }
+                o[c] = acc;
             }
-            o[c] = acc;
+            if (col_on && n < ntok)
+                *reinterpret_cast<float4*>(out + (static_cast<int64_t>(b0 + sb) * ntok + n) * D + j0) =
+                    make_float4(o[0] + pe[u].x, o[1] + pe[u].y, o[2] + pe[u].z, o[3] + pe[u].w);
         }
-        if (col_on && n < ntok)
-            *reinterpret_cast<float4*>(out + (static_cast<int64_t>(b) * ntok + n) * D + j0) =
-                make_float4(o[0] + pe[u].x, o[1] + pe[u].y, o[2] + pe[u].z, o[3] + pe[u].w);
     }
 }
 
@@ -967,8 +972,8 @@ int32_t launch_patch_embed(const float* x, int32_t x_mod, int32_t B, int32_t C, 
     const int ntok = (H / p) * (W / p);
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
     if (C * p * p == 16 && D % 4 == 0 && D <= 4 * kPeThreads && al16(pw) && al16(pb) && al16(pos) && al16(out)) {
-        hipLaunchKernelGGL(patch_embed16v_kernel, dim3((ntok + kPeTok - 1) / kPeTok, B), dim3(kPeThreads), 0, s, x, x_mod,
-                           C, H, W, p, D, pw, pb, pos, out, ntok);
+        hipLaunchKernelGGL(patch_embed16v_kernel, dim3((ntok + kPeTok - 1) / kPeTok, (B + kPeSamples - 1) / kPeSamples),
+                           dim3(kPeThreads), 0, s, x, x_mod, B, C, H, W, p, D, pw, pb, pos, out, ntok);
         return launch_ok() ? FREE_OK : FREE_ERR_HIP;
     }
     if (C * p * p == 16 && D <= 8 * kThreads && (reinterpret_cast<uintptr_t>(pw) & 15u) == 0) {
