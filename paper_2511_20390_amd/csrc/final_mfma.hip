@@ -74,34 +74,60 @@ __global__ __launch_bounds__(kThreads) void final_layer_mfma_kernel(
     const float* scr = scale.base + static_cast<int64_t>(row / scale.rows_per_sample) * scale.stride + k0;
     const int P = p * p * c_out;
     f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    // k-steps in groups of kG: the shift, scale and weight pieces of a whole group are requested together and
+    // only then used - one memory round trip per group on the critical path of the workgroup instead of two per
+    // k-step (left to itself the compiler keeps 72 registers and waits for every piece where it is used)
+    // (groups of two: 152 registers at NS = 9, three wavefronts per SIMD - every workgroup of a 12288-row launch
+    // resident at once; groups of three need 176 and were slower there)
+    constexpr int kG = 2;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        uint32_t hi[4], lo[4];
+    for (int g0 = 0; g0 < NS; g0 += kG) {
+        f32x4_t shv[kG][2], scv[kG][2];
+        u32x4_t wv[kG][2];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const f32x4_t sh = *reinterpret_cast<const f32x4_t*>(shr + 32 * s + 4 * h);
-            const f32x4_t sc = *reinterpret_cast<const f32x4_t*>(scr + 32 * s + 4 * h);
-            float v[4];
+        for (int u = 0; u < kG; ++u) {
+            const int s = g0 + u;
+            if (s >= NS) continue;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) v[c] = fmaf((xa[s][h][c] - mean) * rstd, 1.0f + sc[c], sh[c]);
+            for (int h = 0; h < 2; ++h) {
+                shv[u][h] = *reinterpret_cast<const f32x4_t*>(shr + 32 * s + 4 * h);
+                scv[u][h] = *reinterpret_cast<const f32x4_t*>(scr + 32 * s + 4 * h);
+            }
 #pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2) {
-                const uint32_t hp = pack_bf16_pair(v[2 * c2], v[2 * c2 + 1]);
-                hi[2 * h + c2] = hp;
-                lo[2 * h + c2] = pack_bf16_pair(v[2 * c2] - __uint_as_float(hp << 16),
-                                                v[2 * c2 + 1] - __uint_as_float(hp & 0xffff0000u));
+            for (int t = 0; t < 2; ++t) {
+                const int o = 16 * t + l16;
+                // (outputs past P re-read row 0 and are multiplied into columns that are never stored)
+                wv[u][t] = *reinterpret_cast<const u32x4_t*>(w + static_cast<int64_t>(o < P ? o : 0) * D + k0 + 32 * s);
             }
         }
-        const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, u32x4_t{hi[0], hi[1], hi[2], hi[3]});
-        const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], lo[2], lo[3]});
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int o = 16 * t + l16;
-            u32x4_t wv = {0, 0, 0, 0};
-            if (o < P) wv = *reinterpret_cast<const u32x4_t*>(w + static_cast<int64_t>(o) * D + k0 + 32 * s);
-            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, wv);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
+        for (int u = 0; u < kG; ++u) {
+            const int s = g0 + u;
+            if (s >= NS) continue;
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float v[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[c] = fmaf((xa[s][h][c] - mean) * rstd, 1.0f + scv[u][h][c], shv[u][h][c]);
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2) {
+                    const uint32_t hp = pack_bf16_pair(v[2 * c2], v[2 * c2 + 1]);
+                    hi[2 * h + c2] = hp;
+                    lo[2 * h + c2] = pack_bf16_pair(v[2 * c2] - __uint_as_float(hp << 16),
+                                                    v[2 * c2 + 1] - __uint_as_float(hp & 0xffff0000u));
+                }
+            }
+            const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, u32x4_t{hi[0], hi[1], hi[2], hi[3]});
+            const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], lo[2], lo[3]});
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int o = 16 * t + l16;
+                const bf16x8_t a = __builtin_bit_cast(bf16x8_t, o < P ? wv[u][t] : u32x4_t{0, 0, 0, 0});
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
+            }
         }
     }
     // accumulator register i of lane l: output 16 t + 4 (l / 16) + i, token row l % 16
