@@ -523,9 +523,23 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     // half of every fifth tile) takes part in the staging and the barriers only: its products would be thrown
     // away, and on a chip that runs at its power limit they are not free for the others.
     // (bf16 only: in the fp32 instantiation, whose K loop is matrix-bound, the branch costs 4 % on every launch)
+    // How the test enters the K loop depends on the wavefronts a SIMD holds.  Eight-wavefront workgroups (two per
+    // SIMD) keep it inside the loop: it splits the body into basic blocks, each k-step becomes "LDS traffic, wait
+    // for all of it, eight products", and the two wavefronts of a SIMD alternate - measured faster than the
+    // interleaved form.  Four-wavefront workgroups (one per SIMD: the tiles of problems with few rows) have nobody
+    // to alternate with: there the wait for the NEXT step's fragments in front of every burst is pure latency
+    // (measured 0.66 us per slice for 0.22 us of products), so they take one of two straight-line copies of the
+    // loop (with / without products, chosen once), in which the compiler counts the LDS reads in flight and the
+    // products of a step overlap the reads of the next.
     const bool wave_on = kF32 || ((n0 + wn * TN * 32 < N) && (m0 + wm * TM * 32 < M));
-    auto load_frags = [&](const char* base, int ks, int buf) {
-        if (!wave_on) return;
+    constexpr bool kStraight = !kF32 && WGM * WGN <= 4;
+    struct InLoop {};                                  // tag: test the flag inside the loop
+    auto is_on = [&](auto tag) {
+        if constexpr (std::is_same<decltype(tag), InLoop>::value) return wave_on;
+        else return decltype(tag)::value;
+    };
+    auto load_frags = [&](const char* base, int ks, int buf, auto tag) {
+        if (!is_on(tag)) return;
         const int choff = (((ks << 1) | lhi) ^ sw) << 4;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -545,8 +559,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     constexpr bool kLnEpi = EPI == FREE_EPI_LN_BIAS || EPI == FREE_EPI_LN_BIAS_GELU;
     [[maybe_unused]] float ln_a[TM];                       // folded LayerNorm: r of this lane's rows
 
-    auto mma = [&](int buf) {
-        if (!wave_on) return;
+    auto mma = [&](int buf, auto tag) {
+        if (!is_on(tag)) return;
         if constexpr (kF32) {
             // element e of the chunk: the lanes of group 0 / 1 hold the two k of one 32x32x2 product
 #pragma unroll
@@ -581,28 +595,28 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
     //   k-step 3: multiply | read fragments of step 0 of slice kt+1 from the other stage
     constexpr int MF = TM * TN * (kF32 ? 4 : 1), NR = TM + TN;
     constexpr int C1 = (NS + 2) / 3, C2 = (2 * NS + 2) / 3;      // portion boundaries
-    auto slice = [&](int kt, auto stash_next, auto fetch_ahead) {
+    auto slice = [&](int kt, auto stash_next, auto fetch_ahead, auto tag) {
         constexpr bool kStash = decltype(stash_next)::value, kFetch = decltype(fetch_ahead)::value;
         const char* base = lds + (kt & 1) * kStageBytes;
         const int nst = (kt + 1) & 1;
-        load_frags(base, 1, 1);
+        load_frags(base, 1, 1, tag);
         if (kStash) stash_range(nst, 0, C1);
         if (kFetch) fetch_range(kt + 2, 0, C1);
-        mma(0);
+        mma(0, tag);
         sched_hints<0, MF, NR, kStash ? C1 : 0, kFetch ? C1 : 0>();
-        load_frags(base, 2, 0);
+        load_frags(base, 2, 0, tag);
         if (kStash) stash_range(nst, C1, C2);
         if (kFetch) fetch_range(kt + 2, C1, C2);
-        mma(1);
+        mma(1, tag);
         sched_hints<0, MF, NR, kStash ? C2 - C1 : 0, kFetch ? C2 - C1 : 0>();
-        load_frags(base, 3, 1);
+        load_frags(base, 3, 1, tag);
         if (kStash) stash_range(nst, C2, NS);
         if (kFetch) fetch_range(kt + 2, C2, NS);
-        mma(0);
+        mma(0, tag);
         sched_hints<0, MF, NR, kStash ? NS - C2 : 0, kFetch ? NS - C2 : 0>();
         __syncthreads();
-        if (kStash) load_frags(lds + nst * kStageBytes, 0, 0);
-        mma(1);
+        if (kStash) load_frags(lds + nst * kStageBytes, 0, 0, tag);
+        mma(1, tag);
         sched_hints<0, MF, kStash ? NR : 0, 0, 0>();
     };
     const std::true_type yes{};
@@ -691,16 +705,26 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(
         }
     }
     __syncthreads();
-    load_frags(lds, 0, 0);
     // ---- steady state: slice kt multiplies while slice kt+1 moves registers -> LDS and
     //      slice kt+2 is requested from global memory
-    int kt = 0;
-    for (; kt + 2 < nk; ++kt) slice(kt, yes, yes);
-    if (kt + 1 < nk) {
-        slice(kt, yes, no);
-        ++kt;
+    auto k_loop = [&](auto tag) {
+        load_frags(lds, 0, 0, tag);
+        int kt = 0;
+        for (; kt + 2 < nk; ++kt) slice(kt, yes, yes, tag);
+        if (kt + 1 < nk) {
+            slice(kt, yes, no, tag);
+            ++kt;
+        }
+        slice(kt, no, no, tag);
+    };
+    if constexpr (kF32) {
+        k_loop(yes);
+    } else if constexpr (kStraight) {
+        if (wave_on) k_loop(yes);
+        else k_loop(no);
+    } else {
+        k_loop(InLoop{});
     }
-    slice(kt, no, no);
 
     // ---- epilogue
     // after the barrier of the last slice no wavefront reads the LDS tiles any more: each wavefront
